@@ -1,0 +1,193 @@
+/*
+ * caat.h -- C ABI of the MI355X (gfx950) partial-sync tensor-parallel block library.
+ *
+ * The library computes the hot path of CAAT-Net ("Tensor-Parallelism with Partially Synchronized
+ * Activations"): a tensor-parallel transformer sub-block whose row-parallel outputs are summed over
+ * the T tensor-parallel ranks only on the first hs = floor(h*p) hidden channels ("shared" channels)
+ * and stay rank-local on the others ("private" channels) -- Sec. 3, Eq. A3 (MLP) and Eq. A5
+ * (attention) -- followed by the residual add and the per-rank normalisation of Sec. 4, forward and
+ * backward.  All T ranks live on ONE GPU (the "logical devices" of Sec. 3.2), so the reduce over
+ * ranks is a reduction in HBM.
+ *
+ * Conventions that hold for every entry point
+ *  - Every pointer is a DEVICE pointer unless it is said to be a host pointer.  The caller owns
+ *    every buffer; the library never allocates or frees device memory.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *    on that stream and return without waiting for it.
+ *  - The return value is a caat_status.  Argument errors are detected on the host before anything
+ *    is launched and leave all outputs untouched.
+ *  - Storage is bf16 (IEEE bfloat16 bit patterns, 2 bytes) unless stated; accumulation is fp32;
+ *    results are rounded to bf16 once, round-to-nearest-even.
+ *  - Tensors are row-major with the rank index outermost: an activation is [T, tokens, h].
+ *    Weight shards use the [out_features, in_features] convention per rank.
+ *  - Device pointers must be 16-byte aligned; h, ffn/T and (n_heads/T)*head_dim must be multiples
+ *    of 8.  hs may be any integer in [0, h].
+ *  - Calls that overlap in time must not share output or workspace buffers.
+ */
+#ifndef CAAT_H
+#define CAAT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum caat_status {
+  CAAT_OK = 0,
+  CAAT_EINVAL = 1,      /* null pointer, T < 1, p outside [0,1] or NaN, unknown enum value */
+  CAAT_ESHAPE = 2,      /* ffn % T, n_heads % T, hs > h, a dimension that is not a multiple of 8 ... */
+  CAAT_EALIGN = 3,      /* a device pointer is not 16-byte aligned */
+  CAAT_EWORKSPACE = 4,  /* workspace smaller than caat_workspace_bytes() */
+  CAAT_EHIP = 5,        /* a HIP runtime call (kernel launch) reported an error */
+  CAAT_EUNSUPPORTED = 6 /* valid request that this build does not implement */
+} caat_status;
+
+typedef enum caat_kind {
+  CAAT_MLP_GELU = 0,    /* Y = gelu(X A),               LayerNorm or RMSNorm after the residual */
+  CAAT_MLP_SWIGLU = 1,  /* Y = silu(X Wg) * (X Wu) */
+  CAAT_ATTN = 2,        /* causal multi-head attention with RoPE, prefill / training forward */
+  CAAT_ATTN_DECODE = 3  /* full decoder layer (attention + SwiGLU MLP), one new token per sequence */
+} caat_kind;
+
+typedef enum caat_norm { CAAT_LAYERNORM = 0, CAAT_RMSNORM = 1 } caat_norm;
+
+/* Operand layouts of caat_gemm_bf16: which index of each operand is contiguous in memory. */
+typedef enum caat_gemm_layout {
+  CAAT_GEMM_NT = 0, /* a[M][K], b[N][K]  (forward GEMMs: activation x weight[out,in]^T)          */
+  CAAT_GEMM_NN = 1, /* a[M][K], b[K][N]  (data gradients: grad x weight[out,in])                 */
+  CAAT_GEMM_TN = 2  /* a[K][M], b[K][N]  (weight gradients: reduction over tokens)               */
+} caat_gemm_layout;
+
+/*
+ * Problem statement of one block call, following the paper's notation: hidden size h, tensor-
+ * parallel degree T (the paper's r), synchronisation factor p entering only through
+ * hs = floor(h*p) (Eq. A3), tokens = batch*seq.
+ */
+typedef struct caat_desc {
+  int kind;             /* caat_kind */
+  int norm;             /* caat_norm */
+  int h;                /* hidden size */
+  int ffn;              /* FFN size f over ALL ranks (each rank owns ffn/T columns); 0 for CAAT_ATTN */
+  int T;                /* number of emulated tensor-parallel ranks */
+  int hs;               /* number of shared channels, 0 <= hs <= h; see caat_shared_channels() */
+  long long tokens;     /* batch*seq */
+  int batch, seq;       /* attention kinds need both; MLP kinds only use tokens */
+  int n_heads, head_dim;/* attention kinds; each rank owns n_heads/T heads */
+  long long kv_len;     /* decode: number of filled cache positions; the new token sits at kv_len */
+  long long kv_cap;     /* decode: capacity (positions) of the cache buffers, > kv_len */
+  float eps;            /* norm epsilon */
+  float private_scale;  /* factor applied to private channels (Sec. 4 private channel scaling,
+                           sqrt(T) in the paper); 1.0f switches it off */
+  float rope_base;      /* RoPE base (10000) */
+} caat_desc;
+
+/* Byte offsets of the tensors caat_block_fwd leaves in the workspace (0 size = not present).  For tests
+ * and for callers that want the saved activations; everything else in the workspace is scratch. */
+typedef struct caat_ws_layout {
+  size_t total_bytes;
+  size_t off_P, bytes_P;       /* pre-activations: [T,tokens,ffn/T] (GELU) or [T,tokens,2*ffn/T] gate|up (SwiGLU) */
+  size_t off_Y, bytes_Y;       /* sigma output [T,tokens,ffn/T]; attention kinds: heads output H [T,tokens,hd_r] */
+  size_t off_mean, bytes_mean; /* fp32 [T,tokens] (LayerNorm only) */
+  size_t off_rstd, bytes_rstd; /* fp32 [T,tokens] */
+  size_t off_dZt, bytes_dZt;   /* backward: reduced gradient [T,tokens,h] */
+  size_t off_dP, bytes_dP;     /* backward: gradient of the pre-activations, same shape as P */
+  size_t off_Q, bytes_Q;       /* attention: rotated q, [T,batch,heads/T,seq,d]; K and V follow with the same size */
+  size_t off_scratch, bytes_scratch;
+} caat_ws_layout;
+
+/* Sec. 3 / Eq. A3: number of shared channels floor(h*p), evaluated in IEEE double.  Host function.
+ * Returns -1 if h < 0 or p is NaN or outside [0,1]. */
+int caat_shared_channels(int h, double p);
+
+/* Static, NUL-terminated description of a caat_status; never freed by the caller.  Host function. */
+const char* caat_status_string(int status);
+
+/* Workspace (bytes) that caat_block_fwd / caat_block_bwd need for `d` (host pointer).  0 on an invalid
+ * descriptor.  caat_workspace_layout fills `out` (host pointer) and returns a caat_status. */
+size_t caat_workspace_bytes(const caat_desc* d);
+int caat_workspace_layout(const caat_desc* d, caat_ws_layout* out);
+
+/*
+ * Partial channel-reduce (Eq. A3 / A5, second line) plus optional residual (Sec. 4):
+ *   out[m,i,l] = sum_{m'} y[m',i,l]            + resid[m,i,l]   for l <  hs   (shared)
+ *   out[m,i,l] = private_scale * y[m,i,l]      + resid[m,i,l]   for l >= hs   (private)
+ * y, resid, out: [T, tokens, h] bf16.  resid may be NULL (no residual; this is the backward reduce
+ * of Fig. 2b, accumulated in fp32).  out may alias y exactly (in place); then, if resid is NULL and
+ * private_scale == 1, only the hs shared columns are read and written, so HBM traffic is
+ * 4*T*hs bytes per token, proportional to p.  The sum runs over ranks in ascending order in fp32 and
+ * is rounded once, so the shared channels are bit-identical on all ranks.
+ */
+int caat_partial_sync(const void* y, const void* resid, void* out, int T, long long tokens, int h, int hs,
+                      float private_scale, void* hip_stream);
+
+/*
+ * Per-rank, per-token normalisation (the Norm of Sec. 4): x, y [T,tokens,h] bf16; gamma, beta [h] bf16
+ * (beta NULL for RMSNorm); mean (LayerNorm only, may be NULL for RMSNorm) and rstd: [T,tokens] fp32 outputs.
+ */
+int caat_norm_fwd(const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd,
+                  int norm, int T, long long tokens, int h, float eps, void* hip_stream);
+
+/*
+ * Backward of the norm placed BEFORE the reduce (Sec. 4, Fig. 2b):
+ *   g[m] = dres[m] + NormBwd(dy[m]; x[m], gamma)                (dres may be NULL)
+ * g is written to `g_out` (the un-reduced residual gradient, App. B) and, if `g_scaled` is not NULL,
+ * also to `g_scaled` with its private columns (l >= hs) multiplied by private_scale -- the buffer the
+ * backward partial channel-reduce then runs on in place.  dgamma/dbeta: [h] fp32, summed over tokens AND
+ * over ranks in a fixed order (Sec. 4: norm parameters are replicated, their gradients reduced).
+ * dbeta may be NULL for RMSNorm.  workspace: at least caat_norm_bwd_workspace_bytes() bytes.
+ */
+size_t caat_norm_bwd_workspace_bytes(int T, long long tokens, int h);
+int caat_norm_bwd(const void* dy, const void* dres, const void* x, const void* gamma, const float* mean,
+                  const float* rstd, void* g_out, void* g_scaled, float* dgamma, float* dbeta, int norm, int T,
+                  long long tokens, int h, int hs, float private_scale, void* workspace, size_t ws_bytes,
+                  void* hip_stream);
+
+/*
+ * Grouped bf16 shard GEMM with fp32 accumulation, the building block of Eq. A3's two contractions and of
+ * their gradients: for g in [0,G): c_g[M,N] = op(a_g) op(b_g), layouts per caat_gemm_layout.
+ * lda/ldb/ldc are row strides in elements, stride_* the distance between groups in elements.
+ * M,N,K >= 1 arbitrary except: the contiguous dimension of every operand and N must be multiples of 8.
+ */
+int caat_gemm_bf16(const void* a, const void* b, void* c, int layout, int G, long long M, long long N, long long K,
+                   long long lda, long long ldb, long long ldc, long long stride_a, long long stride_b,
+                   long long stride_c, void* hip_stream);
+
+/*
+ * Forward of one sub-block (Eq. A3 / A5 + Sec. 4):  Zt_m = SubLayer_m(x_m);  r_out_m = r_m + PCR(Zt)_m;
+ * x_out_m = Norm(r_out_m).
+ *   weights (host array of device pointers), by kind:
+ *     CAAT_MLP_GELU   : {A [T][ffn/T][h], B [T][h][ffn/T], gamma [h], beta [h] or NULL}
+ *     CAAT_MLP_SWIGLU : {Wgu [T][2*ffn/T][h] (gate rows then up rows), B [T][h][ffn/T], gamma, beta or NULL}
+ *     CAAT_ATTN       : {Wqkv [T][3*hd_r][h] (q rows, k rows, v rows; heads contiguous), Wo [T][h][hd_r],
+ *                        gamma, beta or NULL},  hd_r = (n_heads/T)*head_dim
+ *     CAAT_ATTN_DECODE: {gamma_attn [h], Wqkv, Wo, gamma_mlp [h], Wgu, B}; RMSNorm only
+ *   x, r       : [T,tokens,h] inputs (x already normalised; decode ignores x and normalises r itself)
+ *   r_out      : [T,tokens,h] new residual stream R'
+ *   x_out      : [T,tokens,h] Norm(R'); decode: may be NULL (not produced)
+ *   kv_k, kv_v : decode only, [T][batch][n_heads/T][kv_cap][head_dim]; row kv_len is written
+ *   workspace  : caat_workspace_bytes(d) bytes; keeps what caat_block_bwd needs
+ */
+int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x, const void* r, void* r_out,
+                   void* x_out, void* kv_k, void* kv_v, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Backward of caat_block_fwd for the MLP kinds (Fig. 2b): norm backward per rank, residual gradient
+ * dr_m = g_m un-reduced, the SAME partial channel-reduce on g (fp32 accumulation), then the GEMM chain
+ * rule per rank; dx_m is NOT reduced over ranks.
+ *   x, r_out           : the forward's input x and output r_out
+ *   workspace          : the forward's workspace (also used as scratch here)
+ *   dx_out, dr_out     : [T,tokens,h] gradients w.r.t. x_out and r_out
+ *   dx, dr             : [T,tokens,h] outputs
+ *   dweights           : host array of device pointers, bf16, same shapes/order as the weight matrices
+ *                        ({dA, dB} or {dWgu, dB})
+ *   dgamma, dbeta      : [h] fp32, summed over ranks; dbeta NULL for RMSNorm
+ */
+int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x, const void* r_out,
+                   void* workspace, size_t ws_bytes, const void* dx_out, const void* dr_out, void* dx, void* dr,
+                   void* const* dweights, float* dgamma, float* dbeta, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAAT_H */

@@ -1,0 +1,309 @@
+// C ABI of libcaat: host-side argument validation and the launch sequences of the block forward / backward.
+// No device memory is allocated here; everything is enqueued on the caller's stream.
+#include "../../include/caat.h"
+#include "caat_internal.h"
+
+#include <cmath>
+#include <cstring>
+
+using namespace caat;
+
+namespace {
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int hip_status(hipError_t e) { return e == hipSuccess ? CAAT_OK : CAAT_EHIP; }
+
+bool is_mlp(int kind) { return kind == CAAT_MLP_GELU || kind == CAAT_MLP_SWIGLU; }
+
+int validate_desc(const caat_desc* d) {
+  if (!d) return CAAT_EINVAL;
+  if (d->kind < CAAT_MLP_GELU || d->kind > CAAT_ATTN_DECODE) return CAAT_EINVAL;
+  if (d->norm != CAAT_LAYERNORM && d->norm != CAAT_RMSNORM) return CAAT_EINVAL;
+  if (d->T < 1 || d->h < 1 || d->tokens < 0) return CAAT_EINVAL;
+  if (!(d->eps >= 0.0f) || std::isnan(d->private_scale)) return CAAT_EINVAL;
+  if (d->hs < 0 || d->hs > d->h) return CAAT_ESHAPE;
+  if (d->h % 8 != 0 || d->h > 8192) return CAAT_ESHAPE;
+  if (d->tokens > 0x7FFFFFFFLL) return CAAT_ESHAPE;
+  if (is_mlp(d->kind) || d->kind == CAAT_ATTN_DECODE) {
+    if (d->ffn < 1 || d->ffn % d->T != 0 || (d->ffn / d->T) % 8 != 0) return CAAT_ESHAPE;
+  }
+  if (d->kind == CAAT_ATTN || d->kind == CAAT_ATTN_DECODE) {
+    if (d->n_heads < 1 || d->head_dim < 1 || d->n_heads % d->T != 0) return CAAT_ESHAPE;
+    if (d->batch < 1 || d->seq < 1 || (long long)d->batch * d->seq != d->tokens) return CAAT_ESHAPE;
+    if (((d->n_heads / d->T) * d->head_dim) % 8 != 0) return CAAT_ESHAPE;
+  }
+  return CAAT_OK;
+}
+
+int layout_of(const caat_desc* d, caat_ws_layout* L) {
+  std::memset(L, 0, sizeof(*L));
+  int st = validate_desc(d);
+  if (st != CAAT_OK) return st;
+  const size_t T = d->T, n = (size_t)d->tokens, h = d->h;
+  size_t off = 0;
+  auto take = [&](size_t bytes, size_t* o, size_t* b) {
+    *o = off;
+    *b = bytes;
+    off += align256(bytes);
+  };
+  if (is_mlp(d->kind)) {
+    const size_t fr = d->ffn / d->T;
+    const size_t pw = d->kind == CAAT_MLP_SWIGLU ? 2 * fr : fr;
+    take(T * n * pw * 2, &L->off_P, &L->bytes_P);
+    take(T * n * fr * 2, &L->off_Y, &L->bytes_Y);
+    if (d->norm == CAAT_LAYERNORM) take(T * n * 4, &L->off_mean, &L->bytes_mean);
+    take(T * n * 4, &L->off_rstd, &L->bytes_rstd);
+    take(T * n * h * 2, &L->off_dZt, &L->bytes_dZt);
+    take(T * n * pw * 2, &L->off_dP, &L->bytes_dP);
+    take(norm_bwd_workspace_bytes(d->T, d->tokens, d->h), &L->off_scratch, &L->bytes_scratch);
+  } else {
+    return CAAT_EUNSUPPORTED;
+  }
+  L->total_bytes = off;
+  return CAAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int caat_shared_channels(int h, double p) {
+  if (h < 0 || !(p >= 0.0 && p <= 1.0)) return -1;
+  double v = std::floor((double)h * p);
+  if (v < 0) v = 0;
+  if (v > h) v = h;
+  return (int)v;
+}
+
+const char* caat_status_string(int status) {
+  switch (status) {
+    case CAAT_OK: return "ok";
+    case CAAT_EINVAL: return "invalid argument (null pointer, bad T / p / enum)";
+    case CAAT_ESHAPE: return "unsupported shape (divisibility by T or 8, hs > h, h > 8192)";
+    case CAAT_EALIGN: return "device pointer not 16-byte aligned";
+    case CAAT_EWORKSPACE: return "workspace too small";
+    case CAAT_EHIP: return "HIP runtime error at kernel launch";
+    case CAAT_EUNSUPPORTED: return "valid request not implemented in this build";
+    default: return "unknown status";
+  }
+}
+
+size_t caat_workspace_bytes(const caat_desc* d) {
+  caat_ws_layout L;
+  if (layout_of(d, &L) != CAAT_OK) return 0;
+  return L.total_bytes;
+}
+
+int caat_workspace_layout(const caat_desc* d, caat_ws_layout* out) {
+  if (!out) return CAAT_EINVAL;
+  return layout_of(d, out);
+}
+
+int caat_partial_sync(const void* y, const void* resid, void* out, int T, long long tokens, int h, int hs,
+                      float private_scale, void* hip_stream) {
+  if (!y || !out || T < 1 || tokens < 0 || h < 1 || std::isnan(private_scale)) return CAAT_EINVAL;
+  if (hs < 0 || hs > h || h % 8 != 0) return CAAT_ESHAPE;
+  if (misaligned(y) || misaligned(out) || (resid && misaligned(resid))) return CAAT_EALIGN;
+  return hip_status(launch_partial_sync((const bf16_t*)y, (const bf16_t*)resid, (bf16_t*)out, T, tokens, h, hs,
+                                        private_scale, (hipStream_t)hip_stream));
+}
+
+int caat_norm_fwd(const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd, int norm,
+                  int T, long long tokens, int h, float eps, void* hip_stream) {
+  if (!x || !gamma || !y || !rstd || T < 1 || tokens < 0 || h < 1) return CAAT_EINVAL;
+  if (norm != CAAT_LAYERNORM && norm != CAAT_RMSNORM) return CAAT_EINVAL;
+  if (norm == CAAT_LAYERNORM && (!beta || !mean)) return CAAT_EINVAL;
+  if (h % 8 != 0 || h > 8192) return CAAT_ESHAPE;
+  if (misaligned(x) || misaligned(gamma) || misaligned(y) || (beta && misaligned(beta))) return CAAT_EALIGN;
+  return hip_status(launch_norm_fwd((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, mean, rstd,
+                                    norm, T, tokens, h, eps, (hipStream_t)hip_stream));
+}
+
+size_t caat_norm_bwd_workspace_bytes(int T, long long tokens, int h) {
+  if (T < 1 || tokens < 0 || h < 1) return 0;
+  return norm_bwd_workspace_bytes(T, tokens, h);
+}
+
+int caat_norm_bwd(const void* dy, const void* dres, const void* x, const void* gamma, const float* mean,
+                  const float* rstd, void* g_out, void* g_scaled, float* dgamma, float* dbeta, int norm, int T,
+                  long long tokens, int h, int hs, float private_scale, void* workspace, size_t ws_bytes,
+                  void* hip_stream) {
+  if (!dy || !x || !gamma || !rstd || !g_out || !dgamma || !workspace || T < 1 || tokens < 0 || h < 1)
+    return CAAT_EINVAL;
+  if (norm != CAAT_LAYERNORM && norm != CAAT_RMSNORM) return CAAT_EINVAL;
+  if (norm == CAAT_LAYERNORM && (!mean || !dbeta)) return CAAT_EINVAL;
+  if (h % 8 != 0 || h > 8192 || hs < 0 || hs > h) return CAAT_ESHAPE;
+  if (misaligned(dy) || misaligned(x) || misaligned(gamma) || misaligned(g_out) || (dres && misaligned(dres)) ||
+      (g_scaled && misaligned(g_scaled)) || misaligned(workspace))
+    return CAAT_EALIGN;
+  if (ws_bytes < norm_bwd_workspace_bytes(T, tokens, h)) return CAAT_EWORKSPACE;
+  return hip_status(launch_norm_bwd((const bf16_t*)dy, (const bf16_t*)dres, (const bf16_t*)x, (const bf16_t*)gamma, mean,
+                                    rstd, (bf16_t*)g_out, (bf16_t*)g_scaled, dgamma, dbeta, norm, T, tokens, h, hs,
+                                    private_scale, workspace, (hipStream_t)hip_stream));
+}
+
+int caat_gemm_bf16(const void* a, const void* b, void* c, int layout, int G, long long M, long long N, long long K,
+                   long long lda, long long ldb, long long ldc, long long stride_a, long long stride_b,
+                   long long stride_c, void* hip_stream) {
+  if (!a || !b || !c || G < 1 || M < 1 || N < 1 || K < 1) return CAAT_EINVAL;
+  if (layout < CAAT_GEMM_NT || layout > CAAT_GEMM_TN) return CAAT_EINVAL;
+  if (M > 0x7FFFFFFFLL || N > 0x7FFFFFFFLL || K > 0x7FFFFFFFLL) return CAAT_ESHAPE;
+  if (N % 8 != 0 || ldc % 8 != 0 || lda % 8 != 0 || ldb % 8 != 0) return CAAT_ESHAPE;
+  if (stride_a % 8 != 0 || stride_b % 8 != 0 || stride_c % 8 != 0) return CAAT_ESHAPE;
+  const bool a_kcontig = layout != CAAT_GEMM_TN, b_kcontig = layout == CAAT_GEMM_NT;
+  if ((a_kcontig || b_kcontig) && K % 8 != 0) return CAAT_ESHAPE;
+  if (!a_kcontig && M % 8 != 0) return CAAT_ESHAPE;
+  if (lda < (a_kcontig ? K : M) || ldb < (b_kcontig ? K : N) || ldc < N) return CAAT_ESHAPE;
+  if (misaligned(a) || misaligned(b) || misaligned(c)) return CAAT_EALIGN;
+  GemmParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.a = (const bf16_t*)a;
+  p.b = (const bf16_t*)b;
+  p.c = (bf16_t*)c;
+  p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
+  p.G = G; p.M = (int)M; p.N = (int)N; p.K = (int)K;
+  return hip_status(launch_gemm(p, layout, EPI_PLAIN, (hipStream_t)hip_stream));
+}
+
+int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x, const void* r, void* r_out,
+                   void* x_out, void* kv_k, void* kv_v, void* workspace, size_t ws_bytes, void* hip_stream) {
+  (void)kv_k; (void)kv_v;
+  caat_ws_layout L;
+  int st = layout_of(d, &L);
+  if (st != CAAT_OK) return st;
+  if (!weights || !x || !r || !r_out || !x_out || !workspace) return CAAT_EINVAL;
+  if (!is_mlp(d->kind)) return CAAT_EUNSUPPORTED;
+  const void* w0 = weights[0]; const void* w1 = weights[1]; const void* gamma = weights[2]; const void* beta = weights[3];
+  if (!w0 || !w1 || !gamma || (d->norm == CAAT_LAYERNORM && !beta)) return CAAT_EINVAL;
+  if (misaligned(w0) || misaligned(w1) || misaligned(gamma) || (beta && misaligned(beta)) || misaligned(x) ||
+      misaligned(r) || misaligned(r_out) || misaligned(x_out) || misaligned(workspace))
+    return CAAT_EALIGN;
+  if (ws_bytes < L.total_bytes) return CAAT_EWORKSPACE;
+  if (d->tokens == 0) return CAAT_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const long long T = d->T, n = d->tokens, h = d->h, fr = d->ffn / d->T;
+  const bool swi = d->kind == CAAT_MLP_SWIGLU;
+  const long long pw = swi ? 2 * fr : fr;
+  bf16_t* P = (bf16_t*)(ws + L.off_P);
+  bf16_t* Y = (bf16_t*)(ws + L.off_Y);
+  float* mean = d->norm == CAAT_LAYERNORM ? (float*)(ws + L.off_mean) : nullptr;
+  float* rstd = (float*)(ws + L.off_rstd);
+
+  // a1: column-parallel GEMM + activation (Eq. A3, inner sum and sigma): P_m = X_m A_m^T, Y_m = sigma(P_m)
+  GemmParams g1;
+  std::memset(&g1, 0, sizeof(g1));
+  g1.a = (const bf16_t*)x; g1.lda = h; g1.stride_a = n * h;
+  g1.b = (const bf16_t*)w0; g1.ldb = h; g1.stride_b = pw * h;
+  g1.c = P; g1.ldc = pw; g1.stride_c = n * pw;
+  g1.c2 = Y; g1.ldc2 = fr; g1.stride_c2 = n * fr;
+  g1.G = (int)T; g1.M = (int)n; g1.N = (int)fr; g1.K = (int)h; g1.half = (int)fr;
+  hipError_t e = launch_gemm(g1, 0, swi ? EPI_SWIGLU_FWD : EPI_GELU_FWD, s);
+  if (e != hipSuccess) return CAAT_EHIP;
+
+  // a2 + private half of a3/a4: Zt_m = Y_m B_m^T; columns >= hs become scale*Zt + R (final), columns < hs hold
+  // the rank's partial sum inside r_out until the reduce below
+  GemmParams g2;
+  std::memset(&g2, 0, sizeof(g2));
+  g2.a = Y; g2.lda = fr; g2.stride_a = n * fr;
+  g2.b = (const bf16_t*)w1; g2.ldb = fr; g2.stride_b = h * fr;
+  g2.c = (bf16_t*)r_out; g2.ldc = h; g2.stride_c = n * h;
+  g2.aux = (const bf16_t*)r; g2.ldaux = h; g2.stride_aux = n * h;
+  g2.G = (int)T; g2.M = (int)n; g2.N = (int)h; g2.K = (int)fr;
+  g2.hs = d->hs; g2.scale = d->private_scale;
+  e = launch_gemm(g2, 0, EPI_ROWPAR, s);
+  if (e != hipSuccess) return CAAT_EHIP;
+
+  // a3/a4 shared half: sum the T partials on the hs shared channels, add each rank's residual, in place
+  if (d->hs > 0) {
+    e = launch_partial_sync_shared((bf16_t*)r_out, (const bf16_t*)r, (int)T, n, (int)h, d->hs, s);
+    if (e != hipSuccess) return CAAT_EHIP;
+  }
+  // a5: per-rank norm on the now rank-divergent residual stream
+  e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd, d->norm,
+                      (int)T, n, (int)h, d->eps, s);
+  return hip_status(e);
+}
+
+int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x, const void* r_out, void* workspace,
+                   size_t ws_bytes, const void* dx_out, const void* dr_out, void* dx, void* dr, void* const* dweights,
+                   float* dgamma, float* dbeta, void* hip_stream) {
+  caat_ws_layout L;
+  int st = layout_of(d, &L);
+  if (st != CAAT_OK) return st;
+  if (!weights || !dweights || !x || !r_out || !workspace || !dx_out || !dr_out || !dx || !dr || !dgamma)
+    return CAAT_EINVAL;
+  if (!is_mlp(d->kind)) return CAAT_EUNSUPPORTED;
+  const void* w0 = weights[0]; const void* w1 = weights[1]; const void* gamma = weights[2];
+  void* dw0 = dweights[0]; void* dw1 = dweights[1];
+  if (!w0 || !w1 || !gamma || !dw0 || !dw1 || (d->norm == CAAT_LAYERNORM && !dbeta)) return CAAT_EINVAL;
+  if (misaligned(w0) || misaligned(w1) || misaligned(gamma) || misaligned(dw0) || misaligned(dw1) || misaligned(x) ||
+      misaligned(r_out) || misaligned(workspace) || misaligned(dx_out) || misaligned(dr_out) || misaligned(dx) ||
+      misaligned(dr))
+    return CAAT_EALIGN;
+  if (ws_bytes < L.total_bytes) return CAAT_EWORKSPACE;
+  if (d->tokens == 0) return CAAT_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const long long T = d->T, n = d->tokens, h = d->h, fr = d->ffn / d->T;
+  const bool swi = d->kind == CAAT_MLP_SWIGLU;
+  const long long pw = swi ? 2 * fr : fr;
+  const bf16_t* P = (const bf16_t*)(ws + L.off_P);
+  const bf16_t* Y = (const bf16_t*)(ws + L.off_Y);
+  const float* mean = d->norm == CAAT_LAYERNORM ? (const float*)(ws + L.off_mean) : nullptr;
+  const float* rstd = (const float*)(ws + L.off_rstd);
+  bf16_t* dZt = (bf16_t*)(ws + L.off_dZt);
+  bf16_t* dP = (bf16_t*)(ws + L.off_dP);
+
+  // a6/a7: norm backward per rank FIRST (Fig. 2b): g_m = dr_out_m + NormBwd(dx_out_m); dr_m = g_m un-reduced;
+  // a copy with scaled private channels goes to dZt; dgamma/dbeta summed over tokens and ranks
+  hipError_t e = launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
+                                 mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
+                                 d->private_scale, ws + L.off_scratch, s);
+  if (e != hipSuccess) return CAAT_EHIP;
+  // a8: the same partial channel-reduce on the gradients, in place on the shared channels, fp32 accumulation
+  e = launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s);
+  if (e != hipSuccess) return CAAT_EHIP;
+
+  // a9 + a10: dY_m = dZt_m B_m (NN), fused with the activation derivative -> dP_m
+  GemmParams q;
+  std::memset(&q, 0, sizeof(q));
+  q.a = dZt; q.lda = h; q.stride_a = n * h;
+  q.b = (const bf16_t*)w1; q.ldb = fr; q.stride_b = h * fr;
+  q.c = dP; q.ldc = pw; q.stride_c = n * pw;
+  q.aux = P; q.ldaux = pw; q.stride_aux = n * pw;
+  q.G = (int)T; q.M = (int)n; q.N = (int)fr; q.K = (int)h; q.half = (int)fr;
+  e = launch_gemm(q, 1, swi ? EPI_SWIGLU_BWD : EPI_GELU_BWD, s);
+  if (e != hipSuccess) return CAAT_EHIP;
+
+  // a9: dB_m [h, f/T] = dZt_m^T Y_m (TN, reduction over tokens)
+  std::memset(&q, 0, sizeof(q));
+  q.a = dZt; q.lda = h; q.stride_a = n * h;
+  q.b = Y; q.ldb = fr; q.stride_b = n * fr;
+  q.c = (bf16_t*)dw1; q.ldc = fr; q.stride_c = h * fr;
+  q.G = (int)T; q.M = (int)h; q.N = (int)fr; q.K = (int)n;
+  e = launch_gemm(q, 2, EPI_PLAIN, s);
+  if (e != hipSuccess) return CAAT_EHIP;
+
+  // a11: dX_m = dP_m A_m (NN); NOT reduced over ranks (Sec. 4: the only reduce sits at the row-parallel output)
+  std::memset(&q, 0, sizeof(q));
+  q.a = dP; q.lda = pw; q.stride_a = n * pw;
+  q.b = (const bf16_t*)w0; q.ldb = h; q.stride_b = pw * h;
+  q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h;
+  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)pw;
+  e = launch_gemm(q, 1, EPI_PLAIN, s);
+  if (e != hipSuccess) return CAAT_EHIP;
+
+  // a11: dA_m [pw, h] = dP_m^T X_m (TN)
+  std::memset(&q, 0, sizeof(q));
+  q.a = dP; q.lda = pw; q.stride_a = n * pw;
+  q.b = (const bf16_t*)x; q.ldb = h; q.stride_b = n * h;
+  q.c = (bf16_t*)dw0; q.ldc = h; q.stride_c = pw * h;
+  q.G = (int)T; q.M = (int)pw; q.N = (int)h; q.K = (int)n;
+  e = launch_gemm(q, 2, EPI_PLAIN, s);
+  return hip_status(e);
+}
+
+}  // extern "C"

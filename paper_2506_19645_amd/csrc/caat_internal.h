@@ -1,0 +1,73 @@
+// Internal declarations shared by the HIP translation units of libcaat (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace caat {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bit pattern in memory
+
+__device__ __forceinline__ float bf2f(bf16_t u) { return __uint_as_float(((unsigned)u) << 16); }
+
+// fp32 -> bf16, round-to-nearest-even (finite inputs; NaN payloads are not preserved)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  unsigned u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ unsigned pack2bf(float lo, float hi) {
+  return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16);
+}
+__device__ __forceinline__ float lo_bf(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_bf(unsigned w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// x * Phi(x) with the exact erf form, and its derivative Phi(x) + x phi(x)
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  return 0.5f * (1.0f + erff(x * 0.70710678118654752f)) + x * 0.39894228040143268f * __expf(-0.5f * x * x);
+}
+__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
+
+// ---------------------------------------------------------------- GEMM
+enum GemmEpilogue {
+  EPI_PLAIN = 0,       // c = acc
+  EPI_GELU_FWD = 1,    // c = acc (pre-activation P), c2 = gelu(acc)
+  EPI_SWIGLU_FWD = 2,  // b holds gate rows then up rows; c = [gate|up] pre-activations, c2 = silu(gate)*up
+  EPI_ROWPAR = 3,      // col < hs: c = acc (partial sum);  col >= hs: c = scale*acc + resid
+  EPI_GELU_BWD = 4,    // c = acc * gelu'(aux)
+  EPI_SWIGLU_BWD = 5   // c[:, col] = acc*up*silu'(gate), c[:, half+col] = acc*silu(gate); aux = [gate|up]
+};
+
+struct GemmParams {
+  const bf16_t* a;
+  const bf16_t* b;
+  bf16_t* c;
+  bf16_t* c2;          // second output (EPI_*_FWD)
+  const bf16_t* aux;   // saved pre-activations (EPI_*_BWD) or residual (EPI_ROWPAR)
+  long long lda, ldb, ldc, ldc2, ldaux;
+  long long stride_a, stride_b, stride_c, stride_c2, stride_aux;  // per group, elements
+  int G;
+  int M, N, K;         // N = number of output columns of the accumulator tile grid (for SWIGLU_FWD: ffn/T)
+  int half;            // SWIGLU: ffn/T (offset between gate and up columns / rows)
+  int hs;              // EPI_ROWPAR
+  float scale;         // EPI_ROWPAR private scale
+};
+
+// layout: 0 NT, 1 NN, 2 TN (see caat_gemm_layout).  Returns hipError_t of the launch.
+hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_t s);
+
+// ---------------------------------------------------------------- streaming kernels
+hipError_t launch_partial_sync(const bf16_t* y, const bf16_t* resid, bf16_t* out, int T, long long tokens, int h,
+                               int hs, float private_scale, hipStream_t s);
+hipError_t launch_partial_sync_shared(bf16_t* io, const bf16_t* resid, int T, long long tokens, int h, int hs,
+                                      hipStream_t s);
+hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
+                           float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s);
+size_t norm_bwd_workspace_bytes(int T, long long tokens, int h);
+hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
+                           const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,
+                           float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
+                           void* workspace, hipStream_t s);
+
+}  // namespace caat

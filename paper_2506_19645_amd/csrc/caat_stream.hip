@@ -1,0 +1,425 @@
+// HBM-bound streaming kernels of the partial-sync block (gfx950): the partial channel-reduce of Eq. A3/A5 with
+// the residual add of Sec. 4, and the per-rank LayerNorm / RMSNorm forward and backward (Sec. 4, Fig. 2b).
+// All of them move 16-byte vectors (8 bf16), keep arithmetic in fp32 and round once.
+#include "caat_internal.h"
+
+namespace caat {
+
+__device__ __forceinline__ void unpack8(const uint4& v, float* f) {
+  f[0] = lo_bf(v.x); f[1] = hi_bf(v.x); f[2] = lo_bf(v.y); f[3] = hi_bf(v.y);
+  f[4] = lo_bf(v.z); f[5] = hi_bf(v.z); f[6] = lo_bf(v.w); f[7] = hi_bf(v.w);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  uint4 v;
+  v.x = pack2bf(f[0], f[1]); v.y = pack2bf(f[2], f[3]); v.z = pack2bf(f[4], f[5]); v.w = pack2bf(f[6], f[7]);
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Partial channel-reduce.  One thread owns one group of 8 channels of one token for ALL ranks: it reads the T
+// partial vectors, sums them in ascending rank order in fp32, and writes the T outputs.  Because a thread
+// reads every input of its group before it writes, out may alias y.  `ncg` = number of 8-channel groups per
+// row that are processed: ceil(hs/8) when the private channels need no work, h/8 otherwise.
+// TT > 0: compile-time rank count (loads fully unrolled and in flight together); TT == 0: any T.
+template <int TT, bool HAS_RES>
+__global__ __launch_bounds__(256) void partial_sync_kernel(const bf16_t* y, const bf16_t* resid,
+                                                           bf16_t* out, int T_, long long n, int h, int hs,
+                                                           float scale, int ncg, int shared_only) {
+  const int T = TT > 0 ? TT : T_;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n * (long long)ncg) return;
+  const long long i = idx / ncg;
+  const int col = (int)(idx - i * ncg) * 8;
+  const long long plane = n * (long long)h;  // elements per rank
+  const long long off = i * h + col;
+
+  if (col + 8 <= hs) {  // all 8 channels shared
+    float sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (TT > 0) {
+      uint4 v[TT > 0 ? TT : 1];
+#pragma unroll
+      for (int m = 0; m < TT; ++m) v[m] = *reinterpret_cast<const uint4*>(y + m * plane + off);
+#pragma unroll
+      for (int m = 0; m < TT; ++m) {
+        float f[8];
+        unpack8(v[m], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum[e] += f[e];
+      }
+    } else {
+      for (int m = 0; m < T; ++m) {
+        float f[8];
+        unpack8(*reinterpret_cast<const uint4*>(y + m * plane + off), f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum[e] += f[e];
+      }
+    }
+    if constexpr (HAS_RES) {
+#pragma unroll 4
+      for (int m = 0; m < T; ++m) {
+        float r[8], o[8];
+        unpack8(*reinterpret_cast<const uint4*>(resid + m * plane + off), r);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = sum[e] + r[e];
+        *reinterpret_cast<uint4*>(out + m * plane + off) = pack8(o);
+      }
+    } else {
+      const uint4 o = pack8(sum);  // one rounding, the same bits on every rank
+#pragma unroll 4
+      for (int m = 0; m < T; ++m) *reinterpret_cast<uint4*>(out + m * plane + off) = o;
+    }
+    return;
+  }
+
+  // group straddles hs or is entirely private: channel-wise case split of Eq. A3
+  float sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (col < hs) {
+    for (int m = 0; m < T; ++m) {
+      float f[8];
+      unpack8(*reinterpret_cast<const uint4*>(y + m * plane + off), f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum[e] += f[e];
+    }
+  }
+  for (int m = 0; m < T; ++m) {
+    float f[8], r[8], o[8];
+    unpack8(*reinterpret_cast<const uint4*>(y + m * plane + off), f);  // rank m's own values (not yet overwritten)
+    if constexpr (HAS_RES) {
+      unpack8(*reinterpret_cast<const uint4*>(resid + m * plane + off), r);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r[e] = 0.0f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (col + e < hs) o[e] = sum[e] + r[e];
+      else o[e] = shared_only ? f[e] : scale * f[e] + r[e];  // shared_only: private channels are already final
+    }
+    *reinterpret_cast<uint4*>(out + m * plane + off) = pack8(o);
+  }
+}
+
+template <int TT>
+static hipError_t sync_dispatch(const bf16_t* y, const bf16_t* resid, bf16_t* out, int T, long long n, int h, int hs,
+                                float scale, int ncg, int shared_only, hipStream_t s) {
+  const long long work = n * (long long)ncg;
+  const long long blocks = (work + 255) / 256;
+  if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  if (resid)
+    hipLaunchKernelGGL((partial_sync_kernel<TT, true>), dim3((unsigned)blocks), dim3(256), 0, s, y, resid, out, T, n,
+                       h, hs, scale, ncg, shared_only);
+  else
+    hipLaunchKernelGGL((partial_sync_kernel<TT, false>), dim3((unsigned)blocks), dim3(256), 0, s, y, resid, out, T, n,
+                       h, hs, scale, ncg, shared_only);
+  return hipGetLastError();
+}
+
+static hipError_t sync_any(const bf16_t* y, const bf16_t* resid, bf16_t* out, int T, long long tokens, int h, int hs,
+                           float private_scale, int shared_only, hipStream_t s) {
+  const bool private_work = !shared_only && ((out != y) || (resid != nullptr) || (private_scale != 1.0f));
+  const int ncg = private_work ? h / 8 : (hs + 7) / 8;
+  if (ncg == 0 || tokens == 0) return hipSuccess;  // p = 0 in place: nothing moves
+  switch (T) {
+    case 2: return sync_dispatch<2>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
+    case 4: return sync_dispatch<4>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
+    case 8: return sync_dispatch<8>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
+    default: return sync_dispatch<0>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
+  }
+}
+
+hipError_t launch_partial_sync(const bf16_t* y, const bf16_t* resid, bf16_t* out, int T, long long tokens, int h,
+                               int hs, float private_scale, hipStream_t s) {
+  return sync_any(y, resid, out, T, tokens, h, hs, private_scale, 0, s);
+}
+
+// In place on the shared channels only, with the residual added there; private channels are left as they are
+// (the row-parallel GEMM's epilogue has already finished them).
+hipError_t launch_partial_sync_shared(bf16_t* io, const bf16_t* resid, int T, long long tokens, int h, int hs,
+                                      hipStream_t s) {
+  return sync_any(io, resid, io, T, tokens, h, hs, 1.0f, 1, s);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Norm forward: one wavefront per row, the row stays in registers (VPL 16-byte vectors per lane), statistics
+// by wave reduction in fp32 (two passes over registers: mean, then centred second moment).
+template <int VPL, bool LN>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+                                                       const bf16_t* __restrict__ beta, bf16_t* __restrict__ y,
+                                                       float* __restrict__ mean, float* __restrict__ rstd,
+                                                       long long rows, int h, float eps) {
+  const int lane = threadIdx.x & 63;
+  const long long wave0 = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long nwaves = (long long)gridDim.x * 4;
+  const int nvec = h >> 3;
+  const float inv_h = 1.0f / (float)h;
+  for (long long row = wave0; row < rows; row += nwaves) {
+    const bf16_t* xr = x + row * h;
+    float f[VPL][8];
+    float s = 0.0f;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int vi = v * 64 + lane;
+      uint4 w = make_uint4(0u, 0u, 0u, 0u);
+      if (vi < nvec) w = *reinterpret_cast<const uint4*>(xr + vi * 8);
+      unpack8(w, f[v]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += LN ? f[v][e] : f[v][e] * f[v][e];
+    }
+    s = wave_sum(s);
+    float mu = 0.0f, var;
+    if constexpr (LN) {
+      mu = s * inv_h;
+      float q = 0.0f;
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        if (v * 64 + lane < nvec) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float d = f[v][e] - mu;
+            q += d * d;
+          }
+        }
+      }
+      var = wave_sum(q) * inv_h;
+    } else {
+      var = s * inv_h;
+    }
+    const float rs = rsqrtf(var + eps);
+    if (lane == 0) {
+      if (LN && mean) mean[row] = mu;
+      rstd[row] = rs;
+    }
+    bf16_t* yr = y + row * h;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int vi = v * 64 + lane;
+      if (vi < nvec) {
+        float g[8], b[8], o[8];
+        unpack8(*reinterpret_cast<const uint4*>(gamma + vi * 8), g);
+        if constexpr (LN) unpack8(*reinterpret_cast<const uint4*>(beta + vi * 8), b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = LN ? ((f[v][e] - mu) * rs * g[e] + b[e]) : (f[v][e] * rs * g[e]);
+        *reinterpret_cast<uint4*>(yr + vi * 8) = pack8(o);
+      }
+    }
+  }
+}
+
+template <int VPL>
+static hipError_t norm_fwd_dispatch(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
+                                    float* rstd, int norm, long long rows, int h, float eps, hipStream_t s) {
+  long long blocks = (rows + 3) / 4;
+  if (blocks > 65536) blocks = 65536;
+  if (blocks == 0) return hipSuccess;
+  if (norm == 0)
+    hipLaunchKernelGGL((norm_fwd_kernel<VPL, true>), dim3((unsigned)blocks), dim3(256), 0, s, x, gamma, beta, y, mean,
+                       rstd, rows, h, eps);
+  else
+    hipLaunchKernelGGL((norm_fwd_kernel<VPL, false>), dim3((unsigned)blocks), dim3(256), 0, s, x, gamma, beta, y, mean,
+                       rstd, rows, h, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
+                           float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s) {
+  const long long rows = (long long)T * tokens;
+  const int vpl = (h / 8 + 63) / 64;
+  if (vpl <= 1) return norm_fwd_dispatch<1>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
+  if (vpl <= 2) return norm_fwd_dispatch<2>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
+  if (vpl <= 4) return norm_fwd_dispatch<4>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
+  if (vpl <= 8) return norm_fwd_dispatch<8>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
+  if (vpl <= 16) return norm_fwd_dispatch<16>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
+  return hipErrorInvalidValue;  // h > 8192
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Norm backward, placed before the reduce (Fig. 2b): g = dres + NormBwd(dy).  Each wave walks a contiguous
+// range of rows and keeps its lanes' columns of dgamma / dbeta in registers; a workgroup combines its 4 waves
+// through LDS and writes one partial row [2][h] to the workspace; a second kernel sums the partials in order.
+static constexpr int NORM_BWD_MAX_BLOCKS = 1024;
+
+template <int VPL, bool LN>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ dres,
+                                                       const bf16_t* __restrict__ x,
+                                                       const bf16_t* __restrict__ gamma,
+                                                       const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                       bf16_t* __restrict__ g_out, bf16_t* __restrict__ g_scaled,
+                                                       float* __restrict__ partial, long long rows, int h, int hs,
+                                                       float scale, long long rows_per_block) {
+  __shared__ float red[4][64 * 8];  // one vector column group at a time
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int nvec = h >> 3;
+  const float inv_h = 1.0f / (float)h;
+  // per-lane column accumulators; gamma and the row's raw vectors stay packed (bf16) to save registers
+  float dgam[VPL][8], dbet[LN ? VPL : 1][8];
+  uint4 gam[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int vi = v * 64 + lane;
+    gam[v] = make_uint4(0u, 0u, 0u, 0u);
+    if (vi < nvec) gam[v] = *reinterpret_cast<const uint4*>(gamma + vi * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dgam[v][e] = 0.0f;
+      if constexpr (LN) dbet[v][e] = 0.0f;
+    }
+  }
+  const long long r0 = (long long)blockIdx.x * rows_per_block;
+  long long r1 = r0 + rows_per_block;
+  if (r1 > rows) r1 = rows;
+  for (long long row = r0 + wave; row < r1; row += 4) {
+    const float mu = LN ? mean[row] : 0.0f;
+    const float rs = rstd[row];
+    uint4 wx[VPL], wd[VPL];
+    float c1 = 0.0f, c2 = 0.0f;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int vi = v * 64 + lane;
+      wx[v] = make_uint4(0u, 0u, 0u, 0u);
+      wd[v] = wx[v];
+      if (vi < nvec) {
+        wx[v] = *reinterpret_cast<const uint4*>(x + row * h + vi * 8);
+        wd[v] = *reinterpret_cast<const uint4*>(dy + row * h + vi * 8);
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      float fx[8], fd[8], g[8];
+      unpack8(wx[v], fx);
+      unpack8(wd[v], fd);
+      unpack8(gam[v], g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xh = (fx[e] - mu) * rs;  // idle lanes: fd = 0 and gamma = 0, so they add nothing
+        const float dxh = fd[e] * g[e];
+        c1 += dxh;
+        c2 += dxh * xh;
+        dgam[v][e] += fd[e] * xh;
+        if constexpr (LN) dbet[v][e] += fd[e];
+      }
+    }
+    if constexpr (LN) c1 = wave_sum(c1) * inv_h;
+    c2 = wave_sum(c2) * inv_h;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int vi = v * 64 + lane;
+      if (vi < nvec) {
+        float fx[8], fd[8], g[8], r[8], o[8];
+        unpack8(wx[v], fx);
+        unpack8(wd[v], fd);
+        unpack8(gam[v], g);
+        if (dres) {
+          unpack8(*reinterpret_cast<const uint4*>(dres + row * h + vi * 8), r);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) r[e] = 0.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (fx[e] - mu) * rs;
+          const float dxh = fd[e] * g[e];
+          o[e] = r[e] + rs * (LN ? (dxh - c1 - xh * c2) : (dxh - xh * c2));
+        }
+        *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
+        if (g_scaled) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (vi * 8 + e >= hs) o[e] *= scale;
+          *reinterpret_cast<uint4*>(g_scaled + row * h + vi * 8) = pack8(o);
+        }
+      }
+    }
+  }
+  // combine the 4 waves of the block in a fixed order, one 512-column slab at a time
+  float* prow = partial + (long long)blockIdx.x * 2 * h;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+#pragma unroll
+    for (int which = 0; which < (LN ? 2 : 1); ++which) {
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = (LN && which) ? dbet[LN ? v : 0][e] : dgam[v][e];
+      __syncthreads();
+      for (int c = threadIdx.x; c < 512; c += 256) {
+        const int colg = v * 512 + c;
+        if (colg < h) prow[which * h + colg] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
+      }
+    }
+  }
+}
+
+// sums partial[nb][2][h] over nb in ascending order; thread = one column of dgamma or dbeta
+__global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __restrict__ partial, int nb, int h,
+                                                                float* __restrict__ dgamma,
+                                                                float* __restrict__ dbeta) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= 2 * h) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int b = 0;
+  for (; b + 4 <= nb; b += 4) {
+    s0 += partial[(long long)(b + 0) * 2 * h + c];
+    s1 += partial[(long long)(b + 1) * 2 * h + c];
+    s2 += partial[(long long)(b + 2) * 2 * h + c];
+    s3 += partial[(long long)(b + 3) * 2 * h + c];
+  }
+  for (; b < nb; ++b) s0 += partial[(long long)b * 2 * h + c];
+  const float s = (s0 + s1) + (s2 + s3);
+  if (c < h) dgamma[c] = s;
+  else if (dbeta) dbeta[c - h] = s;
+}
+
+static long long norm_bwd_blocks(long long rows) {
+  long long nb = (rows + 3) / 4;
+  if (nb > NORM_BWD_MAX_BLOCKS) nb = NORM_BWD_MAX_BLOCKS;
+  if (nb < 1) nb = 1;
+  return nb;
+}
+
+size_t norm_bwd_workspace_bytes(int T, long long tokens, int h) {
+  return (size_t)norm_bwd_blocks((long long)T * tokens) * 2 * (size_t)h * sizeof(float);
+}
+
+template <int VPL>
+static hipError_t norm_bwd_dispatch(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
+                                    const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled,
+                                    float* partial, int norm, long long rows, int h, int hs, float scale, long long nb,
+                                    long long rpb, hipStream_t s) {
+  if (norm == 0)
+    hipLaunchKernelGGL((norm_bwd_kernel<VPL, true>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+  else
+    hipLaunchKernelGGL((norm_bwd_kernel<VPL, false>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
+                           const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,
+                           float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
+                           void* workspace, hipStream_t s) {
+  const long long rows = (long long)T * tokens;
+  if (rows == 0) return hipSuccess;
+  const long long nb = norm_bwd_blocks(rows);
+  const long long rpb = (rows + nb - 1) / nb;
+  float* partial = reinterpret_cast<float*>(workspace);
+  const int vpl = (h / 8 + 63) / 64;
+  hipError_t e;
+  if (vpl <= 1) e = norm_bwd_dispatch<1>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+  else if (vpl <= 2) e = norm_bwd_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+  else if (vpl <= 4) e = norm_bwd_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+  else if (vpl <= 8) e = norm_bwd_dispatch<8>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+  else if (vpl <= 16) e = norm_bwd_dispatch<16>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+  else return hipErrorInvalidValue;
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 255) / 256)), dim3(256), 0, s, partial, (int)nb,
+                     h, dgamma, dbeta);
+  return hipGetLastError();
+}
+
+}  // namespace caat

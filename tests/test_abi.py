@@ -1,0 +1,93 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol include/caat.h declares, and the
+host-side validation returns error codes before anything is launched (no compute here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2506_19645_amd import binding as B
+from paper_2506_19645_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "caat.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(caat_[a-z0-9_]+)\s*\(", txt)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    L = B.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_shared_channels_matches_floor():
+    assert B.shared_channels(768, 0.5) == 384
+    assert B.shared_channels(768, 0.3) == 230
+    assert B.shared_channels(4096, 0.703125) == 2880
+    assert B.shared_channels(4096, 0.7) == 2867
+    assert B.shared_channels(4096, 1.0) == 4096 and B.shared_channels(4096, 0.0) == 0
+    for bad in (-0.01, 1.01, float("nan")):
+        assert B.shared_channels(16, bad) == -1
+    for cfg in I.CONFIGS.values():
+        for p in (1.0, 0.5, 0.25, 0.0):
+            assert B.shared_channels(cfg.h, p) == cfg.with_(p=p).hs
+
+
+def test_status_strings():
+    seen = {B.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and B.status_string(0) == "ok"
+
+
+def test_validation_errors_before_launch():
+    # host-side checks only: all pointers are fake but validation fails before they are used
+    fake = 0x1000
+    assert B.partial_sync(None, None, fake, 2, 4, 16, 8, stream=0, check=False) == B.EINVAL
+    assert B.partial_sync(fake, None, fake, 0, 4, 16, 8, stream=0, check=False) == B.EINVAL
+    assert B.partial_sync(fake, None, fake, 2, 4, 16, 17, stream=0, check=False) == B.ESHAPE
+    assert B.partial_sync(fake, None, fake, 2, 4, 12, 4, stream=0, check=False) == B.ESHAPE      # h % 8
+    assert B.partial_sync(fake + 2, None, fake, 2, 4, 16, 8, stream=0, check=False) == B.EALIGN
+    assert B.partial_sync(fake, None, fake, 2, 4, 16, 8, private_scale=float("nan"), stream=0, check=False) == B.EINVAL
+    assert B.norm_fwd(fake, fake, None, fake, fake, fake, B.LAYERNORM, 2, 4, 16, 1e-5, stream=0, check=False) == B.EINVAL
+    assert B.norm_fwd(fake, fake, None, fake, None, fake, 7, 2, 4, 16, 1e-5, stream=0, check=False) == B.EINVAL
+    assert B.gemm_bf16(fake, fake, fake, B.GEMM_NT, 1, 8, 12, 8, 8, 8, 16, 0, 0, 0, stream=0, check=False) == B.ESHAPE
+    assert B.gemm_bf16(fake, fake, fake, 5, 1, 8, 8, 8, 8, 8, 8, 0, 0, 0, stream=0, check=False) == B.EINVAL
+    assert B.gemm_bf16(fake, fake, fake + 4, B.GEMM_NT, 1, 8, 8, 8, 8, 8, 8, 0, 0, 0, stream=0, check=False) == B.EALIGN
+
+
+def test_descriptor_validation_and_workspace():
+    d = B.make_desc(I.C1)
+    assert B.workspace_bytes(d) > 0
+    L = B.workspace_layout(d)
+    assert L.total_bytes == B.workspace_bytes(d)
+    assert L.bytes_P == 2 * 256 * 1536 * 2 and L.bytes_Y == L.bytes_P and L.bytes_dZt == 2 * 256 * 768 * 2
+    d3 = B.make_desc(I.C3)
+    L3 = B.workspace_layout(d3)
+    assert L3.bytes_P == 2 * L3.bytes_Y                      # gate|up pre-activations
+    bad = B.make_desc(I.C1)
+    bad.ffn = 3073
+    assert B.workspace_bytes(bad) == 0
+    bad = B.make_desc(I.C1)
+    bad.hs = 769
+    assert B.workspace_bytes(bad) == 0
+    bad = B.make_desc(I.C1)
+    bad.T = 0
+    assert B.workspace_bytes(bad) == 0
+    fake = 0x1000
+    w = [fake, fake, fake, fake]
+    assert B.block_fwd(d, w, fake, fake, fake, fake, None, stream=0, check=False) == B.EINVAL       # no workspace
+    bad = B.make_desc(I.C1)
+    bad.hs = -1
+    assert B.block_fwd(bad, w, fake, fake, fake, fake, None, stream=0, check=False) == B.ESHAPE
+
+
+def test_no_fallback_when_library_missing(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError):
+        B.lib()

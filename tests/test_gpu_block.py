@@ -1,0 +1,163 @@
+"""GPU parity of caat_block_fwd / caat_block_bwd (MLP kinds) against the CPU oracle, through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import caat_oracle as O
+from paper_2506_19645_amd import binding as B
+from paper_2506_19645_amd import inputs as I
+from tests.util import assert_close, bits_to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def run_mlp_block(cfg, d, backward=True):
+    """Marshal the bit patterns in d to the GPU, run fwd (+bwd) through the C ABI, return host arrays."""
+    import torch
+    desc = B.make_desc(cfg)
+    swi = cfg.kind == I.KIND_MLP_SWIGLU
+    ln = cfg.norm == I.NORM_LAYERNORM
+    T, n, h, fr = cfg.T, cfg.tokens, cfg.h, cfg.f_r
+    w0 = B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1) if swi else d["A"])
+    w1 = B.to_device(d["B"])
+    gamma = B.to_device(d["gamma"])
+    beta = B.to_device(d["beta"]) if ln else None
+    x, r = B.to_device(d["X"]), B.to_device(d["R"])
+    r_out, x_out = torch.empty_like(x), torch.empty_like(x)
+    ws = torch.zeros(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    weights = [w0, w1, gamma, beta]
+    B.block_fwd(desc, weights, x, r, r_out, x_out, ws)
+    torch.cuda.synchronize()
+    L = B.workspace_layout(desc)
+    pw = 2 * fr if swi else fr
+
+    def ws_bf16(off, nbytes, shape):
+        return bits_to_f64(ws[off:off + nbytes].view(torch.int16).cpu().numpy().view(np.uint16).reshape(shape))
+
+    out = {"Rp_bits": B.to_host_bits(r_out), "Xp_bits": B.to_host_bits(x_out)}
+    out["Rp"], out["Xp"] = bits_to_f64(out["Rp_bits"]), bits_to_f64(out["Xp_bits"])
+    out["P"] = ws_bf16(L.off_P, L.bytes_P, (T, n, pw))
+    out["Y"] = ws_bf16(L.off_Y, L.bytes_Y, (T, n, fr))
+    if backward:
+        dxo, dro = B.to_device(d["dXo"]), B.to_device(d["dRo"])
+        dx, dr = torch.empty_like(x), torch.empty_like(x)
+        dw0, dw1 = torch.empty_like(w0), torch.empty_like(w1)
+        dgamma = torch.empty(h, dtype=torch.float32, device="cuda")
+        dbeta = torch.empty(h, dtype=torch.float32, device="cuda") if ln else None
+        B.block_bwd(desc, weights, x, r_out, ws, dxo, dro, dx, dr, [dw0, dw1], dgamma, dbeta)
+        torch.cuda.synchronize()
+        out["dX"], out["dR"] = bits_to_f64(B.to_host_bits(dx)), bits_to_f64(B.to_host_bits(dr))
+        out["dW0"], out["dB"] = bits_to_f64(B.to_host_bits(dw0)), bits_to_f64(B.to_host_bits(dw1))
+        out["dgamma"] = dgamma.cpu().numpy().astype(np.float64)
+        if ln:
+            out["dbeta"] = dbeta.cpu().numpy().astype(np.float64)
+        out["dZt"] = ws_bf16(L.off_dZt, L.bytes_dZt, (T, n, h))
+        out["dP"] = ws_bf16(L.off_dP, L.bytes_dP, (T, n, pw))
+    return out
+
+
+def oracle_mlp_block(cfg, d, backward=True):
+    w = {k: O.widen_bf16(v) for k, v in d.items()}
+    swi = cfg.kind == I.KIND_MLP_SWIGLU
+    norm = O.LAYERNORM if cfg.norm == I.NORM_LAYERNORM else O.RMSNORM
+    kw = dict(swiglu=swi, norm=norm, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale)
+    fwd = O.mlp_block_fwd(w["X"], w["R"], w, w["gamma"], w.get("beta"), **kw)
+    g = O.mlp_block_bwd(w["X"], fwd, w, w["gamma"], w["dXo"], w["dRo"], **kw) if backward else {}
+    return w, fwd, g
+
+
+def check_mlp_block(cfg, d, got, w, fwd, g, backward=True):
+    swi = cfg.kind == I.KIND_MLP_SWIGLU
+    hs = cfg.hs
+    Pfull = np.concatenate([fwd["P"], fwd["Pu"]], axis=-1) if swi else fwd["P"]
+    assert_close(got["P"], Pfull, "P")
+    assert_close(got["Y"], fwd["Y"], "Y")
+    assert_close(got["Rp"], fwd["Rp"], "Rp")
+    assert_close(got["Xp"], fwd["Xp"], "Xp")
+    # shared channels carry the same bits on every rank when the residual's shared columns are rank-equal
+    if hs > 0 and np.array_equal(d["R"][0, :, :hs], d["R"][-1, :, :hs]):
+        for m in range(1, cfg.T):
+            assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
+    if backward:
+        dPfull = np.concatenate([g["dP"], g["dPu"]], axis=-1) if swi else g["dP"]
+        dW0 = np.concatenate([g["dWg"], g["dWu"]], axis=1) if swi else g["dA"]
+        assert_close(got["dR"], g["dR"], "dR")
+        assert_close(got["dZt"], g["dZt"], "dZt")
+        assert_close(got["dP"], dPfull, "dP")
+        assert_close(got["dX"], g["dX"], "dX")
+        assert_close(got["dB"], g["dB"], "dB")
+        assert_close(got["dW0"], dW0, "dW0")
+        assert_close(got["dgamma"], g["dgamma"], "dgamma")
+        if "dbeta" in g:
+            assert_close(got["dbeta"], g["dbeta"], "dbeta")
+
+
+def _cfg(swi, T, n, h, ffn, p, scale=1.0):
+    return I.BlockConfig("t", I.KIND_MLP_SWIGLU if swi else I.KIND_MLP_GELU,
+                         I.NORM_RMSNORM if swi else I.NORM_LAYERNORM, h=h, T=T, p=p, batch=1, seq=n, ffn=ffn,
+                         private_scale=scale)
+
+
+@pytest.mark.parametrize("swi", [False, True])
+@pytest.mark.parametrize("T,n,h,ffn,p,scale", [
+    (2, 4, 16, 32, 0.5, 1.0),            # the finite-difference shape of the oracle pins
+    (2, 40, 64, 256, 0.3, 1.0),          # hs = 19: not a multiple of 4 or 8
+    (3, 300, 264, 3 * 344, 0.5, 1.0),    # several tiles + ragged tails in M, N and K; T not a power of two
+    (4, 515, 512, 4 * 520, 0.25, math.sqrt(4.0)),   # private channel scaling sqrt(T)
+    (2, 129, 256, 1024, 1.0, 1.0),       # p = 1
+    (2, 129, 256, 1024, 0.0, 1.0),       # p = 0
+])
+def test_mlp_block_fwd_bwd(swi, T, n, h, ffn, p, scale):
+    cfg = _cfg(swi, T, n, h, ffn, p, scale)
+    d = I.make_inputs(cfg, seed=7, weight_std=0.05)
+    got = run_mlp_block(cfg, d)
+    w, fwd, g = oracle_mlp_block(cfg, d)
+    check_mlp_block(cfg, d, got, w, fwd, g)
+
+
+def test_mlp_block_config1_seed0():
+    """The small benchmark configuration, exactly as specified (h=768, ffn=3072, T=2, p=0.5, 256 tokens, seed 0)."""
+    cfg = I.C1
+    d = I.make_inputs(cfg, seed=0)
+    got = run_mlp_block(cfg, d)
+    w, fwd, g = oracle_mlp_block(cfg, d)
+    check_mlp_block(cfg, d, got, w, fwd, g)
+
+
+def test_mlp_block_z_alone_with_zero_residual():
+    """With R = 0 the residual stream IS Z: checks the reduce output without R ~ N(0,1) masking its error."""
+    cfg = _cfg(False, 4, 200, 256, 1024, 0.5)
+    d = I.make_inputs(cfg, seed=9, weight_std=0.05)
+    d["R"][:] = 0
+    got = run_mlp_block(cfg, d, backward=False)
+    w, fwd, _ = oracle_mlp_block(cfg, d, backward=False)
+    assert_close(got["Rp"], fwd["Z"], "Z")
+    hs = cfg.hs
+    for m in range(1, cfg.T):
+        assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
+    assert not np.array_equal(got["Rp_bits"][1, :, hs:], got["Rp_bits"][0, :, hs:])
+
+
+def test_mlp_block_p1_replicated_all_ranks_identical():
+    """p = 1 with replicated inputs is the vanilla transformer: every rank ends with the same bits (Sec. 3)."""
+    cfg = _cfg(True, 4, 100, 256, 1024, 1.0)
+    d = I.make_inputs(cfg, seed=11, mode="replicated", weight_std=0.05)
+    got = run_mlp_block(cfg, d, backward=False)
+    for m in range(1, cfg.T):
+        assert np.array_equal(got["Rp_bits"][m], got["Rp_bits"][0])
+        assert np.array_equal(got["Xp_bits"][m], got["Xp_bits"][0])
+    w, fwd, _ = oracle_mlp_block(cfg, d, backward=False)
+    assert_close(got["Xp"], fwd["Xp"], "Xp")
+
+
+def test_mlp_block_p0_is_local():
+    """p = 0: rank m's output depends on rank m's data only (ensemble limit)."""
+    cfg = _cfg(False, 2, 64, 128, 512, 0.0)
+    d = I.make_inputs(cfg, seed=12, weight_std=0.05)
+    a = run_mlp_block(cfg, d, backward=False)
+    d2 = {k: v.copy() for k, v in d.items()}
+    d2["X"][1] = d2["X"][1][::-1].copy()
+    b = run_mlp_block(cfg, d2, backward=False)
+    assert np.array_equal(a["Rp_bits"][0], b["Rp_bits"][0])
+    assert not np.array_equal(a["Rp_bits"][1], b["Rp_bits"][1])
