@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the partial-sync tensor-parallel MLP block (forward + backward) on ONE MI355X.
+
+One "step" = caat_block_fwd + caat_block_bwd over one batch of the 1.1B-scale GPT MLP configuration
+(h=2048, ffn=8192, GELU, LayerNorm, T=4 emulated ranks, 8192 tokens), synthetic seeded inputs resident in HBM.
+Prints ONE JSON line: whole-step TFLOP/s (algorithmic FLOPs: 6*tokens*h*ffn*k, k=2 GELU / 3 SwiGLU), the
+roofline of the dominant kernel (measured live with HIP events around every launch), the sync kernels' GB/s
+versus p, synced bytes per token versus p, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+
+
+def flops_per_launch(name: str, cfg, which: int = 0) -> float:
+    """Algorithmic FLOPs of one launch (all T ranks) of a kernel family of the MLP block."""
+    n, h, f = cfg.tokens, cfg.h, cfg.ffn
+    k1 = 2 if cfg.kind == 1 else 1            # SwiGLU: gate and up projections
+    table = {
+        "gemm_nt_gelu_fwd": 2.0 * n * h * f, "gemm_nt_swiglu_fwd": 2.0 * n * h * f * 2,
+        "gemm_nt_rowpar": 2.0 * n * f * h,
+        "gemm_nn_gelu_bwd": 2.0 * n * h * f, "gemm_nn_swiglu_bwd": 2.0 * n * h * f,
+        "gemm_nn_dgrad": 2.0 * n * f * h * k1,
+        "gemm_tn_wgrad": (2.0 * n * f * h + 2.0 * n * f * h * k1) / 2.0,   # two launches per step: dB and dA
+    }
+    return table.get(name, 0.0)
+
+
+def sync_bytes(name: str, cfg, hs: int) -> float:
+    """Algorithmic HBM bytes of one launch of a streaming kernel."""
+    T, n, h = cfg.T, cfg.tokens, cfg.h
+    if name == "partial_sync_fwd":       # read T partials + T residual slices, write T outputs, shared channels only
+        return 3.0 * T * n * hs * 2
+    if name == "partial_sync_bwd":       # in place: read T, write T, shared channels only
+        return 2.0 * T * n * hs * 2
+    if name == "norm_fwd":
+        return 2.0 * T * n * h * 2 + T * n * 8
+    if name == "norm_bwd":               # read dy, dres, x; write g and scaled g
+        return 5.0 * T * n * h * 2 + T * n * 8
+    return 0.0
+
+
+class MlpBench:
+    def __init__(self, cfg, seed=0):
+        import numpy as np
+        import torch
+        from paper_2506_19645_amd import binding as B
+        from paper_2506_19645_amd import inputs as I
+        self.B, self.torch, self.cfg = B, torch, cfg
+        t0 = time.time()
+        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.h // 2)
+        self.host = d
+        swi = cfg.kind == I.KIND_MLP_SWIGLU
+        ln = cfg.norm == I.NORM_LAYERNORM
+        self.w0 = B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1) if swi else d["A"])
+        self.w1 = B.to_device(d["B"])
+        self.gamma = B.to_device(d["gamma"])
+        self.beta = B.to_device(d["beta"]) if ln else None
+        self.x, self.r = B.to_device(d["X"]), B.to_device(d["R"])
+        self.dxo, self.dro = B.to_device(d["dXo"]), B.to_device(d["dRo"])
+        self.r_out, self.x_out = torch.empty_like(self.x), torch.empty_like(self.x)
+        self.dx, self.dr = torch.empty_like(self.x), torch.empty_like(self.x)
+        self.dw0, self.dw1 = torch.empty_like(self.w0), torch.empty_like(self.w1)
+        self.dgamma = torch.empty(cfg.h, dtype=torch.float32, device="cuda")
+        self.dbeta = torch.empty(cfg.h, dtype=torch.float32, device="cuda") if ln else None
+        desc = B.make_desc(cfg)
+        self.ws = torch.empty(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+        self.weights = [self.w0, self.w1, self.gamma, self.beta]
+        self.setup_s = time.time() - t0
+
+    def step(self, desc):
+        B = self.B
+        B.block_fwd(desc, self.weights, self.x, self.r, self.r_out, self.x_out, self.ws)
+        B.block_bwd(desc, self.weights, self.x, self.r_out, self.ws, self.dxo, self.dro, self.dx, self.dr,
+                    [self.dw0, self.dw1], self.dgamma, self.dbeta)
+
+    def time_steps(self, desc, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(desc)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            self.step(desc)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+    def profile_steps(self, desc, steps):
+        """Per-launch durations (HIP events on the launch stream around every kernel) averaged per kernel family."""
+        B = self.B
+        B.profile_reset()
+        B.profile_enable(True)
+        for _ in range(steps):
+            self.step(desc)
+        self.torch.cuda.synchronize()
+        B.profile_enable(False)
+        acc = {}
+        for name, ms in B.profile_records():
+            tot, cnt = acc.get(name, (0.0, 0))
+            acc[name] = (tot + ms, cnt + 1)
+        B.profile_reset()
+        return {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / steps} for k, v in acc.items()}
+
+
+def standalone_sync(torch, B, cfg, hs, iters=20, nsets=8):
+    """caat_partial_sync in place on the shared channels, rotating over buffer sets (> 1 GB) so that the
+    last-level cache cannot hold the working set: the HBM-bound figure."""
+    if hs == 0:
+        return 0.0, 0.0
+    T, n, h = cfg.T, cfg.tokens, cfg.h
+    bufs = [torch.randn(T, n, h, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(nsets)]
+    for b in bufs:
+        B.partial_sync(b, None, b, T, n, h, hs, 1.0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        b = bufs[i % nsets]
+        B.partial_sync(b, None, b, T, n, h, hs, 1.0)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    return ms, 4.0 * T * n * hs / ms / 1e6     # GB/s, algorithmic 4*T*hs bytes per token
+
+
+def cpu_baseline(cfg, host, sample_tokens):
+    """The numpy fp64 oracle (as it stands) on the first `sample_tokens` tokens of every rank, fwd + bwd."""
+    import numpy as np
+    from oracle import caat_oracle as O
+    n = min(sample_tokens, cfg.tokens)
+    sub = {k: (v[:, :n] if k in ("X", "R", "dXo", "dRo") else v) for k, v in host.items()}
+    w = {k: O.widen_bf16(v) for k, v in sub.items()}
+    swi = cfg.kind == 1
+    norm = O.LAYERNORM if cfg.norm == 0 else O.RMSNORM
+    kw = dict(swiglu=swi, norm=norm, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale)
+    t0 = time.perf_counter()
+    fwd = O.mlp_block_fwd(w["X"], w["R"], w, w["gamma"], w.get("beta"), **kw)
+    O.mlp_block_bwd(w["X"], fwd, w, w["gamma"], w["dXo"], w["dRo"], **kw)
+    sec = time.perf_counter() - t0
+    flops = 6.0 * n * cfg.h * cfg.ffn * (3 if swi else 2)
+    threads = len(os.sched_getaffinity(0))
+    try:
+        from threadpoolctl import threadpool_info
+        blas = [i["num_threads"] for i in threadpool_info() if i.get("user_api") == "blas"]
+        if blas:
+            threads = max(blas)
+    except Exception:
+        pass
+    return {"value": flops / sec / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "numpy fp64 oracle, fwd+bwd, first %d of %d tokens of each of the %d ranks (%.1f s)"
+                      % (n, cfg.tokens, cfg.T, sec), "seconds": sec}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3"])
+    ap.add_argument("--p", type=float, default=0.5)
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (all T tensor-parallel ranks are emulated on it); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_19645_amd import binding as B
+    from paper_2506_19645_amd import inputs as I
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()
+    base = I.CONFIGS[args.config]
+    cfg = base.with_(p=args.p)
+    bench = MlpBench(cfg, seed=0)
+    desc = B.make_desc(cfg)
+    k = 3 if cfg.kind == I.KIND_MLP_SWIGLU else 2
+    step_flops = 6.0 * cfg.tokens * cfg.h * cfg.ffn * k
+
+    ms, wall_ms = bench.time_steps(desc, args.steps, args.warmup)
+    value = step_flops / ms / 1e9     # TFLOP/s
+
+    # per-kernel durations, live, HIP events on the launch stream
+    prof = bench.profile_steps(desc, max(3, min(args.steps, 10)))
+    gemms = {n: v for n, v in prof.items() if n.startswith("gemm")}
+    dom = max(gemms, key=lambda n: gemms[n]["avg_ms"] * gemms[n]["launches_per_step"])
+    dom_flops = flops_per_launch(dom, cfg)
+    achieved = dom_flops / prof[dom]["avg_ms"] / 1e9
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": dom_flops}
+    kernels = {}
+    for name, v in prof.items():
+        e = {"avg_ms": round(v["avg_ms"], 5), "launches_per_step": v["launches_per_step"]}
+        fl, by = flops_per_launch(name, cfg), sync_bytes(name, cfg, cfg.hs)
+        if fl:
+            e["TFLOP/s"] = round(fl / v["avg_ms"] / 1e9, 1)
+            e["frac_mfma_peak"] = round(fl / v["avg_ms"] / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)
+        if by:
+            e["GB/s"] = round(by / v["avg_ms"] / 1e6, 1)
+            e["frac_hbm_peak"] = round(by / v["avg_ms"] / 1e6 / HBM_PEAK_GBS, 4)
+        kernels[name] = e
+
+    sweep = []
+    if not args.no_sweep:
+        for p in (1.0, 0.5, 0.25, 0.0):
+            c = base.with_(p=p)
+            dsc = B.make_desc(c)
+            ms_p, _ = bench.time_steps(dsc, max(3, args.steps // 2), 2)
+            pr = bench.profile_steps(dsc, 5)
+            sa_ms, sa_gbs = standalone_sync(torch, B, c, c.hs)
+            e = {"p": p, "hs": c.hs, "ms_per_step": round(ms_p, 4), "TFLOP/s": round(step_flops / ms_p / 1e9, 1),
+                 "synced_payload_bytes_per_token_per_reduce": 2 * c.hs,
+                 "in_hbm_sync_bytes_per_token_fwd": 6 * c.T * c.hs, "in_hbm_sync_bytes_per_token_bwd": 4 * c.T * c.hs,
+                 "standalone_sync_ms": round(sa_ms, 5), "standalone_sync_GB/s": round(sa_gbs, 1),
+                 "standalone_sync_frac_hbm": round(sa_gbs / HBM_PEAK_GBS, 4)}
+            for nm in ("partial_sync_fwd", "partial_sync_bwd"):
+                if nm in pr:
+                    e[nm + "_ms"] = round(pr[nm]["avg_ms"], 5)
+                    e[nm + "_GB/s"] = round(sync_bytes(nm, c, c.hs) / pr[nm]["avg_ms"] / 1e6, 1)
+                else:
+                    e[nm + "_ms"] = 0.0
+            sweep.append(e)
+
+    out = {
+        "metric": "partial-sync TP block TFLOP/s (% MFMA peak) + sync GB/s (% HBM) vs p, 1 GPU",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s MLP block fwd+bwd: h=%d ffn=%d %s %s T=%d p=%g (hs=%d) tokens=%d, seed 0, "
+                               "x~N(0,1) w~N(0,0.02^2)" % (cfg.name, cfg.h, cfg.ffn, "SwiGLU" if k == 3 else "GELU",
+                                                            "LayerNorm" if cfg.norm == 0 else "RMSNorm", cfg.T, cfg.p,
+                                                            cfg.hs, cfg.tokens),
+                   "flops_per_step": step_flops, "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,
+                   "wall_ms_per_step": wall_ms},
+        "roofline": roofline, "kernels": kernels, "p_sweep": sweep,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, bench.host, args.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

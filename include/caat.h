@@ -187,6 +187,18 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
                    void* workspace, size_t ws_bytes, const void* dx_out, const void* dr_out, void* dx, void* dr,
                    void* const* dweights, float* dgamma, float* dbeta, void* hip_stream);
 
+/*
+ * Per-launch timing of the block calls (a host-side measuring tool, not part of the method): while enabled,
+ * caat_block_fwd / caat_block_bwd bracket every kernel they enqueue with a pair of HIP events on the caller's
+ * stream.  caat_profile_get waits for record `index` (in launch order since the last reset) and returns a
+ * static kernel-family name (host pointer to a NUL-terminated string) and the elapsed milliseconds.  Events
+ * are created on first use and reused after a reset.  Not thread-safe; off by default.
+ */
+int caat_profile_enable(int on);
+int caat_profile_reset(void);
+int caat_profile_count(void);
+int caat_profile_get(int index, const char** name, float* ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,7 +42,8 @@ class caat_ws_layout(C.Structure):
 
 EXPORTS = ["caat_shared_channels", "caat_status_string", "caat_workspace_bytes", "caat_workspace_layout",
            "caat_partial_sync", "caat_norm_fwd", "caat_norm_bwd_workspace_bytes", "caat_norm_bwd", "caat_gemm_bf16",
-           "caat_block_fwd", "caat_block_bwd"]
+           "caat_block_fwd", "caat_block_bwd", "caat_profile_enable", "caat_profile_reset", "caat_profile_count",
+           "caat_profile_get"]
 
 _lib = None
 
@@ -78,6 +79,14 @@ def lib() -> C.CDLL:
         L.caat_block_bwd.argtypes = [C.POINTER(caat_desc), C.POINTER(vp), vp, vp, vp, sz, vp, vp, vp, vp,
                                      C.POINTER(vp), vp, vp, vp]
         L.caat_block_bwd.restype = i
+        L.caat_profile_enable.argtypes = [i]
+        L.caat_profile_enable.restype = i
+        L.caat_profile_reset.argtypes = []
+        L.caat_profile_reset.restype = i
+        L.caat_profile_count.argtypes = []
+        L.caat_profile_count.restype = i
+        L.caat_profile_get.argtypes = [i, C.POINTER(C.c_char_p), C.POINTER(f)]
+        L.caat_profile_get.restype = i
         _lib = L
     return _lib
 
@@ -215,3 +224,22 @@ def block_bwd(desc: caat_desc, weights: Sequence, x, r_out, workspace, dx_out, d
     if check:
         _check(st, "caat_block_bwd")
     return st
+
+
+def profile_enable(on: bool) -> None:
+    _check(lib().caat_profile_enable(1 if on else 0), "caat_profile_enable")
+
+
+def profile_reset() -> None:
+    _check(lib().caat_profile_reset(), "caat_profile_reset")
+
+
+def profile_records():
+    """[(kernel family name, milliseconds)] in launch order since the last reset (waits for completion)."""
+    L = lib()
+    out = []
+    for k in range(L.caat_profile_count()):
+        name, ms = C.c_char_p(), C.c_float()
+        _check(L.caat_profile_get(k, C.byref(name), C.byref(ms)), "caat_profile_get")
+        out.append((name.value.decode(), float(ms.value)))
+    return out

@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <vector>
 
 using namespace caat;
 
@@ -13,6 +14,35 @@ namespace {
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int hip_status(hipError_t e) { return e == hipSuccess ? CAAT_OK : CAAT_EHIP; }
+
+// ---- optional per-launch timing (host-side tool): hipEvent pairs around every kernel of the block calls
+struct ProfRec {
+  const char* name;
+  hipEvent_t e0, e1;
+};
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;   // event pool, reused after caat_profile_reset
+size_t g_prof_used = 0;
+
+struct ProfScope {
+  hipStream_t s;
+  ProfRec* rec;
+  ProfScope(hipStream_t stream, const char* name) : s(stream), rec(nullptr) {
+    if (!g_prof_on) return;
+    if (g_prof_used == g_prof.size()) {
+      ProfRec r;
+      r.name = name;
+      if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+      g_prof.push_back(r);
+    }
+    rec = &g_prof[g_prof_used++];
+    rec->name = name;
+    (void)hipEventRecord(rec->e0, s);
+  }
+  ~ProfScope() {
+    if (rec) (void)hipEventRecord(rec->e1, s);
+  }
+};
 
 bool is_mlp(int kind) { return kind == CAAT_MLP_GELU || kind == CAAT_MLP_SWIGLU; }
 
@@ -98,6 +128,27 @@ size_t caat_workspace_bytes(const caat_desc* d) {
 int caat_workspace_layout(const caat_desc* d, caat_ws_layout* out) {
   if (!out) return CAAT_EINVAL;
   return layout_of(d, out);
+}
+
+int caat_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return CAAT_OK;
+}
+
+int caat_profile_reset(void) {
+  g_prof_used = 0;
+  return CAAT_OK;
+}
+
+int caat_profile_count(void) { return (int)g_prof_used; }
+
+int caat_profile_get(int index, const char** name, float* ms) {
+  if (index < 0 || (size_t)index >= g_prof_used || !name || !ms) return CAAT_EINVAL;
+  ProfRec& r = g_prof[(size_t)index];
+  if (hipEventSynchronize(r.e1) != hipSuccess) return CAAT_EHIP;
+  if (hipEventElapsedTime(ms, r.e0, r.e1) != hipSuccess) return CAAT_EHIP;
+  *name = r.name;
+  return CAAT_OK;
 }
 
 int caat_partial_sync(const void* y, const void* resid, void* out, int T, long long tokens, int h, int hs,
@@ -200,7 +251,11 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
   g1.c = P; g1.ldc = pw; g1.stride_c = n * pw;
   g1.c2 = Y; g1.ldc2 = fr; g1.stride_c2 = n * fr;
   g1.G = (int)T; g1.M = (int)n; g1.N = (int)fr; g1.K = (int)h; g1.half = (int)fr;
-  hipError_t e = launch_gemm(g1, 0, swi ? EPI_SWIGLU_FWD : EPI_GELU_FWD, s);
+  hipError_t e;
+  {
+    ProfScope ps(s, swi ? "gemm_nt_swiglu_fwd" : "gemm_nt_gelu_fwd");
+    e = launch_gemm(g1, 0, swi ? EPI_SWIGLU_FWD : EPI_GELU_FWD, s);
+  }
   if (e != hipSuccess) return CAAT_EHIP;
 
   // a2 + private half of a3/a4: Zt_m = Y_m B_m^T; columns >= hs become scale*Zt + R (final), columns < hs hold
@@ -213,17 +268,24 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
   g2.aux = (const bf16_t*)r; g2.ldaux = h; g2.stride_aux = n * h;
   g2.G = (int)T; g2.M = (int)n; g2.N = (int)h; g2.K = (int)fr;
   g2.hs = d->hs; g2.scale = d->private_scale;
-  e = launch_gemm(g2, 0, EPI_ROWPAR, s);
+  {
+    ProfScope ps(s, "gemm_nt_rowpar");
+    e = launch_gemm(g2, 0, EPI_ROWPAR, s);
+  }
   if (e != hipSuccess) return CAAT_EHIP;
 
   // a3/a4 shared half: sum the T partials on the hs shared channels, add each rank's residual, in place
   if (d->hs > 0) {
+    ProfScope ps(s, "partial_sync_fwd");
     e = launch_partial_sync_shared((bf16_t*)r_out, (const bf16_t*)r, (int)T, n, (int)h, d->hs, s);
     if (e != hipSuccess) return CAAT_EHIP;
   }
   // a5: per-rank norm on the now rank-divergent residual stream
-  e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd, d->norm,
-                      (int)T, n, (int)h, d->eps, s);
+  {
+    ProfScope ps(s, "norm_fwd");
+    e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd,
+                        d->norm, (int)T, n, (int)h, d->eps, s);
+  }
   return hip_status(e);
 }
 
@@ -259,12 +321,19 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
 
   // a6/a7: norm backward per rank FIRST (Fig. 2b): g_m = dr_out_m + NormBwd(dx_out_m); dr_m = g_m un-reduced;
   // a copy with scaled private channels goes to dZt; dgamma/dbeta summed over tokens and ranks
-  hipError_t e = launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
+  hipError_t e;
+  {
+    ProfScope ps(s, "norm_bwd");
+    e = launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
                                  mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
                                  d->private_scale, ws + L.off_scratch, s);
+  }
   if (e != hipSuccess) return CAAT_EHIP;
   // a8: the same partial channel-reduce on the gradients, in place on the shared channels, fp32 accumulation
-  e = launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s);
+  {
+    ProfScope ps(s, "partial_sync_bwd");
+    e = launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s);
+  }
   if (e != hipSuccess) return CAAT_EHIP;
 
   // a9 + a10: dY_m = dZt_m B_m (NN), fused with the activation derivative -> dP_m
@@ -275,7 +344,10 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   q.c = dP; q.ldc = pw; q.stride_c = n * pw;
   q.aux = P; q.ldaux = pw; q.stride_aux = n * pw;
   q.G = (int)T; q.M = (int)n; q.N = (int)fr; q.K = (int)h; q.half = (int)fr;
-  e = launch_gemm(q, 1, swi ? EPI_SWIGLU_BWD : EPI_GELU_BWD, s);
+  {
+    ProfScope ps(s, swi ? "gemm_nn_swiglu_bwd" : "gemm_nn_gelu_bwd");
+    e = launch_gemm(q, 1, swi ? EPI_SWIGLU_BWD : EPI_GELU_BWD, s);
+  }
   if (e != hipSuccess) return CAAT_EHIP;
 
   // a9: dB_m [h, f/T] = dZt_m^T Y_m (TN, reduction over tokens)
@@ -284,7 +356,10 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   q.b = Y; q.ldb = fr; q.stride_b = n * fr;
   q.c = (bf16_t*)dw1; q.ldc = fr; q.stride_c = h * fr;
   q.G = (int)T; q.M = (int)h; q.N = (int)fr; q.K = (int)n;
-  e = launch_gemm(q, 2, EPI_PLAIN, s);
+  {
+    ProfScope ps(s, "gemm_tn_wgrad");
+    e = launch_gemm(q, 2, EPI_PLAIN, s);
+  }
   if (e != hipSuccess) return CAAT_EHIP;
 
   // a11: dX_m = dP_m A_m (NN); NOT reduced over ranks (Sec. 4: the only reduce sits at the row-parallel output)
@@ -293,7 +368,10 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   q.b = (const bf16_t*)w0; q.ldb = h; q.stride_b = pw * h;
   q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h;
   q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)pw;
-  e = launch_gemm(q, 1, EPI_PLAIN, s);
+  {
+    ProfScope ps(s, "gemm_nn_dgrad");
+    e = launch_gemm(q, 1, EPI_PLAIN, s);
+  }
   if (e != hipSuccess) return CAAT_EHIP;
 
   // a11: dA_m [pw, h] = dP_m^T X_m (TN)
@@ -302,7 +380,10 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   q.b = (const bf16_t*)x; q.ldb = h; q.stride_b = n * h;
   q.c = (bf16_t*)dw0; q.ldc = h; q.stride_c = pw * h;
   q.G = (int)T; q.M = (int)pw; q.N = (int)h; q.K = (int)n;
-  e = launch_gemm(q, 2, EPI_PLAIN, s);
+  {
+    ProfScope ps(s, "gemm_tn_wgrad");
+    e = launch_gemm(q, 2, EPI_PLAIN, s);
+  }
   return hip_status(e);
 }
 

@@ -241,7 +241,7 @@ hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* b
 // Norm backward, placed before the reduce (Fig. 2b): g = dres + NormBwd(dy).  Each wave walks a contiguous
 // range of rows and keeps its lanes' columns of dgamma / dbeta in registers; a workgroup combines its 4 waves
 // through LDS and writes one partial row [2][h] to the workspace; a second kernel sums the partials in order.
-static constexpr int NORM_BWD_MAX_BLOCKS = 1024;
+static constexpr int NORM_BWD_MAX_BLOCKS = 512;
 
 template <int VPL, bool LN>
 __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ dres,
@@ -354,24 +354,35 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
   }
 }
 
-// sums partial[nb][2][h] over nb in ascending order; thread = one column of dgamma or dbeta
+// sums partial[nb][2][h] over nb in a fixed order: a workgroup owns 32 columns, its 8 row groups each add every
+// 8th partial row (4 independent chains), and the 8 group sums are combined in ascending order through LDS
 __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __restrict__ partial, int nb, int h,
                                                                 float* __restrict__ dgamma,
                                                                 float* __restrict__ dbeta) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= 2 * h) return;
+  __shared__ float red[8][32];
+  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
+  const long long w = 2LL * h;
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int b = 0;
-  for (; b + 4 <= nb; b += 4) {
-    s0 += partial[(long long)(b + 0) * 2 * h + c];
-    s1 += partial[(long long)(b + 1) * 2 * h + c];
-    s2 += partial[(long long)(b + 2) * 2 * h + c];
-    s3 += partial[(long long)(b + 3) * 2 * h + c];
+  if (c < 2 * h) {
+    int b = rg;
+    for (; b + 24 < nb; b += 32) {
+      s0 += partial[(long long)b * w + c];
+      s1 += partial[(long long)(b + 8) * w + c];
+      s2 += partial[(long long)(b + 16) * w + c];
+      s3 += partial[(long long)(b + 24) * w + c];
+    }
+    for (; b < nb; b += 8) s0 += partial[(long long)b * w + c];
   }
-  for (; b < nb; ++b) s0 += partial[(long long)b * 2 * h + c];
-  const float s = (s0 + s1) + (s2 + s3);
-  if (c < h) dgamma[c] = s;
-  else if (dbeta) dbeta[c - h] = s;
+  red[rg][cl] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (rg == 0 && c < 2 * h) {
+    float s = red[0][cl];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) s += red[k][cl];
+    if (c < h) dgamma[c] = s;
+    else if (dbeta) dbeta[c - h] = s;
+  }
 }
 
 static long long norm_bwd_blocks(long long rows) {
@@ -417,7 +428,7 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
   else if (vpl <= 16) e = norm_bwd_dispatch<16>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 255) / 256)), dim3(256), 0, s, partial, (int)nb,
+  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 31) / 32)), dim3(256), 0, s, partial, (int)nb,
                      h, dgamma, dbeta);
   return hipGetLastError();
 }
