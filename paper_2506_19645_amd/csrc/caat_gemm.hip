@@ -3,10 +3,13 @@
 
 namespace caat {
 
-typedef TileCfg<256, 256, 2, 2> CfgBig;
+// Measured choices (C2/C3 shard shapes, warm clocks): operands that are K-contiguous in memory go global -> LDS
+// directly and run best with 8 waves (2 x 4) per 256 x 256 tile; the weight-gradient layout (both operands
+// transposed through registers) needs the registers of the 4-wave (2 x 2) arrangement.
+typedef TileCfg<256, 256, 2, 4, 2, true> CfgDma8;
+typedef TileCfg<256, 256, 2, 2, 2, false> CfgReg4;
 
 hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_t s) {
-  typedef CfgBig C;
   // buffer-load offsets are 32-bit and relative to the tile origin: the farthest row a tile touches times the
   // row stride must stay below 2 GiB
   const long long far_rows = (epilogue == EPI_SWIGLU_FWD ? (long long)p.half : 0) + 256 + 64;
@@ -14,21 +17,21 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
   switch (layout) {
     case 0:  // NT
       switch (epilogue) {
-        case EPI_PLAIN: return launch_one<C, false, false, EPI_PLAIN>(p, s);
-        case EPI_GELU_FWD: return launch_one<C, false, false, EPI_GELU_FWD>(p, s);
-        case EPI_SWIGLU_FWD: return launch_one<C, false, false, EPI_SWIGLU_FWD>(p, s);
-        case EPI_ROWPAR: return launch_one<C, false, false, EPI_ROWPAR>(p, s);
+        case EPI_PLAIN: return launch_one<CfgDma8, false, false, EPI_PLAIN>(p, s);
+        case EPI_GELU_FWD: return launch_one<CfgDma8, false, false, EPI_GELU_FWD>(p, s);
+        case EPI_SWIGLU_FWD: return launch_one<CfgDma8, false, false, EPI_SWIGLU_FWD>(p, s);
+        case EPI_ROWPAR: return launch_one<CfgDma8, false, false, EPI_ROWPAR>(p, s);
         default: return hipErrorInvalidValue;
       }
     case 1:  // NN
       switch (epilogue) {
-        case EPI_PLAIN: return launch_one<C, false, true, EPI_PLAIN>(p, s);
-        case EPI_GELU_BWD: return launch_one<C, false, true, EPI_GELU_BWD>(p, s);
-        case EPI_SWIGLU_BWD: return launch_one<C, false, true, EPI_SWIGLU_BWD>(p, s);
+        case EPI_PLAIN: return launch_one<CfgDma8, false, true, EPI_PLAIN>(p, s);
+        case EPI_GELU_BWD: return launch_one<CfgDma8, false, true, EPI_GELU_BWD>(p, s);
+        case EPI_SWIGLU_BWD: return launch_one<CfgDma8, false, true, EPI_SWIGLU_BWD>(p, s);
         default: return hipErrorInvalidValue;
       }
     case 2:  // TN
-      if (epilogue == EPI_PLAIN) return launch_one<C, true, true, EPI_PLAIN>(p, s);
+      if (epilogue == EPI_PLAIN) return launch_one<CfgReg4, true, true, EPI_PLAIN>(p, s);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }

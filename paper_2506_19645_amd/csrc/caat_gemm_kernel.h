@@ -16,7 +16,7 @@
 // in registers across the four 16-wide k sub-steps.
 //
 // The accumulator is computed transposed (operands swapped in the MFMA) so that each lane ends up with 4
-// consecutive columns of one row of C: the epilogue works on 8-byte bf16x4 vectors.
+// consecutive columns of one row of C; the epilogue stages the bf16 tile through LDS and stores whole rows.
 #pragma once
 #include "caat_internal.h"
 
@@ -29,10 +29,11 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 static constexpr int BK = 64;                 // K step: 8 chunks of 8 bf16 per tile row
 static constexpr unsigned OOB = 0x80000000u;  // buffer offset that is always out of range -> load returns 0
 
-template <int BM_, int BN_, int WM_, int WN_, int SCHED_ = 2>
+template <int BM_, int BN_, int WM_, int WN_, int SCHED_ = 2, bool LDSD_ = false>
 struct TileCfg {
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr int SCHED = SCHED_;  // 0: compiler's order, 1: phase fences, 2: fences + MFMA/LDS/VMEM interleave
+  static constexpr bool LDSD = LDSD_;   // K-contiguous operands go global -> LDS directly (no register staging)
   static constexpr int THREADS = 64 * WM * WN;
   static constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;  // 32x32 MFMA tiles per wave
@@ -156,10 +157,62 @@ struct TransLoader {
   }
 };
 
-template <bool TRANS, int ROWS, int THREADS>
-struct LoaderSel { typedef DirectLoader<ROWS, THREADS> type; };
+// ---- K-contiguous source, global -> LDS without passing through registers (buffer_load ... lds): one wave
+// instruction fills 8 consecutive tile rows (64 lanes x 16 B = 1 KiB of LDS, lane order); the XOR swizzle is
+// applied on the global side (lane L fetches the chunk that belongs at LDS position L).
 template <int ROWS, int THREADS>
-struct LoaderSel<true, ROWS, THREADS> { typedef TransLoader<ROWS, THREADS> type; };
+struct DirectLdsLoader {
+  static constexpr int NWAVES = THREADS / 64;
+  static constexpr int NI = ROWS / 8 / NWAVES;
+  static constexpr int N_VMEM = NI, N_DSWRITE = 0;
+  const bf16_t* origin;
+  unsigned voff[NI];
+  int wave, lane;
+
+  __device__ __forceinline__ int kc_of(int it) const { return (lane & 7) ^ (((lane >> 3) ^ (it * NWAVES + wave)) & 7); }
+
+  template <class RowMap>
+  __device__ __forceinline__ void init(const bf16_t* origin_, long long ld, RowMap rowmap) {
+    origin = origin_;
+    lane = threadIdx.x & 63;
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+      const int row = (it * NWAVES + wave) * 8 + (lane >> 3);
+      const long long r = rowmap(row);
+      voff[it] = (r >= 0) ? (unsigned)((r * ld + kc_of(it) * 8) * 2) : OOB;
+    }
+  }
+  __device__ __forceinline__ void load(int k0, int K, uint4* tile) {
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(origin + k0);
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+      const bool kin = (k0 + kc_of(it) * 8) < K;
+      uint4* dst = tile + (it * NWAVES + wave) * 64;  // wave-uniform
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)dst, 16,
+                                               (int)(kin ? voff[it] : OOB), 0, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void store(uint4*) const {}
+};
+
+template <int ROWS, int THREADS>
+struct DirectRegLoader : DirectLoader<ROWS, THREADS> {
+  static constexpr int N_VMEM = DirectLoader<ROWS, THREADS>::NCH, N_DSWRITE = DirectLoader<ROWS, THREADS>::NCH;
+  __device__ __forceinline__ void load(int k0, int K, uint4*) { DirectLoader<ROWS, THREADS>::load(k0, K); }
+};
+template <int ROWS, int THREADS>
+struct TransRegLoader : TransLoader<ROWS, THREADS> {
+  static constexpr int N_VMEM = 8 * TransLoader<ROWS, THREADS>::NB, N_DSWRITE = 8 * TransLoader<ROWS, THREADS>::NB;
+  __device__ __forceinline__ void load(int k0, int K, uint4*) { TransLoader<ROWS, THREADS>::load(k0, K); }
+};
+
+template <bool TRANS, bool LDSD, int ROWS, int THREADS>
+struct LoaderSel { typedef DirectRegLoader<ROWS, THREADS> type; };
+template <int ROWS, int THREADS>
+struct LoaderSel<false, true, ROWS, THREADS> { typedef DirectLdsLoader<ROWS, THREADS> type; };
+template <bool LDSD, int ROWS, int THREADS>
+struct LoaderSel<true, LDSD, ROWS, THREADS> { typedef TransRegLoader<ROWS, THREADS> type; };
 
 __device__ __forceinline__ void store4(bf16_t* dst, float v0, float v1, float v2, float v3) {
   uint2 w;
@@ -171,6 +224,24 @@ __device__ __forceinline__ void store4(bf16_t* dst, float v0, float v1, float v2
 template <int TM, int TN>
 struct Frags {
   bf16x8_t a[TM], b[TN];
+};
+
+// Instruction-order request for one k sub-step (between two scheduling fences): after every MFMA place this
+// MFMA's share of the NR LDS reads (front-loaded: one per MFMA), NV global loads and NW LDS writes.
+template <int I, int NM, int NR, int NV, int NW>
+struct Pipe {
+  static __device__ __forceinline__ void run() {
+    if constexpr (I < NM) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      constexpr int r = (NR <= NM) ? (I < NR ? 1 : 0) : ((NR * (I + 1)) / NM - (NR * I) / NM);
+      constexpr int v = (NV * (I + 1)) / NM - (NV * I) / NM;
+      constexpr int w = (NW * (I + 1)) / NM - (NW * I) / NM;
+      if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+      if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+      if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
+      Pipe<I + 1, NM, NR, NV, NW>::run();
+    }
+  }
 };
 
 template <class CFG, bool AT, bool BT, int EPI>
@@ -219,8 +290,10 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
   const bf16_t* ag = p.a + (long long)g * p.stride_a;
   const bf16_t* bg = p.b + (long long)g * p.stride_b;
 
-  typename LoaderSel<AT, BM, THREADS>::type la;
-  typename LoaderSel<BT, BN, THREADS>::type lb;
+  typedef typename LoaderSel<AT, CFG::LDSD, BM, THREADS>::type LoaderA;
+  typedef typename LoaderSel<BT, CFG::LDSD, BN, THREADS>::type LoaderB;
+  LoaderA la;
+  LoaderB lb;
   {
     const int mrem = p.M - m0;
     la.init(AT ? ag + m0 : ag + (long long)m0 * p.lda, p.lda,
@@ -270,23 +343,26 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
         // operands swapped: the accumulator holds C^T, i.e. lane = row of C, registers = columns of C
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
   };
+  // LDS-direct loads are counted by vmcnt: they must have landed before the barrier that publishes the tile
+  auto wait_lds_dma = [&]() {
+    if constexpr (CFG::LDSD && (!AT || !BT)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
 
-  la.load(0, K);
-  lb.load(0, K);
+  la.load(0, K, smem);
+  lb.load(0, K, smem + BM * 8);
   la.store(smem);
   lb.store(smem + BM * 8);
+  wait_lds_dma();
   __syncthreads();
 
   Frags<TM, TN> f0, f1;
   load_frags(smem, smem + BM * 8, 0, f0);
 
-  // Instruction-order control.  fence(): nothing may be moved across.  interleave<n_mfma, n_other>(mask):
-  // ask for n_other instructions of class `mask` after every MFMA (classes: 0x100 LDS read, 0x200 LDS write,
-  // 0x020 VMEM read), so that the next sub-step's fragment reads, the next tile's global loads and its LDS
-  // writes are spread between the MFMAs of the current sub-step instead of bunching up in front of a wait.
+  // Instruction-order control: fence() = nothing moves across; Pipe<> spreads the next sub-step's fragment
+  // reads, the next tile's global loads and its LDS writes between the MFMAs of the current sub-step.
   constexpr int SCHED = CFG::SCHED;
-  constexpr int NMFMA = TM * TN;
-  constexpr int NFRAG = TM + TN;
+  constexpr int NM = TM * TN, NR = TM + TN;
+  constexpr int NV = LoaderA::N_VMEM + LoaderB::N_VMEM, NW = LoaderA::N_DSWRITE + LoaderB::N_DSWRITE;
   auto fence = [&]() {
     if constexpr (SCHED >= 1) __builtin_amdgcn_sched_barrier(0);
   };
@@ -296,138 +372,147 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
     const uint4* Bs = As + BM * 8;
     uint4* An = smem + ((kt + 1) & 1) * CFG::STAGE_CHUNKS;
     uint4* Bn = An + BM * 8;
-    // tile kt+1 (past the end of K: every offset is out of range, zeros come back, nobody uses them)
-    la.load((kt + 1) * BK, K);
-    lb.load((kt + 1) * BK, K);
-    fence();
+    // k sub-step 0, and the fetch of tile kt+1 (past the end of K every offset is out of range: zeros come
+    // back and nobody uses them, so the loop needs no branch)
+    la.load((kt + 1) * BK, K, An);
+    lb.load((kt + 1) * BK, K, Bn);
+    if constexpr (SCHED == 1) fence();
     load_frags(As, Bs, 1, f1);
     mfma_all(f0);
-    if constexpr (SCHED >= 2) {
-#pragma unroll
-      for (int i = 0; i < NFRAG; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
-    }
+    if constexpr (SCHED >= 2) Pipe<0, NM, NR, NV, 0>::run();
     fence();
     load_frags(As, Bs, 2, f0);
     mfma_all(f1);
-    if constexpr (SCHED >= 2) {
-#pragma unroll
-      for (int i = 0; i < NFRAG; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
-    }
+    if constexpr (SCHED >= 2) Pipe<0, NM, NR, 0, 0>::run();
     fence();
     load_frags(As, Bs, 3, f1);
     mfma_all(f0);
-    if constexpr (SCHED >= 2) {
-#pragma unroll
-      for (int i = 0; i < NFRAG; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
-    }
-    fence();
+    if constexpr (SCHED == 1) fence();
     la.store(An);
     lb.store(Bn);
+    if constexpr (SCHED >= 2) Pipe<0, NM, NR, 0, NW>::run();
+    fence();
+    wait_lds_dma();
     __syncthreads();
     fence();
     load_frags(An, Bn, 0, f0);
     mfma_all(f1);
-    if constexpr (SCHED >= 2) {
-#pragma unroll
-      for (int i = 0; i < NFRAG; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
-    }
+    if constexpr (SCHED >= 2) Pipe<0, NM, NR, 0, 0>::run();
     fence();
   }
 
-  // ---- epilogue: lane holds C[row = m + lane%32][col = n + 8*q + 4*(lane/32) + 0..3] in acc[..][4q..4q+3]
-  const long long M = p.M;
-  bf16_t* cg = p.c + (long long)g * p.stride_c;
+  // ---- epilogue.  Each lane holds C[row = lane%32][col = 8*q + 4*(lane/32) + 0..3] of every 32x32 tile in
+  // acc[..][4q..4q+3].  Writing that to global memory directly would scatter 8-byte pieces over 32 rows per
+  // instruction, so the tile is first rounded to bf16 and parked in LDS (the operand buffers are free now) as
+  // [BM][BN/8] 16-byte chunks, chunk index XOR-swizzled by the row (conflict-free for the column-of-rows
+  // writes and for the row-wise reads); then every wave instruction stores whole rows: 16 bytes per lane,
+  // consecutive lanes = consecutive columns.  The fused element-wise work (activation, its derivative, the
+  // private half of the partial channel-reduce + residual) is done in this second phase on 8 values per lane.
+  constexpr int CH = BN / 8;  // chunks per staged row
+  __syncthreads();            // every wave is done reading the operand tiles
+  {
+    char* stage = reinterpret_cast<char*>(smem);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const long long row = (long long)m0 + wm * WTM + i * 32 + frow;
-    if (row >= M) continue;
-    if constexpr (SWI) {
-      bf16_t* yg = p.c2 + (long long)g * p.stride_c2;
-#pragma unroll
-      for (int jj = 0; jj < TN / 2; ++jj) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = n0 + (wn * (TN / 2) + jj) * 32 + q * 8 + fk * 4;
-          if (col >= p.half) continue;
-          float gt[4], up[4], y[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            gt[e] = acc[i][2 * jj][q * 4 + e];
-            up[e] = acc[i][2 * jj + 1][q * 4 + e];
-            y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
-          }
-          store4(cg + row * p.ldc + col, gt[0], gt[1], gt[2], gt[3]);
-          store4(cg + row * p.ldc + p.half + col, up[0], up[1], up[2], up[3]);
-          store4(yg + row * p.ldc2 + col, y[0], y[1], y[2], y[3]);
-        }
-      }
-    } else {
+    for (int i = 0; i < TM; ++i) {
+      const int row = wm * WTM + i * 32 + frow;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int col = n0 + wn * WTN + j * 32 + q * 8 + fk * 4;
-          if (col >= p.N) continue;
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
-          if constexpr (EPI == EPI_PLAIN) {
-            store4(cg + row * p.ldc + col, v[0], v[1], v[2], v[3]);
-          } else if constexpr (EPI == EPI_GELU_FWD) {
-            bf16_t* yg = p.c2 + (long long)g * p.stride_c2;
-            store4(cg + row * p.ldc + col, v[0], v[1], v[2], v[3]);
-            store4(yg + row * p.ldc2 + col, gelu_f(v[0]), gelu_f(v[1]), gelu_f(v[2]), gelu_f(v[3]));
-          } else if constexpr (EPI == EPI_ROWPAR) {
-            // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual);
-            // columns < hs are stored as this rank's partial sum for the reduce kernel.
-            if (col + 3 >= p.hs) {
-              const bf16_t* rg = p.aux + (long long)g * p.stride_aux + row * p.ldaux + col;
-              const uint2 rw = *reinterpret_cast<const uint2*>(rg);
-              const float r0 = lo_bf(rw.x), r1 = hi_bf(rw.x), r2 = lo_bf(rw.y), r3 = hi_bf(rw.y);
-              if (col + 0 >= p.hs) v[0] = p.scale * v[0] + r0;
-              if (col + 1 >= p.hs) v[1] = p.scale * v[1] + r1;
-              if (col + 2 >= p.hs) v[2] = p.scale * v[2] + r2;
-              if (col + 3 >= p.hs) v[3] = p.scale * v[3] + r3;
-            }
-            store4(cg + row * p.ldc + col, v[0], v[1], v[2], v[3]);
-          } else if constexpr (EPI == EPI_GELU_BWD) {
-            const bf16_t* pg = p.aux + (long long)g * p.stride_aux + row * p.ldaux + col;
-            const uint2 pw = *reinterpret_cast<const uint2*>(pg);
-            store4(cg + row * p.ldc + col, v[0] * gelu_grad_f(lo_bf(pw.x)), v[1] * gelu_grad_f(hi_bf(pw.x)),
-                   v[2] * gelu_grad_f(lo_bf(pw.y)), v[3] * gelu_grad_f(hi_bf(pw.y)));
-          } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-            const bf16_t* pg = p.aux + (long long)g * p.stride_aux + row * p.ldaux + col;
-            const uint2 gw = *reinterpret_cast<const uint2*>(pg);
-            const uint2 uw = *reinterpret_cast<const uint2*>(pg + p.half);
-            const float gt[4] = {lo_bf(gw.x), hi_bf(gw.x), lo_bf(gw.y), hi_bf(gw.y)};
-            const float up[4] = {lo_bf(uw.x), hi_bf(uw.x), lo_bf(uw.y), hi_bf(uw.y)};
-            float dg[4], du[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float s = sigmoid_f(gt[e]);
-              dg[e] = v[e] * up[e] * s * (1.0f + gt[e] * (1.0f - s));
-              du[e] = v[e] * gt[e] * s;
-            }
-            store4(cg + row * p.ldc + col, dg[0], dg[1], dg[2], dg[3]);
-            store4(cg + row * p.ldc + p.half + col, du[0], du[1], du[2], du[3]);
-          }
+          const int c = (wn * WTN + j * 32) / 8 + q;
+          uint2 w;
+          w.x = pack2bf(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
+          w.y = pack2bf(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+          *reinterpret_cast<uint2*>(stage + ((row * CH + (c ^ (row & (CH - 1)))) * 16 + fk * 8)) = w;
         }
+      }
+    }
+  }
+  __syncthreads();
+
+  const int M = p.M;
+  bf16_t* cg = p.c + (long long)g * p.stride_c;
+  auto staged = [&](int row, int c) -> uint4 { return smem[row * CH + (c ^ (row & (CH - 1)))]; };
+  auto unpack = [](const uint4& v, float* f) {
+    f[0] = lo_bf(v.x); f[1] = hi_bf(v.x); f[2] = lo_bf(v.y); f[3] = hi_bf(v.y);
+    f[4] = lo_bf(v.z); f[5] = hi_bf(v.z); f[6] = lo_bf(v.w); f[7] = hi_bf(v.w);
+  };
+  auto pack = [](const float* f) -> uint4 {
+    return make_uint4(pack2bf(f[0], f[1]), pack2bf(f[2], f[3]), pack2bf(f[4], f[5]), pack2bf(f[6], f[7]));
+  };
+  constexpr int OCH = BN_OUT / 8;  // output chunks per row
+  constexpr int STEPS = BM * OCH / THREADS;
+  static_assert((BM * OCH) % THREADS == 0, "epilogue chunks must divide over the threads");
+#pragma unroll 4
+  for (int st = 0; st < STEPS; ++st) {
+    const int idx = st * THREADS + tid;
+    const int row = idx / OCH, oc = idx - row * OCH;
+    const long long grow = (long long)m0 + row;
+    const int gcol = n0 + oc * 8;
+    if (grow >= M || gcol >= p.N) continue;
+    if constexpr (SWI) {
+      // staged columns: per wave [gate 32 | up 32] pairs; output column -> its gate chunk, up chunk = +4
+      const int ocol = oc * 8;
+      const int w = ocol / (WTN / 2), rw = ocol - w * (WTN / 2);
+      const int gc = (w * WTN + (rw >> 5) * 64 + (rw & 31)) / 8;
+      float gt[8], up[8], y[8];
+      unpack(staged(row, gc), gt);
+      unpack(staged(row, gc + 4), up);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
+      bf16_t* yg = p.c2 + (long long)g * p.stride_c2;
+      *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = staged(row, gc);
+      *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = staged(row, gc + 4);
+      *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
+    } else {
+      const uint4 raw = staged(row, oc);
+      if constexpr (EPI == EPI_PLAIN) {
+        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+      } else if constexpr (EPI == EPI_GELU_FWD) {
+        // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
+        float v[8], y[8];
+        unpack(raw, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
+        bf16_t* yg = p.c2 + (long long)g * p.stride_c2;
+        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+        *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
+      } else if constexpr (EPI == EPI_ROWPAR) {
+        // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual); columns < hs are
+        // stored as this rank's partial sum for the reduce kernel.  NOTE: the private value is scaled from the
+        // bf16-rounded partial.
+        if (gcol + 7 >= p.hs) {
+          float v[8], r[8];
+          unpack(raw, v);
+          unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)g * p.stride_aux + grow * p.ldaux + gcol), r);
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (gcol + e >= p.hs) v[e] = p.scale * v[e] + r[e];
+          *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
+        } else {
+          *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+        }
+      } else if constexpr (EPI == EPI_GELU_BWD) {
+        float v[8], pr[8];
+        unpack(raw, v);
+        unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)g * p.stride_aux + grow * p.ldaux + gcol), pr);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
+        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
+      } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+        const bf16_t* pg = p.aux + (long long)g * p.stride_aux + grow * p.ldaux + gcol;
+        float v[8], gt[8], up[8], dg[8], du[8];
+        unpack(raw, v);
+        unpack(*reinterpret_cast<const uint4*>(pg), gt);
+        unpack(*reinterpret_cast<const uint4*>(pg + p.half), up);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float sg = sigmoid_f(gt[e]);
+          dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
+          du[e] = v[e] * gt[e] * sg;
+        }
+        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(dg);
+        *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = pack(du);
       }
     }
   }
