@@ -21,6 +21,11 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+# HBM bytes per launch read off the rocprofv3 --pmc runs of this same command (FETCH_SIZE x 2.00 calibration factor
+# + WRITE_SIZE x 1.00), summarised in profiles/mlp_block_c2_fwd_bwd.md; valid for the default workload only
+PMC_TRAFFIC_BYTES = {("C2", 0.5): {"gemm_tn_wgrad": 403e6 + 34e6, "gemm_nt_gelu_fwd": 404e6 + 268e6,
+                                   "gemm_nt_rowpar": 471e6 + 134e6, "gemm_nn_gelu_bwd": 539e6 + 136e6,
+                                   "gemm_nn_dgrad": 405e6 + 136e6}}
 
 
 def flops_per_launch(name: str, cfg, which: int = 0) -> float:
@@ -169,13 +174,16 @@ def cpu_baseline(cfg, host, sample_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3"])
     ap.add_argument("--p", type=float, default=0.5)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known size) so that a rocprofv3 --pmc run can scale "
+                         "FETCH_SIZE / WRITE_SIZE against it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (all T tensor-parallel ranks are emulated on it); "
@@ -194,6 +202,13 @@ def main():
     k = 3 if cfg.kind == I.KIND_MLP_SWIGLU else 2
     step_flops = 6.0 * cfg.tokens * cfg.h * cfg.ffn * k
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # the calibration kernel: reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
+
     ms, wall_ms = bench.time_steps(desc, args.steps, args.warmup)
     value = step_flops / ms / 1e9     # TFLOP/s
 
@@ -204,7 +219,8 @@ def main():
     dom_flops = flops_per_launch(dom, cfg)
     achieved = dom_flops / prof[dom]["avg_ms"] / 1e9
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": PMC_TRAFFIC_BYTES.get((args.config, args.p), {}).get(dom),
                 "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": dom_flops}
     kernels = {}
     for name, v in prof.items():
