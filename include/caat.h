@@ -92,7 +92,7 @@ typedef struct caat_ws_layout {
   size_t off_rstd, bytes_rstd; /* fp32 [T,tokens] */
   size_t off_dZt, bytes_dZt;   /* backward: reduced gradient [T,tokens,h] */
   size_t off_dP, bytes_dP;     /* backward: gradient of the pre-activations, same shape as P */
-  size_t off_Q, bytes_Q;       /* attention: rotated q, [T,batch,heads/T,seq,d]; K and V follow with the same size */
+  size_t off_Q, bytes_Q;       /* attention: projections [T,tokens,3*hd_r], column blocks q | k | v, q and k rotated (RoPE) */
   size_t off_scratch, bytes_scratch;
 } caat_ws_layout;
 

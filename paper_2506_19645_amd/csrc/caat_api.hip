@@ -87,11 +87,84 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
     take(T * n * h * 2, &L->off_dZt, &L->bytes_dZt);
     take(T * n * pw * 2, &L->off_dP, &L->bytes_dP);
     take(norm_bwd_workspace_bytes(d->T, d->tokens, d->h), &L->off_scratch, &L->bytes_scratch);
+  } else if (d->kind == CAAT_ATTN) {
+    const size_t hd = (size_t)(d->n_heads / d->T) * d->head_dim;
+    take(T * n * 3 * hd * 2, &L->off_Q, &L->bytes_Q);
+    take(T * n * hd * 2, &L->off_Y, &L->bytes_Y);
+    if (d->norm == CAAT_LAYERNORM) take(T * n * 4, &L->off_mean, &L->bytes_mean);
+    take(T * n * 4, &L->off_rstd, &L->bytes_rstd);
   } else {
     return CAAT_EUNSUPPORTED;
   }
   L->total_bytes = off;
   return CAAT_OK;
+}
+
+// Attention sub-block forward (Eq. A5 + Sec. 4): per rank q,k,v = X_m Wqkv_m^T; RoPE(q,k); causal attention per head;
+// Zt_m = H_m Wo_m^T with the private half of the partial channel-reduce in the epilogue; shared half; norm.
+int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* weights, const void* x, const void* r,
+                   void* r_out, void* x_out, void* workspace, size_t ws_bytes, void* hip_stream) {
+  const void* wqkv = weights[0]; const void* wo = weights[1]; const void* gamma = weights[2]; const void* beta = weights[3];
+  if (!wqkv || !wo || !gamma || (d->norm == CAAT_LAYERNORM && !beta)) return CAAT_EINVAL;
+  if (d->head_dim != 128) return CAAT_EUNSUPPORTED;
+  if (misaligned(wqkv) || misaligned(wo) || misaligned(gamma) || (beta && misaligned(beta)) || misaligned(x) ||
+      misaligned(r) || misaligned(r_out) || misaligned(x_out) || misaligned(workspace))
+    return CAAT_EALIGN;
+  if (ws_bytes < L.total_bytes) return CAAT_EWORKSPACE;
+  if (d->tokens == 0) return CAAT_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const long long T = d->T, n = d->tokens, h = d->h, hd = (long long)(d->n_heads / d->T) * d->head_dim;
+  bf16_t* QKV = (bf16_t*)(ws + L.off_Q);
+  bf16_t* H = (bf16_t*)(ws + L.off_Y);
+  float* mean = d->norm == CAAT_LAYERNORM ? (float*)(ws + L.off_mean) : nullptr;
+  float* rstd = (float*)(ws + L.off_rstd);
+  hipError_t e;
+  GemmParams g1;
+  std::memset(&g1, 0, sizeof(g1));
+  g1.a = (const bf16_t*)x; g1.lda = h; g1.stride_a = n * h;
+  g1.b = (const bf16_t*)wqkv; g1.ldb = h; g1.stride_b = 3 * hd * h;
+  g1.c = QKV; g1.ldc = 3 * hd; g1.stride_c = n * 3 * hd;
+  g1.G = (int)T; g1.M = (int)n; g1.N = (int)(3 * hd); g1.K = (int)h;
+  {
+    ProfScope ps(s, "gemm_nt_qkv");
+    e = launch_gemm(g1, 0, EPI_PLAIN, s);
+  }
+  if (e != hipSuccess) return CAAT_EHIP;
+  {
+    ProfScope ps(s, "rope");
+    e = launch_rope(QKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, 0, s);
+  }
+  if (e != hipSuccess) return CAAT_EHIP;
+  {
+    ProfScope ps(s, "flash_attn_fwd");
+    e = launch_flash_fwd(QKV, H, T * d->batch, d->seq, (int)hd, d->head_dim, s);
+  }
+  if (e != hipSuccess) return CAAT_EHIP;
+  GemmParams g2;
+  std::memset(&g2, 0, sizeof(g2));
+  g2.a = H; g2.lda = hd; g2.stride_a = n * hd;
+  g2.b = (const bf16_t*)wo; g2.ldb = hd; g2.stride_b = h * hd;
+  g2.c = (bf16_t*)r_out; g2.ldc = h; g2.stride_c = n * h;
+  g2.aux = (const bf16_t*)r; g2.ldaux = h; g2.stride_aux = n * h;
+  g2.G = (int)T; g2.M = (int)n; g2.N = (int)h; g2.K = (int)hd;
+  g2.hs = d->hs; g2.scale = d->private_scale;
+  {
+    ProfScope ps(s, "gemm_nt_rowpar");
+    e = launch_gemm(g2, 0, EPI_ROWPAR, s);
+  }
+  if (e != hipSuccess) return CAAT_EHIP;
+  if (d->hs > 0) {
+    ProfScope ps(s, "partial_sync_fwd");
+    e = launch_partial_sync_shared((bf16_t*)r_out, (const bf16_t*)r, (int)T, n, (int)h, d->hs, s);
+    if (e != hipSuccess) return CAAT_EHIP;
+  }
+  {
+    ProfScope ps(s, "norm_fwd");
+    e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd, d->norm,
+                        (int)T, n, (int)h, d->eps, s);
+  }
+  return hip_status(e);
 }
 
 }  // namespace
@@ -225,6 +298,7 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
   int st = layout_of(d, &L);
   if (st != CAAT_OK) return st;
   if (!weights || !x || !r || !r_out || !x_out || !workspace) return CAAT_EINVAL;
+  if (d->kind == CAAT_ATTN) return attn_block_fwd(d, L, weights, x, r, r_out, x_out, workspace, ws_bytes, hip_stream);
   if (!is_mlp(d->kind)) return CAAT_EUNSUPPORTED;
   const void* w0 = weights[0]; const void* w1 = weights[1]; const void* gamma = weights[2]; const void* beta = weights[3];
   if (!w0 || !w1 || !gamma || (d->norm == CAAT_LAYERNORM && !beta)) return CAAT_EINVAL;

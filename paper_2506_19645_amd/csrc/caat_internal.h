@@ -87,4 +87,8 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
                            float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
                            void* workspace, hipStream_t s);
 
+// ---------------------------------------------------------------- attention core
+hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int hd, int d, float base, long long pos0, hipStream_t s);
+hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, long long n_seq, int seq, int hd, int d, hipStream_t s);
+
 }  // namespace caat

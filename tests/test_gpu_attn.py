@@ -1,0 +1,91 @@
+"""GPU parity of the attention sub-block forward (Eq. A5 + Sec. 4) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import caat_oracle as O
+from paper_2506_19645_amd import binding as B
+from paper_2506_19645_amd import inputs as I
+from tests.util import assert_close, bits_to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def run_attn_block(cfg, d):
+    import torch
+    desc = B.make_desc(cfg)
+    ln = cfg.norm == I.NORM_LAYERNORM
+    T, n, h, hd = cfg.T, cfg.tokens, cfg.h, cfg.hd_r
+    weights = [B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
+               B.to_device(d["beta"]) if ln else None]
+    x, r = B.to_device(d["X"]), B.to_device(d["R"])
+    r_out, x_out = torch.empty_like(x), torch.empty_like(x)
+    ws = torch.zeros(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    B.block_fwd(desc, weights, x, r, r_out, x_out, ws)
+    torch.cuda.synchronize()
+    L = B.workspace_layout(desc)
+
+    def ws_bf16(off, nbytes, shape):
+        return bits_to_f64(ws[off:off + nbytes].view(torch.int16).cpu().numpy().view(np.uint16).reshape(shape))
+
+    out = {"Rp_bits": B.to_host_bits(r_out), "Xp_bits": B.to_host_bits(x_out)}
+    out["Rp"], out["Xp"] = bits_to_f64(out["Rp_bits"]), bits_to_f64(out["Xp_bits"])
+    out["QKV"] = ws_bf16(L.off_Q, L.bytes_Q, (T, n, 3 * hd))
+    out["H"] = ws_bf16(L.off_Y, L.bytes_Y, (T, n, hd))
+    return out
+
+
+def oracle_attn_block(cfg, d):
+    w = {k: O.widen_bf16(v) for k, v in d.items()}
+    norm = O.LAYERNORM if cfg.norm == I.NORM_LAYERNORM else O.RMSNORM
+    return w, O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], w.get("beta"), batch=cfg.batch,
+                               seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim, norm=norm,
+                               hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base)
+
+
+def check_attn(cfg, d, got, fwd):
+    T, b, s, hpr, dh, hd = cfg.T, cfg.batch, cfg.seq, cfg.n_heads // cfg.T, cfg.head_dim, cfg.hd_r
+    qkv = got["QKV"].reshape(T, b, s, 3, hpr, dh)
+    for k, name in enumerate(("Q", "K", "V")):
+        assert_close(qkv[:, :, :, k].transpose(0, 1, 3, 2, 4), fwd[name], name)
+    assert_close(got["H"], fwd["H"], "H")
+    assert_close(got["Rp"], fwd["Rp"], "Rp")
+    assert_close(got["Xp"], fwd["Xp"], "Xp")
+    hs = cfg.hs
+    if hs > 0 and np.array_equal(d["R"][0, :, :hs], d["R"][-1, :, :hs]):
+        for m in range(1, T):
+            assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
+
+
+def _cfg(T, batch, seq, heads, p, norm=I.NORM_RMSNORM, scale=1.0):
+    return I.BlockConfig("a", I.KIND_ATTN, norm, h=heads * 128, T=T, p=p, batch=batch, seq=seq, n_heads=heads,
+                         head_dim=128, private_scale=scale)
+
+
+@pytest.mark.parametrize("T,batch,seq,heads,p,norm", [
+    (2, 1, 64, 2, 0.5, I.NORM_RMSNORM),        # one key block
+    (2, 2, 200, 4, 0.5, I.NORM_RMSNORM),       # ragged: 2 query blocks, 4 key blocks, tail of 8
+    (1, 1, 333, 2, 1.0, I.NORM_LAYERNORM),     # T = 1, p = 1
+    (4, 1, 130, 4, 0.0, I.NORM_RMSNORM),       # p = 0, just past one query block
+    (2, 3, 1, 2, 0.25, I.NORM_RMSNORM),        # seq = 1: attention output equals v
+])
+def test_attn_block_fwd(T, batch, seq, heads, p, norm):
+    cfg = _cfg(T, batch, seq, heads, p, norm)
+    d = I.make_inputs(cfg, seed=21, with_grads=False, weight_std=0.05)
+    got = run_attn_block(cfg, d)
+    w, fwd = oracle_attn_block(cfg, d)
+    check_attn(cfg, d, got, fwd)
+    if seq == 1:
+        v = got["QKV"].reshape(T, batch, 3, -1)[:, :, 2]
+        assert np.array_equal(got["H"].reshape(T, batch, -1), v)
+
+
+def test_attn_causal_on_gpu():
+    """Perturbing the tokens after position i must not change any output row <= i (bitwise)."""
+    cfg = _cfg(2, 1, 192, 2, 0.5)
+    d = I.make_inputs(cfg, seed=22, with_grads=False, weight_std=0.05)
+    a = run_attn_block(cfg, d)
+    d2 = {k: v.copy() for k, v in d.items()}
+    d2["X"][:, 100:] = d2["X"][:, 100:][:, ::-1].copy()
+    b = run_attn_block(cfg, d2)
+    assert np.array_equal(a["Rp_bits"][:, :100], b["Rp_bits"][:, :100])
+    assert not np.array_equal(a["Rp_bits"][:, 100:], b["Rp_bits"][:, 100:])
