@@ -94,6 +94,12 @@ typedef struct caat_ws_layout {
   size_t off_dP, bytes_dP;     /* backward: gradient of the pre-activations, same shape as P */
   size_t off_Q, bytes_Q;       /* attention: projections [T,tokens,3*hd_r], column blocks q | k | v, q and k rotated (RoPE) */
   size_t off_scratch, bytes_scratch;
+  /* decode layer only: attention heads output [T,batch,hd_r]; first norm output X1, residual after the attention
+   * half R1 and second norm output X2, each [T,batch,h] */
+  size_t off_H, bytes_H;
+  size_t off_X1, bytes_X1;
+  size_t off_R1, bytes_R1;
+  size_t off_X2, bytes_X2;
 } caat_ws_layout;
 
 /* Sec. 3 / Eq. A3: number of shared channels floor(h*p), evaluated in IEEE double.  Host function.

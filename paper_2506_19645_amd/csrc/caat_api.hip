@@ -93,6 +93,16 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
     take(T * n * hd * 2, &L->off_Y, &L->bytes_Y);
     if (d->norm == CAAT_LAYERNORM) take(T * n * 4, &L->off_mean, &L->bytes_mean);
     take(T * n * 4, &L->off_rstd, &L->bytes_rstd);
+  } else if (d->kind == CAAT_ATTN_DECODE) {
+    const size_t hd = (size_t)(d->n_heads / d->T) * d->head_dim, fr = d->ffn / d->T;
+    take(T * n * h * 2, &L->off_X1, &L->bytes_X1);
+    take(T * n * 3 * hd * 2, &L->off_Q, &L->bytes_Q);
+    take(T * n * hd * 2, &L->off_H, &L->bytes_H);
+    take(T * n * h * 2, &L->off_R1, &L->bytes_R1);
+    take(T * n * h * 2, &L->off_X2, &L->bytes_X2);
+    take(T * n * 2 * fr * 2, &L->off_P, &L->bytes_P);
+    take(T * n * fr * 2, &L->off_Y, &L->bytes_Y);
+    take(T * n * 4, &L->off_rstd, &L->bytes_rstd);
   } else {
     return CAAT_EUNSUPPORTED;
   }
@@ -165,6 +175,81 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
                         (int)T, n, (int)h, d->eps, s);
   }
   return hip_status(e);
+}
+
+// One Llama-style decoder layer for one new token per sequence (inference uses the partial channel-reduce too,
+// Sec. 3.2): RMSNorm -> q,k,v -> RoPE at position kv_len -> append k,v -> attention over kv_len+1 keys -> o_proj
+// -> PCR + residual -> RMSNorm -> SwiGLU MLP -> PCR + residual.
+int decode_layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* weights, const void* r, void* r_out,
+                     void* kv_k, void* kv_v, void* workspace, size_t ws_bytes, void* hip_stream) {
+  if (!weights || !r || !r_out || !kv_k || !kv_v || !workspace) return CAAT_EINVAL;
+  const void* g_attn = weights[0]; const void* wqkv = weights[1]; const void* wo = weights[2];
+  const void* g_mlp = weights[3]; const void* wgu = weights[4]; const void* wb = weights[5];
+  if (!g_attn || !wqkv || !wo || !g_mlp || !wgu || !wb) return CAAT_EINVAL;
+  if (d->norm != CAAT_RMSNORM || d->head_dim != 128) return CAAT_EUNSUPPORTED;
+  if (d->seq != 1 || d->kv_len < 0 || d->kv_cap <= d->kv_len || d->kv_cap * 256 >= 0x7FFFFFFFLL) return CAAT_ESHAPE;
+  if (misaligned(g_attn) || misaligned(wqkv) || misaligned(wo) || misaligned(g_mlp) || misaligned(wgu) || misaligned(wb) ||
+      misaligned(r) || misaligned(r_out) || misaligned(kv_k) || misaligned(kv_v) || misaligned(workspace))
+    return CAAT_EALIGN;
+  if (ws_bytes < L.total_bytes) return CAAT_EWORKSPACE;
+  if (d->tokens == 0) return CAAT_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const long long T = d->T, n = d->tokens, h = d->h, hpr = d->n_heads / d->T, hd = hpr * d->head_dim, fr = d->ffn / d->T;
+  bf16_t* X1 = (bf16_t*)(ws + L.off_X1);
+  bf16_t* QKV = (bf16_t*)(ws + L.off_Q);
+  bf16_t* H = (bf16_t*)(ws + L.off_H);
+  bf16_t* R1 = (bf16_t*)(ws + L.off_R1);
+  bf16_t* X2 = (bf16_t*)(ws + L.off_X2);
+  bf16_t* P = (bf16_t*)(ws + L.off_P);
+  bf16_t* Y = (bf16_t*)(ws + L.off_Y);
+  float* rstd = (float*)(ws + L.off_rstd);
+  hipError_t e;
+  GemmParams q;
+#define CAAT_STEP(name, call) { ProfScope ps(s, name); e = (call); } if (e != hipSuccess) return CAAT_EHIP;
+  CAAT_STEP("norm_fwd", launch_norm_fwd((const bf16_t*)r, (const bf16_t*)g_attn, nullptr, X1, nullptr, rstd, CAAT_RMSNORM, (int)T,
+                                        n, (int)h, d->eps, s))
+  std::memset(&q, 0, sizeof(q));
+  q.a = X1; q.lda = h; q.stride_a = n * h;
+  q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = 3 * hd * h;
+  q.c = QKV; q.ldc = 3 * hd; q.stride_c = n * 3 * hd;
+  q.G = (int)T; q.M = (int)n; q.N = (int)(3 * hd); q.K = (int)h;
+  CAAT_STEP("gemm_nt_qkv", launch_gemm(q, 0, EPI_PLAIN, s))
+  CAAT_STEP("rope", launch_rope(QKV, T * n, 1, (int)hd, d->head_dim, d->rope_base, d->kv_len, s))
+  CAAT_STEP("kv_append", launch_kv_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * n, (int)hpr, (int)hd, d->kv_cap, d->kv_len, s))
+  CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)hd,
+                                              d->head_dim, d->kv_cap, d->kv_len + 1, s))
+  std::memset(&q, 0, sizeof(q));
+  q.a = H; q.lda = hd; q.stride_a = n * hd;
+  q.b = (const bf16_t*)wo; q.ldb = hd; q.stride_b = h * hd;
+  q.c = R1; q.ldc = h; q.stride_c = n * h;
+  q.aux = (const bf16_t*)r; q.ldaux = h; q.stride_aux = n * h;
+  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)hd; q.hs = d->hs; q.scale = d->private_scale;
+  CAAT_STEP("gemm_nt_rowpar", launch_gemm(q, 0, EPI_ROWPAR, s))
+  if (d->hs > 0) {
+    CAAT_STEP("partial_sync_fwd", launch_partial_sync_shared(R1, (const bf16_t*)r, (int)T, n, (int)h, d->hs, s))
+  }
+  CAAT_STEP("norm_fwd", launch_norm_fwd(R1, (const bf16_t*)g_mlp, nullptr, X2, nullptr, rstd, CAAT_RMSNORM, (int)T, n, (int)h,
+                                        d->eps, s))
+  std::memset(&q, 0, sizeof(q));
+  q.a = X2; q.lda = h; q.stride_a = n * h;
+  q.b = (const bf16_t*)wgu; q.ldb = h; q.stride_b = 2 * fr * h;
+  q.c = P; q.ldc = 2 * fr; q.stride_c = n * 2 * fr;
+  q.c2 = Y; q.ldc2 = fr; q.stride_c2 = n * fr;
+  q.G = (int)T; q.M = (int)n; q.N = (int)fr; q.K = (int)h; q.half = (int)fr;
+  CAAT_STEP("gemm_nt_swiglu_fwd", launch_gemm(q, 0, EPI_SWIGLU_FWD, s))
+  std::memset(&q, 0, sizeof(q));
+  q.a = Y; q.lda = fr; q.stride_a = n * fr;
+  q.b = (const bf16_t*)wb; q.ldb = fr; q.stride_b = h * fr;
+  q.c = (bf16_t*)r_out; q.ldc = h; q.stride_c = n * h;
+  q.aux = R1; q.ldaux = h; q.stride_aux = n * h;
+  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)fr; q.hs = d->hs; q.scale = d->private_scale;
+  CAAT_STEP("gemm_nt_rowpar", launch_gemm(q, 0, EPI_ROWPAR, s))
+  if (d->hs > 0) {
+    CAAT_STEP("partial_sync_fwd", launch_partial_sync_shared((bf16_t*)r_out, R1, (int)T, n, (int)h, d->hs, s))
+  }
+#undef CAAT_STEP
+  return CAAT_OK;
 }
 
 }  // namespace
@@ -293,10 +378,11 @@ int caat_gemm_bf16(const void* a, const void* b, void* c, int layout, int G, lon
 
 int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x, const void* r, void* r_out,
                    void* x_out, void* kv_k, void* kv_v, void* workspace, size_t ws_bytes, void* hip_stream) {
-  (void)kv_k; (void)kv_v;
   caat_ws_layout L;
   int st = layout_of(d, &L);
   if (st != CAAT_OK) return st;
+  if (d->kind == CAAT_ATTN_DECODE)
+    return decode_layer_fwd(d, L, weights, r, r_out, kv_k, kv_v, workspace, ws_bytes, hip_stream);
   if (!weights || !x || !r || !r_out || !x_out || !workspace) return CAAT_EINVAL;
   if (d->kind == CAAT_ATTN) return attn_block_fwd(d, L, weights, x, r, r_out, x_out, workspace, ws_bytes, hip_stream);
   if (!is_mlp(d->kind)) return CAAT_EUNSUPPORTED;

@@ -261,4 +261,124 @@ hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, long long n_seq, int
   return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// Decode: one new token per sequence.  (a) append the token's rotated k and its v to the caches at position
+// kv_len; (b) attention of the single query over kv_len + 1 cached keys.  Both are pure streaming (the KV read is
+// the layer's dominant HBM traffic), so there is no MFMA here: a workgroup owns one (rank, sequence, head);
+// 16 lanes own one key row (256 B), a wave takes 4 consecutive keys per step, the 4 waves 16; every 16-lane group
+// runs its own online softmax and the 16 partial results are merged through LDS in a fixed order.
+__global__ __launch_bounds__(256) void kv_append_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ kc,
+                                                        bf16_t* __restrict__ vc, long long n_seq, int hpr, int hd,
+                                                        long long cap, long long pos) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;   // (seq, head, chunk of 8)
+  if (idx >= n_seq * hpr * 16) return;
+  const int c = (int)(idx & 15);
+  const long long sh = idx >> 4;                                      // seq * hpr + head
+  const long long sq = sh / hpr;
+  const int head = (int)(sh - sq * hpr);
+  const bf16_t* src = qkv + sq * 3LL * hd + (long long)head * 128 + c * 8;
+  const long long dst = (sh * cap + pos) * 128 + c * 8;
+  *reinterpret_cast<uint4*>(kc + dst) = *reinterpret_cast<const uint4*>(src + hd);
+  *reinterpret_cast<uint4*>(vc + dst) = *reinterpret_cast<const uint4*>(src + 2 * hd);
+}
+
+__global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kc,
+                                                          const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, int hpr,
+                                                          int hd, long long cap, int nkeys, float scale_log2) {
+  __shared__ float s_acc[16][128];
+  __shared__ float s_m[16], s_l[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, c = lane & 15;
+  const long long sh = blockIdx.x;                 // seq * hpr + head
+  const long long sq = sh / hpr;
+  const int head = (int)(sh - sq * hpr);
+  float q[8];
+  {
+    const uint4 w = *reinterpret_cast<const uint4*>(qkv + sq * 3LL * hd + (long long)head * 128 + c * 8);
+    q[0] = lo_bf(w.x); q[1] = hi_bf(w.x); q[2] = lo_bf(w.y); q[3] = hi_bf(w.y);
+    q[4] = lo_bf(w.z); q[5] = hi_bf(w.z); q[6] = lo_bf(w.w); q[7] = hi_bf(w.w);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[e] *= scale_log2;
+  }
+  const __amdgpu_buffer_rsrc_t rk = attn_rsrc(kc + sh * cap * 128);
+  const __amdgpu_buffer_rsrc_t rv = attn_rsrc(vc + sh * cap * 128);
+  float m = -INFINITY, l = 0.0f, acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  constexpr int UN = 4;
+  for (int key0 = wave * 4 + g; key0 < nkeys; key0 += 16 * UN) {
+    u32x4_t kv[UN], vv[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int key = key0 + 16 * u;
+      const unsigned off = key < nkeys ? (unsigned)key * 256u + c * 16 : OOB_OFF;
+      kv[u] = __builtin_amdgcn_raw_buffer_load_b128(rk, (int)off, 0, 0);
+      vv[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)off, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const bool valid = (key0 + 16 * u) < nkeys;
+      float s = q[0] * lo_bf(kv[u].x) + q[1] * hi_bf(kv[u].x) + q[2] * lo_bf(kv[u].y) + q[3] * hi_bf(kv[u].y) +
+                q[4] * lo_bf(kv[u].z) + q[5] * hi_bf(kv[u].z) + q[6] * lo_bf(kv[u].w) + q[7] * hi_bf(kv[u].w);
+      s += __shfl_xor(s, 1, 64);
+      s += __shfl_xor(s, 2, 64);
+      s += __shfl_xor(s, 4, 64);
+      s += __shfl_xor(s, 8, 64);
+      const float m_new = valid ? fmaxf(m, s) : m;
+      const float alpha = valid ? exp2f(m - m_new) : 1.0f;     // m = -inf on the first key: exp2(-inf) = 0
+      const float p = valid ? exp2f(s - m_new) : 0.0f;
+      l = l * alpha + p;
+      const unsigned w[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] = acc[2 * e] * alpha + p * lo_bf(w[e]);
+        acc[2 * e + 1] = acc[2 * e + 1] * alpha + p * hi_bf(w[e]);
+      }
+      m = m_new;
+    }
+  }
+  const int stream = wave * 4 + g;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s_acc[stream][c * 8 + e] = acc[e];
+  if (c == 0) {
+    s_m[stream] = m;
+    s_l[stream] = l;
+  }
+  __syncthreads();
+  if (tid < 128) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) M = fmaxf(M, s_m[i]);
+    float num = 0.0f, den = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float w = (s_m[i] == -INFINITY) ? 0.0f : exp2f(s_m[i] - M);
+      num += s_acc[i][tid] * w;
+      den += s_l[i] * w;
+    }
+    out[sq * (long long)hd + (long long)head * 128 + tid] = f2bf(num / den);
+  }
+}
+
+hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int hpr, int hd, long long cap,
+                            long long pos, hipStream_t s) {
+  const long long work = n_seq * hpr * 16;
+  if (work == 0) return hipSuccess;
+  hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, qkv, kc, vc, n_seq, hpr, hd,
+                     cap, pos);
+  return hipGetLastError();
+}
+
+// out [n_seq, hd] = softmax(q K^T / sqrt(d)) V over keys 0 .. nkeys-1 of caches [n_seq][hpr][cap][128]
+hipError_t launch_decode_attn(const bf16_t* qkv, const bf16_t* kc, const bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
+                              int hd, int d, long long cap, long long nkeys, hipStream_t s) {
+  if (d != HD || nkeys < 1 || nkeys > cap || cap * 256 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  const long long blocks = n_seq * hpr;
+  if (blocks == 0) return hipSuccess;
+  if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)d);
+  hipLaunchKernelGGL(decode_attn_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, kc, vc, out, hpr, hd, cap, (int)nkeys,
+                     scale_log2);
+  return hipGetLastError();
+}
+
 }  // namespace caat

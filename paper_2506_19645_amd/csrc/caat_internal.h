@@ -91,4 +91,9 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
 hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int hd, int d, float base, long long pos0, hipStream_t s);
 hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, long long n_seq, int seq, int hd, int d, hipStream_t s);
 
+hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int hpr, int hd, long long cap,
+                            long long pos, hipStream_t s);
+hipError_t launch_decode_attn(const bf16_t* qkv, const bf16_t* kc, const bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
+                              int hd, int d, long long cap, long long nkeys, hipStream_t s);
+
 }  // namespace caat

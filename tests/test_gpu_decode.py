@@ -1,0 +1,67 @@
+"""GPU parity of the decode layer (one new token per sequence over a KV cache) against the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import caat_oracle as O
+from paper_2506_19645_amd import binding as B
+from paper_2506_19645_amd import inputs as I
+from tests.util import assert_close, bits_to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def run_decode(cfg, d):
+    import torch
+    desc = B.make_desc(cfg)
+    T, b, h, hd = cfg.T, cfg.batch, cfg.h, cfg.hd_r
+    weights = [B.to_device(d["gamma_attn"]), B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
+               B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]
+    r = B.to_device(d["R"])
+    kc, vc = B.to_device(d["Kc"]), B.to_device(d["Vc"])
+    r_out = torch.empty_like(r)
+    ws = torch.zeros(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    B.block_fwd(desc, weights, None, r, r_out, None, ws, kv_k=kc, kv_v=vc)
+    torch.cuda.synchronize()
+    L = B.workspace_layout(desc)
+
+    def ws_bf16(off, nbytes, shape):
+        return bits_to_f64(ws[off:off + nbytes].view(torch.int16).cpu().numpy().view(np.uint16).reshape(shape))
+
+    return {"R2": bits_to_f64(B.to_host_bits(r_out)), "R2_bits": B.to_host_bits(r_out),
+            "X1": ws_bf16(L.off_X1, L.bytes_X1, (T, b, h)), "H": ws_bf16(L.off_H, L.bytes_H, (T, b, hd)),
+            "R1": ws_bf16(L.off_R1, L.bytes_R1, (T, b, h)), "X2": ws_bf16(L.off_X2, L.bytes_X2, (T, b, h)),
+            "Kc_bits": B.to_host_bits(kc), "Vc_bits": B.to_host_bits(vc)}
+
+
+def _cfg(T, b, heads, ffn, L, p):
+    return I.BlockConfig("dec", I.KIND_DECODE, I.NORM_RMSNORM, h=heads * 128, T=T, p=p, batch=b, seq=1, ffn=ffn,
+                         n_heads=heads, head_dim=128, kv_len=L)
+
+
+@pytest.mark.parametrize("T,b,heads,ffn,L,p", [
+    (2, 3, 4, 2 * 344, 37, 0.5),      # fewer keys than one 64-key sweep, ragged ffn shard
+    (2, 64, 4, 2 * 256, 300, 0.25),   # the benchmark's batch, several sweeps + tail
+    (4, 5, 4, 4 * 128, 0, 1.0),       # empty cache: the token attends to itself only
+    (1, 2, 2, 256, 129, 0.0),
+])
+def test_decode_layer(T, b, heads, ffn, L, p):
+    cfg = _cfg(T, b, heads, ffn, L, p)
+    d = I.make_inputs(cfg, seed=31, weight_std=0.05)
+    got = run_decode(cfg, d)
+    w = {k: O.widen_bf16(v) for k, v in d.items()}
+    hpr = heads // T
+    ref = O.decode_layer_fwd(w["R"], w, w["Kc"], w["Vc"], kv_len=L, heads_per_rank=hpr, head_dim=128, hs=cfg.hs)
+    assert_close(got["X1"], ref["X1"], "X1")
+    assert_close(got["H"], ref["H"], "H")
+    assert_close(got["R1"], ref["R1"], "R1")
+    assert_close(got["X2"], ref["X2"], "X2")
+    assert_close(got["R2"], ref["R2"], "R2")
+    # the new token's rotated k and its v were appended at position L; every older cache row keeps its bits
+    assert_close(bits_to_f64(got["Kc_bits"][:, :, :, L]), ref["k_new"], "k_new")
+    assert_close(bits_to_f64(got["Vc_bits"][:, :, :, L]), ref["v_new"], "v_new")
+    assert np.array_equal(got["Kc_bits"][:, :, :, :L], d["Kc"][:, :, :, :L])
+    assert np.array_equal(got["Vc_bits"][:, :, :, :L], d["Vc"][:, :, :, :L])
+    hs = cfg.hs
+    if hs > 0 and T > 1 and np.array_equal(d["R"][0, :, :hs], d["R"][-1, :, :hs]):
+        for m in range(1, T):
+            assert np.array_equal(got["R2_bits"][m, :, :hs], got["R2_bits"][0, :, :hs])
