@@ -171,12 +171,121 @@ def cpu_baseline(cfg, host, sample_tokens):
                       % (n, cfg.tokens, cfg.T, sec), "seconds": sec}
 
 
+class AttnBench(MlpBench):
+    """Attention sub-block forward (C4): QKV GEMM, RoPE, causal attention, o_proj + partial sync, norm."""
+
+    def __init__(self, cfg, seed=0):
+        import torch
+        from paper_2506_19645_amd import binding as B
+        from paper_2506_19645_amd import inputs as I
+        self.B, self.torch, self.cfg = B, torch, cfg
+        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.h // 2, with_grads=False)
+        self.host = d
+        self.weights = [B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]), None]
+        self.x, self.r = B.to_device(d["X"]), B.to_device(d["R"])
+        self.r_out, self.x_out = torch.empty_like(self.x), torch.empty_like(self.x)
+        self.ws = torch.empty(B.workspace_bytes(B.make_desc(cfg)), dtype=torch.uint8, device="cuda")
+
+    def step(self, desc):
+        self.B.block_fwd(desc, self.weights, self.x, self.r, self.r_out, self.x_out, self.ws)
+
+
+class DecodeBench(MlpBench):
+    """Decode layer (C5): one new token per sequence over a KV cache of kv_len positions."""
+
+    def __init__(self, cfg, seed=0):
+        import numpy as np
+        import torch
+        from paper_2506_19645_amd import binding as B
+        from paper_2506_19645_amd import inputs as I
+        self.B, self.torch, self.cfg = B, torch, cfg
+        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.h // 2)
+        self.host = d
+        self.weights = [B.to_device(d["gamma_attn"]), B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
+                        B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]
+        self.r = B.to_device(d["R"])
+        self.kc, self.vc = B.to_device(d["Kc"]), B.to_device(d["Vc"])
+        self.r_out = torch.empty_like(self.r)
+        self.ws = torch.empty(B.workspace_bytes(B.make_desc(cfg)), dtype=torch.uint8, device="cuda")
+
+    def step(self, desc):
+        self.B.block_fwd(desc, self.weights, None, self.r, self.r_out, None, self.ws, kv_k=self.kc, kv_v=self.vc)
+
+
+def bench_attention_kinds(args, cfg, base):
+    """JSON for the attention forward (C4, TFLOP/s) and the decode layer (C5, GB/s and per-token latency)."""
+    from paper_2506_19645_amd import binding as B
+    T, n, h, hd = cfg.T, cfg.tokens, cfg.h, cfg.hd_r
+    if args.config == "C4":
+        bench = AttnBench(cfg)
+        s = cfg.seq
+        fl = {"gemm_nt_qkv": 2.0 * n * h * 3 * h, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,   # causal half of 4 s^2 h
+              "gemm_nt_rowpar": 2.0 * n * h * h}
+        by = {"rope": 2.0 * T * n * 2 * hd * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
+              "norm_fwd": 2.0 * T * n * h * 2}
+        work, unit, peak = sum(fl.values()), "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
+        workload = "%s attention sub-block fwd: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
+            cfg.name, h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, cfg.hs)
+    else:
+        bench = DecodeBench(cfg)
+        fr = cfg.f_r
+        kv_bytes = 2.0 * T * cfg.batch * (cfg.n_heads // T) * (cfg.kv_len + 1) * cfg.head_dim * 2
+        w_bytes = 2.0 * T * (3 * hd * h + h * hd + 2 * fr * h + h * fr)
+        fl = {}
+        by = {"decode_attn": kv_bytes, "gemm_nt_qkv": 2.0 * T * 3 * hd * h, "gemm_nt_swiglu_fwd": 2.0 * T * 2 * fr * h,
+              "gemm_nt_rowpar": 2.0 * T * (h * hd + h * fr) / 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
+              "norm_fwd": 2.0 * T * n * h * 2}
+        work, unit, peak = kv_bytes + w_bytes, "GB/s", HBM_PEAK_GBS
+        workload = "%s decode layer: h=%d ffn=%d heads=%d d=%d batch=%d kv_len=%d T=%d p=%g (hs=%d)" % (
+            cfg.name, h, cfg.ffn, cfg.n_heads, cfg.head_dim, cfg.batch, cfg.kv_len, T, cfg.p, cfg.hs)
+    desc = B.make_desc(cfg)
+    ms, wall_ms = bench.time_steps(desc, args.steps, args.warmup)
+    prof = bench.profile_steps(desc, max(3, min(args.steps, 10)))
+    kernels = {}
+    for name, v in prof.items():
+        e = {"avg_ms": round(v["avg_ms"], 5), "launches_per_step": v["launches_per_step"]}
+        if name in fl:
+            e["TFLOP/s"] = round(fl[name] / v["avg_ms"] / 1e9, 1)
+            e["frac_mfma_peak"] = round(fl[name] / v["avg_ms"] / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)
+        if name in by:
+            e["GB/s"] = round(by[name] / v["avg_ms"] / 1e6, 1)
+            e["frac_hbm_peak"] = round(by[name] / v["avg_ms"] / 1e6 / HBM_PEAK_GBS, 4)
+        kernels[name] = e
+    dom = max(prof, key=lambda k: prof[k]["avg_ms"] * prof[k]["launches_per_step"])
+    if args.config == "C4":
+        value = work / ms / 1e9
+        ach = fl.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e9
+        roof = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+                "traffic": None, "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": fl.get(dom, 0.0)}
+    else:
+        value = work / ms / 1e6
+        ach = by.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e6
+        roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+                "traffic": None, "avg_launch_ms": prof[dom]["avg_ms"], "bytes_per_launch": by.get(dom, 0.0)}
+    out = {"metric": "partial-sync TP block TFLOP/s (% MFMA peak) + sync GB/s (% HBM) vs p, 1 GPU",
+           "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": workload, "work_per_step": work, "frac_peak": value / peak, "wall_ms_per_step": wall_ms},
+           "roofline": roof, "kernels": kernels}
+    if args.config == "C5":
+        out["config"]["latency_us_per_token_step"] = ms * 1e3
+        sweep = []
+        if not args.no_sweep:
+            for p in (1.0, 0.5, 0.25, 0.0):
+                c = base.with_(p=p)
+                ms_p, _ = bench.time_steps(B.make_desc(c), max(3, args.steps // 2), 2)
+                sweep.append({"p": p, "hs": c.hs, "ms_per_step": round(ms_p, 5), "GB/s": round(work / ms_p / 1e6, 1),
+                              "synced_payload_bytes_per_token_per_reduce": 2 * c.hs})
+        out["p_sweep"] = sweep
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--p", type=float, default=0.5)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -197,6 +306,9 @@ def main():
     B.lib()
     base = I.CONFIGS[args.config]
     cfg = base.with_(p=args.p)
+    if args.config in ("C4", "C5"):
+        print(json.dumps(bench_attention_kinds(args, cfg, base)))
+        return
     bench = MlpBench(cfg, seed=0)
     desc = B.make_desc(cfg)
     k = 3 if cfg.kind == I.KIND_MLP_SWIGLU else 2

@@ -1,0 +1,76 @@
+"""Parity at the benchmark's full sizes (seed 0), in the launch configuration bench.py times: the whole oracle is run
+on the host for each configuration (tens of seconds on the GPU machine) and every output tensor is compared."""
+import numpy as np
+import pytest
+
+from paper_2506_19645_amd import inputs as I
+from tests.test_gpu_attn import check_attn, oracle_attn_block, run_attn_block
+from tests.test_gpu_block import check_mlp_block, oracle_mlp_block, run_mlp_block
+from tests.test_gpu_decode import run_decode
+from tests.util import assert_close, bits_to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config2_gpt_mlp_full_size():
+    """h=2048 ffn=8192 GELU LayerNorm T=4 p=0.5, 8192 tokens, forward + backward."""
+    cfg = I.C2
+    d = I.make_inputs(cfg, seed=0)
+    got = run_mlp_block(cfg, d)
+    w, fwd, g = oracle_mlp_block(cfg, d)
+    check_mlp_block(cfg, d, got, w, fwd, g)
+
+
+@pytest.mark.parametrize("p", [1.0, 0.25, 0.0])
+def test_config2_p_sweep_forward_sampled_tokens(p):
+    """The other points of the p sweep: MLP rows are independent per token, so the oracle runs on a token sample."""
+    cfg = I.C2.with_(p=p)
+    d = I.make_inputs(cfg, seed=0, with_grads=False)
+    got = run_mlp_block(cfg, d, backward=False)
+    rows = np.sort(np.random.default_rng(5).choice(cfg.tokens, size=96, replace=False))
+    sub = {k: (v[:, rows] if k in ("X", "R") else v) for k, v in d.items()}
+    small = cfg.with_(batch=1, seq=len(rows))
+    w, fwd, _ = oracle_mlp_block(small, sub, backward=False)
+    assert_close(got["P"][:, rows], fwd["P"], "P")
+    assert_close(got["Y"][:, rows], fwd["Y"], "Y")
+    assert_close(got["Rp"][:, rows], fwd["Rp"], "Rp")
+    assert_close(got["Xp"][:, rows], fwd["Xp"], "Xp")
+    hs = cfg.hs
+    if hs > 0:
+        for m in range(1, cfg.T):
+            assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
+
+
+def test_config3_llama_mlp_full_size():
+    """h=4096 SwiGLU ffn=11008 RMSNorm T=8 (1376 columns per rank) p=0.5, 4096 tokens, forward + backward."""
+    cfg = I.C3
+    d = I.make_inputs(cfg, seed=0)
+    got = run_mlp_block(cfg, d)
+    w, fwd, g = oracle_mlp_block(cfg, d)
+    check_mlp_block(cfg, d, got, w, fwd, g)
+
+
+def test_config4_llama_attention_full_size():
+    """h=4096, 32 heads of 128, RoPE, causal, seq 4096, T=8, p=0.5, forward."""
+    cfg = I.C4
+    d = I.make_inputs(cfg, seed=0, with_grads=False)
+    got = run_attn_block(cfg, d)
+    w, fwd = oracle_attn_block(cfg, d)
+    check_attn(cfg, d, got, fwd)
+
+
+def test_config5_llama_decode_full_size():
+    """batch 64, one new token, KV cache of 2048 positions per sequence, T=8, p=0.5."""
+    from oracle import caat_oracle as O
+    cfg = I.C5
+    d = I.make_inputs(cfg, seed=0)
+    got = run_decode(cfg, d)
+    w = {k: O.widen_bf16(v, np.float32 if k in ("Kc", "Vc") else np.float64) for k, v in d.items()}   # caches: exact in fp32
+    ref = O.decode_layer_fwd(w["R"], w, w["Kc"], w["Vc"], kv_len=cfg.kv_len, heads_per_rank=cfg.n_heads // cfg.T,
+                             head_dim=cfg.head_dim, hs=cfg.hs)
+    for name in ("X1", "H", "R1", "X2", "R2"):
+        assert_close(got[name], ref[name], name)
+    L = cfg.kv_len
+    assert_close(bits_to_f64(got["Kc_bits"][:, :, :, L]), ref["k_new"], "k_new")
+    assert_close(bits_to_f64(got["Vc_bits"][:, :, :, L]), ref["v_new"], "v_new")
+    assert np.array_equal(got["Kc_bits"][:, :, :, :L], d["Kc"][:, :, :, :L])
