@@ -3,20 +3,17 @@
 
 namespace caat {
 
-// Measured choices (C2/C3 shard shapes, warm clocks): operands that are K-contiguous in memory go global -> LDS
-// directly and run best with 8 waves (2 x 4) per 256 x 256 tile; the weight-gradient layout (both operands
-// transposed through registers) needs the registers of the 4-wave (2 x 2) arrangement.
-typedef TileCfg<256, 256, 2, 4, 2, true> CfgDma8;
-typedef TileCfg<256, 256, 2, 2, 2, false> CfgReg4;
-// Decode (at most 64 token rows per rank): the GEMM is a weight stream, so small tiles that put one workgroup on
-// every 64 weight rows (several per CU) replace the big tile, which would leave most CUs idle.
-typedef TileCfg<64, 64, 2, 2, 2, true> CfgSkinny;
-typedef TileCfg<64, 128, 2, 2, 2, true> CfgSkinnySwi;
+// Tile choices: 256 x 256 tiles with 8 waves (2 x 4) and 4 LDS stages of 32 k for the block-sized GEMMs of every
+// layout; for decode (at most 64 token rows per rank) the GEMM is a weight stream, so small tiles that put a
+// workgroup on every 64 weight rows (several per CU) with a deep 8-stage prefetch replace the big tile.
+typedef TileCfg<256, 256, 2, 4, 4> CfgBig;
+typedef TileCfg<64, 64, 2, 2, 8> CfgSkinny;
+typedef TileCfg<64, 128, 2, 2, 8> CfgSkinnySwi;
 
 hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_t s) {
   // buffer-load offsets are 32-bit and relative to the tile origin: the farthest row a tile touches times the
   // row stride must stay below 2 GiB
-  const long long far_rows = (epilogue == EPI_SWIGLU_FWD ? (long long)p.half : 0) + 256 + 64;
+  const long long far_rows = (epilogue == EPI_SWIGLU_FWD ? (long long)p.half : 0) + 256 + 64;  // rows or k-rows
   if (far_rows * p.lda * 2 >= 0x7FFFFFFFLL || far_rows * p.ldb * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
   if (layout == 0 && p.M <= 64) {
     switch (epilogue) {
@@ -30,21 +27,21 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
   switch (layout) {
     case 0:  // NT
       switch (epilogue) {
-        case EPI_PLAIN: return launch_one<CfgDma8, false, false, EPI_PLAIN>(p, s);
-        case EPI_GELU_FWD: return launch_one<CfgDma8, false, false, EPI_GELU_FWD>(p, s);
-        case EPI_SWIGLU_FWD: return launch_one<CfgDma8, false, false, EPI_SWIGLU_FWD>(p, s);
-        case EPI_ROWPAR: return launch_one<CfgDma8, false, false, EPI_ROWPAR>(p, s);
+        case EPI_PLAIN: return launch_one<CfgBig, false, false, EPI_PLAIN>(p, s);
+        case EPI_GELU_FWD: return launch_one<CfgBig, false, false, EPI_GELU_FWD>(p, s);
+        case EPI_SWIGLU_FWD: return launch_one<CfgBig, false, false, EPI_SWIGLU_FWD>(p, s);
+        case EPI_ROWPAR: return launch_one<CfgBig, false, false, EPI_ROWPAR>(p, s);
         default: return hipErrorInvalidValue;
       }
     case 1:  // NN
       switch (epilogue) {
-        case EPI_PLAIN: return launch_one<CfgDma8, false, true, EPI_PLAIN>(p, s);
-        case EPI_GELU_BWD: return launch_one<CfgDma8, false, true, EPI_GELU_BWD>(p, s);
-        case EPI_SWIGLU_BWD: return launch_one<CfgDma8, false, true, EPI_SWIGLU_BWD>(p, s);
+        case EPI_PLAIN: return launch_one<CfgBig, false, true, EPI_PLAIN>(p, s);
+        case EPI_GELU_BWD: return launch_one<CfgBig, false, true, EPI_GELU_BWD>(p, s);
+        case EPI_SWIGLU_BWD: return launch_one<CfgBig, false, true, EPI_SWIGLU_BWD>(p, s);
         default: return hipErrorInvalidValue;
       }
     case 2:  // TN
-      if (epilogue == EPI_PLAIN) return launch_one<CfgReg4, true, true, EPI_PLAIN>(p, s);
+      if (epilogue == EPI_PLAIN) return launch_one<CfgBig, true, true, EPI_PLAIN>(p, s);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }

@@ -4,16 +4,17 @@
 // of Eq. A3 (column-parallel X_m A_m with the activation fused, row-parallel Y_m B_m with the private-column
 // half of the partial channel-reduce + residual fused) and their data / weight gradients.
 //
-// Tiling: a workgroup owns a BM x BN tile of C and walks K in steps of BK = 64.  Both operand tiles live in
-// LDS as [rows][64] bf16, K-contiguous, 16-byte chunks XOR-swizzled so that MFMA fragment reads (32
-// consecutive rows x one chunk) and tile writes are bank-conflict free.  Operands whose contiguous memory
-// dimension is NOT K (layouts NN / TN) are transposed in registers (8x8 blocks of 16-bit values) on their way
-// from global memory to LDS, so the MFMA inner loop is the same for the three layouts.
-//
-// Global memory is read with buffer loads: rows / k positions outside the matrix get an out-of-range offset
-// and come back as zeros, so the main loop has no branches.  Tile kt+1 is fetched into registers while the
-// MFMAs of tile kt run; LDS is double buffered (one barrier per K step); MFMA fragments are double buffered
-// in registers across the four 16-wide k sub-steps.
+// Tiling: a workgroup owns a BM x BN tile of C and walks K in stages of BKS = 32.  NSTAGE stages of both
+// operand tiles live in LDS and every operand goes global -> LDS directly (buffer_load ... lds, no register
+// staging), NSTAGE-1 stages ahead of the MFMAs, so a global / L2 round trip of several stage times is hidden.
+//   * operand contiguous along K in memory (NT's a and b, NN's a): stage = [rows][32 k], 64-byte rows, fragment
+//     reads are ds_read_b128 (32 consecutive rows x one 16-byte chunk);
+//   * operand contiguous along its row index in memory (NN's b, TN's a and b): stage = [32 k][rows], the memory
+//     layout as it is, and the MFMA fragments (8 consecutive k of one row per lane) are gathered by the LDS
+//     transpose read ds_read_b64_tr_b16 (16 lanes fetch 4 k-rows x 16 rows and lane j receives row j's 4 k).
+// 16-byte chunks are XOR-swizzled (applied on the global side of the copy) so that both kinds of reads are
+// bank-conflict free.  Rows / k outside the matrix get an out-of-range buffer offset and arrive as zeros, so
+// the main loop has no branch.  MFMA fragments are double buffered over the two 16-wide k sub-steps of a stage.
 //
 // The accumulator is computed transposed (operands swapped in the MFMA) so that each lane ends up with 4
 // consecutive columns of one row of C; the epilogue stages the bf16 tile through LDS and stores whole rows.
@@ -24,202 +25,154 @@ namespace caat {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef short short8_t __attribute__((ext_vector_type(8)));
 
-static constexpr int BK = 64;                 // K step: 8 chunks of 8 bf16 per tile row
+static constexpr int BKS = 32;                // k extent of one LDS stage
 static constexpr unsigned OOB = 0x80000000u;  // buffer offset that is always out of range -> load returns 0
 
-template <int BM_, int BN_, int WM_, int WN_, int SCHED_ = 2, bool LDSD_ = false>
+template <int BM_, int BN_, int WM_, int WN_, int NSTAGE_ = 4, int SCHED_ = 2>
 struct TileCfg {
-  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-  static constexpr int SCHED = SCHED_;  // 0: compiler's order, 1: phase fences, 2: fences + MFMA/LDS/VMEM interleave
-  static constexpr bool LDSD = LDSD_;   // K-contiguous operands go global -> LDS directly (no register staging)
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NSTAGE = NSTAGE_;
+  static constexpr int SCHED = SCHED_;  // 0: compiler's order, 1: fences between sub-steps, 2: + LDS reads spread 1:1 between
+                                        // the MFMAs, 3: + all LDS reads of a sub-step issued ahead of its MFMAs
   static constexpr int THREADS = 64 * WM * WN;
+  static constexpr int NWAVES = WM * WN;
   static constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;  // 32x32 MFMA tiles per wave
-  static constexpr int STAGE_CHUNKS = (BM + BN) * 8;  // uint4 per LDS stage
+  static constexpr int STAGE_CHUNKS = (BM + BN) * (BKS / 8);  // uint4 per LDS stage
+  static constexpr int SMEM_CHUNKS = NSTAGE * STAGE_CHUNKS;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
-  static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "tile chunks must divide over the threads");
+  static_assert(SMEM_CHUNKS * 16 >= BM * BN * 2, "the epilogue parks the bf16 tile in the operand buffers");
+  static_assert(SMEM_CHUNKS * 16 <= 160 * 1024, "LDS capacity");
 };
 
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
-__device__ __forceinline__ int lds_index(int row, int chunk) { return row * 8 + (chunk ^ swz(row)); }
-
-// raw buffer descriptor over [p, p + 2 GiB): offsets >= 0x80000000 are out of range and read as zero
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)0x80000000, 0x00020000);
+// Raw buffer descriptor over [p, p + 2 GiB): offsets >= 0x80000000 are out of range and read as zero.
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4_t make_rsrc(const void* p) {
+  const unsigned long long a = (unsigned long long)p;
+  i32x4_t r;
+  r.x = (int)(unsigned)a;
+  r.y = (int)((unsigned)(a >> 32) & 0xFFFFu);
+  r.z = (int)0x80000000;
+  r.w = 0x00020000;
+  return r;
 }
-__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned voff) {
-  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
-  return make_uint4(v.x, v.y, v.z, v.w);
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+  return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
+}
+// One global -> LDS copy instruction: lane L's 16 bytes from rs[voff] land at lds_wave_uniform + 16*L.
+// Written as inline assembly on purpose: the compiler then does not know that LDS is written by a vector-memory
+// operation and does not force "wait for every outstanding copy" in front of each later LDS read; the kernel
+// orders copies and reads itself (wait_vmcnt + barrier), which is what lets NSTAGE-1 stages stay in flight.
+__device__ __forceinline__ void dma16(i32x4_t rs, unsigned voff, const uint4* lds_wave_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+               :
+               : "v"(voff), "s"(rs), "s"(lds_addr(lds_wave_uniform))
+               : "memory");
 }
 
-// ---- K-contiguous source: tile rows x 64 k; a thread moves 16-byte chunks straight through registers.
-// `origin` points at the tile's first row (uniform); rowmap(rr) gives the row of tile row rr RELATIVE to the
-// origin, or -1 if that row does not exist.
-template <int ROWS, int THREADS>
-struct DirectLoader {
-  static constexpr int NCH = ROWS * 8 / THREADS;
+// ---- operand contiguous along K: stage [ROWS][32 k], row = 64 B = 4 chunks; chunk c of row r sits at c ^ ((r>>2)&3).
+// One wave instruction fills 16 rows (64 lanes x 16 B, lane order).  `origin` points at the tile's first row;
+// rowmap(rr) gives the row of tile row rr RELATIVE to the origin, or -1 if that row does not exist.
+template <int ROWS, int NWAVES>
+struct KContigOperand {
+  static constexpr int NI = ROWS / 16 / NWAVES;  // copy instructions per wave per stage
+  static constexpr int N_VMEM = NI;
+  static constexpr int READS_PER_FRAG = 1;
+  static_assert(ROWS % (16 * NWAVES) == 0, "rows must divide over the waves");
   const bf16_t* origin;
-  unsigned voff[NCH];  // byte offset of (row, kc) from origin, OOB for missing rows
-  uint4 reg[NCH];
-  int kc;
+  unsigned voff[NI];
+  int wave, kc;
 
   template <class RowMap>
   __device__ __forceinline__ void init(const bf16_t* origin_, long long ld, RowMap rowmap) {
     origin = origin_;
-    const int tid = threadIdx.x;
-    kc = tid & 7;
+    const int lane = threadIdx.x & 63;
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    kc = (lane & 3) ^ ((lane >> 4) & 3);  // logical chunk this lane fetches: physical slot lane&3, row (..)*16 + lane/4
 #pragma unroll
-    for (int it = 0; it < NCH; ++it) {
-      const int rr = it * (THREADS / 8) + (tid >> 3);
-      const long long r = rowmap(rr);
+    for (int it = 0; it < NI; ++it) {
+      const int row = (it * NWAVES + wave) * 16 + (lane >> 2);
+      const long long r = rowmap(row);
       voff[it] = (r >= 0) ? (unsigned)((r * ld + kc * 8) * 2) : OOB;
     }
   }
-  __device__ __forceinline__ void load(int k0, int K) {
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(origin + k0);
+  __device__ __forceinline__ void issue(int k0, int K, uint4* tile) const {
+    const i32x4_t rs = make_rsrc(origin + k0);
     const bool kin = (k0 + kc * 8) < K;
 #pragma unroll
-    for (int it = 0; it < NCH; ++it) reg[it] = buf_load16(rs, kin ? voff[it] : OOB);
+    for (int it = 0; it < NI; ++it) dma16(rs, kin ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
   }
-  __device__ __forceinline__ void store(uint4* tile) const {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int it = 0; it < NCH; ++it) {
-      const int rr = it * (THREADS / 8) + (tid >> 3);
-      tile[lds_index(rr, kc)] = reg[it];
-    }
+  // fragment for MFMA rows row0 .. row0+31, k sub-step ks (16 wide): lane (row0 + lane%32, k = 16 ks + 8 (lane/32) ..+7)
+  static __device__ __forceinline__ bf16x8_t frag(const uint4* tile, int row0, int ks, int lane) {
+    const int row = row0 + (lane & 31);
+    const int c = ks * 2 + (lane >> 5);
+    return __builtin_bit_cast(bf16x8_t, tile[row * 4 + (c ^ ((row >> 2) & 3))]);
   }
 };
 
-// ---- row-contiguous source ([K][rows]): thread loads an 8(k) x 8(rows) block, transposes it in registers.
-// `origin` points at (k = 0, first row of the tile); rowmap as above (8 consecutive rows share validity).
-template <int ROWS, int THREADS>
-struct TransLoader {
-  static constexpr int NBLK = ROWS;  // (ROWS/8) row blocks x 8 k groups
-  static constexpr int NB = (NBLK + THREADS - 1) / THREADS;
+// ---- operand contiguous along its row index ([K][rows] in memory): stage [32 k][ROWS] as in memory, k-row =
+// ROWS*2 bytes; chunk c of k-row k sits at c ^ ((k&3)<<2).  One wave instruction fills 512/ROWS k-rows.
+// `origin` points at (k = 0, first row of the tile); rows_valid = rows of the tile that exist (multiple of 8).
+template <int ROWS, int NWAVES>
+struct RowContigOperand {
+  static constexpr int CPR = ROWS / 8;       // chunks per k-row
+  static constexpr int KPI = 64 / CPR;       // k-rows per copy instruction
+  static constexpr int NI = BKS / KPI / NWAVES;
+  static constexpr int N_VMEM = NI;
+  static constexpr int READS_PER_FRAG = 2;
+  static_assert(ROWS >= 128 && ROWS <= 512 && BKS % (KPI * NWAVES) == 0, "unsupported tile shape for a transposed operand");
   const bf16_t* origin;
   long long ld;
-  unsigned voff[NB];  // byte offset of (k = kg*8, row block) from origin + k0*ld, OOB if missing / idle
-  unsigned ld2;
-  uint4 reg[NB][8];
+  unsigned voff[NI];
+  int wave, klocal;  // klocal: k-row inside an instruction's group
 
   template <class RowMap>
   __device__ __forceinline__ void init(const bf16_t* origin_, long long ld_, RowMap rowmap) {
     origin = origin_;
     ld = ld_;
-    ld2 = (unsigned)(ld_ * 2);
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int it = 0; it < NB; ++it) {
-      const int blk = it * THREADS + tid;
-      const int rb = blk % (ROWS / 8);
-      const int kg = blk / (ROWS / 8);
-      const long long r = (blk < NBLK) ? rowmap(rb * 8) : -1;
-      voff[it] = (r >= 0) ? (unsigned)(((long long)kg * 8 * ld_ + r) * 2) : OOB;
-    }
-  }
-  __device__ __forceinline__ void load(int k0, int K) {
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(origin + (long long)k0 * ld);
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int it = 0; it < NB; ++it) {
-      const int kg = (it * THREADS + tid) / (ROWS / 8);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const bool in = (voff[it] != OOB) && (k0 + kg * 8 + j < K);
-        reg[it][j] = buf_load16(rs, in ? voff[it] + (unsigned)j * ld2 : OOB);
-      }
-    }
-  }
-  __device__ __forceinline__ void store(uint4* tile) const {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int it = 0; it < NB; ++it) {
-      const int blk = it * THREADS + tid;
-      if (NBLK % THREADS != 0 && blk >= NBLK) continue;
-      const int rb = blk % (ROWS / 8);
-      const int kg = blk / (ROWS / 8);
-      const unsigned* in = reinterpret_cast<const unsigned*>(&reg[it][0]);  // in[j*4 + q]: k=j, rows 2q (lo), 2q+1 (hi)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {  // output row rb*8+i gets k = 0..7
-        unsigned o[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const unsigned a = in[(2 * d) * 4 + (i >> 1)];
-          const unsigned b = in[(2 * d + 1) * 4 + (i >> 1)];
-          o[d] = (i & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
-        }
-        tile[lds_index(rb * 8 + i, kg)] = make_uint4(o[0], o[1], o[2], o[3]);
-      }
-    }
-  }
-};
-
-// ---- K-contiguous source, global -> LDS without passing through registers (buffer_load ... lds): one wave
-// instruction fills 8 consecutive tile rows (64 lanes x 16 B = 1 KiB of LDS, lane order); the XOR swizzle is
-// applied on the global side (lane L fetches the chunk that belongs at LDS position L).
-template <int ROWS, int THREADS>
-struct DirectLdsLoader {
-  static constexpr int NWAVES = THREADS / 64;
-  static constexpr int NI = ROWS / 8 / NWAVES;
-  static constexpr int N_VMEM = NI, N_DSWRITE = 0;
-  const bf16_t* origin;
-  unsigned voff[NI];
-  int wave, lane;
-
-  __device__ __forceinline__ int kc_of(int it) const { return (lane & 7) ^ (((lane >> 3) ^ (it * NWAVES + wave)) & 7); }
-
-  template <class RowMap>
-  __device__ __forceinline__ void init(const bf16_t* origin_, long long ld, RowMap rowmap) {
-    origin = origin_;
-    lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63;
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    klocal = lane / CPR;
+    const int phys = lane % CPR;
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
-      const int row = (it * NWAVES + wave) * 8 + (lane >> 3);
-      const long long r = rowmap(row);
-      voff[it] = (r >= 0) ? (unsigned)((r * ld + kc_of(it) * 8) * 2) : OOB;
+      const int k = (it * NWAVES + wave) * KPI + klocal;
+      const int c = phys ^ ((k & 3) << 2);
+      const long long r = rowmap(c * 8);  // 8 consecutive rows share validity (dims % 8 == 0)
+      voff[it] = (r >= 0) ? (unsigned)(((long long)k * ld_ + r) * 2) : OOB;
     }
   }
-  __device__ __forceinline__ void load(int k0, int K, uint4* tile) {
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(origin + k0);
+  __device__ __forceinline__ void issue(int k0, int K, uint4* tile) const {
+    const i32x4_t rs = make_rsrc(origin + (long long)k0 * ld);
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
-      const bool kin = (k0 + kc_of(it) * 8) < K;
-      uint4* dst = tile + (it * NWAVES + wave) * 64;  // wave-uniform
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)dst, 16,
-                                               (int)(kin ? voff[it] : OOB), 0, 0, 0);
+      const int k = (it * NWAVES + wave) * KPI + klocal;
+      dma16(rs, (k0 + k < K) ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
     }
   }
-  __device__ __forceinline__ void store(uint4*) const {}
+  // same fragment as KContigOperand::frag, gathered by two transpose reads of 4 k each
+  static __device__ __forceinline__ bf16x8_t frag(const uint4* tile, int row0, int ks, int lane) {
+    const int i16 = lane & 15;
+    const int m = row0 + ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;  // the 4 rows this lane's 8 bytes cover
+    const int kq = i16 >> 2;                                      // which of the 4 k-rows this lane fetches
+    const int kb = ks * 16 + (lane >> 5) * 8;
+    const char* base = reinterpret_cast<const char*>(tile);
+    const int coff = (((m >> 3) ^ (kq << 2)) << 4) + ((m & 7) << 1);  // (k & 3) == kq for both reads
+    const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) short4_t*)(base + (kb + kq) * (ROWS * 2) + coff));
+    const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) short4_t*)(base + (kb + 4 + kq) * (ROWS * 2) + coff));
+    const short8_t v = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+    return __builtin_bit_cast(bf16x8_t, v);
+  }
 };
 
-template <int ROWS, int THREADS>
-struct DirectRegLoader : DirectLoader<ROWS, THREADS> {
-  static constexpr int N_VMEM = DirectLoader<ROWS, THREADS>::NCH, N_DSWRITE = DirectLoader<ROWS, THREADS>::NCH;
-  __device__ __forceinline__ void load(int k0, int K, uint4*) { DirectLoader<ROWS, THREADS>::load(k0, K); }
-};
-template <int ROWS, int THREADS>
-struct TransRegLoader : TransLoader<ROWS, THREADS> {
-  static constexpr int N_VMEM = 8 * TransLoader<ROWS, THREADS>::NB, N_DSWRITE = 8 * TransLoader<ROWS, THREADS>::NB;
-  __device__ __forceinline__ void load(int k0, int K, uint4*) { TransLoader<ROWS, THREADS>::load(k0, K); }
-};
-
-template <bool TRANS, bool LDSD, int ROWS, int THREADS>
-struct LoaderSel { typedef DirectRegLoader<ROWS, THREADS> type; };
-template <int ROWS, int THREADS>
-struct LoaderSel<false, true, ROWS, THREADS> { typedef DirectLdsLoader<ROWS, THREADS> type; };
-template <bool LDSD, int ROWS, int THREADS>
-struct LoaderSel<true, LDSD, ROWS, THREADS> { typedef TransRegLoader<ROWS, THREADS> type; };
-
-__device__ __forceinline__ void store4(bf16_t* dst, float v0, float v1, float v2, float v3) {
-  uint2 w;
-  w.x = pack2bf(v0, v1);
-  w.y = pack2bf(v2, v3);
-  *reinterpret_cast<uint2*>(dst) = w;
-}
+template <bool ROWCONTIG, int ROWS, int NWAVES>
+struct OperandSel { typedef KContigOperand<ROWS, NWAVES> type; };
+template <int ROWS, int NWAVES>
+struct OperandSel<true, ROWS, NWAVES> { typedef RowContigOperand<ROWS, NWAVES> type; };
 
 template <int TM, int TN>
 struct Frags {
@@ -227,32 +180,35 @@ struct Frags {
 };
 
 // Instruction-order request for one k sub-step (between two scheduling fences): after every MFMA place this
-// MFMA's share of the NR LDS reads (front-loaded: one per MFMA), NV global loads and NW LDS writes.
-template <int I, int NM, int NR, int NV, int NW>
+// MFMA's share of the NR LDS reads and NV global->LDS copies.
+template <int I, int NM, int NR, int NV>
 struct Pipe {
   static __device__ __forceinline__ void run() {
     if constexpr (I < NM) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      constexpr int r = (NR <= NM) ? (I < NR ? 1 : 0) : ((NR * (I + 1)) / NM - (NR * I) / NM);
+      constexpr int r = (NR * (I + 1)) / NM - (NR * I) / NM;
       constexpr int v = (NV * (I + 1)) / NM - (NV * I) / NM;
-      constexpr int w = (NW * (I + 1)) / NM - (NW * I) / NM;
       if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
       if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
-      if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
-      Pipe<I + 1, NM, NR, NV, NW>::run();
+      Pipe<I + 1, NM, NR, NV>::run();
     }
   }
 };
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 template <class CFG, bool AT, bool BT, int EPI>
 __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) {
-  constexpr int BM = CFG::BM, BN = CFG::BN, THREADS = CFG::THREADS;
+  constexpr int BM = CFG::BM, BN = CFG::BN, THREADS = CFG::THREADS, NSTAGE = CFG::NSTAGE;
   constexpr int TM = CFG::TM, TN = CFG::TN, WTM = CFG::WTM, WTN = CFG::WTN;
   constexpr bool SWI = (EPI == EPI_SWIGLU_FWD);
   constexpr int BN_OUT = SWI ? BN / 2 : BN;  // output columns covered by one tile
   static_assert(!SWI || TN % 2 == 0, "SwiGLU pairing needs an even number of N tiles per wave");
 
-  __shared__ uint4 smem[2 * CFG::STAGE_CHUNKS];
+  __shared__ uint4 smem[CFG::SMEM_CHUNKS];
 
   // ---- which tile: spread consecutive tile ids over the 8 XCDs' L2s, then a grouped (8 tile rows) order
   const int tiles_m = (p.M + BM - 1) / BM;
@@ -290,10 +246,10 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
   const bf16_t* ag = p.a + (long long)g * p.stride_a;
   const bf16_t* bg = p.b + (long long)g * p.stride_b;
 
-  typedef typename LoaderSel<AT, CFG::LDSD, BM, THREADS>::type LoaderA;
-  typedef typename LoaderSel<BT, CFG::LDSD, BN, THREADS>::type LoaderB;
-  LoaderA la;
-  LoaderB lb;
+  typedef typename OperandSel<AT, BM, CFG::NWAVES>::type OpA;
+  typedef typename OperandSel<BT, BN, CFG::NWAVES>::type OpB;
+  OpA la;
+  OpB lb;
   {
     const int mrem = p.M - m0;
     la.init(AT ? ag + m0 : ag + (long long)m0 * p.lda, p.lda,
@@ -323,17 +279,19 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int K = p.K;
-  const int nk = (K + BK - 1) / BK;
-  const int frow = lane & 31;  // fragment row within a 32-row MFMA tile
-  const int fk = lane >> 5;    // which 8-wide half of a 16-wide k step
+  const int nk = (K + BKS - 1) / BKS;
+  const int frow = lane & 31;  // accumulator row within a 32-row MFMA tile
+  const int fk = lane >> 5;    // which half of the tile's columns / k this lane holds
 
-  auto load_frags = [&](const uint4* As, const uint4* Bs, int ks, Frags<TM, TN>& f) {
+  constexpr int A_CHUNKS = BM * (BKS / 8);
+  auto stage_a = [&](int s) -> uint4* { return smem + (s % NSTAGE) * CFG::STAGE_CHUNKS; };
+  auto load_frags = [&](int s, int ks, Frags<TM, TN>& f) {
+    const uint4* As = stage_a(s);
+    const uint4* Bs = As + A_CHUNKS;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-      f.a[i] = __builtin_bit_cast(bf16x8_t, As[lds_index(wm * WTM + i * 32 + frow, ks * 2 + fk)]);
+    for (int i = 0; i < TM; ++i) f.a[i] = OpA::frag(As, wm * WTM + i * 32, ks, lane);
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-      f.b[j] = __builtin_bit_cast(bf16x8_t, Bs[lds_index(wn * WTN + j * 32 + frow, ks * 2 + fk)]);
+    for (int j = 0; j < TN; ++j) f.b[j] = OpB::frag(Bs, wn * WTN + j * 32, ks, lane);
   };
   auto mfma_all = [&](const Frags<TM, TN>& f) {
 #pragma unroll
@@ -343,63 +301,53 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
         // operands swapped: the accumulator holds C^T, i.e. lane = row of C, registers = columns of C
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
   };
-  // LDS-direct loads are counted by vmcnt: they must have landed before the barrier that publishes the tile
-  auto wait_lds_dma = [&]() {
-    if constexpr (CFG::LDSD && (!AT || !BT)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  auto issue_stage = [&](int s) {  // past the end of K every offset is out of range: zeros land in a slot nobody reads
+    uint4* As = stage_a(s);
+    la.issue(s * BKS, K, As);
+    lb.issue(s * BKS, K, As + A_CHUNKS);
   };
 
-  la.load(0, K, smem);
-  lb.load(0, K, smem + BM * 8);
-  la.store(smem);
-  lb.store(smem + BM * 8);
-  wait_lds_dma();
-  __syncthreads();
-
-  Frags<TM, TN> f0, f1;
-  load_frags(smem, smem + BM * 8, 0, f0);
-
-  // Instruction-order control: fence() = nothing moves across; Pipe<> spreads the next sub-step's fragment
-  // reads, the next tile's global loads and its LDS writes between the MFMAs of the current sub-step.
   constexpr int SCHED = CFG::SCHED;
-  constexpr int NM = TM * TN, NR = TM + TN;
-  constexpr int NV = LoaderA::N_VMEM + LoaderB::N_VMEM, NW = LoaderA::N_DSWRITE + LoaderB::N_DSWRITE;
+  constexpr int NM = TM * TN;
+  constexpr int NR = TM * OpA::READS_PER_FRAG + TN * OpB::READS_PER_FRAG;
+  constexpr int NV = OpA::N_VMEM + OpB::N_VMEM;  // copies per wave per stage
   auto fence = [&]() {
     if constexpr (SCHED >= 1) __builtin_amdgcn_sched_barrier(0);
   };
 
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s);
+  wait_vmcnt<(NSTAGE - 2) * NV>();  // copies complete in order: stage 0 has landed
+  __syncthreads();
+  Frags<TM, TN> f0, f1;
+  load_frags(0, 0, f0);
+  fence();
+
   for (int kt = 0; kt < nk; ++kt) {
-    const uint4* As = smem + (kt & 1) * CFG::STAGE_CHUNKS;
-    const uint4* Bs = As + BM * 8;
-    uint4* An = smem + ((kt + 1) & 1) * CFG::STAGE_CHUNKS;
-    uint4* Bn = An + BM * 8;
-    // k sub-step 0, and the fetch of tile kt+1 (past the end of K every offset is out of range: zeros come
-    // back and nobody uses them, so the loop needs no branch)
-    la.load((kt + 1) * BK, K, An);
-    lb.load((kt + 1) * BK, K, Bn);
-    if constexpr (SCHED == 1) fence();
-    load_frags(As, Bs, 1, f1);
+    // sub-step 0; the slot of stage kt-1 is free (everyone passed the barrier below in the previous iteration)
+    issue_stage(kt + NSTAGE - 1);
+    load_frags(kt, 1, f1);
     mfma_all(f0);
-    if constexpr (SCHED >= 2) Pipe<0, NM, NR, NV, 0>::run();
+    if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
+    if constexpr (SCHED == 3) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+    }
     fence();
-    load_frags(As, Bs, 2, f0);
-    mfma_all(f1);
-    if constexpr (SCHED >= 2) Pipe<0, NM, NR, 0, 0>::run();
-    fence();
-    load_frags(As, Bs, 3, f1);
-    mfma_all(f0);
-    if constexpr (SCHED == 1) fence();
-    la.store(An);
-    lb.store(Bn);
-    if constexpr (SCHED >= 2) Pipe<0, NM, NR, 0, NW>::run();
-    fence();
-    wait_lds_dma();
+    // sub-step 1; stage kt+1 must have landed (the two newest stages may still be in flight) and be visible
+    wait_vmcnt<(NSTAGE - 2) * NV>();
     __syncthreads();
     fence();
-    load_frags(An, Bn, 0, f0);
+    load_frags(kt + 1, 0, f0);
     mfma_all(f1);
-    if constexpr (SCHED >= 2) Pipe<0, NM, NR, 0, 0>::run();
+    if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
+    if constexpr (SCHED == 3) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+    }
     fence();
   }
+  wait_vmcnt<0>();  // the zero-filled stages past K still target LDS: let them land before the buffers are reused
 
   // ---- epilogue.  Each lane holds C[row = lane%32][col = 8*q + 4*(lane/32) + 0..3] of every 32x32 tile in
   // acc[..][4q..4q+3].  Writing that to global memory directly would scatter 8-byte pieces over 32 rows per
