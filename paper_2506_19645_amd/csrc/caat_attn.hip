@@ -90,9 +90,10 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, hf = lane >> 5;
-  // heavy (late) query blocks first
-  const int qb = n_qblk - 1 - (int)(blockIdx.x % n_qblk);
-  const int bh = blockIdx.x / n_qblk;            // (rank*batch + b) * heads + head
+  // longest-first over the whole launch: the last (heaviest, causal) query blocks of every head come first
+  const int n_bh = gridDim.x / n_qblk;
+  const int qb = n_qblk - 1 - (int)(blockIdx.x / n_bh);
+  const int bh = blockIdx.x % n_bh;              // (rank*batch + b) * heads + head
   const int head = bh % heads;
   const long long seq_row0 = (long long)(bh / heads) * seq;   // first row of this sequence in qkv
   const long long ld = 3LL * hd;
@@ -127,8 +128,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
   // global -> LDS: a wave instruction fills 4 rows (64 lanes x 16 B); 64 rows = 16 instructions per tile, 4 per wave
   auto issue_tile = [&](int blk, int stage) {
     const int kv0 = blk * BKV;
-    const __amdgpu_buffer_rsrc_t rk = attn_rsrc(kbase + (long long)kv0 * ld);
-    const __amdgpu_buffer_rsrc_t rv = attn_rsrc(vbase + (long long)kv0 * ld);
+    const i32x4_t rk = make_rsrc(kbase + (long long)kv0 * ld);
+    const i32x4_t rv = make_rsrc(vbase + (long long)kv0 * ld);
     uint4* kt = smem + stage * (2 * BKV * KCH);
     uint4* vt = kt + BKV * KCH;
 #pragma unroll
@@ -138,15 +139,15 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
       const bool in = (kv0 + row) < seq;
       const unsigned ko = in ? (unsigned)((long long)row * ld * 2 + kswz(row, phys) * 16) : OOB_OFF;
       const unsigned vo = in ? (unsigned)((long long)row * ld * 2 + vswz(row, phys) * 16) : OOB_OFF;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (__attribute__((address_space(3))) void*)(kt + rg * 64), 16, (int)ko, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (__attribute__((address_space(3))) void*)(vt + rg * 64), 16, (int)vo, 0, 0, 0);
+      dma16(rk, ko, kt + rg * 64);
+      dma16(rv, vo, vt + rg * 64);
     }
   };
 
   issue_tile(0, 0);
   for (int blk = 0; blk < nblk; ++blk) {
     const int stage = blk & 1;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_vmcnt<0>();
     __syncthreads();                                   // tile blk landed; everyone is done with the other stage
     if (blk + 1 < nblk) issue_tile(blk + 1, stage ^ 1);
     const uint4* kt = smem + stage * (2 * BKV * KCH);
@@ -168,20 +169,23 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
     }
     // ---- causal mask + online softmax for query qrow (keys of register r: kv0 + 32j + 8(r/4) + 4hf + r%4)
     float mx = -INFINITY;
-    const bool diag = (kv0 + BKV - 1) > (q0 + wave * 32);   // some key of this block may exceed some query of this wave
+    // wave-uniform: does some key of this block exceed some query of this wave?  (only the last blocks of a tile)
+    if ((kv0 + BKV - 1) > (q0 + wave * 32)) {
 #pragma unroll
-    for (int j = 0; j < BKV / 32; ++j)
+      for (int j = 0; j < BKV / 32; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (diag) {
+        for (int r = 0; r < 16; ++r) {
           const int key = kv0 + j * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
           if (key > qrow) sacc[j][r] = -INFINITY;
         }
-        mx = fmaxf(mx, sacc[j][r]);
-      }
+    }
+#pragma unroll
+    for (int j = 0; j < BKV / 32; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[j][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));            // the other half of the row lives in lane ^ 32
     const float m_new = fmaxf(m_run, mx);               // finite: key 0 is visible to every query
-    const float alpha = exp2f((m_run - m_new) * scale_log2);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
     const float mb = m_new * scale_log2;
     float psum = 0.0f;
     bf16x8_t pf[BKV / 16];
@@ -192,18 +196,21 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
         float pv[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          pv[e] = exp2f(sacc[j][t * 8 + e] * scale_log2 - mb);
+          pv[e] = __builtin_amdgcn_exp2f(sacc[j][t * 8 + e] * scale_log2 - mb);   // arguments <= 0; tiny results flush to 0
           psum += pv[e];
         }
         const uint4 w = make_uint4(pack2bf(pv[0], pv[1]), pack2bf(pv[2], pv[3]), pack2bf(pv[4], pv[5]), pack2bf(pv[6], pv[7]));
         pf[j * 2 + t] = __builtin_bit_cast(bf16x8_t, w);
       }
     l_run = l_run * alpha + psum;
+    // the running maximum settles after the first blocks: rescale the accumulators only if some row's maximum moved
+    if (__any(m_new != m_run)) {
+#pragma unroll
+      for (int t = 0; t < HD / 32; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[t][r] *= alpha;
+    }
     m_run = m_new;
-#pragma unroll
-    for (int t = 0; t < HD / 32; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[t][r] *= alpha;
 
     // ---- O^T += V^T P^T : A operand = V columns (head-dim index frow of tile dt), B operand = P (query frow).
     // k-slice u (16 keys) of the block: lane half hf contributes keys 16u + 4hf + {0..3} and 16u + 8 + 4hf + {0..3}

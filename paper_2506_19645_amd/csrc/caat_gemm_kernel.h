@@ -47,31 +47,6 @@ struct TileCfg {
   static_assert(SMEM_CHUNKS * 16 <= 160 * 1024, "LDS capacity");
 };
 
-// Raw buffer descriptor over [p, p + 2 GiB): offsets >= 0x80000000 are out of range and read as zero.
-typedef int i32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ i32x4_t make_rsrc(const void* p) {
-  const unsigned long long a = (unsigned long long)p;
-  i32x4_t r;
-  r.x = (int)(unsigned)a;
-  r.y = (int)((unsigned)(a >> 32) & 0xFFFFu);
-  r.z = (int)0x80000000;
-  r.w = 0x00020000;
-  return r;
-}
-__device__ __forceinline__ unsigned lds_addr(const void* p) {
-  return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
-}
-// One global -> LDS copy instruction: lane L's 16 bytes from rs[voff] land at lds_wave_uniform + 16*L.
-// Written as inline assembly on purpose: the compiler then does not know that LDS is written by a vector-memory
-// operation and does not force "wait for every outstanding copy" in front of each later LDS read; the kernel
-// orders copies and reads itself (wait_vmcnt + barrier), which is what lets NSTAGE-1 stages stay in flight.
-__device__ __forceinline__ void dma16(i32x4_t rs, unsigned voff, const uint4* lds_wave_uniform) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
-               :
-               : "v"(voff), "s"(rs), "s"(lds_addr(lds_wave_uniform))
-               : "memory");
-}
-
 // ---- operand contiguous along K: stage [ROWS][32 k], row = 64 B = 4 chunks; chunk c of row r sits at c ^ ((r>>2)&3).
 // One wave instruction fills 16 rows (64 lanes x 16 B, lane order).  `origin` points at the tile's first row;
 // rowmap(rr) gives the row of tile row rr RELATIVE to the origin, or -1 if that row does not exist.
@@ -194,11 +169,6 @@ struct Pipe {
     }
   }
 };
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
 
 template <class CFG, bool AT, bool BT, int EPI>
 __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) {

@@ -10,15 +10,13 @@ typedef unsigned short bf16_t;  // raw bfloat16 bit pattern in memory
 
 __device__ __forceinline__ float bf2f(bf16_t u) { return __uint_as_float(((unsigned)u) << 16); }
 
-// fp32 -> bf16, round-to-nearest-even (finite inputs; NaN payloads are not preserved)
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  unsigned u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// fp32 -> bf16, round-to-nearest-even: gfx950's v_cvt_pk_bf16_f32 (two values per instruction)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned pack2bf(float lo, float hi) {
-  return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16);
+  const bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(unsigned, v);
 }
+__device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack2bf(f, 0.0f) & 0xFFFFu); }
 __device__ __forceinline__ float lo_bf(unsigned w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_bf(unsigned w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -45,6 +43,37 @@ __device__ __forceinline__ float gelu_grad_f(float x) {  // Phi(x) + x phi(x)
   return c + x * d;
 }
 __device__ __forceinline__ float sigmoid_f(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+
+// ---------------------------------------------------------------- global -> LDS copies
+// Raw buffer descriptor over [p, p + 2 GiB): offsets >= 0x80000000 are out of range and read as zero.
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4_t make_rsrc(const void* p) {
+  const unsigned long long a = (unsigned long long)p;
+  i32x4_t r;
+  r.x = (int)(unsigned)a;
+  r.y = (int)((unsigned)(a >> 32) & 0xFFFFu);
+  r.z = (int)0x80000000;
+  r.w = 0x00020000;
+  return r;
+}
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+  return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
+}
+// One global -> LDS copy instruction: lane L's 16 bytes from rs[voff] land at lds_wave_uniform + 16*L.
+// Written as inline assembly on purpose: the compiler then does not know that LDS is written by a vector-memory
+// operation and does not force "wait for every outstanding copy" in front of each later LDS read; the kernel
+// orders copies and reads itself (wait_vmcnt + barrier), which is what lets NSTAGE-1 stages stay in flight.
+__device__ __forceinline__ void dma16(i32x4_t rs, unsigned voff, const uint4* lds_wave_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+               :
+               : "v"(voff), "s"(rs), "s"(lds_addr(lds_wave_uniform))
+               : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // ---------------------------------------------------------------- GEMM
 enum GemmEpilogue {
