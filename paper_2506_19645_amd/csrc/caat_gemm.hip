@@ -7,8 +7,8 @@ namespace caat {
 // layout; for decode (at most 64 token rows per rank) the GEMM is a weight stream, so small tiles that put a
 // workgroup on every 64 weight rows (several per CU) with a deep 8-stage prefetch replace the big tile.
 typedef TileCfg<256, 256, 2, 4, 4> CfgBig;
-typedef TileCfg<64, 64, 2, 2, 8> CfgSkinny;
-typedef TileCfg<64, 128, 2, 2, 8> CfgSkinnySwi;
+typedef TileCfg<64, 64, 2, 2, 8, 2, false> CfgSkinny;
+typedef TileCfg<64, 128, 2, 2, 8, 2, false> CfgSkinnySwi;
 
 hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_t s) {
   // buffer-load offsets are 32-bit and relative to the tile origin: the farthest row a tile touches times the

@@ -17,7 +17,9 @@
 // the main loop has no branch.  MFMA fragments are double buffered over the two 16-wide k sub-steps of a stage.
 //
 // The accumulator is computed transposed (operands swapped in the MFMA) so that each lane ends up with 4
-// consecutive columns of one row of C; the epilogue stages the bf16 tile through LDS and stores whole rows.
+// consecutive columns of one row of C; in the epilogue every wave passes its sub-tile, 32 rows at a time, through a
+// private LDS scratch and stores row segments of 16 bytes per lane (no workgroup barrier).  With PERSIST a workgroup
+// walks several tiles and the first NSTAGE-1 stages of the next tile are already in flight during the epilogue.
 #pragma once
 #include "caat_internal.h"
 
@@ -31,8 +33,10 @@ typedef short short8_t __attribute__((ext_vector_type(8)));
 static constexpr int BKS = 32;                // k extent of one LDS stage
 static constexpr unsigned OOB = 0x80000000u;  // buffer offset that is always out of range -> load returns 0
 
-template <int BM_, int BN_, int WM_, int WN_, int NSTAGE_ = 4, int SCHED_ = 2>
+template <int BM_, int BN_, int WM_, int WN_, int NSTAGE_ = 4, int SCHED_ = 2, bool PERSIST_ = true>
 struct TileCfg {
+  // PERSIST: one workgroup per CU walks several tiles and fetches the next tile's first stages under the epilogue
+  static constexpr bool PERSIST = PERSIST_;
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NSTAGE = NSTAGE_;
   static constexpr int SCHED = SCHED_;  // 0: compiler's order, 1: fences between sub-steps, 2: + LDS reads spread 1:1 between
                                         // the MFMAs, 3: + all LDS reads of a sub-step issued ahead of its MFMAs
@@ -43,7 +47,10 @@ struct TileCfg {
   static constexpr int STAGE_CHUNKS = (BM + BN) * (BKS / 8);  // uint4 per LDS stage
   static constexpr int SMEM_CHUNKS = NSTAGE * STAGE_CHUNKS;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
-  static_assert(SMEM_CHUNKS * 16 >= BM * BN * 2, "the epilogue parks the bf16 tile in the operand buffers");
+  // epilogue scratch: every wave parks 32 rows x its WTN columns of bf16 at a time, at the tail of the LDS buffer
+  static constexpr int SCRATCH_BYTES = NWAVES * 32 * WTN * 2;
+  static_assert(SCRATCH_BYTES <= SMEM_CHUNKS * 16, "epilogue scratch must fit");
+  static_assert(!PERSIST || SCRATCH_BYTES <= STAGE_CHUNKS * 16, "persistent tiles keep NSTAGE-1 stages free of the scratch");
   static_assert(SMEM_CHUNKS * 16 <= 160 * 1024, "LDS capacity");
 };
 
@@ -172,7 +179,7 @@ struct Pipe {
 
 template <class CFG, bool AT, bool BT, int EPI>
 __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) {
-  constexpr int BM = CFG::BM, BN = CFG::BN, THREADS = CFG::THREADS, NSTAGE = CFG::NSTAGE;
+  constexpr int BM = CFG::BM, BN = CFG::BN, NSTAGE = CFG::NSTAGE;
   constexpr int TM = CFG::TM, TN = CFG::TN, WTM = CFG::WTM, WTN = CFG::WTN;
   constexpr bool SWI = (EPI == EPI_SWIGLU_FWD);
   constexpr int BN_OUT = SWI ? BN / 2 : BN;  // output columns covered by one tile
@@ -180,57 +187,59 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
 
   __shared__ uint4 smem[CFG::SMEM_CHUNKS];
 
-  // ---- which tile: spread consecutive tile ids over the 8 XCDs' L2s, then a grouped (8 tile rows) order
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / CFG::WN;
+  const int wn = wave - wm * CFG::WN;
+  const int frow = lane & 31;  // accumulator row within a 32-row MFMA tile
+  const int fk = lane >> 5;    // which half of the tile's columns / k this lane holds
+
+  // ---- tiles of this workgroup.  Tile ids are cut into 8 contiguous ranges, one per XCD (workgroup b runs on XCD
+  // b % 8), so that the workgroups sharing an L2 work on neighbouring tiles; inside a range the workgroups of the XCD
+  // take tiles round-robin.  A tile id maps to (rank g, tile row, tile column) in a grouped (8 tile rows) order.
   const int tiles_m = (p.M + BM - 1) / BM;
   const int tiles_n = (p.N + BN_OUT - 1) / BN_OUT;
   const int tiles = tiles_m * tiles_n;
   const int total = tiles * p.G;
-  int pid;
+  int pid, pid_end, pid_step;
   {
-    const int bid = blockIdx.x;
+    const int bid = blockIdx.x, nb = gridDim.x;
     const int q = total >> 3, rem = total & 7, x = bid & 7;
-    pid = x * q + (x < rem ? x : rem) + (bid >> 3);
+    const int start = x * q + (x < rem ? x : rem);
+    pid_end = start + q + (x < rem ? 1 : 0);
+    pid = start + (bid >> 3);
+    pid_step = (nb - x + 7) >> 3;  // workgroups on this XCD
   }
-  const int g = pid / tiles;
-  const int t = pid - g * tiles;
-  int tm, tn;
-  {
+
+  typedef typename OperandSel<AT, BM, CFG::NWAVES>::type OpA;
+  typedef typename OperandSel<BT, BN, CFG::NWAVES>::type OpB;
+  OpA la;
+  OpB lb;
+  int g = 0, m0 = 0, n0 = 0;
+  auto setup_tile = [&](int id) {
+    g = id / tiles;
+    const int t = id - g * tiles;
     constexpr int GROUP = 8;
     const int width = GROUP * tiles_n;
     const int grp = t / width;
     const int first = grp * GROUP;
     const int gsize = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
     const int r = t - grp * width;
-    tm = first + r % gsize;
-    tn = r / gsize;
-  }
-  const int m0 = tm * BM;
-  const int n0 = tn * BN_OUT;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wm = wave / CFG::WN;
-  const int wn = wave - wm * CFG::WN;
-
-  const bf16_t* ag = p.a + (long long)g * p.stride_a;
-  const bf16_t* bg = p.b + (long long)g * p.stride_b;
-
-  typedef typename OperandSel<AT, BM, CFG::NWAVES>::type OpA;
-  typedef typename OperandSel<BT, BN, CFG::NWAVES>::type OpB;
-  OpA la;
-  OpB lb;
-  {
+    m0 = (first + r % gsize) * BM;
+    n0 = (r / gsize) * BN_OUT;
+    const bf16_t* ag = p.a + (long long)g * p.stride_a;
+    const bf16_t* bg = p.b + (long long)g * p.stride_b;
     const int mrem = p.M - m0;
     la.init(AT ? ag + m0 : ag + (long long)m0 * p.lda, p.lda,
             [=](int rr) -> long long { return (rr < mrem) ? (long long)rr : -1; });
     if constexpr (SWI) {
-      const int half = p.half;
+      const int half = p.half, n0c = n0;
       lb.init(bg + (long long)n0 * p.ldb, p.ldb, [=](int rr) -> long long {
         const int w = rr / WTN, rw = rr - w * WTN;
         const int j = rw >> 5, c = rw & 31;
         const int col = (w * (TN / 2) + (j >> 1)) * 32 + c;  // output column relative to n0
-        if (n0 + col >= half) return -1;
+        if (n0c + col >= half) return -1;
         return (long long)col + ((j & 1) ? half : 0);
       });
     } else {
@@ -238,39 +247,12 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
       lb.init(BT ? bg + n0 : bg + (long long)n0 * p.ldb, p.ldb,
               [=](int rr) -> long long { return (rr < nrem) ? (long long)rr : -1; });
     }
-  }
-
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+  };
 
   const int K = p.K;
   const int nk = (K + BKS - 1) / BKS;
-  const int frow = lane & 31;  // accumulator row within a 32-row MFMA tile
-  const int fk = lane >> 5;    // which half of the tile's columns / k this lane holds
-
   constexpr int A_CHUNKS = BM * (BKS / 8);
   auto stage_a = [&](int s) -> uint4* { return smem + (s % NSTAGE) * CFG::STAGE_CHUNKS; };
-  auto load_frags = [&](int s, int ks, Frags<TM, TN>& f) {
-    const uint4* As = stage_a(s);
-    const uint4* Bs = As + A_CHUNKS;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) f.a[i] = OpA::frag(As, wm * WTM + i * 32, ks, lane);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) f.b[j] = OpB::frag(Bs, wn * WTN + j * 32, ks, lane);
-  };
-  auto mfma_all = [&](const Frags<TM, TN>& f) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        // operands swapped: the accumulator holds C^T, i.e. lane = row of C, registers = columns of C
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
-  };
   auto issue_stage = [&](int s) {  // past the end of K every offset is out of range: zeros land in a slot nobody reads
     uint4* As = stage_a(s);
     la.issue(s * BKS, K, As);
@@ -285,154 +267,206 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
     if constexpr (SCHED >= 1) __builtin_amdgcn_sched_barrier(0);
   };
 
+  if (pid >= pid_end) return;
+  setup_tile(pid);
 #pragma unroll
   for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s);
-  wait_vmcnt<(NSTAGE - 2) * NV>();  // copies complete in order: stage 0 has landed
-  __syncthreads();
-  Frags<TM, TN> f0, f1;
-  load_frags(0, 0, f0);
-  fence();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    // sub-step 0; the slot of stage kt-1 is free (everyone passed the barrier below in the previous iteration)
-    issue_stage(kt + NSTAGE - 1);
-    load_frags(kt, 1, f1);
-    mfma_all(f0);
-    if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
-    if constexpr (SCHED == 3) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
-    }
-    fence();
-    // sub-step 1; stage kt+1 must have landed (the two newest stages may still be in flight) and be visible
+  while (true) {
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    auto load_frags = [&](int s, int ks, Frags<TM, TN>& f) {
+      const uint4* As = stage_a(s);
+      const uint4* Bs = As + A_CHUNKS;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) f.a[i] = OpA::frag(As, wm * WTM + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) f.b[j] = OpB::frag(Bs, wn * WTN + j * 32, ks, lane);
+    };
+    auto mfma_all = [&](const Frags<TM, TN>& f) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          // operands swapped: the accumulator holds C^T, i.e. lane = row of C, registers = columns of C
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+    };
+
+    // copies complete in order: with at most the two newest stages outstanding, stage 0 has landed.  (Younger
+    // epilogue loads / stores of the previous tile only make this wait stricter.)  The barrier also separates the
+    // previous tile's epilogue scratch from the copies that will reuse its LDS slot.
     wait_vmcnt<(NSTAGE - 2) * NV>();
     __syncthreads();
+    Frags<TM, TN> f0, f1;
+    load_frags(0, 0, f0);
     fence();
-    load_frags(kt + 1, 0, f0);
-    mfma_all(f1);
-    if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
-    if constexpr (SCHED == 3) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
-    }
-    fence();
-  }
-  wait_vmcnt<0>();  // the zero-filled stages past K still target LDS: let them land before the buffers are reused
 
-  // ---- epilogue.  Each lane holds C[row = lane%32][col = 8*q + 4*(lane/32) + 0..3] of every 32x32 tile in
-  // acc[..][4q..4q+3].  Writing that to global memory directly would scatter 8-byte pieces over 32 rows per
-  // instruction, so the tile is first rounded to bf16 and parked in LDS (the operand buffers are free now) as
-  // [BM][BN/8] 16-byte chunks, chunk index XOR-swizzled by the row (conflict-free for the column-of-rows
-  // writes and for the row-wise reads); then every wave instruction stores whole rows: 16 bytes per lane,
-  // consecutive lanes = consecutive columns.  The fused element-wise work (activation, its derivative, the
-  // private half of the partial channel-reduce + residual) is done in this second phase on 8 values per lane.
-  constexpr int CH = BN / 8;  // chunks per staged row
-  __syncthreads();            // every wave is done reading the operand tiles
-  {
-    char* stage = reinterpret_cast<char*>(smem);
+    for (int kt = 0; kt < nk; ++kt) {
+      // sub-step 0; the slot of stage kt-1 is free (everyone passed the barrier below in the previous iteration)
+      issue_stage(kt + NSTAGE - 1);
+      load_frags(kt, 1, f1);
+      mfma_all(f0);
+      if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
+      if constexpr (SCHED == 3) {
+        __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+      }
+      fence();
+      // sub-step 1; stage kt+1 must have landed (the two newest stages may still be in flight) and be visible
+      wait_vmcnt<(NSTAGE - 2) * NV>();
+      __syncthreads();
+      fence();
+      load_frags(kt + 1, 0, f0);
+      mfma_all(f1);
+      if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
+      if constexpr (SCHED == 3) {
+        __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+      }
+      fence();
+    }
+    // the zero-filled stages past K still target LDS: let them land, and let every wave finish its fragment reads,
+    // before the buffers are reused
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    // ---- the finished tile's coordinates; then start on the next tile's data before the epilogue
+    const int eg = g, em0 = m0, en0 = n0;
+    const int next = pid + pid_step;
+    const bool has_next = CFG::PERSIST && next < pid_end;
+    if (has_next) {
+      setup_tile(next);
+#pragma unroll
+      for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s);  // slots 0 .. NSTAGE-2; the scratch below is in the last slot
+    }
+
+    // ---- epilogue.  Each lane holds C[row = lane%32][col = 8*q + 4*(lane/32) + 0..3] of every 32x32 tile in
+    // acc[..][4q..4q+3].  Stored as they are, these 8-byte pieces would scatter over 32 rows per instruction; so each
+    // wave rounds 32 rows x WTN columns to bf16 into its own LDS scratch (chunk index XOR-swizzled by the row) and
+    // reads them back row-wise: 16 bytes per lane, consecutive lanes = consecutive columns.  The fused element-wise
+    // work (activation, its derivative, the private half of the partial channel-reduce + residual) happens there.
+    constexpr int CHW = WTN / 8;  // 16-byte chunks per scratch row
+    char* scratch = reinterpret_cast<char*>(smem) + (CFG::SMEM_CHUNKS * 16 - CFG::SCRATCH_BYTES) + wave * (32 * WTN * 2);
+    const uint4* scr4 = reinterpret_cast<const uint4*>(scratch);
+    auto staged = [&](int row, int c) -> uint4 { return scr4[row * CHW + (c ^ (row & (CHW - 1)))]; };
+    auto unpack = [](const uint4& v, float* f) {
+      f[0] = lo_bf(v.x); f[1] = hi_bf(v.x); f[2] = lo_bf(v.y); f[3] = hi_bf(v.y);
+      f[4] = lo_bf(v.z); f[5] = hi_bf(v.z); f[6] = lo_bf(v.w); f[7] = hi_bf(v.w);
+    };
+    auto pack = [](const float* f) -> uint4 {
+      return make_uint4(pack2bf(f[0], f[1]), pack2bf(f[2], f[3]), pack2bf(f[4], f[5]), pack2bf(f[6], f[7]));
+    };
+    bf16_t* cg = p.c + (long long)eg * p.stride_c;
+    const int M = p.M;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      const int row = wm * WTM + i * 32 + frow;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int c = (wn * WTN + j * 32) / 8 + q;
+          const int c = j * 4 + q;
           uint2 w;
           w.x = pack2bf(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
           w.y = pack2bf(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-          *reinterpret_cast<uint2*>(stage + ((row * CH + (c ^ (row & (CH - 1)))) * 16 + fk * 8)) = w;
+          *reinterpret_cast<uint2*>(scratch + ((frow * CHW + (c ^ (frow & (CHW - 1)))) * 16 + fk * 8)) = w;
+        }
+      // the wave reads back what its other lanes wrote: LDS executes a wave's operations in order; the compiler
+      // must not reorder across this point either
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      const long long row_base = (long long)em0 + wm * WTM + i * 32;
+      if constexpr (SWI) {
+        // scratch columns: [gate 32 | up 32] pairs; output chunk oc -> gate chunk (oc/4)*8 + oc%4, up chunk = +4
+        constexpr int OCW = CHW / 2;
+        constexpr int STEPS = 32 * OCW / 64;
+        bf16_t* yg = p.c2 + (long long)eg * p.stride_c2;
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+          const int idx = st * 64 + lane;
+          const int row = idx / OCW, oc = idx - row * OCW;
+          const long long grow = row_base + row;
+          const int gcol = en0 + (wn * (TN / 2) + (oc >> 2)) * 32 + (oc & 3) * 8;
+          if (grow >= M || gcol >= p.half) continue;
+          const int gc = (oc >> 2) * 8 + (oc & 3);
+          const uint4 gw = staged(row, gc), uw = staged(row, gc + 4);
+          float gt[8], up[8], y[8];
+          unpack(gw, gt);
+          unpack(uw, up);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
+          *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = gw;
+          *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = uw;
+          *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
+        }
+      } else {
+        constexpr int STEPS = 32 * CHW / 64;
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+          const int idx = st * 64 + lane;
+          const int row = idx / CHW, c = idx - row * CHW;
+          const long long grow = row_base + row;
+          const int gcol = en0 + wn * WTN + c * 8;
+          if (grow >= M || gcol >= p.N) continue;
+          const uint4 raw = staged(row, c);
+          if constexpr (EPI == EPI_PLAIN) {
+            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+          } else if constexpr (EPI == EPI_GELU_FWD) {
+            // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
+            float v[8], y[8];
+            unpack(raw, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
+            bf16_t* yg = p.c2 + (long long)eg * p.stride_c2;
+            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+            *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
+          } else if constexpr (EPI == EPI_ROWPAR) {
+            // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual); columns < hs are
+            // stored as this rank's partial sum for the reduce kernel.  The private value is scaled from the
+            // bf16-rounded partial.
+            if (gcol + 7 >= p.hs) {
+              float v[8], r[8];
+              unpack(raw, v);
+              unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol), r);
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (gcol + e >= p.hs) v[e] = p.scale * v[e] + r[e];
+              *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
+            } else {
+              *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+            }
+          } else if constexpr (EPI == EPI_GELU_BWD) {
+            float v[8], pr[8];
+            unpack(raw, v);
+            unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol), pr);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
+            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
+          } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+            const bf16_t* pg = p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol;
+            float v[8], gt[8], up[8], dg[8], du[8];
+            unpack(raw, v);
+            unpack(*reinterpret_cast<const uint4*>(pg), gt);
+            unpack(*reinterpret_cast<const uint4*>(pg + p.half), up);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float sg = sigmoid_f(gt[e]);
+              dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
+              du[e] = v[e] * gt[e] * sg;
+            }
+            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(dg);
+            *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = pack(du);
+          }
         }
       }
+      asm volatile("" ::: "memory");  // keep the next 32 rows' scratch writes behind these reads
     }
-  }
-  __syncthreads();
-
-  const int M = p.M;
-  bf16_t* cg = p.c + (long long)g * p.stride_c;
-  auto staged = [&](int row, int c) -> uint4 { return smem[row * CH + (c ^ (row & (CH - 1)))]; };
-  auto unpack = [](const uint4& v, float* f) {
-    f[0] = lo_bf(v.x); f[1] = hi_bf(v.x); f[2] = lo_bf(v.y); f[3] = hi_bf(v.y);
-    f[4] = lo_bf(v.z); f[5] = hi_bf(v.z); f[6] = lo_bf(v.w); f[7] = hi_bf(v.w);
-  };
-  auto pack = [](const float* f) -> uint4 {
-    return make_uint4(pack2bf(f[0], f[1]), pack2bf(f[2], f[3]), pack2bf(f[4], f[5]), pack2bf(f[6], f[7]));
-  };
-  constexpr int OCH = BN_OUT / 8;  // output chunks per row
-  constexpr int STEPS = BM * OCH / THREADS;
-  static_assert((BM * OCH) % THREADS == 0, "epilogue chunks must divide over the threads");
-#pragma unroll 4
-  for (int st = 0; st < STEPS; ++st) {
-    const int idx = st * THREADS + tid;
-    const int row = idx / OCH, oc = idx - row * OCH;
-    const long long grow = (long long)m0 + row;
-    const int gcol = n0 + oc * 8;
-    if (grow >= M || gcol >= p.N) continue;
-    if constexpr (SWI) {
-      // staged columns: per wave [gate 32 | up 32] pairs; output column -> its gate chunk, up chunk = +4
-      const int ocol = oc * 8;
-      const int w = ocol / (WTN / 2), rw = ocol - w * (WTN / 2);
-      const int gc = (w * WTN + (rw >> 5) * 64 + (rw & 31)) / 8;
-      float gt[8], up[8], y[8];
-      unpack(staged(row, gc), gt);
-      unpack(staged(row, gc + 4), up);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
-      bf16_t* yg = p.c2 + (long long)g * p.stride_c2;
-      *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = staged(row, gc);
-      *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = staged(row, gc + 4);
-      *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
-    } else {
-      const uint4 raw = staged(row, oc);
-      if constexpr (EPI == EPI_PLAIN) {
-        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
-      } else if constexpr (EPI == EPI_GELU_FWD) {
-        // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
-        float v[8], y[8];
-        unpack(raw, v);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
-        bf16_t* yg = p.c2 + (long long)g * p.stride_c2;
-        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
-        *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
-      } else if constexpr (EPI == EPI_ROWPAR) {
-        // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual); columns < hs are
-        // stored as this rank's partial sum for the reduce kernel.  NOTE: the private value is scaled from the
-        // bf16-rounded partial.
-        if (gcol + 7 >= p.hs) {
-          float v[8], r[8];
-          unpack(raw, v);
-          unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)g * p.stride_aux + grow * p.ldaux + gcol), r);
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (gcol + e >= p.hs) v[e] = p.scale * v[e] + r[e];
-          *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
-        } else {
-          *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
-        }
-      } else if constexpr (EPI == EPI_GELU_BWD) {
-        float v[8], pr[8];
-        unpack(raw, v);
-        unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)g * p.stride_aux + grow * p.ldaux + gcol), pr);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
-        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
-      } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-        const bf16_t* pg = p.aux + (long long)g * p.stride_aux + grow * p.ldaux + gcol;
-        float v[8], gt[8], up[8], dg[8], du[8];
-        unpack(raw, v);
-        unpack(*reinterpret_cast<const uint4*>(pg), gt);
-        unpack(*reinterpret_cast<const uint4*>(pg + p.half), up);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float sg = sigmoid_f(gt[e]);
-          dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
-          du[e] = v[e] * gt[e] * sg;
-        }
-        *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(dg);
-        *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = pack(du);
-      }
-    }
+    if (!has_next) break;
+    pid = next;
   }
 }
 
@@ -443,7 +477,18 @@ static hipError_t launch_one(const GemmParams& p, hipStream_t s) {
   const long long tiles_n = (p.N + BN_OUT - 1) / BN_OUT;
   const long long total = tiles_m * tiles_n * p.G;
   if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((gemm_kernel<CFG, AT, BT, EPI>), dim3((unsigned)total), dim3(CFG::THREADS), 0, s, p);
+  long long blocks = total;
+  if (CFG::PERSIST) {
+    static int n_cu = 0;  // one workgroup per compute unit (a workgroup's LDS leaves no room for a second one)
+    if (n_cu == 0) {
+      int dev = 0, v = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return hipErrorInvalidValue;
+      n_cu = v > 0 ? v : 256;
+    }
+    if (blocks > n_cu) blocks = n_cu;
+  }
+  hipLaunchKernelGGL((gemm_kernel<CFG, AT, BT, EPI>), dim3((unsigned)blocks), dim3(CFG::THREADS), 0, s, p);
   return hipGetLastError();
 }
 
