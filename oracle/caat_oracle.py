@@ -299,6 +299,94 @@ def attn_block_fwd(X, R, Wqkv, Wo, gamma, beta, *, batch: int, seq: int, heads_p
     return out
 
 
+def rope_adjoint(dy: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:
+    """Gradient of rope w.r.t. its input: rope is, per pair (j, j+d/2), a plane rotation by +angle, so its
+    transpose (= adjoint, the Jacobian is orthogonal) is the rotation by -angle:
+      dx[j]     =  dy[j] cos + dy[j+d/2] sin
+      dx[j+d/2] = -dy[j] sin + dy[j+d/2] cos
+    """
+    d = dy.shape[-1]
+    half = d // 2
+    j = np.arange(half, dtype=np.float64)
+    inv = base ** (-2.0 * j / d)
+    ang = np.asarray(pos, dtype=np.float64)[:, None] * inv[None, :]
+    c, s = np.cos(ang).astype(dy.dtype), np.sin(ang).astype(dy.dtype)
+    g1, g2 = dy[..., :half], dy[..., half:]
+    return np.concatenate([g1 * c + g2 * s, g2 * c - g1 * s], axis=-1)
+
+
+def causal_attention_bwd(q: np.ndarray, k: np.ndarray, v: np.ndarray, dO: np.ndarray, q_pos0: int = 0):
+    """Gradient of causal_attention for one head, chain rule written out.
+
+    With S = q k^T / sqrt(d) (masked), P = softmax_rows(S), O = P v:
+      dv = P^T dO;  dP = dO v^T;  dS_ij = P_ij (dP_ij - sum_j' dP_ij' P_ij')  (softmax Jacobian);
+      dq = dS k / sqrt(d);  dk = dS^T q / sqrt(d).   Masked entries have P = 0, hence dS = 0.
+    Returns (dq, dk, dv).
+    """
+    sq, d = q.shape
+    sk = k.shape[0]
+    s = (q @ k.T) / math.sqrt(d)
+    qi = np.arange(sq)[:, None] + q_pos0
+    kj = np.arange(sk)[None, :]
+    s = np.where(kj <= qi, s, -np.inf)
+    s = s - s.max(axis=-1, keepdims=True)
+    e = np.exp(s)
+    P = e / e.sum(axis=-1, keepdims=True)
+    dv = P.T @ dO
+    dP = dO @ v.T
+    dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
+    dq = (dS @ k) / math.sqrt(d)
+    dk = (dS.T @ q) / math.sqrt(d)
+    return dq, dk, dv
+
+
+def attn_block_bwd(X, fwd: Dict[str, np.ndarray], Wqkv, Wo, gamma, dXo, dRo, *, batch: int, seq: int,
+                   heads_per_rank: int, head_dim: int, norm: int, hs: int, eps: float = 1e-5,
+                   private_scale: float = 1.0, rope_base: float = 10000.0) -> Dict[str, np.ndarray]:
+    """Backward of attn_block_fwd given dL/dX' (dXo) and dL/dR' (dRo), both [T,n,h].
+
+    Same placement as the MLP block (Fig. 2b, Sec. 4): norm backward per rank first, G_m = dRo_m + NormBwd(dXo_m),
+    dR_m = G_m un-reduced (App. B), the partial channel-reduce on G, then the chain rule of Eq. A5 per rank:
+      dH_m = dZt_m O_m ; dO_m = dZt_m^T H_m ; per (sequence, head) the attention gradient, the RoPE adjoint on
+      dq, dk ; dqkv_m = [dq | dk | dv] ; dX_m = dqkv_m Wqkv_m (no reduce over ranks) ; dWqkv_m = dqkv_m^T X_m.
+    fwd is attn_block_fwd's result (needs Rp, H and the rotated Q, K and V).
+    """
+    T, n, h = X.shape
+    d = head_dim
+    hd = heads_per_rank * d
+    pos = np.arange(seq)
+    dn, dgamma_m, dbeta_m = norm_bwd(dXo, fwd["Rp"], gamma, norm, eps)
+    G = dRo + dn
+    dZt = partial_channel_reduce(G, hs, private_scale)
+    g: Dict[str, np.ndarray] = {"dR": G, "dZt": dZt, "dgamma": dgamma_m.sum(axis=0)}
+    if norm == LAYERNORM:
+        g["dbeta"] = dbeta_m.sum(axis=0)
+    dXs, dWos, dWqkvs, dHs, dqkvs = [], [], [], [], []
+    for m in range(T):
+        dH = dZt[m] @ Wo[m]                       # [n,h] x [h,hd]
+        dWos.append(dZt[m].T @ fwd["H"][m])       # [h,hd]
+        dqkv = np.empty((n, 3 * hd), dtype=X.dtype)
+        for b in range(batch):
+            rows = slice(b * seq, (b + 1) * seq)
+            for a in range(heads_per_rank):
+                cols = slice(a * d, (a + 1) * d)
+                dq, dk, dv = causal_attention_bwd(fwd["Q"][m, b, a], fwd["K"][m, b, a], fwd["V"][m, b, a],
+                                                  dH[rows, cols])
+                dqkv[rows, a * d:(a + 1) * d] = rope_adjoint(dq, pos, rope_base)
+                dqkv[rows, hd + a * d:hd + (a + 1) * d] = rope_adjoint(dk, pos, rope_base)
+                dqkv[rows, 2 * hd + a * d:2 * hd + (a + 1) * d] = dv
+        dHs.append(dH)
+        dqkvs.append(dqkv)
+        dXs.append(dqkv @ Wqkv[m])                # [n,3hd] x [3hd,h]
+        dWqkvs.append(dqkv.T @ X[m])              # [3hd,h]
+    g["dH"] = np.stack(dHs)
+    g["dqkv"] = np.stack(dqkvs)
+    g["dX"] = np.stack(dXs)
+    g["dWo"] = np.stack(dWos)
+    g["dWqkv"] = np.stack(dWqkvs)
+    return g
+
+
 def decode_layer_fwd(R, W: Dict[str, np.ndarray], Kc, Vc, *, kv_len: int, heads_per_rank: int, head_dim: int,
                      hs: int, eps: float = 1e-5, private_scale: float = 1.0,
                      rope_base: float = 10000.0) -> Dict[str, np.ndarray]:

@@ -453,6 +453,116 @@ def test_attention_block_sequences_independent_and_causal():
     assert not np.allclose(a["Rp"][:, 6 + 4:], b["Rp"][:, 6 + 4:])
 
 
+# --------------------------------------------------------------------------- attention backward
+def test_rope_adjoint_is_transpose_and_inverse():
+    r = _rng(21)
+    d, s = 8, 6
+    x, y = r.standard_normal((s, d)), r.standard_normal((s, d))
+    pos = np.arange(s) + 3
+    # <rope(x), y> = <x, rope_adjoint(y)> (transpose), and the rotation is orthogonal so adjoint = inverse
+    lhs = (O.rope(x, pos, 10000.0) * y).sum()
+    rhs = (x * O.rope_adjoint(y, pos, 10000.0)).sum()
+    assert abs(lhs - rhs) < 1e-12
+    np.testing.assert_allclose(O.rope_adjoint(O.rope(x, pos, 10000.0), pos, 10000.0), x, atol=1e-14)
+
+
+def _softmax_jacobian_attention_bwd(q, k, v, dO):
+    """Attention gradient with the softmax Jacobian written entry by entry (python loops)."""
+    sq, d = q.shape
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for i in range(sq):
+        sc = np.array([q[i] @ k[j] / math.sqrt(d) for j in range(i + 1)])
+        pr = np.exp(sc - sc.max())
+        pr /= pr.sum()
+        dp = np.array([dO[i] @ v[j] for j in range(i + 1)])
+        for j in range(i + 1):
+            dv[j] += pr[j] * dO[i]
+            ds = sum(dp[t] * pr[t] * ((1.0 if t == j else 0.0) - pr[j]) for t in range(i + 1))
+            dq[i] += ds * k[j] / math.sqrt(d)
+            dk[j] += ds * q[i] / math.sqrt(d)
+    return dq, dk, dv
+
+
+def test_causal_attention_bwd_vs_jacobian_loops_and_fd():
+    r = _rng(22)
+    sq, d = 6, 4
+    q, k, v, dO = (r.standard_normal((sq, d)) for _ in range(4))
+    dq, dk, dv = O.causal_attention_bwd(q, k, v, dO)
+    jq, jk, jv = _softmax_jacobian_attention_bwd(q, k, v, dO)
+    np.testing.assert_allclose(dq, jq, atol=1e-13)
+    np.testing.assert_allclose(dk, jk, atol=1e-13)
+    np.testing.assert_allclose(dv, jv, atol=1e-13)
+    # central differences of L = <dO, attention(q,k,v)>
+    e = 1e-6
+    for arr, grad in ((q, dq), (k, dk), (v, dv)):
+        for idx in [(0, 0), (2, 3), (5, 1), (3, 2)]:
+            old = arr[idx]
+            arr[idx] = old + e
+            lp = (O.causal_attention(q, k, v) * dO).sum()
+            arr[idx] = old - e
+            lm = (O.causal_attention(q, k, v) * dO).sum()
+            arr[idx] = old
+            assert abs((lp - lm) / (2 * e) - grad[idx]) < 1e-8
+    # causality of the gradient: the last key / value only receives gradient from the last query
+    dO2 = dO.copy()
+    dO2[:sq - 1] = 0.0
+    _, dk2, dv2 = O.causal_attention_bwd(q, k, v, dO2)
+    np.testing.assert_allclose(dk2[sq - 1], dk[sq - 1], atol=1e-14)
+    np.testing.assert_allclose(dv2[sq - 1], dv[sq - 1], atol=1e-14)
+    # softmax rows sum to one => a constant added to all values moves O by that constant: sum_j dv_j = sum_i dO_i
+    np.testing.assert_allclose(dv.sum(0), dO.sum(0), atol=1e-13)
+
+
+def _attn_loss(cfg, w, Wt, Vt, hs, scale, norm):
+    out = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], w.get("beta"), batch=cfg.batch,
+                           seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim, norm=norm,
+                           hs=hs, private_scale=scale)
+    return (out["Xp"] * Wt).sum() + (out["Rp"] * Vt).sum()
+
+
+@pytest.mark.parametrize("hs,scale", [(0, 1.0), (5, 1.0), (8, math.sqrt(2.0)), (16, 1.0)])
+def test_attention_block_backward_finite_differences(hs, scale):
+    """L = sum_m <W_m, X'_m> + <V_m, R'_m>; every gradient of the attention block vs central differences."""
+    cfg, w = _tiny_attn(T=2, batch=2, seq=5, heads=4, d=4, seed=4)
+    r = _rng(23)
+    Wt, Vt = r.standard_normal(w["X"].shape), r.standard_normal(w["X"].shape)
+    kw = dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim,
+              norm=O.RMSNORM, hs=hs, private_scale=scale)
+    fwd = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], None, **kw)
+    g = O.attn_block_bwd(w["X"], fwd, w["Wqkv"], w["Wo"], w["gamma"], Wt, Vt, **kw)
+    e = 1e-6
+    for key, gname in {"X": "dX", "R": "dR", "Wqkv": "dWqkv", "Wo": "dWo", "gamma": "dgamma"}.items():
+        arr = w[key]
+        for fi in r.choice(arr.size, size=min(8, arr.size), replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            old = arr[idx]
+            arr[idx] = old + e
+            lp = _attn_loss(cfg, w, Wt, Vt, hs, scale, O.RMSNORM)
+            arr[idx] = old - e
+            lm = _attn_loss(cfg, w, Wt, Vt, hs, scale, O.RMSNORM)
+            arr[idx] = old
+            fd = (lp - lm) / (2 * e)
+            assert abs(fd - g[gname][idx]) < 2e-6 * (1 + abs(fd)), (key, idx, fd, g[gname][idx])
+
+
+def test_attention_backward_no_reduce_at_input_and_sequences_independent():
+    """dX_m depends only on rank m's upstream gradient when hs = 0 (Sec. 4: no reduce at the column-parallel input),
+    and a gradient entering sequence 1 leaves sequence 0's dX untouched."""
+    cfg, w = _tiny_attn(T=2, batch=2, seq=4, heads=4, d=4, seed=6)
+    r = _rng(24)
+    dXo, dRo = r.standard_normal(w["X"].shape), r.standard_normal(w["X"].shape)
+    kw = dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim,
+              norm=O.RMSNORM, hs=0)
+    fwd = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], None, **kw)
+    g0 = O.attn_block_bwd(w["X"], fwd, w["Wqkv"], w["Wo"], w["gamma"], dXo, dRo, **kw)
+    d2 = dXo.copy()
+    d2[1, cfg.seq:] += 1.0          # rank 1, sequence 1 only
+    g1 = O.attn_block_bwd(w["X"], fwd, w["Wqkv"], w["Wo"], w["gamma"], d2, dRo, **kw)
+    assert np.array_equal(g0["dX"][0], g1["dX"][0])
+    assert np.array_equal(g0["dX"][1, :cfg.seq], g1["dX"][1, :cfg.seq])
+    assert not np.array_equal(g0["dX"][1, cfg.seq:], g1["dX"][1, cfg.seq:])
+
+
 # --------------------------------------------------------------------------- decode layer
 def test_decode_equals_last_row_of_prefill():
     """The decode step over a cache of L rotated keys equals row L of a causal prefill over L+1 tokens."""
