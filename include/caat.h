@@ -46,7 +46,7 @@ typedef enum caat_status {
 typedef enum caat_kind {
   CAAT_MLP_GELU = 0,    /* Y = gelu(X A),               LayerNorm or RMSNorm after the residual */
   CAAT_MLP_SWIGLU = 1,  /* Y = silu(X Wg) * (X Wu) */
-  CAAT_ATTN = 2,        /* causal multi-head attention with RoPE, prefill / training forward */
+  CAAT_ATTN = 2,        /* causal multi-head attention with RoPE, prefill / training forward and backward */
   CAAT_ATTN_DECODE = 3  /* full decoder layer (attention + SwiGLU MLP), one new token per sequence */
 } caat_kind;
 
@@ -91,7 +91,8 @@ typedef struct caat_ws_layout {
   size_t off_mean, bytes_mean; /* fp32 [T,tokens] (LayerNorm only) */
   size_t off_rstd, bytes_rstd; /* fp32 [T,tokens] */
   size_t off_dZt, bytes_dZt;   /* backward: reduced gradient [T,tokens,h] */
-  size_t off_dP, bytes_dP;     /* backward: gradient of the pre-activations, same shape as P */
+  size_t off_dP, bytes_dP;     /* backward: gradient of the pre-activations, same shape as P; CAAT_ATTN: gradient of the
+                                  un-rotated projections [T,tokens,3*hd_r], column blocks dq | dk | dv */
   size_t off_Q, bytes_Q;       /* attention: projections [T,tokens,3*hd_r], column blocks q | k | v, q and k rotated (RoPE) */
   size_t off_scratch, bytes_scratch;
   /* decode layer only: attention heads output [T,batch,hd_r]; first norm output X1, residual after the attention
@@ -100,6 +101,11 @@ typedef struct caat_ws_layout {
   size_t off_X1, bytes_X1;
   size_t off_R1, bytes_R1;
   size_t off_X2, bytes_X2;
+  /* CAAT_ATTN only: fp32 per-query softmax statistics [T*batch*n_heads/T][2][seq rounded up to 64] (row 0: log2-domain
+   * log-sum-exp of the scaled scores, saved by the forward; row 1: sum_d dH*H, written by the backward), and the
+   * backward's gradient of the heads output dH [T,tokens,hd_r] */
+  size_t off_stats, bytes_stats;
+  size_t off_dH, bytes_dH;
 } caat_ws_layout;
 
 /* Sec. 3 / Eq. A3: number of shared channels floor(h*p), evaluated in IEEE double.  Host function.
@@ -178,15 +184,17 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
                    void* x_out, void* kv_k, void* kv_v, void* workspace, size_t ws_bytes, void* hip_stream);
 
 /*
- * Backward of caat_block_fwd for the MLP kinds (Fig. 2b): norm backward per rank, residual gradient
- * dr_m = g_m un-reduced, the SAME partial channel-reduce on g (fp32 accumulation), then the GEMM chain
- * rule per rank; dx_m is NOT reduced over ranks.
+ * Backward of caat_block_fwd for the MLP kinds and CAAT_ATTN (Fig. 2b): norm backward per rank, residual
+ * gradient dr_m = g_m un-reduced, the SAME partial channel-reduce on g (fp32 accumulation), then the chain
+ * rule of Eq. A3 / A5 per rank (for CAAT_ATTN: o_proj, the causal attention core rebuilt from the saved
+ * softmax statistics, the inverse RoPE rotation, the q/k/v projections); dx_m is NOT reduced over ranks.
+ * CAAT_ATTN_DECODE has no backward (CAAT_EUNSUPPORTED).
  *   x, r_out           : the forward's input x and output r_out
  *   workspace          : the forward's workspace (also used as scratch here)
  *   dx_out, dr_out     : [T,tokens,h] gradients w.r.t. x_out and r_out
  *   dx, dr             : [T,tokens,h] outputs
  *   dweights           : host array of device pointers, bf16, same shapes/order as the weight matrices
- *                        ({dA, dB} or {dWgu, dB})
+ *                        ({dA, dB}, {dWgu, dB} or {dWqkv, dWo})
  *   dgamma, dbeta      : [h] fp32, summed over ranks; dbeta NULL for RMSNorm
  */
 int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x, const void* r_out,

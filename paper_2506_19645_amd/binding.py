@@ -38,7 +38,7 @@ class caat_ws_layout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in (
         "total_bytes", "off_P", "bytes_P", "off_Y", "bytes_Y", "off_mean", "bytes_mean", "off_rstd", "bytes_rstd",
         "off_dZt", "bytes_dZt", "off_dP", "bytes_dP", "off_Q", "bytes_Q", "off_scratch", "bytes_scratch", "off_H", "bytes_H",
-        "off_X1", "bytes_X1", "off_R1", "bytes_R1", "off_X2", "bytes_X2")]
+        "off_X1", "bytes_X1", "off_R1", "bytes_R1", "off_X2", "bytes_X2", "off_stats", "bytes_stats", "off_dH", "bytes_dH")]
 
 
 EXPORTS = ["caat_shared_channels", "caat_status_string", "caat_workspace_bytes", "caat_workspace_layout",

@@ -93,6 +93,11 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
     take(T * n * hd * 2, &L->off_Y, &L->bytes_Y);
     if (d->norm == CAAT_LAYERNORM) take(T * n * 4, &L->off_mean, &L->bytes_mean);
     take(T * n * 4, &L->off_rstd, &L->bytes_rstd);
+    take(attn_stats_bytes((long long)T * d->batch, d->n_heads / d->T, d->seq), &L->off_stats, &L->bytes_stats);
+    take(T * n * h * 2, &L->off_dZt, &L->bytes_dZt);
+    take(T * n * hd * 2, &L->off_dH, &L->bytes_dH);
+    take(T * n * 3 * hd * 2, &L->off_dP, &L->bytes_dP);
+    take(norm_bwd_workspace_bytes(d->T, d->tokens, d->h), &L->off_scratch, &L->bytes_scratch);
   } else if (d->kind == CAAT_ATTN_DECODE) {
     const size_t hd = (size_t)(d->n_heads / d->T) * d->head_dim, fr = d->ffn / d->T;
     take(T * n * h * 2, &L->off_X1, &L->bytes_X1);
@@ -129,6 +134,7 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   bf16_t* H = (bf16_t*)(ws + L.off_Y);
   float* mean = d->norm == CAAT_LAYERNORM ? (float*)(ws + L.off_mean) : nullptr;
   float* rstd = (float*)(ws + L.off_rstd);
+  float* stats = (float*)(ws + L.off_stats);
   hipError_t e;
   GemmParams g1;
   std::memset(&g1, 0, sizeof(g1));
@@ -143,12 +149,12 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   if (e != hipSuccess) return CAAT_EHIP;
   {
     ProfScope ps(s, "rope");
-    e = launch_rope(QKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, 0, s);
+    e = launch_rope(QKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, 0, false, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
   {
     ProfScope ps(s, "flash_attn_fwd");
-    e = launch_flash_fwd(QKV, H, T * d->batch, d->seq, (int)hd, d->head_dim, s);
+    e = launch_flash_fwd(QKV, H, stats, T * d->batch, d->seq, (int)hd, d->head_dim, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
   GemmParams g2;
@@ -175,6 +181,74 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
                         (int)T, n, (int)h, d->eps, s);
   }
   return hip_status(e);
+}
+
+// Attention sub-block backward (Fig. 2b applied to Eq. A5): norm backward per rank first, dr_m = g_m un-reduced, the
+// partial channel-reduce on g, then per rank dH = dZt Wo, dWo = dZt^T H, the attention-core gradient w.r.t. the rotated
+// q, k and v, the inverse rotation of dq and dk, dX = dqkv Wqkv (never reduced over ranks) and dWqkv = dqkv^T X.
+int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* const* weights, const void* x, const void* r_out,
+                   void* workspace, size_t ws_bytes, const void* dx_out, const void* dr_out, void* dx, void* dr,
+                   void* const* dweights, float* dgamma, float* dbeta, void* hip_stream) {
+  const void* wqkv = weights[0]; const void* wo = weights[1]; const void* gamma = weights[2];
+  void* dwqkv = dweights[0]; void* dwo = dweights[1];
+  if (!wqkv || !wo || !gamma || !dwqkv || !dwo || (d->norm == CAAT_LAYERNORM && !dbeta)) return CAAT_EINVAL;
+  if (d->head_dim != 128) return CAAT_EUNSUPPORTED;
+  if (misaligned(wqkv) || misaligned(wo) || misaligned(gamma) || misaligned(dwqkv) || misaligned(dwo) || misaligned(x) ||
+      misaligned(r_out) || misaligned(workspace) || misaligned(dx_out) || misaligned(dr_out) || misaligned(dx) ||
+      misaligned(dr))
+    return CAAT_EALIGN;
+  if (ws_bytes < L.total_bytes) return CAAT_EWORKSPACE;
+  if (d->tokens == 0) return CAAT_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  const long long T = d->T, n = d->tokens, h = d->h, hd = (long long)(d->n_heads / d->T) * d->head_dim;
+  const bf16_t* QKV = (const bf16_t*)(ws + L.off_Q);
+  const bf16_t* H = (const bf16_t*)(ws + L.off_Y);
+  const float* mean = d->norm == CAAT_LAYERNORM ? (const float*)(ws + L.off_mean) : nullptr;
+  const float* rstd = (const float*)(ws + L.off_rstd);
+  float* stats = (float*)(ws + L.off_stats);
+  bf16_t* dZt = (bf16_t*)(ws + L.off_dZt);
+  bf16_t* dH = (bf16_t*)(ws + L.off_dH);
+  bf16_t* dQKV = (bf16_t*)(ws + L.off_dP);
+  hipError_t e;
+  GemmParams q;
+#define CAAT_STEP(name, call) { ProfScope ps(s, name); e = (call); } if (e != hipSuccess) return CAAT_EHIP;
+  CAAT_STEP("norm_bwd", launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
+                                        mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
+                                        d->private_scale, ws + L.off_scratch, s))
+  CAAT_STEP("partial_sync_bwd", launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s))
+  // dH_m = dZt_m Wo_m (NN): [n,h] x [h,hd]
+  std::memset(&q, 0, sizeof(q));
+  q.a = dZt; q.lda = h; q.stride_a = n * h;
+  q.b = (const bf16_t*)wo; q.ldb = hd; q.stride_b = h * hd;
+  q.c = dH; q.ldc = hd; q.stride_c = n * hd;
+  q.G = (int)T; q.M = (int)n; q.N = (int)hd; q.K = (int)h;
+  CAAT_STEP("gemm_nn_dgrad", launch_gemm(q, 1, EPI_PLAIN, s))
+  // dWo_m [h,hd] = dZt_m^T H_m (TN, reduction over tokens)
+  std::memset(&q, 0, sizeof(q));
+  q.a = dZt; q.lda = h; q.stride_a = n * h;
+  q.b = H; q.ldb = hd; q.stride_b = n * hd;
+  q.c = (bf16_t*)dwo; q.ldc = hd; q.stride_c = h * hd;
+  q.G = (int)T; q.M = (int)h; q.N = (int)hd; q.K = (int)n;
+  CAAT_STEP("gemm_tn_wgrad", launch_gemm(q, 2, EPI_PLAIN, s))
+  CAAT_STEP("flash_attn_bwd", launch_flash_bwd(QKV, H, dH, stats, dQKV, T * d->batch, d->seq, (int)hd, d->head_dim, s))
+  CAAT_STEP("rope_bwd", launch_rope(dQKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, 0, true, s))
+  // dX_m = dqkv_m Wqkv_m (NN): [n,3hd] x [3hd,h]; not reduced over ranks
+  std::memset(&q, 0, sizeof(q));
+  q.a = dQKV; q.lda = 3 * hd; q.stride_a = n * 3 * hd;
+  q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = 3 * hd * h;
+  q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h;
+  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)(3 * hd);
+  CAAT_STEP("gemm_nn_dgrad", launch_gemm(q, 1, EPI_PLAIN, s))
+  // dWqkv_m [3hd,h] = dqkv_m^T X_m (TN)
+  std::memset(&q, 0, sizeof(q));
+  q.a = dQKV; q.lda = 3 * hd; q.stride_a = n * 3 * hd;
+  q.b = (const bf16_t*)x; q.ldb = h; q.stride_b = n * h;
+  q.c = (bf16_t*)dwqkv; q.ldc = h; q.stride_c = 3 * hd * h;
+  q.G = (int)T; q.M = (int)(3 * hd); q.N = (int)h; q.K = (int)n;
+  CAAT_STEP("gemm_tn_wgrad", launch_gemm(q, 2, EPI_PLAIN, s))
+#undef CAAT_STEP
+  return CAAT_OK;
 }
 
 // One Llama-style decoder layer for one new token per sequence (inference uses the partial channel-reduce too,
@@ -215,7 +289,7 @@ int decode_layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* co
   q.c = QKV; q.ldc = 3 * hd; q.stride_c = n * 3 * hd;
   q.G = (int)T; q.M = (int)n; q.N = (int)(3 * hd); q.K = (int)h;
   CAAT_STEP("gemm_nt_qkv", launch_gemm(q, 0, EPI_PLAIN, s))
-  CAAT_STEP("rope", launch_rope(QKV, T * n, 1, (int)hd, d->head_dim, d->rope_base, d->kv_len, s))
+  CAAT_STEP("rope", launch_rope(QKV, T * n, 1, (int)hd, d->head_dim, d->rope_base, d->kv_len, false, s))
   CAAT_STEP("kv_append", launch_kv_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * n, (int)hpr, (int)hd, d->kv_cap, d->kv_len, s))
   CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)hd,
                                               d->head_dim, d->kv_cap, d->kv_len + 1, s))
@@ -457,6 +531,9 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   if (st != CAAT_OK) return st;
   if (!weights || !dweights || !x || !r_out || !workspace || !dx_out || !dr_out || !dx || !dr || !dgamma)
     return CAAT_EINVAL;
+  if (d->kind == CAAT_ATTN)
+    return attn_block_bwd(d, L, weights, x, r_out, workspace, ws_bytes, dx_out, dr_out, dx, dr, dweights, dgamma, dbeta,
+                          hip_stream);
   if (!is_mlp(d->kind)) return CAAT_EUNSUPPORTED;
   const void* w0 = weights[0]; const void* w1 = weights[1]; const void* gamma = weights[2];
   void* dw0 = dweights[0]; void* dw1 = dweights[1];

@@ -27,8 +27,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t attn_rsrc(const void* p) {
 // ---------------------------------------------------------------------------------------------------------
 // RoPE in place on the q and k column blocks of qkv [rows, 3*hd] (row = rank*tokens + batch*seq + pos):
 // pairs (j, j + d/2), angle pos * base^(-2j/d).  One thread rotates 8 pairs of one head of one row.
+// sign = +1 rotates forward; sign = -1 applies the transpose of that rotation (its inverse), which is what the
+// gradients of the rotated q and k need on their way back to the projection outputs.
 __global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, int seq, int hd, int d, float log2_base,
-                                                   long long pos0) {
+                                                   long long pos0, float sign) {
   const int half = d >> 1;
   const int groups_per_head = half >> 3;            // 8 pairs per thread
   const int heads2 = 2 * (hd / d);                  // q heads then k heads
@@ -53,6 +55,7 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, 
       const float inv = exp2f(-2.0f * (float)j / (float)d * log2_base);
       float s, c;
       sincosf(pos * inv, &s, &c);
+      s *= sign;
       y1[e] = x1[e] * c - x2[e] * s;
       y2[e] = x2[e] * c + x1[e] * s;
     }
@@ -63,12 +66,14 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, 
   *reinterpret_cast<uint4*>(p + half) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
 }
 
-hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int hd, int d, float base, long long pos0, hipStream_t s) {
+hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int hd, int d, float base, long long pos0, bool inverse,
+                       hipStream_t s) {
   const long long work = rows * 2LL * (hd / d) * (d / 16);
   if (work == 0) return hipSuccess;
   const long long blocks = (work + 255) / 256;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, rows, seq, hd, d, log2f(base), pos0);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, rows, seq, hd, d, log2f(base), pos0,
+                     inverse ? -1.0f : 1.0f);
   return hipGetLastError();
 }
 
@@ -78,14 +83,22 @@ static constexpr int BQ = 128;    // queries per workgroup (32 per wave)
 static constexpr int BKV = 64;    // keys per step
 static constexpr int KCH = HD / 8;  // 16-byte chunks per K/V row
 
+// Per-query attention statistics, fp32 [n_seq*heads][2][seq_pad] with seq_pad = seq rounded up to 64: row 0 of a
+// (sequence, head) holds the forward's log2-domain log-sum-exp of the scaled scores, row 1 the backward's
+// D = sum_d dO*O.  Entries seq .. seq_pad-1 are written as 0.
+long long attn_seq_pad(int seq) { return ((long long)seq + 63) / 64 * 64; }
+size_t attn_stats_bytes(long long n_seq, int heads, int seq) { return (size_t)(n_seq * heads * 2 * attn_seq_pad(seq)) * 4; }
+
 // LDS chunk swizzles (chunk = 16 bytes of a 256-byte row): K is read as MFMA fragments (32 consecutive rows, one
 // chunk) -> spread by row & 15; V is read by the transpose read (4 consecutive rows x 64 bytes) -> spread by row & 3.
 __device__ __forceinline__ int kswz(int row, int c) { return c ^ (row & 15); }
 __device__ __forceinline__ int vswz(int row, int c) { return c ^ ((row & 3) << 2); }
 
 // qkv: [T*tokens, 3*hd] with q | k | v column blocks (q, k already rotated); out: [T*tokens, hd]
-__global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out, int seq,
-                                                        int hd, int heads, int n_qblk, float scale_log2) {
+// stats (may be null): the forward fills the log-sum-exp rows (what the backward needs to rebuild the probabilities).
+__global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+                                                        float* __restrict__ stats, int seq, int seq_pad, int hd, int heads,
+                                                        int n_qblk, float scale_log2) {
   __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -240,6 +253,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
 
   // ---- normalise and store: lane holds out[qrow][32dt + 8(r/4) + 4hf + r%4]
   l_run += __shfl_xor(l_run, 32, 64);
+  if (stats != nullptr && hf == 0 && qrow < seq_pad)
+    stats[(long long)bh * 2 * seq_pad + qrow] = qrow < seq ? m_run * scale_log2 + __log2f(l_run) : 0.0f;
   if (qrow < seq) {
     const float inv = 1.0f / l_run;
     bf16_t* o = out + (seq_row0 + qrow) * (long long)hd + (long long)head * HD;
@@ -256,7 +271,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
 }
 
 // qkv [n_seq*seq, 3*hd] (q|k|v, rotated) -> out [n_seq*seq, hd]; n_seq = T*batch sequences, heads = hd / 128 per rank
-hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, long long n_seq, int seq, int hd, int d, hipStream_t s) {
+hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, float* stats, long long n_seq, int seq, int hd, int d,
+                            hipStream_t s) {
   if (d != HD) return hipErrorInvalidValue;
   const int heads = hd / HD;
   const int n_qblk = (seq + BQ - 1) / BQ;
@@ -264,7 +280,357 @@ hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, long long n_seq, int
   if (blocks == 0) return hipSuccess;
   if (blocks > 0x7FFFFFFFLL || (long long)(seq + BKV) * 3 * hd * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)d);
-  hipLaunchKernelGGL(flash_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, out, seq, hd, heads, n_qblk, scale_log2);
+  hipLaunchKernelGGL(flash_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, out, stats, seq, (int)attn_seq_pad(seq), hd,
+                     heads, n_qblk, scale_log2);
+  return hipGetLastError();
+}
+
+
+// ---------------------------------------------------------------------------------------------------------
+// Backward of the attention core (chain rule of Eq. A5's Attention(.)): with S = q k^T / sqrt(d) (causal),
+// P = softmax(S), O = P v and D_i = sum_d dO_id O_id:
+//   dV = P^T dO;  dP = dO V^T;  dS = P o (dP - D);  dQ = dS K / sqrt(d);  dK = dS^T Q / sqrt(d).
+// P is rebuilt from the forward's log-sum-exp, never stored.  Two kernels, each without atomics so that every
+// output element is summed in one fixed order: one owns a block of keys and walks the queries (dK, dV), the other
+// owns a block of queries and walks the keys (dQ).  Both keep the "lane owns one row" register layout of the
+// forward so that the exponentiated score registers are directly the k-slices of the next MFMA.
+//
+// LDS tiles here are read both as row fragments (32 consecutive rows, one 16-byte chunk) and through the transpose
+// read (4 consecutive rows x 64 bytes), so the chunk swizzle spreads 16 consecutive rows over all 16 chunks AND 4
+// consecutive rows over the four 64-byte groups.
+__device__ __forceinline__ int fswz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+// 8 consecutive bf16 of a tile row: chunk index c of row `row` ([rows][16 chunks], swizzled)
+__device__ __forceinline__ bf16x8_t frag_rows(const uint4* tile, int row, int c) {
+  return __builtin_bit_cast(bf16x8_t, tile[row * KCH + (c ^ fswz(row))]);
+}
+// A operand of X^T (X = tile [rows][128]): lane (l%32 = column 32*dt + l%32 of X) receives the 8 rows
+// r16 + 4hf + {0..3} and r16 + 8 + 4hf + {0..3}, the order in which a lane's score registers run over rows
+__device__ __forceinline__ bf16x8_t frag_cols(const uint4* tile, int dt, int r16, int lane) {
+  const int i16 = lane & 15, grp = (lane >> 4) & 1, hf = lane >> 5;
+  const int col = dt * 32 + grp * 16 + (i16 & 3) * 4;
+  const char* base = reinterpret_cast<const char*>(tile);
+  const int row0 = r16 + 4 * hf + (i16 >> 2), row1 = row0 + 8;
+  const char* a0 = base + (row0 * KCH + ((col >> 3) ^ fswz(row0))) * 16 + (col & 7) * 2;
+  const char* a1 = base + (row1 * KCH + ((col >> 3) ^ fswz(row1))) * 16 + (col & 7) * 2;
+  const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)a0);
+  const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)a1);
+  typedef short short8_t __attribute__((ext_vector_type(8)));
+  const short8_t vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+  return __builtin_bit_cast(bf16x8_t, vv);
+}
+// global -> LDS copy of a 64-row x 128-column tile (rows of `ld` elements starting at `src`, rows >= valid read
+// as zero): a wave instruction fills 4 rows, 16 instructions per tile, 4 per wave
+__device__ __forceinline__ void issue_tile64(const bf16_t* src, long long ld, int valid, uint4* tile, int wave, int lane) {
+  const i32x4_t rs = make_rsrc(src);
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int rg = it * 4 + wave;
+    const int row = rg * 4 + (lane >> 4), phys = lane & 15;
+    const unsigned off = row < valid ? (unsigned)((long long)row * ld * 2 + ((phys ^ fswz(row)) * 16)) : OOB_OFF;
+    dma16(rs, off, tile + rg * 64);
+  }
+}
+// 8 fragments (one row of 128, this lane's k-half) straight from global memory
+__device__ __forceinline__ void load_row_frags(const bf16_t* base, long long ld, int row, bool valid, int hf, bf16x8_t* f) {
+  const __amdgpu_buffer_rsrc_t rs = attn_rsrc(base);
+  const unsigned base_off = valid ? (unsigned)((long long)row * ld * 2 + hf * 16) : OOB_OFF;
+#pragma unroll
+  for (int ks = 0; ks < HD / 16; ++ks) {
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(valid ? base_off + ks * 32 : OOB_OFF), 0, 0);
+    f[ks] = __builtin_bit_cast(bf16x8_t, v);
+  }
+}
+__device__ __forceinline__ bf16x8_t pack8(const float* v) {
+  const uint4 w = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+  return __builtin_bit_cast(bf16x8_t, w);
+}
+
+// D rows of the statistics: D[query] = sum_d dO * O, fp32; 16 lanes per (row, head).
+__global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __restrict__ dout, const bf16_t* __restrict__ out,
+                                                            float* __restrict__ stats, long long n_seq, int seq, int seq_pad,
+                                                            int hd, int heads) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int c = (int)(idx & 15);
+  const long long item = idx >> 4;                         // (sequence * heads + head) * seq_pad + pos
+  if (item >= n_seq * heads * seq_pad) return;
+  const int pos = (int)(item % seq_pad);
+  const long long sh = item / seq_pad;
+  const int head = (int)(sh % heads);
+  const long long sq = sh / heads;
+  float acc = 0.0f;
+  if (pos < seq) {
+    const long long o = (sq * seq + pos) * (long long)hd + (long long)head * HD + c * 8;
+    const uint4 a = *reinterpret_cast<const uint4*>(dout + o);
+    const uint4 b = *reinterpret_cast<const uint4*>(out + o);
+    acc = lo_bf(a.x) * lo_bf(b.x) + hi_bf(a.x) * hi_bf(b.x) + lo_bf(a.y) * lo_bf(b.y) + hi_bf(a.y) * hi_bf(b.y) +
+          lo_bf(a.z) * lo_bf(b.z) + hi_bf(a.z) * hi_bf(b.z) + lo_bf(a.w) * lo_bf(b.w) + hi_bf(a.w) * hi_bf(b.w);
+  }
+  acc += __shfl_xor(acc, 1, 64);
+  acc += __shfl_xor(acc, 2, 64);
+  acc += __shfl_xor(acc, 4, 64);
+  acc += __shfl_xor(acc, 8, 64);
+  if (c == 0) stats[(sh * 2 + 1) * seq_pad + pos] = acc;
+}
+
+// ---- dQ: a workgroup owns 128 queries of one (sequence, head), a wave 32 of them (lane = query), keys in blocks of 64.
+//   S^T = K q^T and dP^T = V dO^T (A operand = K / V row fragments from LDS, B operand = q / dO registers);
+//   dS^T registers, rounded to bf16, are the B operand of dQ^T += K^T dS^T (A operand = transpose reads of K).
+__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                           const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
+                                                           int seq_pad, int hd, int heads, int n_qblk, float scale_log2,
+                                                           float scale) {
+  __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int frow = lane & 31, hf = lane >> 5;
+  const int n_bh = gridDim.x / n_qblk;
+  const int qb = n_qblk - 1 - (int)(blockIdx.x / n_bh);      // heaviest (last) query blocks first
+  const int bh = blockIdx.x % n_bh;
+  const int head = bh % heads;
+  const long long seq_row0 = (long long)(bh / heads) * seq;
+  const long long ld = 3LL * hd;
+  const int q0 = qb * BQ;
+  const bf16_t* qbase = qkv + seq_row0 * ld + (long long)head * HD;
+  const bf16_t* kbase = qbase + hd;
+  const bf16_t* vbase = qbase + 2 * hd;
+  const bf16_t* dobase = dout + seq_row0 * (long long)hd + (long long)head * HD;
+  const int qrow = q0 + wave * 32 + frow;
+  const bool qvalid = qrow < seq;
+
+  bf16x8_t qf[HD / 16], dof[HD / 16];
+  load_row_frags(qbase, ld, qrow, qvalid, hf, qf);
+  load_row_frags(dobase, hd, qrow, qvalid, hf, dof);
+  const float my_lse = qvalid ? stats[(long long)bh * 2 * seq_pad + qrow] : 0.0f;
+  const float my_d = qvalid ? stats[((long long)bh * 2 + 1) * seq_pad + qrow] : 0.0f;
+
+  f32x16_t acc[HD / 32];
+#pragma unroll
+  for (int t = 0; t < HD / 32; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+  const int kv_end = min(seq, q0 + BQ);
+  const int nblk = (kv_end + BKV - 1) / BKV;
+  auto issue = [&](int blk, int stage) {
+    const int kv0 = blk * BKV;
+    uint4* kt = smem + stage * (2 * BKV * KCH);
+    issue_tile64(kbase + (long long)kv0 * ld, ld, seq - kv0, kt, wave, lane);
+    issue_tile64(vbase + (long long)kv0 * ld, ld, seq - kv0, kt + BKV * KCH, wave, lane);
+  };
+  issue(0, 0);
+  for (int blk = 0; blk < nblk; ++blk) {
+    const int stage = blk & 1;
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (blk + 1 < nblk) issue(blk + 1, stage ^ 1);
+    const uint4* kt = smem + stage * (2 * BKV * KCH);
+    const uint4* vt = kt + BKV * KCH;
+    const int kv0 = blk * BKV;
+    if (kv0 > q0 + wave * 32 + 31) continue;               // wave-uniform: every key of the block is masked for this wave
+    const bool diag = (kv0 + BKV - 1) > (q0 + wave * 32);  // wave-uniform: some key exceeds some query
+    bf16x8_t dsf[BKV / 16];
+#pragma unroll
+    for (int j = 0; j < BKV / 32; ++j) {
+      f32x16_t sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = 0.0f, pacc[r] = 0.0f;
+      const int row = j * 32 + frow;
+#pragma unroll
+      for (int ks = 0; ks < HD / 16; ++ks) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt, row, ks * 2 + hf), qf[ks], sacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt, row, ks * 2 + hf), dof[ks], pacc, 0, 0, 0);
+      }
+      float ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - my_lse);
+        if (diag) {
+          const int key = kv0 + j * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          p = key > qrow ? 0.0f : p;
+        }
+        ds[r] = p * (pacc[r] - my_d);
+      }
+      dsf[j * 2 + 0] = pack8(ds);
+      dsf[j * 2 + 1] = pack8(ds + 8);
+    }
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+      for (int u = 0; u < BKV / 16; ++u)
+        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt, dt, u * 16, lane), dsf[u], acc[dt], 0, 0, 0);
+  }
+  // lane holds dQ[qrow][32dt + 8(r/4) + 4hf + r%4]
+  if (qvalid) {
+    bf16_t* o = dqkv + (seq_row0 + qrow) * ld + (long long)head * HD;
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint2 w;
+        w.x = pack2bf(acc[dt][q * 4 + 0] * scale, acc[dt][q * 4 + 1] * scale);
+        w.y = pack2bf(acc[dt][q * 4 + 2] * scale, acc[dt][q * 4 + 3] * scale);
+        *reinterpret_cast<uint2*>(o + dt * 32 + q * 8 + hf * 4) = w;
+      }
+  }
+}
+
+// ---- dK, dV: a workgroup owns 128 keys of one (sequence, head), a wave 32 of them (lane = key), queries in blocks of 64
+// from the diagonal to the end of the sequence.  S = Q k^T and dP = dO v^T (A operand = Q / dO row fragments from LDS,
+// B operand = k / v registers); the P and dS registers, rounded to bf16, are the B operands of dV^T += dO^T P and
+// dK^T += Q^T dS (A operands = transpose reads of the same dO and Q tiles).  The per-query lse and D of the block sit
+// next to the tiles in LDS: lane registers run over queries here.
+static constexpr int BQB = 64;                              // queries per step of the dK/dV kernel
+static constexpr int DKV_STAGE = 2 * BQB * KCH + 64;        // uint4 per stage: Q tile, dO tile, 1 KB of statistics
+
+__global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+                                                            const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
+                                                            int seq_pad, int hd, int heads, int n_kblk, float scale_log2,
+                                                            float scale) {
+  __shared__ uint4 smem[2 * DKV_STAGE];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int frow = lane & 31, hf = lane >> 5;
+  const int n_bh = gridDim.x / n_kblk;
+  const int kb = (int)(blockIdx.x / n_bh);                    // heaviest (first) key blocks first
+  const int bh = blockIdx.x % n_bh;
+  const int head = bh % heads;
+  const long long seq_row0 = (long long)(bh / heads) * seq;
+  const long long ld = 3LL * hd;
+  const int k0 = kb * 128;
+  const int kw0 = k0 + wave * 32;
+  const int krow = kw0 + frow;
+  const bool kvalid = krow < seq;
+  const bf16_t* qbase = qkv + seq_row0 * ld + (long long)head * HD;
+  const bf16_t* kbase = qbase + hd;
+  const bf16_t* vbase = qbase + 2 * hd;
+  const bf16_t* dobase = dout + seq_row0 * (long long)hd + (long long)head * HD;
+  const float* stats_bh = stats + (long long)bh * 2 * seq_pad;     // lse row, then D row
+
+  bf16x8_t kf[HD / 16], vf[HD / 16];
+  load_row_frags(kbase, ld, krow, kvalid, hf, kf);
+  load_row_frags(vbase, ld, krow, kvalid, hf, vf);
+
+  f32x16_t dk[HD / 32], dv[HD / 32];
+#pragma unroll
+  for (int t = 0; t < HD / 32; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dk[t][r] = 0.0f, dv[t][r] = 0.0f;
+
+  const int nqb = (seq + BQB - 1) / BQB;
+  const int qb0 = k0 / BQB;
+  auto issue = [&](int qb, int stage) {
+    const int q0 = qb * BQB;
+    uint4* qt = smem + stage * DKV_STAGE;
+    issue_tile64(qbase + (long long)q0 * ld, ld, seq - q0, qt, wave, lane);
+    issue_tile64(dobase + (long long)q0 * hd, hd, seq - q0, qt + BQB * KCH, wave, lane);
+    if (wave == 0) {
+      // lanes 0..15: lse of queries q0 + 4*lane .. +3; lanes 16..31: D likewise; the rest reads zeros.
+      // q0 + 63 < seq_pad always, so the 16-byte pieces stay inside this (sequence, head)'s rows of statistics.
+      const i32x4_t rs = make_rsrc(stats_bh);
+      const unsigned off = lane < 32 ? (unsigned)(((lane >> 4) * seq_pad + q0 + 4 * (lane & 15)) * 4) : OOB_OFF;
+      dma16(rs, off, qt + 2 * BQB * KCH);
+    }
+  };
+  if (qb0 < nqb) issue(qb0, 0);
+  for (int qb = qb0; qb < nqb; ++qb) {
+    const int stage = (qb - qb0) & 1;
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (qb + 1 < nqb) issue(qb + 1, stage ^ 1);
+    const uint4* qt = smem + stage * DKV_STAGE;
+    const uint4* dot = qt + BQB * KCH;
+    const float4* st = reinterpret_cast<const float4*>(qt + 2 * BQB * KCH);
+    const int q0 = qb * BQB;
+#pragma unroll
+    for (int j = 0; j < BQB / 32; ++j) {
+      const int qs = q0 + j * 32;
+      if (qs + 31 < kw0) continue;                           // wave-uniform: all 32 queries precede this wave's keys
+      f32x16_t sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = 0.0f, pacc[r] = 0.0f;
+      const int row = j * 32 + frow;
+#pragma unroll
+      for (int ks = 0; ks < HD / 16; ++ks) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt, row, ks * 2 + hf), kf[ks], sacc, 0, 0, 0);
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot, row, ks * 2 + hf), vf[ks], pacc, 0, 0, 0);
+      }
+      // register r <-> query qs + 8(r/4) + 4hf + r%4, lane <-> key krow
+      const bool diag = qs < kw0 + 31;                        // wave-uniform: some key exceeds some query
+      float pv[16], ds[16];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 l4 = st[8 * j + 2 * i + hf];
+        const float4 d4 = st[16 + 8 * j + 2 * i + hf];
+        const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, dd[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * i + e;
+          float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - ls[e]);
+          if (diag) {
+            const int q = qs + 8 * i + 4 * hf + e;
+            p = krow > q ? 0.0f : p;
+          }
+          pv[r] = p;
+          ds[r] = p * (pacc[r] - dd[e]);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8_t pf = pack8(pv + 8 * t), df = pack8(ds + 8 * t);
+#pragma unroll
+        for (int dt = 0; dt < HD / 32; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot, dt, j * 32 + t * 16, lane), pf, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt, dt, j * 32 + t * 16, lane), df, dk[dt], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // lane holds dK[krow][32dt + 8(r/4) + 4hf + r%4] and dV likewise
+  if (kvalid) {
+    bf16_t* ok = dqkv + (seq_row0 + krow) * ld + hd + (long long)head * HD;
+    bf16_t* ov = ok + hd;
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint2 w;
+        w.x = pack2bf(dk[dt][q * 4 + 0] * scale, dk[dt][q * 4 + 1] * scale);
+        w.y = pack2bf(dk[dt][q * 4 + 2] * scale, dk[dt][q * 4 + 3] * scale);
+        *reinterpret_cast<uint2*>(ok + dt * 32 + q * 8 + hf * 4) = w;
+        w.x = pack2bf(dv[dt][q * 4 + 0], dv[dt][q * 4 + 1]);
+        w.y = pack2bf(dv[dt][q * 4 + 2], dv[dt][q * 4 + 3]);
+        *reinterpret_cast<uint2*>(ov + dt * 32 + q * 8 + hf * 4) = w;
+      }
+  }
+}
+
+// Backward of the attention core for every (sequence, head): qkv (rotated q | k | v), out = forward output, dout its
+// gradient, stats with the forward's lse rows -> dqkv (gradients w.r.t. the ROTATED q, k and w.r.t. v, same layout
+// as qkv).  The D rows of stats are filled here.
+hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, float* stats, bf16_t* dqkv,
+                            long long n_seq, int seq, int hd, int d, hipStream_t s) {
+  if (d != HD) return hipErrorInvalidValue;
+  const int heads = hd / HD;
+  const long long n_bh = n_seq * heads;
+  if (n_bh == 0 || seq == 0) return hipSuccess;
+  const int seq_pad = (int)attn_seq_pad(seq);
+  const int n_qblk = (seq + BQ - 1) / BQ;
+  if (n_bh * n_qblk > 0x7FFFFFFFLL || (long long)(seq + 128) * 3 * hd * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+  const float scale_log2 = 1.4426950408889634f * inv_sqrt_d;
+  const long long prep_threads = n_bh * seq_pad * 16;
+  if ((prep_threads + 255) / 256 > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(attn_bwd_prep_kernel, dim3((unsigned)((prep_threads + 255) / 256)), dim3(256), 0, s, dout, out, stats, n_seq,
+                     seq, seq_pad, hd, heads);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(flash_bwd_dkv_kernel, dim3((unsigned)(n_bh * n_qblk)), dim3(256), 0, s, qkv, dout, stats, dqkv, seq, seq_pad,
+                     hd, heads, n_qblk, scale_log2, inv_sqrt_d);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(flash_bwd_dq_kernel, dim3((unsigned)(n_bh * n_qblk)), dim3(256), 0, s, qkv, dout, stats, dqkv, seq, seq_pad,
+                     hd, heads, n_qblk, scale_log2, inv_sqrt_d);
   return hipGetLastError();
 }
 

@@ -1,4 +1,5 @@
-"""GPU parity of the attention sub-block forward (Eq. A5 + Sec. 4) against the CPU oracle, through the C ABI."""
+"""GPU parity of the attention sub-block forward and backward (Eq. A5 + Sec. 4, Fig. 2b) against the CPU oracle,
+through the C ABI."""
 import numpy as np
 import pytest
 
@@ -10,7 +11,7 @@ from tests.util import assert_close, bits_to_f64
 pytestmark = pytest.mark.gpu
 
 
-def run_attn_block(cfg, d):
+def run_attn_block(cfg, d, backward=False):
     import torch
     desc = B.make_desc(cfg)
     ln = cfg.norm == I.NORM_LAYERNORM
@@ -31,15 +32,45 @@ def run_attn_block(cfg, d):
     out["Rp"], out["Xp"] = bits_to_f64(out["Rp_bits"]), bits_to_f64(out["Xp_bits"])
     out["QKV"] = ws_bf16(L.off_Q, L.bytes_Q, (T, n, 3 * hd))
     out["H"] = ws_bf16(L.off_Y, L.bytes_Y, (T, n, hd))
+    if backward:
+        dxo, dro = B.to_device(d["dXo"]), B.to_device(d["dRo"])
+        dx, dr = torch.empty_like(x), torch.empty_like(x)
+        dwqkv, dwo = torch.empty_like(weights[0]), torch.empty_like(weights[1])
+        dgamma = torch.empty(h, dtype=torch.float32, device="cuda")
+        dbeta = torch.empty(h, dtype=torch.float32, device="cuda") if ln else None
+        B.block_bwd(desc, weights, x, r_out, ws, dxo, dro, dx, dr, [dwqkv, dwo], dgamma, dbeta)
+        torch.cuda.synchronize()
+        out["dX"], out["dR"] = bits_to_f64(B.to_host_bits(dx)), bits_to_f64(B.to_host_bits(dr))
+        out["dWqkv"], out["dWo"] = bits_to_f64(B.to_host_bits(dwqkv)), bits_to_f64(B.to_host_bits(dwo))
+        out["dgamma"] = dgamma.cpu().numpy().astype(np.float64)
+        if ln:
+            out["dbeta"] = dbeta.cpu().numpy().astype(np.float64)
+        out["dZt"] = ws_bf16(L.off_dZt, L.bytes_dZt, (T, n, h))
+        out["dH"] = ws_bf16(L.off_dH, L.bytes_dH, (T, n, hd))
+        out["dqkv"] = ws_bf16(L.off_dP, L.bytes_dP, (T, n, 3 * hd))
     return out
+
+
+def _oracle_kw(cfg):
+    norm = O.LAYERNORM if cfg.norm == I.NORM_LAYERNORM else O.RMSNORM
+    return dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim, norm=norm,
+                hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base)
 
 
 def oracle_attn_block(cfg, d):
     w = {k: O.widen_bf16(v) for k, v in d.items()}
-    norm = O.LAYERNORM if cfg.norm == I.NORM_LAYERNORM else O.RMSNORM
-    return w, O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], w.get("beta"), batch=cfg.batch,
-                               seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim, norm=norm,
-                               hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base)
+    return w, O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], w.get("beta"), **_oracle_kw(cfg))
+
+
+def oracle_attn_bwd(cfg, w, fwd):
+    return O.attn_block_bwd(w["X"], fwd, w["Wqkv"], w["Wo"], w["gamma"], w["dXo"], w["dRo"], **_oracle_kw(cfg))
+
+
+def check_attn_bwd(got, g):
+    for name in ("dR", "dZt", "dH", "dqkv", "dX", "dWo", "dWqkv", "dgamma"):
+        assert_close(got[name], g[name], name)
+    if "dbeta" in g:
+        assert_close(got["dbeta"], g["dbeta"], "dbeta")
 
 
 def check_attn(cfg, d, got, fwd):
@@ -89,3 +120,42 @@ def test_attn_causal_on_gpu():
     b = run_attn_block(cfg, d2)
     assert np.array_equal(a["Rp_bits"][:, :100], b["Rp_bits"][:, :100])
     assert not np.array_equal(a["Rp_bits"][:, 100:], b["Rp_bits"][:, 100:])
+
+
+@pytest.mark.parametrize("T,batch,seq,heads,p,norm,scale", [
+    (2, 1, 64, 2, 0.5, I.NORM_RMSNORM, 1.0),         # one key block, one query block
+    (2, 2, 200, 4, 0.5, I.NORM_RMSNORM, 1.0),        # ragged: 2 key blocks of 128, 4 query blocks of 64, tail of 8
+    (1, 1, 333, 2, 1.0, I.NORM_LAYERNORM, 1.0),      # T = 1, p = 1, LayerNorm (dbeta)
+    (4, 1, 130, 4, 0.0, I.NORM_RMSNORM, 2.0),        # p = 0 with private-channel scaling sqrt(T), just past one block
+    (2, 3, 1, 2, 0.25, I.NORM_RMSNORM, 1.0),         # seq = 1: P = 1, dS = 0, so dq = dk = 0 and dv = dH
+    (2, 1, 450, 2, 0.3, I.NORM_RMSNORM, 1.0),        # hs not a multiple of 8, 4 key blocks, tail of 2
+])
+def test_attn_block_bwd(T, batch, seq, heads, p, norm, scale):
+    cfg = _cfg(T, batch, seq, heads, p, norm, scale)
+    d = I.make_inputs(cfg, seed=23, with_grads=True, weight_std=0.05)
+    got = run_attn_block(cfg, d, backward=True)
+    w, fwd = oracle_attn_block(cfg, d)
+    check_attn(cfg, d, got, fwd)
+    g = oracle_attn_bwd(cfg, w, fwd)
+    check_attn_bwd(got, g)
+    if seq == 1:
+        hd = cfg.hd_r
+        dqkv = got["dqkv"].reshape(T, batch, 3, hd)
+        # dS = P (dP - D) with P = 1 and dP = D up to the summation order of two fp32 dot products
+        assert np.abs(dqkv[:, :, :2]).max() <= 1e-4 * np.abs(dqkv[:, :, 2]).max()
+        assert np.array_equal(dqkv[:, :, 2], got["dH"].reshape(T, batch, hd))
+
+
+def test_attn_bwd_causal_on_gpu():
+    """An upstream gradient that is zero at positions < i gives dq rows < i that are exactly zero, while the keys and
+    values before i still receive gradient from the later queries: gradients flow from queries to earlier keys."""
+    cfg = _cfg(2, 1, 192, 2, 0.5)
+    d = I.make_inputs(cfg, seed=24, with_grads=True, weight_std=0.05)
+    d["dXo"][:, :100] = 0
+    d["dRo"][:, :100] = 0
+    got = run_attn_block(cfg, d, backward=True)
+    hd = cfg.hd_r
+    dq = got["dqkv"][:, :, :hd]
+    assert not dq[:, :100].any()            # queries before position 100 received no gradient
+    assert dq[:, 100:].any()
+    assert got["dqkv"][:, :100, hd:].any()  # earlier keys / values do receive gradient from later queries
