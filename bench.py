@@ -172,22 +172,31 @@ def cpu_baseline(cfg, host, sample_tokens):
 
 
 class AttnBench(MlpBench):
-    """Attention sub-block forward (C4): QKV GEMM, RoPE, causal attention, o_proj + partial sync, norm."""
+    """Attention sub-block (C4): forward = QKV GEMM, RoPE, causal attention, o_proj + partial sync, norm; backward =
+    norm backward, partial sync, o_proj gradients, attention-core gradient, inverse RoPE, QKV gradients."""
 
-    def __init__(self, cfg, seed=0):
+    def __init__(self, cfg, seed=0, backward=True):
         import torch
         from paper_2506_19645_amd import binding as B
         from paper_2506_19645_amd import inputs as I
-        self.B, self.torch, self.cfg = B, torch, cfg
-        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.h // 2, with_grads=False)
+        self.B, self.torch, self.cfg, self.backward = B, torch, cfg, backward
+        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.h // 2, with_grads=backward)
         self.host = d
         self.weights = [B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]), None]
         self.x, self.r = B.to_device(d["X"]), B.to_device(d["R"])
         self.r_out, self.x_out = torch.empty_like(self.x), torch.empty_like(self.x)
         self.ws = torch.empty(B.workspace_bytes(B.make_desc(cfg)), dtype=torch.uint8, device="cuda")
+        if backward:
+            self.dxo, self.dro = B.to_device(d["dXo"]), B.to_device(d["dRo"])
+            self.dx, self.dr = torch.empty_like(self.x), torch.empty_like(self.x)
+            self.dw = [torch.empty_like(self.weights[0]), torch.empty_like(self.weights[1])]
+            self.dgamma = torch.empty(cfg.h, dtype=torch.float32, device="cuda")
 
     def step(self, desc):
         self.B.block_fwd(desc, self.weights, self.x, self.r, self.r_out, self.x_out, self.ws)
+        if self.backward:
+            self.B.block_bwd(desc, self.weights, self.x, self.r_out, self.ws, self.dxo, self.dro, self.dx, self.dr,
+                             self.dw, self.dgamma, None)
 
 
 class DecodeBench(MlpBench):
@@ -213,19 +222,29 @@ class DecodeBench(MlpBench):
 
 
 def bench_attention_kinds(args, cfg, base):
-    """JSON for the attention forward (C4, TFLOP/s) and the decode layer (C5, GB/s and per-token latency)."""
+    """JSON for the attention sub-block (C4, TFLOP/s) and the decode layer (C5, GB/s and per-token latency)."""
     from paper_2506_19645_amd import binding as B
     T, n, h, hd = cfg.T, cfg.tokens, cfg.h, cfg.hd_r
     if args.config == "C4":
-        bench = AttnBench(cfg)
+        bwd = not args.fwd_only
+        bench = AttnBench(cfg, backward=bwd)
         s = cfg.seq
         fl = {"gemm_nt_qkv": 2.0 * n * h * 3 * h, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,   # causal half of 4 s^2 h
               "gemm_nt_rowpar": 2.0 * n * h * h}
         by = {"rope": 2.0 * T * n * 2 * hd * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
               "norm_fwd": 2.0 * T * n * h * 2}
-        work, unit, peak = sum(fl.values()), "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
-        workload = "%s attention sub-block fwd: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
-            cfg.name, h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, cfg.hs)
+        work = sum(fl.values())
+        if bwd:
+            # five contractions instead of two in the attention core; the two NN and the two TN launches of a step
+            # (o_proj: 2nh^2, qkv: 6nh^2) share a kernel family, so the per-launch figure is their mean
+            fl.update({"flash_attn_bwd": 5.0 * cfg.batch * s * s * h, "gemm_nn_dgrad": 4.0 * n * h * h,
+                       "gemm_tn_wgrad": 4.0 * n * h * h})
+            by.update({"rope_bwd": 2.0 * T * n * 2 * hd * 2, "partial_sync_bwd": 2.0 * T * n * cfg.hs * 2,
+                       "norm_bwd": 5.0 * T * n * h * 2})
+            work += 5.0 * cfg.batch * s * s * h + 16.0 * n * h * h
+        unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
+        workload = "%s attention sub-block %s: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
+            cfg.name, "fwd+bwd" if bwd else "fwd", h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, cfg.hs)
     else:
         bench = DecodeBench(cfg)
         fr = cfg.f_r
@@ -289,6 +308,7 @@ def main():
     ap.add_argument("--p", type=float, default=0.5)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--fwd-only", action="store_true", help="C4: time the forward alone")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known size) so that a rocprofv3 --pmc run can scale "

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2506_19645_amd import inputs as I
-from tests.test_gpu_attn import check_attn, oracle_attn_block, run_attn_block
+from tests.test_gpu_attn import check_attn, check_attn_bwd, oracle_attn_block, oracle_attn_bwd, run_attn_block
 from tests.test_gpu_block import check_mlp_block, oracle_mlp_block, run_mlp_block
 from tests.test_gpu_decode import run_decode
 from tests.util import assert_close, bits_to_f64
@@ -51,12 +51,13 @@ def test_config3_llama_mlp_full_size():
 
 
 def test_config4_llama_attention_full_size():
-    """h=4096, 32 heads of 128, RoPE, causal, seq 4096, T=8, p=0.5, forward."""
+    """h=4096, 32 heads of 128, RoPE, causal, seq 4096, T=8, p=0.5, forward + backward."""
     cfg = I.C4
-    d = I.make_inputs(cfg, seed=0, with_grads=False)
-    got = run_attn_block(cfg, d)
+    d = I.make_inputs(cfg, seed=0)
+    got = run_attn_block(cfg, d, backward=True)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
+    check_attn_bwd(got, oracle_attn_bwd(cfg, w, fwd))
 
 
 def test_config5_llama_decode_full_size():
