@@ -432,6 +432,36 @@ def decode_layer_fwd(R, W: Dict[str, np.ndarray], Kc, Vc, *, kv_len: int, heads_
     return {"X1": X1, "H": Hall, "Zt": Zt, "R1": R1, "X2": X2, "Zt2": Zt2, "R2": R2, "k_new": k_new, "v_new": v_new}
 
 
+def prefill_layer_fwd(R, W: Dict[str, np.ndarray], *, batch: int, seq: int, heads_per_rank: int, head_dim: int,
+                      hs: int, eps: float = 1e-5, private_scale: float = 1.0,
+                      rope_base: float = 10000.0) -> Dict[str, np.ndarray]:
+    """One Llama-style decoder layer over a whole prompt (the time-to-first-token workload of Sec. 5.2): the
+    attention sub-block of Eq. A5 followed by the SwiGLU MLP sub-block of Eq. A3, each closed by its partial
+    channel-reduce and residual add, RMSNorm in front of each (Sec. 4).
+
+    R: [T, batch*seq, h] per-rank residual stream.  W as for decode_layer_fwd.
+      X1 = RMSNorm(R; gamma_attn); attention sub-block on (X1, R) -> R1 = R + PCR(H Wo), X2 = RMSNorm(R1; gamma)
+      MLP sub-block on (X2, R1)  -> R2 = R1 + PCR((silu(X2 Wg) * (X2 Wu)) B)
+    Returns R1, X2, R2, intermediates and the rotated keys K and the values V [T, batch, heads_per_rank, seq, d]
+    that a KV cache holds after the prompt.
+    """
+    X1, _, _ = norm_fwd(R, W["gamma_attn"], None, RMSNORM, eps)
+    att = attn_block_fwd(X1, R, W["Wqkv"], W["Wo"], W["gamma"], None, batch=batch, seq=seq,
+                         heads_per_rank=heads_per_rank, head_dim=head_dim, norm=RMSNORM, hs=hs, eps=eps,
+                         private_scale=private_scale, rope_base=rope_base)
+    R1, X2 = att["Rp"], att["Xp"]
+    T = R.shape[0]
+    Zt2 = np.empty_like(R)
+    Ys = []
+    for m in range(T):
+        Y = silu(X2[m] @ W["Wg"][m].T) * (X2[m] @ W["Wu"][m].T)
+        Ys.append(Y)
+        Zt2[m] = Y @ W["B"][m].T
+    R2 = R1 + partial_channel_reduce(Zt2, hs, private_scale)
+    return {"X1": X1, "Q": att["Q"], "K": att["K"], "V": att["V"], "H": att["H"], "Zt": att["Zt"], "R1": R1, "X2": X2,
+            "Y": np.stack(Ys), "Zt2": Zt2, "R2": R2}
+
+
 # ----------------------------------------------------------------------------- App. C closed forms
 def comm_payload_elements(s: int, h: int, p: float) -> float:
     """P(p) = 2 s h p elements per device per layer forward (App. C)."""

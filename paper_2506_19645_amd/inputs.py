@@ -27,6 +27,7 @@ KIND_MLP_GELU = 0
 KIND_MLP_SWIGLU = 1
 KIND_ATTN = 2
 KIND_DECODE = 3
+KIND_PREFILL = 4
 NORM_LAYERNORM = 0
 NORM_RMSNORM = 1
 
@@ -81,7 +82,11 @@ C4 = BlockConfig("C4-llama7b-attn", KIND_ATTN, NORM_RMSNORM, h=4096, T=8, p=0.5,
                  n_heads=32, head_dim=128)
 C5 = BlockConfig("C5-llama7b-decode", KIND_DECODE, NORM_RMSNORM, h=4096, T=8, p=0.5, batch=64, seq=1,
                  ffn=11008, n_heads=32, head_dim=128, kv_len=2048)
-CONFIGS = {c.name.split("-")[0]: c for c in (C1, C2, C3, C4, C5)}
+# Beyond the five: one decoder layer over a whole prompt batch, the shape of the paper's time-to-first-token runs
+# (Sec. 5.2: 2K-token prompts, batch 16 and up, Llama-7B dimensions, TP 8).
+C6 = BlockConfig("C6-llama7b-prefill-layer", KIND_PREFILL, NORM_RMSNORM, h=4096, T=8, p=0.5, batch=16, seq=2048,
+                 ffn=11008, n_heads=32, head_dim=128)
+CONFIGS = {c.name.split("-")[0]: c for c in (C1, C2, C3, C4, C5, C6)}
 
 
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
@@ -116,13 +121,14 @@ def _small_int_bf16(rng: np.random.Generator, shape, lo: int = -3, hi: int = 3) 
     return f32_to_bf16_bits(rng.integers(lo, hi + 1, size=shape).astype(np.float32))
 
 
-def _activations(rng, cfg: BlockConfig, n: int, mode: str, hs_struct: Optional[int]):
+def _activations(rng, cfg: BlockConfig, n: int, mode: str, hs_struct: Optional[int], with_x: bool = True):
     """X_m ~ N(0,1) per rank; R_m ~ N(0,1) with its shared columns equal on all ranks."""
     T, h = cfg.T, cfg.h
-    X = _normal_bf16(rng, (T, n, h))
+    X = _normal_bf16(rng, (T, n, h)) if with_x else None
     R = _normal_bf16(rng, (T, n, h))
     if mode == "replicated":
-        X[1:] = X[0]
+        if with_x:
+            X[1:] = X[0]
         R[1:] = R[0]
     elif mode == "divergent":
         k = cfg.hs if hs_struct is None else hs_struct
@@ -147,7 +153,10 @@ def make_inputs(cfg: BlockConfig, seed: int = 0, mode: str = "divergent", with_g
     rng = np.random.default_rng(seed)
     T, h, n = cfg.T, cfg.h, cfg.tokens
     d: Dict[str, np.ndarray] = {}
-    d["X"], d["R"] = _activations(rng, cfg, n, mode, hs_struct)
+    if cfg.kind == KIND_PREFILL:       # the layer normalises R itself: no X is drawn
+        _, d["R"] = _activations(rng, cfg, n, mode, hs_struct, with_x=False)
+    else:
+        d["X"], d["R"] = _activations(rng, cfg, n, mode, hs_struct)
     if cfg.kind == KIND_MLP_GELU:
         d["A"] = _normal_bf16(rng, (T, cfg.f_r, h), std=weight_std)        # column-parallel shard, [out,in]
         d["B"] = _normal_bf16(rng, (T, h, cfg.f_r), std=weight_std)        # row-parallel shard, [out,in]
@@ -158,7 +167,7 @@ def make_inputs(cfg: BlockConfig, seed: int = 0, mode: str = "divergent", with_g
     elif cfg.kind == KIND_ATTN:
         d["Wqkv"] = _normal_bf16(rng, (T, 3 * cfg.hd_r, h), std=weight_std)  # rows: q heads, k heads, v heads
         d["Wo"] = _normal_bf16(rng, (T, h, cfg.hd_r), std=weight_std)
-    elif cfg.kind == KIND_DECODE:
+    elif cfg.kind in (KIND_DECODE, KIND_PREFILL):
         d["gamma_attn"] = _normal_bf16(rng, (h,), mean=1.0, std=0.1)
         d["Wqkv"] = _normal_bf16(rng, (T, 3 * cfg.hd_r, h), std=weight_std)
         d["Wo"] = _normal_bf16(rng, (T, h, cfg.hd_r), std=weight_std)
@@ -170,7 +179,7 @@ def make_inputs(cfg: BlockConfig, seed: int = 0, mode: str = "divergent", with_g
     d["gamma"] = _normal_bf16(rng, (h,), mean=1.0, std=0.1)
     if cfg.norm == NORM_LAYERNORM:
         d["beta"] = _normal_bf16(rng, (h,), std=0.1)
-    if with_grads and cfg.kind != KIND_DECODE:
+    if with_grads and cfg.kind not in (KIND_DECODE, KIND_PREFILL):
         d["dXo"] = _normal_bf16(rng, (T, n, h))   # dL/dX'
         d["dRo"] = _normal_bf16(rng, (T, n, h))   # dL/dR'
     if cfg.kind == KIND_DECODE:

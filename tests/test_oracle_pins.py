@@ -595,6 +595,80 @@ def test_decode_equals_last_row_of_prefill():
     np.testing.assert_allclose(dec["R2"], mlp["Rp"], atol=1e-13)
 
 
+# --------------------------------------------------------------------------- prefill layer
+def _tiny_prefill(T=2, b=2, heads=4, d=4, seq=6, f=24, p=0.5, seed=3, mode="divergent"):
+    cfg = I.BlockConfig("tinypre", I.KIND_PREFILL, I.NORM_RMSNORM, h=heads * d, T=T, p=p, batch=b, seq=seq, ffn=f,
+                        n_heads=heads, head_dim=d)
+    dd = I.make_inputs(cfg, seed=seed, weight_std=0.3, mode=mode)
+    return cfg, {k: O.widen_bf16(v) for k, v in dd.items()}
+
+
+def test_prefill_layer_last_row_equals_decode_step():
+    """A prompt of L+1 tokens through the prefill layer gives, in its last row, what the decode step gives for token
+    L over the cache that the first L prompt tokens left (same weights): both halves of the layer, R1 and R2."""
+    L = 5
+    cfg, w = _tiny_prefill(seq=L + 1)
+    hpr, d = cfg.n_heads // cfg.T, cfg.head_dim
+    pre = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, hs=cfg.hs)
+    Kc = np.zeros((cfg.T, cfg.batch, hpr, L + 1, d))
+    Vc = np.zeros_like(Kc)
+    Kc[:, :, :, :L] = pre["K"][:, :, :, :L]
+    Vc[:, :, :, :L] = pre["V"][:, :, :, :L]
+    last = [s * (L + 1) + L for s in range(cfg.batch)]
+    dec = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=cfg.hs)
+    np.testing.assert_allclose(dec["R1"], pre["R1"][:, last], atol=1e-12)
+    np.testing.assert_allclose(dec["R2"], pre["R2"][:, last], atol=1e-12)
+    np.testing.assert_allclose(dec["k_new"], pre["K"][:, :, :, L], atol=1e-13)
+    np.testing.assert_allclose(dec["v_new"], pre["V"][:, :, :, L], atol=1e-13)
+
+
+def test_prefill_layer_p1_replicated_equals_dense_llama_layer():
+    """p = 1 with replicated inputs is ordinary tensor parallelism, so every rank's output equals the dense layer with
+    the shards concatenated; the dense layer is written here independently (complex-number RoPE, per-head loops)."""
+    cfg, w = _tiny_prefill(T=2, b=1, heads=4, d=4, seq=5, f=24, p=1.0, seed=8, mode="replicated")
+    T, h, d, s = cfg.T, cfg.h, cfg.head_dim, cfg.seq
+    hpr, hd = cfg.n_heads // T, cfg.hd_r
+    out = O.prefill_layer_fwd(w["R"], w, batch=1, seq=s, heads_per_rank=hpr, head_dim=d, hs=cfg.hs)
+    x = w["R"][0]
+
+    def rms(v, g):
+        return v / np.sqrt((v * v).mean(-1, keepdims=True) + 1e-5) * g
+
+    x1 = rms(x, w["gamma_attn"])
+    att = np.zeros_like(x)
+    for m in range(T):
+        qkv = x1 @ w["Wqkv"][m].T
+        for a in range(hpr):
+            def rot(t):
+                z = (t[:, :d // 2] + 1j * t[:, d // 2:]) * np.exp(
+                    1j * np.arange(s)[:, None] * 10000.0 ** (-2.0 * np.arange(d // 2) / d)[None, :])
+                return np.concatenate([z.real, z.imag], axis=1)
+            q, k = rot(qkv[:, a * d:(a + 1) * d]), rot(qkv[:, hd + a * d:hd + (a + 1) * d])
+            v = qkv[:, 2 * hd + a * d:2 * hd + (a + 1) * d]
+            att += _naive_attention(q, k, v) @ w["Wo"][m][:, a * d:(a + 1) * d].T
+    r1 = x + att
+    x2 = rms(r1, w["gamma"])
+    Wg, Wu = np.concatenate(list(w["Wg"]), axis=0), np.concatenate(list(w["Wu"]), axis=0)
+    Bd = np.concatenate(list(w["B"]), axis=1)
+    g = x2 @ Wg.T
+    r2 = r1 + ((g / (1.0 + np.exp(-g))) * (x2 @ Wu.T)) @ Bd.T
+    for m in range(T):
+        np.testing.assert_allclose(out["R1"][m], r1, atol=1e-11)
+        np.testing.assert_allclose(out["R2"][m], r2, atol=1e-11)
+
+
+def test_prefill_layer_p0_keeps_ranks_independent():
+    """p = 0: no channel is shared, so rank m's output depends on rank m's residual stream only."""
+    cfg, w = _tiny_prefill(p=0.0)
+    kw = dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim, hs=0)
+    a = O.prefill_layer_fwd(w["R"], w, **kw)
+    R2 = w["R"].copy()
+    R2[1] += 0.5
+    b = O.prefill_layer_fwd(R2, w, **kw)
+    assert np.array_equal(a["R2"][0], b["R2"][0])
+    assert not np.array_equal(a["R2"][1], b["R2"][1])
+
+
 # --------------------------------------------------------------------------- App. C closed forms
 def test_comm_model_closed_forms():
     s, h = 2048, 4096
