@@ -47,7 +47,9 @@ typedef enum caat_kind {
   CAAT_MLP_GELU = 0,    /* Y = gelu(X A),               LayerNorm or RMSNorm after the residual */
   CAAT_MLP_SWIGLU = 1,  /* Y = silu(X Wg) * (X Wu) */
   CAAT_ATTN = 2,        /* causal multi-head attention with RoPE, prefill / training forward and backward */
-  CAAT_ATTN_DECODE = 3  /* full decoder layer (attention + SwiGLU MLP), one new token per sequence */
+  CAAT_ATTN_DECODE = 3, /* full decoder layer (attention + SwiGLU MLP), one new token per sequence */
+  CAAT_LAYER_PREFILL = 4 /* the same decoder layer over a whole prompt (batch x seq tokens) that fills the KV cache:
+                            the time-to-first-token workload of Sec. 5.2; forward only */
 } caat_kind;
 
 typedef enum caat_norm { CAAT_LAYERNORM = 0, CAAT_RMSNORM = 1 } caat_norm;
@@ -74,8 +76,8 @@ typedef struct caat_desc {
   long long tokens;     /* batch*seq */
   int batch, seq;       /* attention kinds need both; MLP kinds only use tokens */
   int n_heads, head_dim;/* attention kinds; each rank owns n_heads/T heads */
-  long long kv_len;     /* decode: number of filled cache positions; the new token sits at kv_len */
-  long long kv_cap;     /* decode: capacity (positions) of the cache buffers, > kv_len */
+  long long kv_len;     /* decode: number of filled cache positions; the new token sits at kv_len.  prefill: 0 */
+  long long kv_cap;     /* decode: capacity (positions) of the cache buffers, > kv_len; prefill: >= seq */
   float eps;            /* norm epsilon */
   float private_scale;  /* factor applied to private channels (Sec. 4 private channel scaling,
                            sqrt(T) in the paper); 1.0f switches it off */
@@ -95,8 +97,8 @@ typedef struct caat_ws_layout {
                                   un-rotated projections [T,tokens,3*hd_r], column blocks dq | dk | dv */
   size_t off_Q, bytes_Q;       /* attention: projections [T,tokens,3*hd_r], column blocks q | k | v, q and k rotated (RoPE) */
   size_t off_scratch, bytes_scratch;
-  /* decode layer only: attention heads output [T,batch,hd_r]; first norm output X1, residual after the attention
-   * half R1 and second norm output X2, each [T,batch,h] */
+  /* decode and prefill layers only: attention heads output [T,tokens,hd_r]; first norm output X1, residual after the
+   * attention half R1 and second norm output X2, each [T,tokens,h] */
   size_t off_H, bytes_H;
   size_t off_X1, bytes_X1;
   size_t off_R1, bytes_R1;
@@ -173,11 +175,12 @@ int caat_gemm_bf16(const void* a, const void* b, void* c, int layout, int G, lon
  *     CAAT_MLP_SWIGLU : {Wgu [T][2*ffn/T][h] (gate rows then up rows), B [T][h][ffn/T], gamma, beta or NULL}
  *     CAAT_ATTN       : {Wqkv [T][3*hd_r][h] (q rows, k rows, v rows; heads contiguous), Wo [T][h][hd_r],
  *                        gamma, beta or NULL},  hd_r = (n_heads/T)*head_dim
- *     CAAT_ATTN_DECODE: {gamma_attn [h], Wqkv, Wo, gamma_mlp [h], Wgu, B}; RMSNorm only
- *   x, r       : [T,tokens,h] inputs (x already normalised; decode ignores x and normalises r itself)
+ *     CAAT_ATTN_DECODE, CAAT_LAYER_PREFILL: {gamma_attn [h], Wqkv, Wo, gamma_mlp [h], Wgu, B}; RMSNorm only
+ *   x, r       : [T,tokens,h] inputs (x already normalised; the layer kinds ignore x and normalise r themselves)
  *   r_out      : [T,tokens,h] new residual stream R'
- *   x_out      : [T,tokens,h] Norm(R'); decode: may be NULL (not produced)
- *   kv_k, kv_v : decode only, [T][batch][n_heads/T][kv_cap][head_dim]; row kv_len is written
+ *   x_out      : [T,tokens,h] Norm(R'); layer kinds: may be NULL (not produced)
+ *   kv_k, kv_v : layer kinds only, [T][batch][n_heads/T][kv_cap][head_dim]; decode writes row kv_len, prefill
+ *                rows 0 .. seq-1 (rotated keys, values)
  *   workspace  : caat_workspace_bytes(d) bytes; keeps what caat_block_bwd needs
  */
 int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x, const void* r, void* r_out,
@@ -188,7 +191,7 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
  * gradient dr_m = g_m un-reduced, the SAME partial channel-reduce on g (fp32 accumulation), then the chain
  * rule of Eq. A3 / A5 per rank (for CAAT_ATTN: o_proj, the causal attention core rebuilt from the saved
  * softmax statistics, the inverse RoPE rotation, the q/k/v projections); dx_m is NOT reduced over ranks.
- * CAAT_ATTN_DECODE has no backward (CAAT_EUNSUPPORTED).
+ * The layer kinds have no backward (CAAT_EUNSUPPORTED).
  *   x, r_out           : the forward's input x and output r_out
  *   workspace          : the forward's workspace (also used as scratch here)
  *   dx_out, dr_out     : [T,tokens,h] gradients w.r.t. x_out and r_out

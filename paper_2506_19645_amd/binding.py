@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcaat.so")
 
 OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EHIP, EUNSUPPORTED = range(7)
-MLP_GELU, MLP_SWIGLU, ATTN, ATTN_DECODE = range(4)
+MLP_GELU, MLP_SWIGLU, ATTN, ATTN_DECODE, LAYER_PREFILL = range(5)
 LAYERNORM, RMSNORM = 0, 1
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
 
@@ -131,11 +131,14 @@ def to_host_bits(t) -> np.ndarray:
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def make_desc(cfg, hs: Optional[int] = None) -> caat_desc:
-    """caat_desc from a paper_2506_19645_amd.inputs.BlockConfig."""
+def make_desc(cfg, hs: Optional[int] = None, kv_cap: Optional[int] = None) -> caat_desc:
+    """caat_desc from a paper_2506_19645_amd.inputs.BlockConfig (cache capacity: one position more than what the
+    call fills, unless given)."""
+    if kv_cap is None:
+        kv_cap = cfg.seq + 1 if cfg.kind == LAYER_PREFILL else cfg.kv_len + 1
     return caat_desc(kind=cfg.kind, norm=cfg.norm, h=cfg.h, ffn=cfg.ffn, T=cfg.T,
                      hs=cfg.hs if hs is None else hs, tokens=cfg.tokens, batch=cfg.batch, seq=cfg.seq,
-                     n_heads=cfg.n_heads, head_dim=cfg.head_dim, kv_len=cfg.kv_len, kv_cap=cfg.kv_len + 1,
+                     n_heads=cfg.n_heads, head_dim=cfg.head_dim, kv_len=cfg.kv_len, kv_cap=kv_cap,
                      eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base)
 
 

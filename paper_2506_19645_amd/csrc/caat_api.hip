@@ -45,20 +45,21 @@ struct ProfScope {
 };
 
 bool is_mlp(int kind) { return kind == CAAT_MLP_GELU || kind == CAAT_MLP_SWIGLU; }
+bool is_layer(int kind) { return kind == CAAT_ATTN_DECODE || kind == CAAT_LAYER_PREFILL; }
 
 int validate_desc(const caat_desc* d) {
   if (!d) return CAAT_EINVAL;
-  if (d->kind < CAAT_MLP_GELU || d->kind > CAAT_ATTN_DECODE) return CAAT_EINVAL;
+  if (d->kind < CAAT_MLP_GELU || d->kind > CAAT_LAYER_PREFILL) return CAAT_EINVAL;
   if (d->norm != CAAT_LAYERNORM && d->norm != CAAT_RMSNORM) return CAAT_EINVAL;
   if (d->T < 1 || d->h < 1 || d->tokens < 0) return CAAT_EINVAL;
   if (!(d->eps >= 0.0f) || std::isnan(d->private_scale)) return CAAT_EINVAL;
   if (d->hs < 0 || d->hs > d->h) return CAAT_ESHAPE;
   if (d->h % 8 != 0 || d->h > 8192) return CAAT_ESHAPE;
   if (d->tokens > 0x7FFFFFFFLL) return CAAT_ESHAPE;
-  if (is_mlp(d->kind) || d->kind == CAAT_ATTN_DECODE) {
+  if (is_mlp(d->kind) || is_layer(d->kind)) {
     if (d->ffn < 1 || d->ffn % d->T != 0 || (d->ffn / d->T) % 8 != 0) return CAAT_ESHAPE;
   }
-  if (d->kind == CAAT_ATTN || d->kind == CAAT_ATTN_DECODE) {
+  if (d->kind == CAAT_ATTN || is_layer(d->kind)) {
     if (d->n_heads < 1 || d->head_dim < 1 || d->n_heads % d->T != 0) return CAAT_ESHAPE;
     if (d->batch < 1 || d->seq < 1 || (long long)d->batch * d->seq != d->tokens) return CAAT_ESHAPE;
     if (((d->n_heads / d->T) * d->head_dim) % 8 != 0) return CAAT_ESHAPE;
@@ -98,7 +99,7 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
     take(T * n * hd * 2, &L->off_dH, &L->bytes_dH);
     take(T * n * 3 * hd * 2, &L->off_dP, &L->bytes_dP);
     take(norm_bwd_workspace_bytes(d->T, d->tokens, d->h), &L->off_scratch, &L->bytes_scratch);
-  } else if (d->kind == CAAT_ATTN_DECODE) {
+  } else if (is_layer(d->kind)) {
     const size_t hd = (size_t)(d->n_heads / d->T) * d->head_dim, fr = d->ffn / d->T;
     take(T * n * h * 2, &L->off_X1, &L->bytes_X1);
     take(T * n * 3 * hd * 2, &L->off_Q, &L->bytes_Q);
@@ -251,17 +252,25 @@ int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   return CAAT_OK;
 }
 
-// One Llama-style decoder layer for one new token per sequence (inference uses the partial channel-reduce too,
-// Sec. 3.2): RMSNorm -> q,k,v -> RoPE at position kv_len -> append k,v -> attention over kv_len+1 keys -> o_proj
-// -> PCR + residual -> RMSNorm -> SwiGLU MLP -> PCR + residual.
-int decode_layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* weights, const void* r, void* r_out,
-                     void* kv_k, void* kv_v, void* workspace, size_t ws_bytes, void* hip_stream) {
+// One Llama-style decoder layer at inference (which uses the partial channel-reduce too, Sec. 3.2), either for one
+// new token per sequence over a KV cache (decode) or for a whole prompt that fills the cache (prefill, the
+// time-to-first-token workload of Sec. 5.2): RMSNorm -> q,k,v -> RoPE -> store k,v in the cache -> attention
+// (streaming over kv_len+1 keys / causal flash attention over the prompt) -> o_proj -> PCR + residual -> RMSNorm ->
+// SwiGLU MLP -> PCR + residual.
+int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* weights, const void* r, void* r_out,
+              void* kv_k, void* kv_v, void* workspace, size_t ws_bytes, void* hip_stream) {
+  const bool prefill = d->kind == CAAT_LAYER_PREFILL;
   if (!weights || !r || !r_out || !kv_k || !kv_v || !workspace) return CAAT_EINVAL;
   const void* g_attn = weights[0]; const void* wqkv = weights[1]; const void* wo = weights[2];
   const void* g_mlp = weights[3]; const void* wgu = weights[4]; const void* wb = weights[5];
   if (!g_attn || !wqkv || !wo || !g_mlp || !wgu || !wb) return CAAT_EINVAL;
   if (d->norm != CAAT_RMSNORM || d->head_dim != 128) return CAAT_EUNSUPPORTED;
-  if (d->seq != 1 || d->kv_len < 0 || d->kv_cap <= d->kv_len || d->kv_cap * 256 >= 0x7FFFFFFFLL) return CAAT_ESHAPE;
+  if (prefill) {
+    if (d->kv_len != 0 || d->kv_cap < d->seq) return CAAT_ESHAPE;     // the prompt starts an empty cache
+  } else {
+    if (d->seq != 1 || d->kv_len < 0 || d->kv_cap <= d->kv_len) return CAAT_ESHAPE;
+  }
+  if (d->kv_cap * 256 >= 0x7FFFFFFFLL) return CAAT_ESHAPE;
   if (misaligned(g_attn) || misaligned(wqkv) || misaligned(wo) || misaligned(g_mlp) || misaligned(wgu) || misaligned(wb) ||
       misaligned(r) || misaligned(r_out) || misaligned(kv_k) || misaligned(kv_v) || misaligned(workspace))
     return CAAT_EALIGN;
@@ -289,10 +298,15 @@ int decode_layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* co
   q.c = QKV; q.ldc = 3 * hd; q.stride_c = n * 3 * hd;
   q.G = (int)T; q.M = (int)n; q.N = (int)(3 * hd); q.K = (int)h;
   CAAT_STEP("gemm_nt_qkv", launch_gemm(q, 0, EPI_PLAIN, s))
-  CAAT_STEP("rope", launch_rope(QKV, T * n, 1, (int)hd, d->head_dim, d->rope_base, d->kv_len, false, s))
-  CAAT_STEP("kv_append", launch_kv_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * n, (int)hpr, (int)hd, d->kv_cap, d->kv_len, s))
-  CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)hd,
-                                              d->head_dim, d->kv_cap, d->kv_len + 1, s))
+  CAAT_STEP("rope", launch_rope(QKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, d->kv_len, false, s))
+  CAAT_STEP("kv_append", launch_kv_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * d->batch, d->seq, (int)hpr, (int)hd,
+                                          d->kv_cap, d->kv_len, s))
+  if (prefill) {
+    CAAT_STEP("flash_attn_fwd", launch_flash_fwd(QKV, H, nullptr, T * d->batch, d->seq, (int)hd, d->head_dim, s))
+  } else {
+    CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)hd,
+                                                d->head_dim, d->kv_cap, d->kv_len + 1, s))
+  }
   std::memset(&q, 0, sizeof(q));
   q.a = H; q.lda = hd; q.stride_a = n * hd;
   q.b = (const bf16_t*)wo; q.ldb = hd; q.stride_b = h * hd;
@@ -455,8 +469,7 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
   caat_ws_layout L;
   int st = layout_of(d, &L);
   if (st != CAAT_OK) return st;
-  if (d->kind == CAAT_ATTN_DECODE)
-    return decode_layer_fwd(d, L, weights, r, r_out, kv_k, kv_v, workspace, ws_bytes, hip_stream);
+  if (is_layer(d->kind)) return layer_fwd(d, L, weights, r, r_out, kv_k, kv_v, workspace, ws_bytes, hip_stream);
   if (!weights || !x || !r || !r_out || !x_out || !workspace) return CAAT_EINVAL;
   if (d->kind == CAAT_ATTN) return attn_block_fwd(d, L, weights, x, r, r_out, x_out, workspace, ws_bytes, hip_stream);
   if (!is_mlp(d->kind)) return CAAT_EUNSUPPORTED;

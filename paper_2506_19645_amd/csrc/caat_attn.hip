@@ -637,21 +637,23 @@ hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* 
 
 // ---------------------------------------------------------------------------------------------------------
 // Decode: one new token per sequence.  (a) append the token's rotated k and its v to the caches at position
-// kv_len; (b) attention of the single query over kv_len + 1 cached keys.  Both are pure streaming (the KV read is
+// kv_len (the same kernel stores a whole prompt's k and v at positions 0 .. seq-1 after a prefill); (b) attention of the single query over kv_len + 1 cached keys.  Both are pure streaming (the KV read is
 // the layer's dominant HBM traffic), so there is no MFMA here: a workgroup owns one (rank, sequence, head);
 // 16 lanes own one key row (256 B), a wave takes 4 consecutive keys per step, the 4 waves 16; every 16-lane group
 // runs its own online softmax and the 16 partial results are merged through LDS in a fixed order.
 __global__ __launch_bounds__(256) void kv_append_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ kc,
-                                                        bf16_t* __restrict__ vc, long long n_seq, int hpr, int hd,
+                                                        bf16_t* __restrict__ vc, long long n_seq, int seq, int hpr, int hd,
                                                         long long cap, long long pos) {
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;   // (seq, head, chunk of 8)
-  if (idx >= n_seq * hpr * 16) return;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;   // ((sequence, token), head, chunk of 8)
+  if (idx >= n_seq * seq * hpr * 16) return;
   const int c = (int)(idx & 15);
-  const long long sh = idx >> 4;                                      // seq * hpr + head
-  const long long sq = sh / hpr;
-  const int head = (int)(sh - sq * hpr);
-  const bf16_t* src = qkv + sq * 3LL * hd + (long long)head * 128 + c * 8;
-  const long long dst = (sh * cap + pos) * 128 + c * 8;
+  const long long rh = idx >> 4;                                      // row * hpr + head
+  const long long row = rh / hpr;                                     // sequence * seq + token
+  const int head = (int)(rh - row * hpr);
+  const long long sq = row / seq;
+  const long long t = row - sq * seq;
+  const bf16_t* src = qkv + row * 3LL * hd + (long long)head * 128 + c * 8;
+  const long long dst = ((sq * hpr + head) * cap + pos + t) * 128 + c * 8;
   *reinterpret_cast<uint4*>(kc + dst) = *reinterpret_cast<const uint4*>(src + hd);
   *reinterpret_cast<uint4*>(vc + dst) = *reinterpret_cast<const uint4*>(src + 2 * hd);
 }
@@ -732,12 +734,14 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restri
   }
 }
 
-hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int hpr, int hd, long long cap,
-                            long long pos, hipStream_t s) {
-  const long long work = n_seq * hpr * 16;
+// rotated k and v of `seq` consecutive tokens per sequence (rows of qkv) -> cache positions pos .. pos+seq-1
+hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int seq, int hpr, int hd,
+                            long long cap, long long pos, hipStream_t s) {
+  const long long work = n_seq * seq * hpr * 16;
   if (work == 0) return hipSuccess;
-  hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, qkv, kc, vc, n_seq, hpr, hd,
-                     cap, pos);
+  if (pos < 0 || pos + seq > cap || (work + 255) / 256 > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, qkv, kc, vc, n_seq, seq, hpr,
+                     hd, cap, pos);
   return hipGetLastError();
 }
 

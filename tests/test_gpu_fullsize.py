@@ -7,6 +7,7 @@ from paper_2506_19645_amd import inputs as I
 from tests.test_gpu_attn import check_attn, check_attn_bwd, oracle_attn_block, oracle_attn_bwd, run_attn_block
 from tests.test_gpu_block import check_mlp_block, oracle_mlp_block, run_mlp_block
 from tests.test_gpu_decode import run_decode
+from tests.test_gpu_prefill import check_prefill, oracle_prefill, run_prefill
 from tests.util import assert_close, bits_to_f64
 
 pytestmark = pytest.mark.gpu
@@ -75,3 +76,21 @@ def test_config5_llama_decode_full_size():
     assert_close(bits_to_f64(got["Kc_bits"][:, :, :, L]), ref["k_new"], "k_new")
     assert_close(bits_to_f64(got["Vc_bits"][:, :, :, L]), ref["v_new"], "v_new")
     assert np.array_equal(got["Kc_bits"][:, :, :, :L], d["Kc"][:, :, :, :L])
+
+
+def test_config6_prefill_layer_full_size_sampled_sequence():
+    """Llama-7B decoder layer over 16 prompts of 2048 tokens (T=8, p=0.5): the GPU runs the whole batch; sequences are
+    independent, so the oracle runs on one of them (all ranks) and is compared with that sequence's rows."""
+    cfg = I.C6
+    d = I.make_inputs(cfg, seed=0)
+    got = run_prefill(cfg, d, keep=("H", "R1"))
+    sq = 11
+    rows = slice(sq * cfg.seq, (sq + 1) * cfg.seq)
+    one = cfg.with_(batch=1)
+    w, ref = oracle_prefill(one, dict(d, R=np.ascontiguousarray(d["R"][:, rows])))
+    check_prefill(one, d, got, ref, rows=rows)
+    assert_close(bits_to_f64(got["Kc_bits"][:, sq:sq + 1, :, :cfg.seq]), ref["K"], "K cache")
+    assert_close(bits_to_f64(got["Vc_bits"][:, sq:sq + 1, :, :cfg.seq]), ref["V"], "V cache")
+    hs = cfg.hs
+    for m in range(1, cfg.T):
+        assert np.array_equal(got["R2_bits"][m, :, :hs], got["R2_bits"][0, :, :hs])
