@@ -221,6 +221,31 @@ class DecodeBench(MlpBench):
         self.B.block_fwd(desc, self.weights, None, self.r, self.r_out, None, self.ws, kv_k=self.kc, kv_v=self.vc)
 
 
+class PrefillBench(MlpBench):
+    """Prefill decoder layer (C6): a batch of whole prompts through attention + SwiGLU MLP, KV cache filled."""
+
+    def __init__(self, cfg, seed=0):
+        import numpy as np
+        import torch
+        from paper_2506_19645_amd import binding as B
+        from paper_2506_19645_amd import inputs as I
+        self.B, self.torch, self.cfg = B, torch, cfg
+        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.h // 2)
+        self.weights = [B.to_device(d["gamma_attn"]), B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
+                        B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]
+        self.r = B.to_device(d["R"])
+        del d
+        desc = B.make_desc(cfg)
+        self.kc = torch.zeros((cfg.T, cfg.batch, cfg.n_heads // cfg.T, desc.kv_cap, cfg.head_dim), dtype=torch.bfloat16,
+                              device="cuda")
+        self.vc = torch.zeros_like(self.kc)
+        self.r_out = torch.empty_like(self.r)
+        self.ws = torch.empty(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+
+    def step(self, desc):
+        self.B.block_fwd(desc, self.weights, None, self.r, self.r_out, None, self.ws, kv_k=self.kc, kv_v=self.vc)
+
+
 def bench_attention_kinds(args, cfg, base):
     """JSON for the attention sub-block (C4, TFLOP/s) and the decode layer (C5, GB/s and per-token latency)."""
     from paper_2506_19645_amd import binding as B
@@ -245,6 +270,18 @@ def bench_attention_kinds(args, cfg, base):
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
         workload = "%s attention sub-block %s: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
             cfg.name, "fwd+bwd" if bwd else "fwd", h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, cfg.hs)
+    elif args.config == "C6":
+        bench = PrefillBench(cfg)
+        s, f = cfg.seq, cfg.ffn
+        # the two row-parallel launches of a step (o_proj 2nh^2, down projection 2nhf) share a kernel family
+        fl = {"gemm_nt_qkv": 2.0 * n * h * 3 * h, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,
+              "gemm_nt_rowpar": n * h * h + n * h * f, "gemm_nt_swiglu_fwd": 4.0 * n * h * f}
+        by = {"rope": 2.0 * T * n * 2 * hd * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
+              "norm_fwd": 2.0 * T * n * h * 2, "kv_append": 2.0 * T * n * 2 * hd * 2}
+        work = n * (8.0 * h * h + 6.0 * h * f) + 2.0 * cfg.batch * s * s * h
+        unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
+        workload = ("%s prefill decoder layer fwd: h=%d ffn=%d heads=%d d=%d RoPE causal, %d prompts x %d tokens, T=%d p=%g "
+                    "(hs=%d)" % (cfg.name, h, f, cfg.n_heads, cfg.head_dim, cfg.batch, s, T, cfg.p, cfg.hs))
     else:
         bench = DecodeBench(cfg)
         fr = cfg.f_r
@@ -271,7 +308,7 @@ def bench_attention_kinds(args, cfg, base):
             e["frac_hbm_peak"] = round(by[name] / v["avg_ms"] / 1e6 / HBM_PEAK_GBS, 4)
         kernels[name] = e
     dom = max(prof, key=lambda k: prof[k]["avg_ms"] * prof[k]["launches_per_step"])
-    if args.config == "C4":
+    if args.config in ("C4", "C6"):
         value = work / ms / 1e9
         ach = fl.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e9
         roof = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
@@ -286,6 +323,32 @@ def bench_attention_kinds(args, cfg, base):
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": workload, "work_per_step": work, "frac_peak": value / peak, "wall_ms_per_step": wall_ms},
            "roofline": roof, "kernels": kernels}
+    if args.config == "C6":
+        # time to first token of a 32-layer model of this layer, and the paper's analytic model (App. C) next to the
+        # measured p sweep.  On one GPU the "communication" is the in-HBM reduce over the T emulated ranks, so the
+        # compute / communication capacity ratio C of the model is not a property of this machine; the model's linear
+        # dependence on (1 - p) is what can be compared, with C fitted from the two end points p = 1 and p = 0.
+        layers = 32
+        out["config"]["ttft_ms_%d_layers" % layers] = ms * layers
+        sweep = []
+        if not args.no_sweep:
+            t = {}
+            for p in (1.0, 0.5, 0.25, 0.0):
+                c = base.with_(p=p)
+                t[p], _ = bench.time_steps(B.make_desc(c), max(3, args.steps // 3), 2)
+            s0 = (t[1.0] - t[0.0]) / t[1.0]                       # measured speed-up at p = 0 = 1 / (1 + (12h+2s)/(C r))
+            c_fit = (12.0 * h + 2.0 * cfg.seq) / (T * (1.0 / s0 - 1.0)) if 0.0 < s0 < 1.0 else None
+            for p in (1.0, 0.5, 0.25, 0.0):
+                c = base.with_(p=p)
+                sweep.append({"p": p, "hs": c.hs, "ms_per_layer": round(t[p], 4), "ttft_ms_%d_layers" % layers: round(t[p] * layers, 2),
+                              "TFLOP/s": round(work / t[p] / 1e9, 1),
+                              "speedup_vs_p1_measured": round((t[1.0] - t[p]) / t[1.0], 5),
+                              "speedup_vs_p1_model": round((1.0 - p) * s0, 5),
+                              "synced_payload_bytes_per_token_per_layer": 2 * 2 * c.hs})
+            out["analytic_model"] = {"form": "(T(1)-T(p))/T(1) = (1-p) / (1 + (12h+2s)/(C r)), G = (24sh^2+4s^2h)/r, P(p) = 2shp",
+                                     "r": T, "h": h, "s": cfg.seq, "C_fitted_from_p1_and_p0": c_fit,
+                                     "p_star_at_fitted_C": None if c_fit is None else min((12.0 * h + 2.0 * cfg.seq) / (c_fit * T), 1.0)}
+        out["p_sweep"] = sweep
     if args.config == "C5":
         out["config"]["latency_us_per_token_step"] = ms * 1e3
         sweep = []
@@ -304,7 +367,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "C6"])
     ap.add_argument("--p", type=float, default=0.5)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -326,7 +389,7 @@ def main():
     B.lib()
     base = I.CONFIGS[args.config]
     cfg = base.with_(p=args.p)
-    if args.config in ("C4", "C5"):
+    if args.config in ("C4", "C5", "C6"):
         print(json.dumps(bench_attention_kinds(args, cfg, base)))
         return
     bench = MlpBench(cfg, seed=0)
