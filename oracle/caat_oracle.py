@@ -13,7 +13,7 @@ the paper's index notation of App. A.2 (X_{ijm}, Z_{ilm}).
 
 Layouts (row-major): activations [T, n, h]; column-parallel shard A_m stored
 [f/T, h] (out, in); row-parallel shard B_m stored [h, f/T] (out, in); QKV shard
-[3*hd_r, h] with rows q|k|v, heads contiguous; O shard [h, hd_r].
+[3*hd_r, h] with rows q|k|v, heads contiguous (grouped-query attention: fewer k and v rows); O shard [h, hd_r].
 
 Pins (tests/test_oracle_*.py): every function below is checked against a
 closed form, an invariant, brute-force Python loops on tiny shapes or central
@@ -261,32 +261,39 @@ def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos0: int = 
 
 def attn_block_fwd(X, R, Wqkv, Wo, gamma, beta, *, batch: int, seq: int, heads_per_rank: int, head_dim: int,
                    norm: int, hs: int, eps: float = 1e-5, private_scale: float = 1.0,
-                   rope_base: float = 10000.0) -> Dict[str, np.ndarray]:
+                   rope_base: float = 10000.0, kv_heads_per_rank: Optional[int] = None) -> Dict[str, np.ndarray]:
     """Attention sub-block with partial channel-reduce (Eq. A5), then residual and norm.
 
     Per rank m: q,k,v = X_m Wq_m, X_m Wk_m, X_m Wv_m; RoPE on q,k; causal
     attention per head within each sequence; Zt_m = H_m O_m; Z = PCR(Zt);
     R' = R + Z; X' = Norm(R').  X, R: [T, batch*seq, h].
+    Grouped-query attention (the 34B / 70B models of App. E, additional speed-up results): a rank owns kv_heads_per_rank key / value heads
+    (default: one per query head); query head a reads key / value head a // (heads_per_rank / kv_heads_per_rank).
+    The projection shard has heads_per_rank*d q rows, then kv_heads_per_rank*d k rows, then as many v rows.
     """
     T, n, h = X.shape
     d = head_dim
     hd = heads_per_rank * d
+    kvpr = heads_per_rank if kv_heads_per_rank is None else kv_heads_per_rank
+    grp = heads_per_rank // kvpr
+    kvd = kvpr * d
     pos = np.arange(seq)
     Hs, Zts, Qs, Ks, Vs = [], [], [], [], []
     for m in range(T):
-        qkv = X[m] @ Wqkv[m].T                       # [n, 3*hd]
+        qkv = X[m] @ Wqkv[m].T                       # [n, hd + 2*kvd]
         H = np.empty((n, hd), dtype=X.dtype)
         Qm = np.empty((batch, heads_per_rank, seq, d), dtype=X.dtype)
-        Km = np.empty_like(Qm)
-        Vm = np.empty_like(Qm)
+        Km = np.empty((batch, kvpr, seq, d), dtype=X.dtype)
+        Vm = np.empty_like(Km)
         for b in range(batch):
             rows = slice(b * seq, (b + 1) * seq)
+            for c in range(kvpr):
+                Km[b, c] = rope(qkv[rows, hd + c * d:hd + (c + 1) * d], pos, rope_base)
+                Vm[b, c] = qkv[rows, hd + kvd + c * d:hd + kvd + (c + 1) * d]
             for a in range(heads_per_rank):
                 q = rope(qkv[rows, a * d:(a + 1) * d], pos, rope_base)
-                k = rope(qkv[rows, hd + a * d:hd + (a + 1) * d], pos, rope_base)
-                v = qkv[rows, 2 * hd + a * d:2 * hd + (a + 1) * d]
-                Qm[b, a], Km[b, a], Vm[b, a] = q, k, v
-                H[rows, a * d:(a + 1) * d] = causal_attention(q, k, v)
+                Qm[b, a] = q
+                H[rows, a * d:(a + 1) * d] = causal_attention(q, Km[b, a // grp], Vm[b, a // grp])
         Hs.append(H)
         Qs.append(Qm)
         Ks.append(Km)
@@ -342,18 +349,23 @@ def causal_attention_bwd(q: np.ndarray, k: np.ndarray, v: np.ndarray, dO: np.nda
 
 def attn_block_bwd(X, fwd: Dict[str, np.ndarray], Wqkv, Wo, gamma, dXo, dRo, *, batch: int, seq: int,
                    heads_per_rank: int, head_dim: int, norm: int, hs: int, eps: float = 1e-5,
-                   private_scale: float = 1.0, rope_base: float = 10000.0) -> Dict[str, np.ndarray]:
+                   private_scale: float = 1.0, rope_base: float = 10000.0,
+                   kv_heads_per_rank: Optional[int] = None) -> Dict[str, np.ndarray]:
     """Backward of attn_block_fwd given dL/dX' (dXo) and dL/dR' (dRo), both [T,n,h].
 
     Same placement as the MLP block (Fig. 2b, Sec. 4): norm backward per rank first, G_m = dRo_m + NormBwd(dXo_m),
     dR_m = G_m un-reduced (App. B), the partial channel-reduce on G, then the chain rule of Eq. A5 per rank:
       dH_m = dZt_m O_m ; dO_m = dZt_m^T H_m ; per (sequence, head) the attention gradient, the RoPE adjoint on
       dq, dk ; dqkv_m = [dq | dk | dv] ; dX_m = dqkv_m Wqkv_m (no reduce over ranks) ; dWqkv_m = dqkv_m^T X_m.
-    fwd is attn_block_fwd's result (needs Rp, H and the rotated Q, K and V).
+    fwd is attn_block_fwd's result (needs Rp, H and the rotated Q, K and V).  With grouped-query attention a
+    key / value head collects the gradients of every query head that read it.
     """
     T, n, h = X.shape
     d = head_dim
     hd = heads_per_rank * d
+    kvpr = heads_per_rank if kv_heads_per_rank is None else kv_heads_per_rank
+    grp = heads_per_rank // kvpr
+    kvd = kvpr * d
     pos = np.arange(seq)
     dn, dgamma_m, dbeta_m = norm_bwd(dXo, fwd["Rp"], gamma, norm, eps)
     G = dRo + dn
@@ -365,20 +377,25 @@ def attn_block_bwd(X, fwd: Dict[str, np.ndarray], Wqkv, Wo, gamma, dXo, dRo, *, 
     for m in range(T):
         dH = dZt[m] @ Wo[m]                       # [n,h] x [h,hd]
         dWos.append(dZt[m].T @ fwd["H"][m])       # [h,hd]
-        dqkv = np.empty((n, 3 * hd), dtype=X.dtype)
+        dqkv = np.empty((n, hd + 2 * kvd), dtype=X.dtype)
         for b in range(batch):
             rows = slice(b * seq, (b + 1) * seq)
-            for a in range(heads_per_rank):
-                cols = slice(a * d, (a + 1) * d)
-                dq, dk, dv = causal_attention_bwd(fwd["Q"][m, b, a], fwd["K"][m, b, a], fwd["V"][m, b, a],
-                                                  dH[rows, cols])
-                dqkv[rows, a * d:(a + 1) * d] = rope_adjoint(dq, pos, rope_base)
-                dqkv[rows, hd + a * d:hd + (a + 1) * d] = rope_adjoint(dk, pos, rope_base)
-                dqkv[rows, 2 * hd + a * d:2 * hd + (a + 1) * d] = dv
+            for c in range(kvpr):
+                dk_sum = np.zeros((seq, d), dtype=X.dtype)
+                dv_sum = np.zeros((seq, d), dtype=X.dtype)
+                for a in range(c * grp, (c + 1) * grp):      # the query heads that read key / value head c
+                    cols = slice(a * d, (a + 1) * d)
+                    dq, dk, dv = causal_attention_bwd(fwd["Q"][m, b, a], fwd["K"][m, b, c], fwd["V"][m, b, c],
+                                                      dH[rows, cols])
+                    dqkv[rows, a * d:(a + 1) * d] = rope_adjoint(dq, pos, rope_base)
+                    dk_sum = dk_sum + dk
+                    dv_sum = dv_sum + dv
+                dqkv[rows, hd + c * d:hd + (c + 1) * d] = rope_adjoint(dk_sum, pos, rope_base)
+                dqkv[rows, hd + kvd + c * d:hd + kvd + (c + 1) * d] = dv_sum
         dHs.append(dH)
         dqkvs.append(dqkv)
-        dXs.append(dqkv @ Wqkv[m])                # [n,3hd] x [3hd,h]
-        dWqkvs.append(dqkv.T @ X[m])              # [3hd,h]
+        dXs.append(dqkv @ Wqkv[m])                # [n,hd+2kvd] x [hd+2kvd,h]
+        dWqkvs.append(dqkv.T @ X[m])              # [hd+2kvd,h]
     g["dH"] = np.stack(dHs)
     g["dqkv"] = np.stack(dqkvs)
     g["dX"] = np.stack(dXs)
@@ -388,11 +405,11 @@ def attn_block_bwd(X, fwd: Dict[str, np.ndarray], Wqkv, Wo, gamma, dXo, dRo, *, 
 
 
 def decode_layer_fwd(R, W: Dict[str, np.ndarray], Kc, Vc, *, kv_len: int, heads_per_rank: int, head_dim: int,
-                     hs: int, eps: float = 1e-5, private_scale: float = 1.0,
-                     rope_base: float = 10000.0) -> Dict[str, np.ndarray]:
+                     hs: int, eps: float = 1e-5, private_scale: float = 1.0, rope_base: float = 10000.0,
+                     kv_heads_per_rank: Optional[int] = None) -> Dict[str, np.ndarray]:
     """One Llama-style decoder layer for one new token per sequence (RMSNorm, SwiGLU).
 
-    R: [T, b, h] per-rank residual stream.  Kc, Vc: [T, b, heads_per_rank, cap, d]
+    R: [T, b, h] per-rank residual stream.  Kc, Vc: [T, b, kv_heads_per_rank, cap, d]
     caches whose first kv_len positions are filled (keys already rotated); the
     new token sits at position kv_len and its k, v are appended at that index.
       X1 = RMSNorm(R; gamma_attn); q,k,v = X1 Wqkv; RoPE(q,k at kv_len)
@@ -404,23 +421,27 @@ def decode_layer_fwd(R, W: Dict[str, np.ndarray], Kc, Vc, *, kv_len: int, heads_
     T, b, h = R.shape
     d = head_dim
     hd = heads_per_rank * d
+    kvpr = heads_per_rank if kv_heads_per_rank is None else kv_heads_per_rank
+    grp = heads_per_rank // kvpr
+    kvd = kvpr * d
     X1, _, _ = norm_fwd(R, W["gamma_attn"], None, RMSNORM, eps)
     Zt = np.empty_like(R)
-    k_new = np.empty((T, b, heads_per_rank, d), dtype=R.dtype)
+    k_new = np.empty((T, b, kvpr, d), dtype=R.dtype)
     v_new = np.empty_like(k_new)
     Hall = np.empty((T, b, hd), dtype=R.dtype)
     pos = np.array([kv_len])
     for m in range(T):
         qkv = X1[m] @ W["Wqkv"][m].T
         for s in range(b):
-            for a in range(heads_per_rank):
-                q = rope(qkv[s:s + 1, a * d:(a + 1) * d], pos, rope_base)
-                k = rope(qkv[s:s + 1, hd + a * d:hd + (a + 1) * d], pos, rope_base)
-                v = qkv[s:s + 1, 2 * hd + a * d:2 * hd + (a + 1) * d]
-                k_new[m, s, a], v_new[m, s, a] = k[0], v[0]
-                Kall = np.concatenate([Kc[m, s, a, :kv_len], k], axis=0)
-                Vall = np.concatenate([Vc[m, s, a, :kv_len], v], axis=0)
-                Hall[m, s, a * d:(a + 1) * d] = causal_attention(q, Kall, Vall, q_pos0=kv_len)[0]
+            for c in range(kvpr):
+                k = rope(qkv[s:s + 1, hd + c * d:hd + (c + 1) * d], pos, rope_base)
+                v = qkv[s:s + 1, hd + kvd + c * d:hd + kvd + (c + 1) * d]
+                k_new[m, s, c], v_new[m, s, c] = k[0], v[0]
+                Kall = np.concatenate([Kc[m, s, c, :kv_len], k], axis=0)
+                Vall = np.concatenate([Vc[m, s, c, :kv_len], v], axis=0)
+                for a in range(c * grp, (c + 1) * grp):
+                    q = rope(qkv[s:s + 1, a * d:(a + 1) * d], pos, rope_base)
+                    Hall[m, s, a * d:(a + 1) * d] = causal_attention(q, Kall, Vall, q_pos0=kv_len)[0]
         Zt[m] = Hall[m] @ W["Wo"][m].T
     R1 = R + partial_channel_reduce(Zt, hs, private_scale)
     X2, _, _ = norm_fwd(R1, W["gamma"], None, RMSNORM, eps)
@@ -433,8 +454,8 @@ def decode_layer_fwd(R, W: Dict[str, np.ndarray], Kc, Vc, *, kv_len: int, heads_
 
 
 def prefill_layer_fwd(R, W: Dict[str, np.ndarray], *, batch: int, seq: int, heads_per_rank: int, head_dim: int,
-                      hs: int, eps: float = 1e-5, private_scale: float = 1.0,
-                      rope_base: float = 10000.0) -> Dict[str, np.ndarray]:
+                      hs: int, eps: float = 1e-5, private_scale: float = 1.0, rope_base: float = 10000.0,
+                      kv_heads_per_rank: Optional[int] = None) -> Dict[str, np.ndarray]:
     """One Llama-style decoder layer over a whole prompt (the time-to-first-token workload of Sec. 5.2): the
     attention sub-block of Eq. A5 followed by the SwiGLU MLP sub-block of Eq. A3, each closed by its partial
     channel-reduce and residual add, RMSNorm in front of each (Sec. 4).
@@ -442,13 +463,13 @@ def prefill_layer_fwd(R, W: Dict[str, np.ndarray], *, batch: int, seq: int, head
     R: [T, batch*seq, h] per-rank residual stream.  W as for decode_layer_fwd.
       X1 = RMSNorm(R; gamma_attn); attention sub-block on (X1, R) -> R1 = R + PCR(H Wo), X2 = RMSNorm(R1; gamma)
       MLP sub-block on (X2, R1)  -> R2 = R1 + PCR((silu(X2 Wg) * (X2 Wu)) B)
-    Returns R1, X2, R2, intermediates and the rotated keys K and the values V [T, batch, heads_per_rank, seq, d]
+    Returns R1, X2, R2, intermediates and the rotated keys K and the values V [T, batch, kv_heads_per_rank, seq, d]
     that a KV cache holds after the prompt.
     """
     X1, _, _ = norm_fwd(R, W["gamma_attn"], None, RMSNORM, eps)
     att = attn_block_fwd(X1, R, W["Wqkv"], W["Wo"], W["gamma"], None, batch=batch, seq=seq,
                          heads_per_rank=heads_per_rank, head_dim=head_dim, norm=RMSNORM, hs=hs, eps=eps,
-                         private_scale=private_scale, rope_base=rope_base)
+                         private_scale=private_scale, rope_base=rope_base, kv_heads_per_rank=kv_heads_per_rank)
     R1, X2 = att["Rp"], att["Xp"]
     T = R.shape[0]
     Zt2 = np.empty_like(R)

@@ -48,6 +48,7 @@ class BlockConfig:
     n_heads: int = 0
     head_dim: int = 0
     kv_len: int = 0
+    n_kv_heads: int = 0        # grouped-query attention: number of key / value heads (0 = n_heads, plain MHA)
     eps: float = 1e-5
     private_scale: float = 1.0
     rope_base: float = 10000.0
@@ -69,6 +70,20 @@ class BlockConfig:
     def hd_r(self) -> int:
         """attention width owned by one rank = heads per rank * head_dim"""
         return (self.n_heads // self.T) * self.head_dim
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads if self.n_kv_heads > 0 else self.n_heads
+
+    @property
+    def kvd_r(self) -> int:
+        """key (= value) width owned by one rank = kv heads per rank * head_dim"""
+        return (self.kv_heads // self.T) * self.head_dim
+
+    @property
+    def qkv_r(self) -> int:
+        """rows of one rank's fused projection shard: q heads, then k heads, then v heads"""
+        return self.hd_r + 2 * self.kvd_r
 
     def with_(self, **kw) -> "BlockConfig":
         return dataclasses.replace(self, **kw)
@@ -165,11 +180,11 @@ def make_inputs(cfg: BlockConfig, seed: int = 0, mode: str = "divergent", with_g
         d["Wu"] = _normal_bf16(rng, (T, cfg.f_r, h), std=weight_std)
         d["B"] = _normal_bf16(rng, (T, h, cfg.f_r), std=weight_std)
     elif cfg.kind == KIND_ATTN:
-        d["Wqkv"] = _normal_bf16(rng, (T, 3 * cfg.hd_r, h), std=weight_std)  # rows: q heads, k heads, v heads
+        d["Wqkv"] = _normal_bf16(rng, (T, cfg.qkv_r, h), std=weight_std)  # rows: q heads, k heads, v heads
         d["Wo"] = _normal_bf16(rng, (T, h, cfg.hd_r), std=weight_std)
     elif cfg.kind in (KIND_DECODE, KIND_PREFILL):
         d["gamma_attn"] = _normal_bf16(rng, (h,), mean=1.0, std=0.1)
-        d["Wqkv"] = _normal_bf16(rng, (T, 3 * cfg.hd_r, h), std=weight_std)
+        d["Wqkv"] = _normal_bf16(rng, (T, cfg.qkv_r, h), std=weight_std)
         d["Wo"] = _normal_bf16(rng, (T, h, cfg.hd_r), std=weight_std)
         d["Wg"] = _normal_bf16(rng, (T, cfg.f_r, h), std=weight_std)
         d["Wu"] = _normal_bf16(rng, (T, cfg.f_r, h), std=weight_std)
@@ -183,10 +198,10 @@ def make_inputs(cfg: BlockConfig, seed: int = 0, mode: str = "divergent", with_g
         d["dXo"] = _normal_bf16(rng, (T, n, h))   # dL/dX'
         d["dRo"] = _normal_bf16(rng, (T, n, h))   # dL/dR'
     if cfg.kind == KIND_DECODE:
-        hpr = cfg.n_heads // cfg.T
+        kvpr = cfg.kv_heads // cfg.T
         cap = cfg.kv_len + 1
-        d["Kc"] = _normal_bf16(rng, (T, cfg.batch, hpr, cap, cfg.head_dim))
-        d["Vc"] = _normal_bf16(rng, (T, cfg.batch, hpr, cap, cfg.head_dim))
+        d["Kc"] = _normal_bf16(rng, (T, cfg.batch, kvpr, cap, cfg.head_dim))
+        d["Vc"] = _normal_bf16(rng, (T, cfg.batch, kvpr, cap, cfg.head_dim))
     return d
 
 

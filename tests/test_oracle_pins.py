@@ -595,6 +595,69 @@ def test_decode_equals_last_row_of_prefill():
     np.testing.assert_allclose(dec["R2"], mlp["Rp"], atol=1e-13)
 
 
+# --------------------------------------------------------------------------- grouped-query attention
+def _tiny_gqa(T=2, batch=2, seq=5, heads=8, kv_heads=4, d=4, p=0.5, seed=9, kind=I.KIND_ATTN, ffn=0, kv_len=0):
+    cfg = I.BlockConfig("tinygqa", kind, I.NORM_RMSNORM, h=heads * d, T=T, p=p, batch=batch, seq=seq, ffn=ffn,
+                        n_heads=heads, head_dim=d, n_kv_heads=kv_heads, kv_len=kv_len)
+    dd = I.make_inputs(cfg, seed=seed, weight_std=0.3)
+    return cfg, {k: O.widen_bf16(v) for k, v in dd.items()}
+
+
+def _expand_kv_rows(Wqkv, hpr, kvpr, d):
+    """Multi-head projection shard that repeats every key / value head once per query head of its group."""
+    grp, hd, kvd = hpr // kvpr, hpr * d, kvpr * d
+    q = Wqkv[:, :hd]
+    k = Wqkv[:, hd:hd + kvd].reshape(Wqkv.shape[0], kvpr, d, -1)
+    v = Wqkv[:, hd + kvd:].reshape(Wqkv.shape[0], kvpr, d, -1)
+    rep = lambda t: np.repeat(t, grp, axis=1).reshape(Wqkv.shape[0], hd, -1)
+    return np.concatenate([q, rep(k), rep(v)], axis=1)
+
+
+def test_gqa_equals_mha_with_repeated_kv_heads_forward_and_backward():
+    """Grouped-query attention is multi-head attention whose key / value projections are tied within a group: the
+    forward equals the (already pinned) multi-head block with the tied rows repeated, and the gradient of a tied
+    row is the sum of the gradients of its copies."""
+    cfg, w = _tiny_gqa()
+    hpr, kvpr, d = cfg.n_heads // cfg.T, cfg.kv_heads // cfg.T, cfg.head_dim
+    grp, hd, kvd = hpr // kvpr, hpr * d, kvpr * d
+    kw = dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, norm=O.RMSNORM, hs=cfg.hs)
+    r = _rng(31)
+    dXo, dRo = r.standard_normal(w["X"].shape), r.standard_normal(w["X"].shape)
+    fg = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], None, kv_heads_per_rank=kvpr, **kw)
+    gg = O.attn_block_bwd(w["X"], fg, w["Wqkv"], w["Wo"], w["gamma"], dXo, dRo, kv_heads_per_rank=kvpr, **kw)
+    Wm = _expand_kv_rows(w["Wqkv"], hpr, kvpr, d)
+    fm = O.attn_block_fwd(w["X"], w["R"], Wm, w["Wo"], w["gamma"], None, **kw)
+    gm = O.attn_block_bwd(w["X"], fm, Wm, w["Wo"], w["gamma"], dXo, dRo, **kw)
+    for name in ("H", "Rp", "Xp"):
+        np.testing.assert_allclose(fg[name], fm[name], atol=1e-12)
+    for name in ("dX", "dR", "dWo", "dgamma"):
+        np.testing.assert_allclose(gg[name], gm[name], atol=1e-11)
+    T = cfg.T
+    np.testing.assert_allclose(gg["dWqkv"][:, :hd], gm["dWqkv"][:, :hd], atol=1e-11)
+    dk_m = gm["dWqkv"][:, hd:2 * hd].reshape(T, kvpr, grp, d, -1).sum(axis=2).reshape(T, kvd, -1)
+    dv_m = gm["dWqkv"][:, 2 * hd:].reshape(T, kvpr, grp, d, -1).sum(axis=2).reshape(T, kvd, -1)
+    np.testing.assert_allclose(gg["dWqkv"][:, hd:hd + kvd], dk_m, atol=1e-11)
+    np.testing.assert_allclose(gg["dWqkv"][:, hd + kvd:], dv_m, atol=1e-11)
+
+
+def test_gqa_decode_equals_last_row_of_prefill():
+    L = 4
+    cfg, w = _tiny_gqa(T=2, batch=2, seq=L + 1, heads=8, kv_heads=2, d=4, kind=I.KIND_PREFILL, ffn=24)
+    hpr, kvpr, d = cfg.n_heads // cfg.T, cfg.kv_heads // cfg.T, cfg.head_dim
+    pre = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, hs=cfg.hs,
+                              kv_heads_per_rank=kvpr)
+    assert pre["K"].shape == (cfg.T, cfg.batch, kvpr, L + 1, d)
+    Kc = np.zeros((cfg.T, cfg.batch, kvpr, L + 1, d))
+    Vc = np.zeros_like(Kc)
+    Kc[:, :, :, :L] = pre["K"][:, :, :, :L]
+    Vc[:, :, :, :L] = pre["V"][:, :, :, :L]
+    last = [s * (L + 1) + L for s in range(cfg.batch)]
+    dec = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=cfg.hs,
+                             kv_heads_per_rank=kvpr)
+    np.testing.assert_allclose(dec["R2"], pre["R2"][:, last], atol=1e-12)
+    np.testing.assert_allclose(dec["k_new"], pre["K"][:, :, :, L], atol=1e-13)
+
+
 # --------------------------------------------------------------------------- prefill layer
 def _tiny_prefill(T=2, b=2, heads=4, d=4, seq=6, f=24, p=0.5, seed=3, mode="divergent"):
     cfg = I.BlockConfig("tinypre", I.KIND_PREFILL, I.NORM_RMSNORM, h=heads * d, T=T, p=p, batch=b, seq=seq, ffn=f,
