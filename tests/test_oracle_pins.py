@@ -642,7 +642,7 @@ def test_gqa_equals_mha_with_repeated_kv_heads_forward_and_backward():
 
 def test_gqa_decode_equals_last_row_of_prefill():
     L = 4
-    cfg, w = _tiny_gqa(T=2, batch=2, seq=L + 1, heads=8, kv_heads=2, d=4, kind=I.KIND_PREFILL, ffn=24)
+    cfg, w = _tiny_gqa(T=2, batch=2, seq=L + 1, heads=8, kv_heads=4, d=4, kind=I.KIND_PREFILL, ffn=24)
     hpr, kvpr, d = cfg.n_heads // cfg.T, cfg.kv_heads // cfg.T, cfg.head_dim
     pre = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, hs=cfg.hs,
                               kv_heads_per_rank=kvpr)
