@@ -236,7 +236,7 @@ class PrefillBench(MlpBench):
         self.r = B.to_device(d["R"])
         del d
         desc = B.make_desc(cfg)
-        self.kc = torch.zeros((cfg.T, cfg.batch, cfg.n_heads // cfg.T, desc.kv_cap, cfg.head_dim), dtype=torch.bfloat16,
+        self.kc = torch.zeros((cfg.T, cfg.batch, cfg.kv_heads // cfg.T, desc.kv_cap, cfg.head_dim), dtype=torch.bfloat16,
                               device="cuda")
         self.vc = torch.zeros_like(self.kc)
         self.r_out = torch.empty_like(self.r)

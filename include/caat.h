@@ -82,6 +82,8 @@ typedef struct caat_desc {
   float private_scale;  /* factor applied to private channels (Sec. 4 private channel scaling,
                            sqrt(T) in the paper); 1.0f switches it off */
   float rope_base;      /* RoPE base (10000) */
+  int n_kv_heads;       /* grouped-query attention: key / value heads over all ranks; 0 = n_heads (multi-head).
+                           n_heads % n_kv_heads == 0 and n_kv_heads % T == 0 (each rank owns whole groups) */
 } caat_desc;
 
 /* Byte offsets of the tensors caat_block_fwd leaves in the workspace (0 size = not present).  For tests
@@ -94,8 +96,8 @@ typedef struct caat_ws_layout {
   size_t off_rstd, bytes_rstd; /* fp32 [T,tokens] */
   size_t off_dZt, bytes_dZt;   /* backward: reduced gradient [T,tokens,h] */
   size_t off_dP, bytes_dP;     /* backward: gradient of the pre-activations, same shape as P; CAAT_ATTN: gradient of the
-                                  un-rotated projections [T,tokens,3*hd_r], column blocks dq | dk | dv */
-  size_t off_Q, bytes_Q;       /* attention: projections [T,tokens,3*hd_r], column blocks q | k | v, q and k rotated (RoPE) */
+                                  un-rotated projections [T,tokens,hd_r+2*kvd_r], column blocks dq | dk | dv */
+  size_t off_Q, bytes_Q;       /* attention: projections [T,tokens,hd_r+2*kvd_r], column blocks q | k | v, q and k rotated (RoPE) */
   size_t off_scratch, bytes_scratch;
   /* decode and prefill layers only: attention heads output [T,tokens,hd_r]; first norm output X1, residual after the
    * attention half R1 and second norm output X2, each [T,tokens,h] */
@@ -173,13 +175,13 @@ int caat_gemm_bf16(const void* a, const void* b, void* c, int layout, int G, lon
  *   weights (host array of device pointers), by kind:
  *     CAAT_MLP_GELU   : {A [T][ffn/T][h], B [T][h][ffn/T], gamma [h], beta [h] or NULL}
  *     CAAT_MLP_SWIGLU : {Wgu [T][2*ffn/T][h] (gate rows then up rows), B [T][h][ffn/T], gamma, beta or NULL}
- *     CAAT_ATTN       : {Wqkv [T][3*hd_r][h] (q rows, k rows, v rows; heads contiguous), Wo [T][h][hd_r],
- *                        gamma, beta or NULL},  hd_r = (n_heads/T)*head_dim
+ *     CAAT_ATTN       : {Wqkv [T][hd_r + 2*kvd_r][h] (q rows, k rows, v rows; heads contiguous), Wo [T][h][hd_r],
+ *                        gamma, beta or NULL},  hd_r = (n_heads/T)*head_dim, kvd_r = (n_kv_heads/T)*head_dim
  *     CAAT_ATTN_DECODE, CAAT_LAYER_PREFILL: {gamma_attn [h], Wqkv, Wo, gamma_mlp [h], Wgu, B}; RMSNorm only
  *   x, r       : [T,tokens,h] inputs (x already normalised; the layer kinds ignore x and normalise r themselves)
  *   r_out      : [T,tokens,h] new residual stream R'
  *   x_out      : [T,tokens,h] Norm(R'); layer kinds: may be NULL (not produced)
- *   kv_k, kv_v : layer kinds only, [T][batch][n_heads/T][kv_cap][head_dim]; decode writes row kv_len, prefill
+ *   kv_k, kv_v : layer kinds only, [T][batch][n_kv_heads/T][kv_cap][head_dim]; decode writes row kv_len, prefill
  *                rows 0 .. seq-1 (rotated keys, values)
  *   workspace  : caat_workspace_bytes(d) bytes; keeps what caat_block_bwd needs
  */

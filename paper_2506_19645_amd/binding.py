@@ -31,7 +31,7 @@ class caat_desc(C.Structure):
     _fields_ = [("kind", C.c_int), ("norm", C.c_int), ("h", C.c_int), ("ffn", C.c_int), ("T", C.c_int),
                 ("hs", C.c_int), ("tokens", C.c_longlong), ("batch", C.c_int), ("seq", C.c_int),
                 ("n_heads", C.c_int), ("head_dim", C.c_int), ("kv_len", C.c_longlong), ("kv_cap", C.c_longlong),
-                ("eps", C.c_float), ("private_scale", C.c_float), ("rope_base", C.c_float)]
+                ("eps", C.c_float), ("private_scale", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int)]
 
 
 class caat_ws_layout(C.Structure):
@@ -139,7 +139,8 @@ def make_desc(cfg, hs: Optional[int] = None, kv_cap: Optional[int] = None) -> ca
     return caat_desc(kind=cfg.kind, norm=cfg.norm, h=cfg.h, ffn=cfg.ffn, T=cfg.T,
                      hs=cfg.hs if hs is None else hs, tokens=cfg.tokens, batch=cfg.batch, seq=cfg.seq,
                      n_heads=cfg.n_heads, head_dim=cfg.head_dim, kv_len=cfg.kv_len, kv_cap=kv_cap,
-                     eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base)
+                     eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base,
+                     n_kv_heads=getattr(cfg, "n_kv_heads", 0))
 
 
 # ------------------------------------------------------------------ entry points (same names as the C ABI)

@@ -46,6 +46,12 @@ struct ProfScope {
 
 bool is_mlp(int kind) { return kind == CAAT_MLP_GELU || kind == CAAT_MLP_SWIGLU; }
 bool is_layer(int kind) { return kind == CAAT_ATTN_DECODE || kind == CAAT_LAYER_PREFILL; }
+// key / value heads over all ranks (n_kv_heads = 0 means one per query head) and the width of a rank's fused
+// q | k | v projection
+int kv_heads_of(const caat_desc* d) { return d->n_kv_heads > 0 ? d->n_kv_heads : d->n_heads; }
+long long qkv_width(const caat_desc* d) {
+  return (long long)(d->n_heads / d->T + 2 * (kv_heads_of(d) / d->T)) * d->head_dim;
+}
 
 int validate_desc(const caat_desc* d) {
   if (!d) return CAAT_EINVAL;
@@ -61,6 +67,7 @@ int validate_desc(const caat_desc* d) {
   }
   if (d->kind == CAAT_ATTN || is_layer(d->kind)) {
     if (d->n_heads < 1 || d->head_dim < 1 || d->n_heads % d->T != 0) return CAAT_ESHAPE;
+    if (d->n_kv_heads < 0 || d->n_heads % kv_heads_of(d) != 0 || kv_heads_of(d) % d->T != 0) return CAAT_ESHAPE;
     if (d->batch < 1 || d->seq < 1 || (long long)d->batch * d->seq != d->tokens) return CAAT_ESHAPE;
     if (((d->n_heads / d->T) * d->head_dim) % 8 != 0) return CAAT_ESHAPE;
   }
@@ -89,20 +96,20 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
     take(T * n * pw * 2, &L->off_dP, &L->bytes_dP);
     take(norm_bwd_workspace_bytes(d->T, d->tokens, d->h), &L->off_scratch, &L->bytes_scratch);
   } else if (d->kind == CAAT_ATTN) {
-    const size_t hd = (size_t)(d->n_heads / d->T) * d->head_dim;
-    take(T * n * 3 * hd * 2, &L->off_Q, &L->bytes_Q);
+    const size_t hd = (size_t)(d->n_heads / d->T) * d->head_dim, qw = (size_t)qkv_width(d);
+    take(T * n * qw * 2, &L->off_Q, &L->bytes_Q);
     take(T * n * hd * 2, &L->off_Y, &L->bytes_Y);
     if (d->norm == CAAT_LAYERNORM) take(T * n * 4, &L->off_mean, &L->bytes_mean);
     take(T * n * 4, &L->off_rstd, &L->bytes_rstd);
     take(attn_stats_bytes((long long)T * d->batch, d->n_heads / d->T, d->seq), &L->off_stats, &L->bytes_stats);
     take(T * n * h * 2, &L->off_dZt, &L->bytes_dZt);
     take(T * n * hd * 2, &L->off_dH, &L->bytes_dH);
-    take(T * n * 3 * hd * 2, &L->off_dP, &L->bytes_dP);
+    take(T * n * qw * 2, &L->off_dP, &L->bytes_dP);
     take(norm_bwd_workspace_bytes(d->T, d->tokens, d->h), &L->off_scratch, &L->bytes_scratch);
   } else if (is_layer(d->kind)) {
     const size_t hd = (size_t)(d->n_heads / d->T) * d->head_dim, fr = d->ffn / d->T;
     take(T * n * h * 2, &L->off_X1, &L->bytes_X1);
-    take(T * n * 3 * hd * 2, &L->off_Q, &L->bytes_Q);
+    take(T * n * (size_t)qkv_width(d) * 2, &L->off_Q, &L->bytes_Q);
     take(T * n * hd * 2, &L->off_H, &L->bytes_H);
     take(T * n * h * 2, &L->off_R1, &L->bytes_R1);
     take(T * n * h * 2, &L->off_X2, &L->bytes_X2);
@@ -130,7 +137,8 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   if (d->tokens == 0) return CAAT_OK;
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  const long long T = d->T, n = d->tokens, h = d->h, hd = (long long)(d->n_heads / d->T) * d->head_dim;
+  const long long T = d->T, n = d->tokens, h = d->h, hd = (long long)(d->n_heads / d->T) * d->head_dim, qw = qkv_width(d);
+  const int hpr = d->n_heads / d->T, kvpr = kv_heads_of(d) / d->T;
   bf16_t* QKV = (bf16_t*)(ws + L.off_Q);
   bf16_t* H = (bf16_t*)(ws + L.off_Y);
   float* mean = d->norm == CAAT_LAYERNORM ? (float*)(ws + L.off_mean) : nullptr;
@@ -140,9 +148,9 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   GemmParams g1;
   std::memset(&g1, 0, sizeof(g1));
   g1.a = (const bf16_t*)x; g1.lda = h; g1.stride_a = n * h;
-  g1.b = (const bf16_t*)wqkv; g1.ldb = h; g1.stride_b = 3 * hd * h;
-  g1.c = QKV; g1.ldc = 3 * hd; g1.stride_c = n * 3 * hd;
-  g1.G = (int)T; g1.M = (int)n; g1.N = (int)(3 * hd); g1.K = (int)h;
+  g1.b = (const bf16_t*)wqkv; g1.ldb = h; g1.stride_b = qw * h;
+  g1.c = QKV; g1.ldc = qw; g1.stride_c = n * qw;
+  g1.G = (int)T; g1.M = (int)n; g1.N = (int)qw; g1.K = (int)h;
   {
     ProfScope ps(s, "gemm_nt_qkv");
     e = launch_gemm(g1, 0, EPI_PLAIN, s);
@@ -150,12 +158,12 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   if (e != hipSuccess) return CAAT_EHIP;
   {
     ProfScope ps(s, "rope");
-    e = launch_rope(QKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, 0, false, s);
+    e = launch_rope(QKV, T * n, d->seq, (int)qw, hpr + kvpr, d->head_dim, d->rope_base, 0, false, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
   {
     ProfScope ps(s, "flash_attn_fwd");
-    e = launch_flash_fwd(QKV, H, stats, T * d->batch, d->seq, (int)hd, d->head_dim, s);
+    e = launch_flash_fwd(QKV, H, stats, T * d->batch, d->seq, hpr, kvpr, d->head_dim, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
   GemmParams g2;
@@ -202,7 +210,8 @@ int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   if (d->tokens == 0) return CAAT_OK;
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  const long long T = d->T, n = d->tokens, h = d->h, hd = (long long)(d->n_heads / d->T) * d->head_dim;
+  const long long T = d->T, n = d->tokens, h = d->h, hd = (long long)(d->n_heads / d->T) * d->head_dim, qw = qkv_width(d);
+  const int hpr = d->n_heads / d->T, kvpr = kv_heads_of(d) / d->T;
   const bf16_t* QKV = (const bf16_t*)(ws + L.off_Q);
   const bf16_t* H = (const bf16_t*)(ws + L.off_Y);
   const float* mean = d->norm == CAAT_LAYERNORM ? (const float*)(ws + L.off_mean) : nullptr;
@@ -232,21 +241,21 @@ int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   q.c = (bf16_t*)dwo; q.ldc = hd; q.stride_c = h * hd;
   q.G = (int)T; q.M = (int)h; q.N = (int)hd; q.K = (int)n;
   CAAT_STEP("gemm_tn_wgrad", launch_gemm(q, 2, EPI_PLAIN, s))
-  CAAT_STEP("flash_attn_bwd", launch_flash_bwd(QKV, H, dH, stats, dQKV, T * d->batch, d->seq, (int)hd, d->head_dim, s))
-  CAAT_STEP("rope_bwd", launch_rope(dQKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, 0, true, s))
-  // dX_m = dqkv_m Wqkv_m (NN): [n,3hd] x [3hd,h]; not reduced over ranks
+  CAAT_STEP("flash_attn_bwd", launch_flash_bwd(QKV, H, dH, stats, dQKV, T * d->batch, d->seq, hpr, kvpr, d->head_dim, s))
+  CAAT_STEP("rope_bwd", launch_rope(dQKV, T * n, d->seq, (int)qw, hpr + kvpr, d->head_dim, d->rope_base, 0, true, s))
+  // dX_m = dqkv_m Wqkv_m (NN): [n,qw] x [qw,h]; not reduced over ranks
   std::memset(&q, 0, sizeof(q));
-  q.a = dQKV; q.lda = 3 * hd; q.stride_a = n * 3 * hd;
-  q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = 3 * hd * h;
+  q.a = dQKV; q.lda = qw; q.stride_a = n * qw;
+  q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = qw * h;
   q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h;
-  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)(3 * hd);
+  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)qw;
   CAAT_STEP("gemm_nn_dgrad", launch_gemm(q, 1, EPI_PLAIN, s))
-  // dWqkv_m [3hd,h] = dqkv_m^T X_m (TN)
+  // dWqkv_m [qw,h] = dqkv_m^T X_m (TN)
   std::memset(&q, 0, sizeof(q));
-  q.a = dQKV; q.lda = 3 * hd; q.stride_a = n * 3 * hd;
+  q.a = dQKV; q.lda = qw; q.stride_a = n * qw;
   q.b = (const bf16_t*)x; q.ldb = h; q.stride_b = n * h;
-  q.c = (bf16_t*)dwqkv; q.ldc = h; q.stride_c = 3 * hd * h;
-  q.G = (int)T; q.M = (int)(3 * hd); q.N = (int)h; q.K = (int)n;
+  q.c = (bf16_t*)dwqkv; q.ldc = h; q.stride_c = qw * h;
+  q.G = (int)T; q.M = (int)qw; q.N = (int)h; q.K = (int)n;
   CAAT_STEP("gemm_tn_wgrad", launch_gemm(q, 2, EPI_PLAIN, s))
 #undef CAAT_STEP
   return CAAT_OK;
@@ -279,6 +288,7 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
   hipStream_t s = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
   const long long T = d->T, n = d->tokens, h = d->h, hpr = d->n_heads / d->T, hd = hpr * d->head_dim, fr = d->ffn / d->T;
+  const long long kvpr = kv_heads_of(d) / d->T, qw = qkv_width(d);
   bf16_t* X1 = (bf16_t*)(ws + L.off_X1);
   bf16_t* QKV = (bf16_t*)(ws + L.off_Q);
   bf16_t* H = (bf16_t*)(ws + L.off_H);
@@ -294,17 +304,17 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
                                         n, (int)h, d->eps, s))
   std::memset(&q, 0, sizeof(q));
   q.a = X1; q.lda = h; q.stride_a = n * h;
-  q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = 3 * hd * h;
-  q.c = QKV; q.ldc = 3 * hd; q.stride_c = n * 3 * hd;
-  q.G = (int)T; q.M = (int)n; q.N = (int)(3 * hd); q.K = (int)h;
+  q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = qw * h;
+  q.c = QKV; q.ldc = qw; q.stride_c = n * qw;
+  q.G = (int)T; q.M = (int)n; q.N = (int)qw; q.K = (int)h;
   CAAT_STEP("gemm_nt_qkv", launch_gemm(q, 0, EPI_PLAIN, s))
-  CAAT_STEP("rope", launch_rope(QKV, T * n, d->seq, (int)hd, d->head_dim, d->rope_base, d->kv_len, false, s))
-  CAAT_STEP("kv_append", launch_kv_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * d->batch, d->seq, (int)hpr, (int)hd,
+  CAAT_STEP("rope", launch_rope(QKV, T * n, d->seq, (int)qw, (int)(hpr + kvpr), d->head_dim, d->rope_base, d->kv_len, false, s))
+  CAAT_STEP("kv_append", launch_kv_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * d->batch, d->seq, (int)hpr, (int)kvpr,
                                           d->kv_cap, d->kv_len, s))
   if (prefill) {
-    CAAT_STEP("flash_attn_fwd", launch_flash_fwd(QKV, H, nullptr, T * d->batch, d->seq, (int)hd, d->head_dim, s))
+    CAAT_STEP("flash_attn_fwd", launch_flash_fwd(QKV, H, nullptr, T * d->batch, d->seq, (int)hpr, (int)kvpr, d->head_dim, s))
   } else {
-    CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)hd,
+    CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)kvpr,
                                                 d->head_dim, d->kv_cap, d->kv_len + 1, s))
   }
   std::memset(&q, 0, sizeof(q));

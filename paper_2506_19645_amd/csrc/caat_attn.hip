@@ -25,15 +25,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t attn_rsrc(const void* p) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// RoPE in place on the q and k column blocks of qkv [rows, 3*hd] (row = rank*tokens + batch*seq + pos):
+// RoPE in place on the q and k column blocks of qkv [rows, ld] (row = rank*tokens + batch*seq + pos; the first
+// n_rot heads of a row, i.e. the q heads then the k heads, are rotated, the v heads after them are not):
 // pairs (j, j + d/2), angle pos * base^(-2j/d).  One thread rotates 8 pairs of one head of one row.
 // sign = +1 rotates forward; sign = -1 applies the transpose of that rotation (its inverse), which is what the
 // gradients of the rotated q and k need on their way back to the projection outputs.
-__global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, int seq, int hd, int d, float log2_base,
-                                                   long long pos0, float sign) {
+__global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, int seq, int ld, int n_rot, int d,
+                                                   float log2_base, long long pos0, float sign) {
   const int half = d >> 1;
   const int groups_per_head = half >> 3;            // 8 pairs per thread
-  const int heads2 = 2 * (hd / d);                  // q heads then k heads
+  const int heads2 = n_rot;                         // q heads then k heads
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long per_row = (long long)heads2 * groups_per_head;
   if (idx >= rows * per_row) return;
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, 
   const int rem = (int)(idx - row * per_row);
   const int head = rem / groups_per_head, grp = rem - head * groups_per_head;
   const float pos = (float)(pos0 + row % seq);
-  bf16_t* p = qkv + row * 3LL * hd + (long long)head * d + grp * 8;   // q heads occupy [0,hd), k heads [hd,2hd)
+  bf16_t* p = qkv + row * (long long)ld + (long long)head * d + grp * 8;   // q heads first, k heads right after them
   const uint4 lo = *reinterpret_cast<const uint4*>(p);
   const uint4 hi = *reinterpret_cast<const uint4*>(p + half);
   const unsigned lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
@@ -66,14 +67,14 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, 
   *reinterpret_cast<uint4*>(p + half) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
 }
 
-hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int hd, int d, float base, long long pos0, bool inverse,
-                       hipStream_t s) {
-  const long long work = rows * 2LL * (hd / d) * (d / 16);
+hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int ld, int n_rot, int d, float base, long long pos0,
+                       bool inverse, hipStream_t s) {
+  const long long work = rows * (long long)n_rot * (d / 16);
   if (work == 0) return hipSuccess;
   const long long blocks = (work + 255) / 256;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, rows, seq, hd, d, log2f(base), pos0,
-                     inverse ? -1.0f : 1.0f);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, rows, seq, ld, n_rot, d, log2f(base),
+                     pos0, inverse ? -1.0f : 1.0f);
   return hipGetLastError();
 }
 
@@ -94,11 +95,12 @@ size_t attn_stats_bytes(long long n_seq, int heads, int seq) { return (size_t)(n
 __device__ __forceinline__ int kswz(int row, int c) { return c ^ (row & 15); }
 __device__ __forceinline__ int vswz(int row, int c) { return c ^ ((row & 3) << 2); }
 
-// qkv: [T*tokens, 3*hd] with q | k | v column blocks (q, k already rotated); out: [T*tokens, hd]
+// qkv: [T*tokens, (heads + 2*kv_heads)*128] with q | k | v column blocks (q, k already rotated); out: [T*tokens, hd],
+// hd = heads*128.  Query head a reads key / value head a / (heads / kv_heads) (grouped-query attention).
 // stats (may be null): the forward fills the log-sum-exp rows (what the backward needs to rebuild the probabilities).
 __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                         float* __restrict__ stats, int seq, int seq_pad, int hd, int heads,
-                                                        int n_qblk, float scale_log2) {
+                                                        int kv_heads, int n_qblk, float scale_log2) {
   __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -109,11 +111,11 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
   const int bh = blockIdx.x % n_bh;              // (rank*batch + b) * heads + head
   const int head = bh % heads;
   const long long seq_row0 = (long long)(bh / heads) * seq;   // first row of this sequence in qkv
-  const long long ld = 3LL * hd;
+  const long long ld = (long long)(heads + 2 * kv_heads) * HD;
   const int q0 = qb * BQ;
   const bf16_t* qbase = qkv + seq_row0 * ld + (long long)head * HD;
-  const bf16_t* kbase = qbase + hd;
-  const bf16_t* vbase = qbase + 2 * hd;
+  const bf16_t* kbase = qkv + seq_row0 * ld + hd + (long long)(head / (heads / kv_heads)) * HD;
+  const bf16_t* vbase = kbase + kv_heads * HD;
 
   // ---- Q fragments: B operand of S^T = K q^T: lane (query frow, k-half hf) holds q[16*ks + 8*hf .. +7]
   bf16x8_t qf[HD / 16];
@@ -271,17 +273,18 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict
 }
 
 // qkv [n_seq*seq, 3*hd] (q|k|v, rotated) -> out [n_seq*seq, hd]; n_seq = T*batch sequences, heads = hd / 128 per rank
-hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, float* stats, long long n_seq, int seq, int hd, int d,
-                            hipStream_t s) {
-  if (d != HD) return hipErrorInvalidValue;
-  const int heads = hd / HD;
+hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, float* stats, long long n_seq, int seq, int heads, int kv_heads,
+                            int d, hipStream_t s) {
+  if (d != HD || kv_heads < 1 || heads % kv_heads != 0) return hipErrorInvalidValue;
+  const int hd = heads * HD;
   const int n_qblk = (seq + BQ - 1) / BQ;
   const long long blocks = n_seq * heads * n_qblk;
   if (blocks == 0) return hipSuccess;
-  if (blocks > 0x7FFFFFFFLL || (long long)(seq + BKV) * 3 * hd * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  if (blocks > 0x7FFFFFFFLL || (long long)(seq + BKV) * (heads + 2 * kv_heads) * HD * 2 >= 0x7FFFFFFFLL)
+    return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)d);
   hipLaunchKernelGGL(flash_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, out, stats, seq, (int)attn_seq_pad(seq), hd,
-                     heads, n_qblk, scale_log2);
+                     heads, kv_heads, n_qblk, scale_log2);
   return hipGetLastError();
 }
 
@@ -378,8 +381,8 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __rest
 //   dS^T registers, rounded to bf16, are the B operand of dQ^T += K^T dS^T (A operand = transpose reads of K).
 __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                            const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
-                                                           int seq_pad, int hd, int heads, int n_qblk, float scale_log2,
-                                                           float scale) {
+                                                           int seq_pad, int hd, int heads, int kv_heads, int n_qblk,
+                                                           float scale_log2, float scale) {
   __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -389,11 +392,11 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const bf16_t* __restr
   const int bh = blockIdx.x % n_bh;
   const int head = bh % heads;
   const long long seq_row0 = (long long)(bh / heads) * seq;
-  const long long ld = 3LL * hd;
+  const long long ld = (long long)(heads + 2 * kv_heads) * HD;
   const int q0 = qb * BQ;
   const bf16_t* qbase = qkv + seq_row0 * ld + (long long)head * HD;
-  const bf16_t* kbase = qbase + hd;
-  const bf16_t* vbase = qbase + 2 * hd;
+  const bf16_t* kbase = qkv + seq_row0 * ld + hd + (long long)(head / (heads / kv_heads)) * HD;
+  const bf16_t* vbase = kbase + kv_heads * HD;
   const bf16_t* dobase = dout + seq_row0 * (long long)hd + (long long)head * HD;
   const int qrow = q0 + wave * 32 + frow;
   const bool qvalid = qrow < seq;
@@ -485,27 +488,29 @@ static constexpr int DKV_STAGE = 2 * BQB * KCH + 64;        // uint4 per stage: 
 
 __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
-                                                            int seq_pad, int hd, int heads, int n_kblk, float scale_log2,
-                                                            float scale) {
+                                                            int seq_pad, int hd, int heads, int kv_heads, int n_kblk,
+                                                            float scale_log2, float scale) {
   __shared__ uint4 smem[2 * DKV_STAGE];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, hf = lane >> 5;
-  const int n_bh = gridDim.x / n_kblk;
+  const int n_bh = gridDim.x / n_kblk;                        // sequences x key/value heads
   const int kb = (int)(blockIdx.x / n_bh);                    // heaviest (first) key blocks first
   const int bh = blockIdx.x % n_bh;
-  const int head = bh % heads;
-  const long long seq_row0 = (long long)(bh / heads) * seq;
-  const long long ld = 3LL * hd;
+  const int kvh = bh % kv_heads;
+  const int grp = heads / kv_heads;                           // query heads that read this key / value head
+  const long long sq = bh / kv_heads;
+  const long long seq_row0 = sq * seq;
+  const long long ld = (long long)(heads + 2 * kv_heads) * HD;
   const int k0 = kb * 128;
   const int kw0 = k0 + wave * 32;
   const int krow = kw0 + frow;
   const bool kvalid = krow < seq;
-  const bf16_t* qbase = qkv + seq_row0 * ld + (long long)head * HD;
-  const bf16_t* kbase = qbase + hd;
-  const bf16_t* vbase = qbase + 2 * hd;
-  const bf16_t* dobase = dout + seq_row0 * (long long)hd + (long long)head * HD;
-  const float* stats_bh = stats + (long long)bh * 2 * seq_pad;     // lse row, then D row
+  const bf16_t* qbase = qkv + seq_row0 * ld + (long long)(kvh * grp) * HD;             // first query head of the group
+  const bf16_t* kbase = qkv + seq_row0 * ld + hd + (long long)kvh * HD;
+  const bf16_t* vbase = kbase + kv_heads * HD;
+  const bf16_t* dobase = dout + seq_row0 * (long long)hd + (long long)(kvh * grp) * HD;
+  const float* stats_bh = stats + (sq * heads + kvh * grp) * 2 * seq_pad;              // lse row, then D row, per query head
 
   bf16x8_t kf[HD / 16], vf[HD / 16];
   load_row_frags(kbase, ld, krow, kvalid, hf, kf);
@@ -519,29 +524,32 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
 
   const int nqb = (seq + BQB - 1) / BQB;
   const int qb0 = k0 / BQB;
-  auto issue = [&](int qb, int stage) {
-    const int q0 = qb * BQB;
+  const int nq = nqb - qb0;                                  // query blocks per query head (>= 1: k0 < seq)
+  const int n_it = nq * grp;                                 // walk: query head of the group (outer), query block (inner)
+  auto issue = [&](int it, int stage) {
+    const int g = it / nq;
+    const int q0 = (qb0 + it - g * nq) * BQB;
     uint4* qt = smem + stage * DKV_STAGE;
-    issue_tile64(qbase + (long long)q0 * ld, ld, seq - q0, qt, wave, lane);
-    issue_tile64(dobase + (long long)q0 * hd, hd, seq - q0, qt + BQB * KCH, wave, lane);
+    issue_tile64(qbase + (long long)g * HD + (long long)q0 * ld, ld, seq - q0, qt, wave, lane);
+    issue_tile64(dobase + (long long)g * HD + (long long)q0 * hd, hd, seq - q0, qt + BQB * KCH, wave, lane);
     if (wave == 0) {
       // lanes 0..15: lse of queries q0 + 4*lane .. +3; lanes 16..31: D likewise; the rest reads zeros.
       // q0 + 63 < seq_pad always, so the 16-byte pieces stay inside this (sequence, head)'s rows of statistics.
-      const i32x4_t rs = make_rsrc(stats_bh);
+      const i32x4_t rs = make_rsrc(stats_bh + (long long)g * 2 * seq_pad);
       const unsigned off = lane < 32 ? (unsigned)(((lane >> 4) * seq_pad + q0 + 4 * (lane & 15)) * 4) : OOB_OFF;
       dma16(rs, off, qt + 2 * BQB * KCH);
     }
   };
-  if (qb0 < nqb) issue(qb0, 0);
-  for (int qb = qb0; qb < nqb; ++qb) {
-    const int stage = (qb - qb0) & 1;
+  issue(0, 0);
+  for (int it = 0; it < n_it; ++it) {
+    const int stage = it & 1;
     wait_vmcnt<0>();
     __syncthreads();
-    if (qb + 1 < nqb) issue(qb + 1, stage ^ 1);
+    if (it + 1 < n_it) issue(it + 1, stage ^ 1);
     const uint4* qt = smem + stage * DKV_STAGE;
     const uint4* dot = qt + BQB * KCH;
     const float4* st = reinterpret_cast<const float4*>(qt + 2 * BQB * KCH);
-    const int q0 = qb * BQB;
+    const int q0 = (qb0 + it % nq) * BQB;
 #pragma unroll
     for (int j = 0; j < BQB / 32; ++j) {
       const int qs = q0 + j * 32;
@@ -588,8 +596,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
   }
   // lane holds dK[krow][32dt + 8(r/4) + 4hf + r%4] and dV likewise
   if (kvalid) {
-    bf16_t* ok = dqkv + (seq_row0 + krow) * ld + hd + (long long)head * HD;
-    bf16_t* ov = ok + hd;
+    bf16_t* ok = dqkv + (seq_row0 + krow) * ld + hd + (long long)kvh * HD;
+    bf16_t* ov = ok + kv_heads * HD;
 #pragma unroll
     for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
@@ -609,14 +617,15 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
 // gradient, stats with the forward's lse rows -> dqkv (gradients w.r.t. the ROTATED q, k and w.r.t. v, same layout
 // as qkv).  The D rows of stats are filled here.
 hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, float* stats, bf16_t* dqkv,
-                            long long n_seq, int seq, int hd, int d, hipStream_t s) {
-  if (d != HD) return hipErrorInvalidValue;
-  const int heads = hd / HD;
+                            long long n_seq, int seq, int heads, int kv_heads, int d, hipStream_t s) {
+  if (d != HD || kv_heads < 1 || heads % kv_heads != 0) return hipErrorInvalidValue;
+  const int hd = heads * HD;
   const long long n_bh = n_seq * heads;
   if (n_bh == 0 || seq == 0) return hipSuccess;
   const int seq_pad = (int)attn_seq_pad(seq);
   const int n_qblk = (seq + BQ - 1) / BQ;
-  if (n_bh * n_qblk > 0x7FFFFFFFLL || (long long)(seq + 128) * 3 * hd * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  if (n_bh * n_qblk > 0x7FFFFFFFLL || (long long)(seq + 128) * (heads + 2 * kv_heads) * HD * 2 >= 0x7FFFFFFFLL)
+    return hipErrorInvalidValue;
   const float inv_sqrt_d = 1.0f / sqrtf((float)d);
   const float scale_log2 = 1.4426950408889634f * inv_sqrt_d;
   const long long prep_threads = n_bh * seq_pad * 16;
@@ -625,12 +634,12 @@ hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* 
                      seq, seq_pad, hd, heads);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(flash_bwd_dkv_kernel, dim3((unsigned)(n_bh * n_qblk)), dim3(256), 0, s, qkv, dout, stats, dqkv, seq, seq_pad,
-                     hd, heads, n_qblk, scale_log2, inv_sqrt_d);
+  hipLaunchKernelGGL(flash_bwd_dkv_kernel, dim3((unsigned)(n_seq * kv_heads * n_qblk)), dim3(256), 0, s, qkv, dout, stats, dqkv,
+                     seq, seq_pad, hd, heads, kv_heads, n_qblk, scale_log2, inv_sqrt_d);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(flash_bwd_dq_kernel, dim3((unsigned)(n_bh * n_qblk)), dim3(256), 0, s, qkv, dout, stats, dqkv, seq, seq_pad,
-                     hd, heads, n_qblk, scale_log2, inv_sqrt_d);
+                     hd, heads, kv_heads, n_qblk, scale_log2, inv_sqrt_d);
   return hipGetLastError();
 }
 
@@ -642,25 +651,26 @@ hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* 
 // 16 lanes own one key row (256 B), a wave takes 4 consecutive keys per step, the 4 waves 16; every 16-lane group
 // runs its own online softmax and the 16 partial results are merged through LDS in a fixed order.
 __global__ __launch_bounds__(256) void kv_append_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ kc,
-                                                        bf16_t* __restrict__ vc, long long n_seq, int seq, int hpr, int hd,
+                                                        bf16_t* __restrict__ vc, long long n_seq, int seq, int hpr, int kvpr,
                                                         long long cap, long long pos) {
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;   // ((sequence, token), head, chunk of 8)
-  if (idx >= n_seq * seq * hpr * 16) return;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;   // ((sequence, token), key/value head, chunk of 8)
+  if (idx >= n_seq * seq * kvpr * 16) return;
   const int c = (int)(idx & 15);
-  const long long rh = idx >> 4;                                      // row * hpr + head
-  const long long row = rh / hpr;                                     // sequence * seq + token
-  const int head = (int)(rh - row * hpr);
+  const long long rh = idx >> 4;                                      // row * kvpr + head
+  const long long row = rh / kvpr;                                    // sequence * seq + token
+  const int head = (int)(rh - row * kvpr);
   const long long sq = row / seq;
   const long long t = row - sq * seq;
-  const bf16_t* src = qkv + row * 3LL * hd + (long long)head * 128 + c * 8;
-  const long long dst = ((sq * hpr + head) * cap + pos + t) * 128 + c * 8;
-  *reinterpret_cast<uint4*>(kc + dst) = *reinterpret_cast<const uint4*>(src + hd);
-  *reinterpret_cast<uint4*>(vc + dst) = *reinterpret_cast<const uint4*>(src + 2 * hd);
+  const long long ld = (long long)(hpr + 2 * kvpr) * 128;
+  const bf16_t* src = qkv + row * ld + (long long)(hpr + head) * 128 + c * 8;   // k heads follow the q heads
+  const long long dst = ((sq * kvpr + head) * cap + pos + t) * 128 + c * 8;
+  *reinterpret_cast<uint4*>(kc + dst) = *reinterpret_cast<const uint4*>(src);
+  *reinterpret_cast<uint4*>(vc + dst) = *reinterpret_cast<const uint4*>(src + kvpr * 128);
 }
 
 __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kc,
                                                           const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, int hpr,
-                                                          int hd, long long cap, int nkeys, float scale_log2) {
+                                                          int kvpr, long long cap, int nkeys, float scale_log2) {
   __shared__ float s_acc[16][128];
   __shared__ float s_m[16], s_l[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -670,14 +680,15 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restri
   const int head = (int)(sh - sq * hpr);
   float q[8];
   {
-    const uint4 w = *reinterpret_cast<const uint4*>(qkv + sq * 3LL * hd + (long long)head * 128 + c * 8);
+    const uint4 w = *reinterpret_cast<const uint4*>(qkv + sq * (long long)(hpr + 2 * kvpr) * 128 + (long long)head * 128 + c * 8);
     q[0] = lo_bf(w.x); q[1] = hi_bf(w.x); q[2] = lo_bf(w.y); q[3] = hi_bf(w.y);
     q[4] = lo_bf(w.z); q[5] = hi_bf(w.z); q[6] = lo_bf(w.w); q[7] = hi_bf(w.w);
 #pragma unroll
     for (int e = 0; e < 8; ++e) q[e] *= scale_log2;
   }
-  const __amdgpu_buffer_rsrc_t rk = attn_rsrc(kc + sh * cap * 128);
-  const __amdgpu_buffer_rsrc_t rv = attn_rsrc(vc + sh * cap * 128);
+  const long long kvh = sq * kvpr + head / (hpr / kvpr);               // grouped-query attention: the group's cache rows
+  const __amdgpu_buffer_rsrc_t rk = attn_rsrc(kc + kvh * cap * 128);
+  const __amdgpu_buffer_rsrc_t rv = attn_rsrc(vc + kvh * cap * 128);
   float m = -INFINITY, l = 0.0f, acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   constexpr int UN = 4;
   for (int key0 = wave * 4 + g; key0 < nkeys; key0 += 16 * UN) {
@@ -730,30 +741,32 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restri
       num += s_acc[i][tid] * w;
       den += s_l[i] * w;
     }
-    out[sq * (long long)hd + (long long)head * 128 + tid] = f2bf(num / den);
+    out[sh * 128 + tid] = f2bf(num / den);
   }
 }
 
-// rotated k and v of `seq` consecutive tokens per sequence (rows of qkv) -> cache positions pos .. pos+seq-1
-hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int seq, int hpr, int hd,
+// rotated k and v of `seq` consecutive tokens per sequence (rows of qkv) -> cache positions pos .. pos+seq-1 of
+// caches [n_seq][kvpr][cap][128]
+hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int seq, int hpr, int kvpr,
                             long long cap, long long pos, hipStream_t s) {
-  const long long work = n_seq * seq * hpr * 16;
+  const long long work = n_seq * seq * kvpr * 16;
   if (work == 0) return hipSuccess;
   if (pos < 0 || pos + seq > cap || (work + 255) / 256 > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, qkv, kc, vc, n_seq, seq, hpr,
-                     hd, cap, pos);
+                     kvpr, cap, pos);
   return hipGetLastError();
 }
 
-// out [n_seq, hd] = softmax(q K^T / sqrt(d)) V over keys 0 .. nkeys-1 of caches [n_seq][hpr][cap][128]
+// out [n_seq, hpr*128] = softmax(q K^T / sqrt(d)) V over keys 0 .. nkeys-1 of caches [n_seq][kvpr][cap][128]
 hipError_t launch_decode_attn(const bf16_t* qkv, const bf16_t* kc, const bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
-                              int hd, int d, long long cap, long long nkeys, hipStream_t s) {
-  if (d != HD || nkeys < 1 || nkeys > cap || cap * 256 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+                              int kvpr, int d, long long cap, long long nkeys, hipStream_t s) {
+  if (d != HD || kvpr < 1 || hpr % kvpr != 0 || nkeys < 1 || nkeys > cap || cap * 256 >= 0x7FFFFFFFLL)
+    return hipErrorInvalidValue;
   const long long blocks = n_seq * hpr;
   if (blocks == 0) return hipSuccess;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)d);
-  hipLaunchKernelGGL(decode_attn_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, kc, vc, out, hpr, hd, cap, (int)nkeys,
+  hipLaunchKernelGGL(decode_attn_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, kc, vc, out, hpr, kvpr, cap, (int)nkeys,
                      scale_log2);
   return hipGetLastError();
 }

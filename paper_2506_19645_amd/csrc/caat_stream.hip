@@ -128,6 +128,7 @@ static hipError_t sync_any(const bf16_t* y, const bf16_t* resid, bf16_t* out, in
     case 2: return sync_dispatch<2>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
     case 4: return sync_dispatch<4>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
     case 8: return sync_dispatch<8>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
+    case 16: return sync_dispatch<16>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
     default: return sync_dispatch<0>(y, resid, out, T, tokens, h, hs, private_scale, ncg, shared_only, s);
   }
 }

@@ -30,7 +30,7 @@ def run_attn_block(cfg, d, backward=False):
 
     out = {"Rp_bits": B.to_host_bits(r_out), "Xp_bits": B.to_host_bits(x_out)}
     out["Rp"], out["Xp"] = bits_to_f64(out["Rp_bits"]), bits_to_f64(out["Xp_bits"])
-    out["QKV"] = ws_bf16(L.off_Q, L.bytes_Q, (T, n, 3 * hd))
+    out["QKV"] = ws_bf16(L.off_Q, L.bytes_Q, (T, n, cfg.qkv_r))
     out["H"] = ws_bf16(L.off_Y, L.bytes_Y, (T, n, hd))
     if backward:
         dxo, dro = B.to_device(d["dXo"]), B.to_device(d["dRo"])
@@ -47,14 +47,15 @@ def run_attn_block(cfg, d, backward=False):
             out["dbeta"] = dbeta.cpu().numpy().astype(np.float64)
         out["dZt"] = ws_bf16(L.off_dZt, L.bytes_dZt, (T, n, h))
         out["dH"] = ws_bf16(L.off_dH, L.bytes_dH, (T, n, hd))
-        out["dqkv"] = ws_bf16(L.off_dP, L.bytes_dP, (T, n, 3 * hd))
+        out["dqkv"] = ws_bf16(L.off_dP, L.bytes_dP, (T, n, cfg.qkv_r))
     return out
 
 
 def _oracle_kw(cfg):
     norm = O.LAYERNORM if cfg.norm == I.NORM_LAYERNORM else O.RMSNORM
     return dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim, norm=norm,
-                hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base)
+                hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base,
+                kv_heads_per_rank=cfg.kv_heads // cfg.T)
 
 
 def oracle_attn_block(cfg, d):
@@ -75,9 +76,10 @@ def check_attn_bwd(got, g):
 
 def check_attn(cfg, d, got, fwd):
     T, b, s, hpr, dh, hd = cfg.T, cfg.batch, cfg.seq, cfg.n_heads // cfg.T, cfg.head_dim, cfg.hd_r
-    qkv = got["QKV"].reshape(T, b, s, 3, hpr, dh)
-    for k, name in enumerate(("Q", "K", "V")):
-        assert_close(qkv[:, :, :, k].transpose(0, 1, 3, 2, 4), fwd[name], name)
+    kvpr, kvd = cfg.kv_heads // T, cfg.kvd_r
+    qkv = got["QKV"].reshape(T, b, s, cfg.qkv_r)
+    for name, c0, c1, nh in (("Q", 0, hd, hpr), ("K", hd, hd + kvd, kvpr), ("V", hd + kvd, hd + 2 * kvd, kvpr)):
+        assert_close(qkv[..., c0:c1].reshape(T, b, s, nh, dh).transpose(0, 1, 3, 2, 4), fwd[name], name)
     assert_close(got["H"], fwd["H"], "H")
     assert_close(got["Rp"], fwd["Rp"], "Rp")
     assert_close(got["Xp"], fwd["Xp"], "Xp")
@@ -87,9 +89,9 @@ def check_attn(cfg, d, got, fwd):
             assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
 
 
-def _cfg(T, batch, seq, heads, p, norm=I.NORM_RMSNORM, scale=1.0):
+def _cfg(T, batch, seq, heads, p, norm=I.NORM_RMSNORM, scale=1.0, kv_heads=0):
     return I.BlockConfig("a", I.KIND_ATTN, norm, h=heads * 128, T=T, p=p, batch=batch, seq=seq, n_heads=heads,
-                         head_dim=128, private_scale=scale)
+                         head_dim=128, private_scale=scale, n_kv_heads=kv_heads)
 
 
 @pytest.mark.parametrize("T,batch,seq,heads,p,norm", [
@@ -106,7 +108,7 @@ def test_attn_block_fwd(T, batch, seq, heads, p, norm):
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
     if seq == 1:
-        v = got["QKV"].reshape(T, batch, 3, -1)[:, :, 2]
+        v = got["QKV"].reshape(T, batch, -1)[:, :, 2 * cfg.hd_r:]
         assert np.array_equal(got["H"].reshape(T, batch, -1), v)
 
 
@@ -140,10 +142,10 @@ def test_attn_block_bwd(T, batch, seq, heads, p, norm, scale):
     check_attn_bwd(got, g)
     if seq == 1:
         hd = cfg.hd_r
-        dqkv = got["dqkv"].reshape(T, batch, 3, hd)
+        dqkv = got["dqkv"].reshape(T, batch, 3 * hd)
         # dS = P (dP - D) with P = 1 and dP = D up to the summation order of two fp32 dot products
-        assert np.abs(dqkv[:, :, :2]).max() <= 1e-4 * np.abs(dqkv[:, :, 2]).max()
-        assert np.array_equal(dqkv[:, :, 2], got["dH"].reshape(T, batch, hd))
+        assert np.abs(dqkv[:, :, :2 * hd]).max() <= 1e-4 * np.abs(dqkv[:, :, 2 * hd:]).max()
+        assert np.array_equal(dqkv[:, :, 2 * hd:], got["dH"].reshape(T, batch, hd))
 
 
 def test_attn_bwd_causal_on_gpu():
@@ -159,3 +161,18 @@ def test_attn_bwd_causal_on_gpu():
     assert not dq[:, :100].any()            # queries before position 100 received no gradient
     assert dq[:, 100:].any()
     assert got["dqkv"][:, :100, hd:].any()  # earlier keys / values do receive gradient from later queries
+
+
+@pytest.mark.parametrize("T,batch,seq,heads,kv_heads,p", [
+    (2, 2, 200, 8, 2, 0.5),      # 4 query heads per rank share one key / value head
+    (2, 1, 333, 8, 4, 0.25),     # two groups of two per rank
+    (1, 2, 130, 4, 1, 1.0),      # multi-query attention: one key / value head in all
+])
+def test_gqa_attn_block_fwd_bwd(T, batch, seq, heads, kv_heads, p):
+    """Grouped-query attention (the 34B / 70B shapes of the paper's additional speed-up results), forward + backward."""
+    cfg = _cfg(T, batch, seq, heads, p, kv_heads=kv_heads)
+    d = I.make_inputs(cfg, seed=25, with_grads=True, weight_std=0.05)
+    got = run_attn_block(cfg, d, backward=True)
+    w, fwd = oracle_attn_block(cfg, d)
+    check_attn(cfg, d, got, fwd)
+    check_attn_bwd(got, oracle_attn_bwd(cfg, w, fwd))

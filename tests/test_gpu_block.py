@@ -107,6 +107,7 @@ def _cfg(swi, T, n, h, ffn, p, scale=1.0):
     (4, 515, 512, 4 * 520, 0.25, math.sqrt(4.0)),   # private channel scaling sqrt(T)
     (2, 129, 256, 1024, 1.0, 1.0),       # p = 1
     (2, 129, 256, 1024, 0.0, 1.0),       # p = 0
+    (16, 70, 512, 16 * 136, 0.5, 1.0),   # tensor-parallel degree 16 (the paper's largest), ragged shard of 136 columns
 ])
 def test_mlp_block_fwd_bwd(swi, T, n, h, ffn, p, scale):
     cfg = _cfg(swi, T, n, h, ffn, p, scale)

@@ -33,24 +33,27 @@ def run_decode(cfg, d):
             "Kc_bits": B.to_host_bits(kc), "Vc_bits": B.to_host_bits(vc)}
 
 
-def _cfg(T, b, heads, ffn, L, p):
+def _cfg(T, b, heads, ffn, L, p, kv_heads=0):
     return I.BlockConfig("dec", I.KIND_DECODE, I.NORM_RMSNORM, h=heads * 128, T=T, p=p, batch=b, seq=1, ffn=ffn,
-                         n_heads=heads, head_dim=128, kv_len=L)
+                         n_heads=heads, head_dim=128, kv_len=L, n_kv_heads=kv_heads)
 
 
-@pytest.mark.parametrize("T,b,heads,ffn,L,p", [
-    (2, 3, 4, 2 * 344, 37, 0.5),      # fewer keys than one 64-key sweep, ragged ffn shard
-    (2, 64, 4, 2 * 256, 300, 0.25),   # the benchmark's batch, several sweeps + tail
-    (4, 5, 4, 4 * 128, 0, 1.0),       # empty cache: the token attends to itself only
-    (1, 2, 2, 256, 129, 0.0),
+@pytest.mark.parametrize("T,b,heads,ffn,L,p,kv_heads", [
+    (2, 3, 4, 2 * 344, 37, 0.5, 0),      # fewer keys than one 64-key sweep, ragged ffn shard
+    (2, 64, 4, 2 * 256, 300, 0.25, 0),   # the benchmark's batch, several sweeps + tail
+    (4, 5, 4, 4 * 128, 0, 1.0, 0),       # empty cache: the token attends to itself only
+    (1, 2, 2, 256, 129, 0.0, 0),
+    (2, 5, 8, 2 * 256, 200, 0.5, 2),     # grouped-query attention: 4 query heads per key / value head
+    (2, 3, 8, 2 * 256, 70, 0.5, 4),      # two groups per rank
 ])
-def test_decode_layer(T, b, heads, ffn, L, p):
-    cfg = _cfg(T, b, heads, ffn, L, p)
+def test_decode_layer(T, b, heads, ffn, L, p, kv_heads):
+    cfg = _cfg(T, b, heads, ffn, L, p, kv_heads)
     d = I.make_inputs(cfg, seed=31, weight_std=0.05)
     got = run_decode(cfg, d)
     w = {k: O.widen_bf16(v) for k, v in d.items()}
     hpr = heads // T
-    ref = O.decode_layer_fwd(w["R"], w, w["Kc"], w["Vc"], kv_len=L, heads_per_rank=hpr, head_dim=128, hs=cfg.hs)
+    ref = O.decode_layer_fwd(w["R"], w, w["Kc"], w["Vc"], kv_len=L, heads_per_rank=hpr, head_dim=128, hs=cfg.hs,
+                             kv_heads_per_rank=cfg.kv_heads // T)
     assert_close(got["X1"], ref["X1"], "X1")
     assert_close(got["H"], ref["H"], "H")
     assert_close(got["R1"], ref["R1"], "R1")

@@ -17,7 +17,7 @@ def _torch():
 
 
 # ------------------------------------------------------------------------------------------ partial sync
-@pytest.mark.parametrize("T", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 8, 16])
 def test_partial_sync_integer_bit_exact(T):
     """Small-integer inputs make every sum exact: GPU bits must equal the oracle's, for every hs edge case."""
     torch = _torch()
@@ -41,7 +41,8 @@ def test_partial_sync_integer_bit_exact(T):
                 assert np.array_equal(B.to_host_bits(y2), got), ("inplace", T, hs, scale, use_res)
 
 
-@pytest.mark.parametrize("T,n,h,hs", [(2, 256, 768, 384), (4, 333, 2048, 1000), (8, 129, 4096, 2048), (5, 64, 264, 131)])
+@pytest.mark.parametrize("T,n,h,hs", [(2, 256, 768, 384), (4, 333, 2048, 1000), (8, 129, 4096, 2048), (5, 64, 264, 131),
+                                        (16, 70, 8192, 4096)])
 def test_partial_sync_random_values(T, n, h, hs):
     torch = _torch()
     d = I.make_sync_inputs(T, n, h, seed=3)

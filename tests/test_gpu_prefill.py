@@ -19,7 +19,7 @@ def layer_weights(d):
 def run_prefill(cfg, d, kv_cap=None, keep=("X1", "H", "R1", "X2")):
     import torch
     desc = B.make_desc(cfg, kv_cap=kv_cap)
-    T, n, h, hd, hpr = cfg.T, cfg.tokens, cfg.h, cfg.hd_r, cfg.n_heads // cfg.T
+    T, n, h, hd, hpr = cfg.T, cfg.tokens, cfg.h, cfg.hd_r, cfg.kv_heads // cfg.T     # hpr: key / value heads per rank
     weights = layer_weights(d)
     r = B.to_device(d["R"])
     cap = desc.kv_cap
@@ -47,7 +47,7 @@ def oracle_prefill(cfg, d):
     w = {k: O.widen_bf16(v) for k, v in d.items()}
     return w, O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T,
                                   head_dim=cfg.head_dim, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale,
-                                  rope_base=cfg.rope_base)
+                                  rope_base=cfg.rope_base, kv_heads_per_rank=cfg.kv_heads // cfg.T)
 
 
 def check_prefill(cfg, d, got, ref, rows=None):
@@ -59,20 +59,21 @@ def check_prefill(cfg, d, got, ref, rows=None):
     assert_close(bits_to_f64(sel(got["R2_bits"])), ref["R2"], "R2")
 
 
-def _cfg(T, batch, seq, heads, ffn, p, scale=1.0):
+def _cfg(T, batch, seq, heads, ffn, p, scale=1.0, kv_heads=0):
     return I.BlockConfig("pre", I.KIND_PREFILL, I.NORM_RMSNORM, h=heads * 128, T=T, p=p, batch=batch, seq=seq, ffn=ffn,
-                         n_heads=heads, head_dim=128, private_scale=scale)
+                         n_heads=heads, head_dim=128, private_scale=scale, n_kv_heads=kv_heads)
 
 
-@pytest.mark.parametrize("T,batch,seq,heads,ffn,p,scale", [
-    (2, 1, 64, 2, 2 * 256, 0.5, 1.0),         # one key block
-    (2, 3, 200, 4, 2 * 344, 0.5, 1.0),        # three ragged sequences, ragged ffn shard
-    (4, 2, 130, 4, 4 * 128, 0.25, 2.0),       # private-channel scaling sqrt(T)
-    (1, 1, 333, 2, 512, 1.0, 1.0),            # T = 1
-    (2, 2, 70, 2, 2 * 256, 0.0, 1.0),         # p = 0
+@pytest.mark.parametrize("T,batch,seq,heads,ffn,p,scale,kv_heads", [
+    (2, 1, 64, 2, 2 * 256, 0.5, 1.0, 0),         # one key block
+    (2, 3, 200, 4, 2 * 344, 0.5, 1.0, 0),        # three ragged sequences, ragged ffn shard
+    (4, 2, 130, 4, 4 * 128, 0.25, 2.0, 0),       # private-channel scaling sqrt(T)
+    (1, 1, 333, 2, 512, 1.0, 1.0, 0),            # T = 1
+    (2, 2, 70, 2, 2 * 256, 0.0, 1.0, 0),         # p = 0
+    (2, 2, 200, 8, 2 * 256, 0.5, 1.0, 2),        # grouped-query attention
 ])
-def test_prefill_layer(T, batch, seq, heads, ffn, p, scale):
-    cfg = _cfg(T, batch, seq, heads, ffn, p, scale)
+def test_prefill_layer(T, batch, seq, heads, ffn, p, scale, kv_heads):
+    cfg = _cfg(T, batch, seq, heads, ffn, p, scale, kv_heads)
     d = I.make_inputs(cfg, seed=41, weight_std=0.05)
     got = run_prefill(cfg, d, kv_cap=seq + 3)
     w, ref = oracle_prefill(cfg, d)
