@@ -270,18 +270,21 @@ def bench_attention_kinds(args, cfg, base):
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
         workload = "%s attention sub-block %s: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
             cfg.name, "fwd+bwd" if bwd else "fwd", h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, cfg.hs)
-    elif args.config == "C6":
+    elif args.config in ("C6", "C7"):
         bench = PrefillBench(cfg)
         s, f = cfg.seq, cfg.ffn
+        qkv_cols = T * cfg.qkv_r                    # h + 2 * (key/value width); 3h without grouped-query attention
+        kvd = cfg.kvd_r
         # the two row-parallel launches of a step (o_proj 2nh^2, down projection 2nhf) share a kernel family
-        fl = {"gemm_nt_qkv": 2.0 * n * h * 3 * h, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,
+        fl = {"gemm_nt_qkv": 2.0 * n * h * qkv_cols, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,
               "gemm_nt_rowpar": n * h * h + n * h * f, "gemm_nt_swiglu_fwd": 4.0 * n * h * f}
-        by = {"rope": 2.0 * T * n * 2 * hd * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
-              "norm_fwd": 2.0 * T * n * h * 2, "kv_append": 2.0 * T * n * 2 * hd * 2}
-        work = n * (8.0 * h * h + 6.0 * h * f) + 2.0 * cfg.batch * s * s * h
+        by = {"rope": 2.0 * T * n * (hd + kvd) * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
+              "norm_fwd": 2.0 * T * n * h * 2, "kv_append": 2.0 * T * n * 2 * kvd * 2}
+        work = n * (2.0 * h * qkv_cols + 2.0 * h * h + 6.0 * h * f) + 2.0 * cfg.batch * s * s * h
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
-        workload = ("%s prefill decoder layer fwd: h=%d ffn=%d heads=%d d=%d RoPE causal, %d prompts x %d tokens, T=%d p=%g "
-                    "(hs=%d)" % (cfg.name, h, f, cfg.n_heads, cfg.head_dim, cfg.batch, s, T, cfg.p, cfg.hs))
+        workload = ("%s prefill decoder layer fwd: h=%d ffn=%d heads=%d kv_heads=%d d=%d RoPE causal, %d prompts x %d tokens, "
+                    "T=%d p=%g (hs=%d)" % (cfg.name, h, f, cfg.n_heads, cfg.kv_heads, cfg.head_dim, cfg.batch, s, T, cfg.p,
+                                           cfg.hs))
     else:
         bench = DecodeBench(cfg)
         fr = cfg.f_r
@@ -308,7 +311,7 @@ def bench_attention_kinds(args, cfg, base):
             e["frac_hbm_peak"] = round(by[name] / v["avg_ms"] / 1e6 / HBM_PEAK_GBS, 4)
         kernels[name] = e
     dom = max(prof, key=lambda k: prof[k]["avg_ms"] * prof[k]["launches_per_step"])
-    if args.config in ("C4", "C6"):
+    if args.config in ("C4", "C6", "C7"):
         value = work / ms / 1e9
         ach = fl.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e9
         roof = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
@@ -323,12 +326,12 @@ def bench_attention_kinds(args, cfg, base):
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": workload, "work_per_step": work, "frac_peak": value / peak, "wall_ms_per_step": wall_ms},
            "roofline": roof, "kernels": kernels}
-    if args.config == "C6":
-        # time to first token of a 32-layer model of this layer, and the paper's analytic model (App. C) next to the
+    if args.config in ("C6", "C7"):
+        # time to first token of a model made of this layer of this layer, and the paper's analytic model (App. C) next to the
         # measured p sweep.  On one GPU the "communication" is the in-HBM reduce over the T emulated ranks, so the
         # compute / communication capacity ratio C of the model is not a property of this machine; the model's linear
         # dependence on (1 - p) is what can be compared, with C fitted from the two end points p = 1 and p = 0.
-        layers = 32
+        layers = 32 if args.config == "C6" else 80
         out["config"]["ttft_ms_%d_layers" % layers] = ms * layers
         sweep = []
         if not args.no_sweep:
@@ -367,7 +370,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "C6"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "C6", "C7"])
     ap.add_argument("--p", type=float, default=0.5)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
@@ -389,7 +392,7 @@ def main():
     B.lib()
     base = I.CONFIGS[args.config]
     cfg = base.with_(p=args.p)
-    if args.config in ("C4", "C5", "C6"):
+    if args.config in ("C4", "C5", "C6", "C7"):
         print(json.dumps(bench_attention_kinds(args, cfg, base)))
         return
     bench = MlpBench(cfg, seed=0)

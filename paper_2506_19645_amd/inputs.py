@@ -101,7 +101,11 @@ C5 = BlockConfig("C5-llama7b-decode", KIND_DECODE, NORM_RMSNORM, h=4096, T=8, p=
 # (Sec. 5.2: 2K-token prompts, batch 16 and up, Llama-7B dimensions, TP 8).
 C6 = BlockConfig("C6-llama7b-prefill-layer", KIND_PREFILL, NORM_RMSNORM, h=4096, T=8, p=0.5, batch=16, seq=2048,
                  ffn=11008, n_heads=32, head_dim=128)
-CONFIGS = {c.name.split("-")[0]: c for c in (C1, C2, C3, C4, C5, C6)}
+# The same layer with Llama-2-70B dimensions: grouped-query attention with 8 key / value heads, which caps the
+# tensor-parallel degree at 8 (the paper's additional speed-up results).
+C7 = BlockConfig("C7-llama70b-prefill-layer", KIND_PREFILL, NORM_RMSNORM, h=8192, T=8, p=0.5, batch=8, seq=2048,
+                 ffn=28672, n_heads=64, head_dim=128, n_kv_heads=8)
+CONFIGS = {c.name.split("-")[0]: c for c in (C1, C2, C3, C4, C5, C6, C7)}
 
 
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:

@@ -94,3 +94,18 @@ def test_config6_prefill_layer_full_size_sampled_sequence():
     hs = cfg.hs
     for m in range(1, cfg.T):
         assert np.array_equal(got["R2_bits"][m, :, :hs], got["R2_bits"][0, :, :hs])
+
+
+def test_config7_llama70b_gqa_prefill_layer_sampled_sequence():
+    """Llama-2-70B dimensions (h=8192, 64 query heads, 8 key / value heads, ffn=28672), T=8, 8 prompts of 2048 tokens:
+    the whole batch on the GPU, one sequence through the oracle."""
+    cfg = I.C7
+    d = I.make_inputs(cfg, seed=0)
+    got = run_prefill(cfg, d, keep=("H",))
+    sq = 5
+    rows = slice(sq * cfg.seq, (sq + 1) * cfg.seq)
+    one = cfg.with_(batch=1)
+    w, ref = oracle_prefill(one, dict(d, R=np.ascontiguousarray(d["R"][:, rows])))
+    check_prefill(one, d, got, ref, rows=rows)
+    assert_close(bits_to_f64(got["Kc_bits"][:, sq:sq + 1, :, :cfg.seq]), ref["K"], "K cache")
+    assert_close(bits_to_f64(got["Vc_bits"][:, sq:sq + 1, :, :cfg.seq]), ref["V"], "V cache")
