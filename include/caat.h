@@ -84,6 +84,12 @@ typedef struct caat_desc {
   float rope_base;      /* RoPE base (10000) */
   int n_kv_heads;       /* grouped-query attention: key / value heads over all ranks; 0 = n_heads (multi-head).
                            n_heads % n_kv_heads == 0 and n_kv_heads % T == 0 (each rank owns whole groups) */
+  int reduce_in_gemm;   /* forward only.  0: every rank's partial sum on the shared channels is written out and a reduce
+                           pass sums them (the in-HBM stand-in for the tensor-parallel collective).  1: single-device
+                           serving with logical ranks (Sec. 3.2, the reduce becomes a local summation): the shared
+                           channels come from one GEMM whose contraction runs over all T ranks, so the sum is taken in
+                           the accumulator, no partial sum reaches memory and no reduce pass runs.  Needs hs % 8 == 0
+                           (otherwise the default path is taken).  Same result up to the rounding of the partials. */
 } caat_desc;
 
 /* Byte offsets of the tensors caat_block_fwd leaves in the workspace (0 size = not present).  For tests

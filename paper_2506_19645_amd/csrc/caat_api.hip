@@ -59,6 +59,7 @@ int validate_desc(const caat_desc* d) {
   if (d->norm != CAAT_LAYERNORM && d->norm != CAAT_RMSNORM) return CAAT_EINVAL;
   if (d->T < 1 || d->h < 1 || d->tokens < 0) return CAAT_EINVAL;
   if (!(d->eps >= 0.0f) || std::isnan(d->private_scale)) return CAAT_EINVAL;
+  if (d->reduce_in_gemm != 0 && d->reduce_in_gemm != 1) return CAAT_EINVAL;
   if (d->hs < 0 || d->hs > d->h) return CAAT_ESHAPE;
   if (d->h % 8 != 0 || d->h > 8192) return CAAT_ESHAPE;
   if (d->tokens > 0x7FFFFFFFLL) return CAAT_ESHAPE;
@@ -123,6 +124,70 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
   return CAAT_OK;
 }
 
+// Row-parallel projection closed by the partial channel-reduce and the residual add (Eq. A3 / A5, second line + Sec. 4):
+//   out_m = PCR_p(a_m W_m^T)_m + resid_m,   a [T,n,kdim], W [T][h][kdim], resid / out [T,n,h].
+// Default: one grouped GEMM whose epilogue finishes the private channels and leaves each rank's partial sum on the
+// shared ones, then the reduce kernel over the T partials (the stand-in for the tensor-parallel collective).
+// reduce_in_gemm (single-device serving with logical ranks, Sec. 3.2: the reduce becomes a local summation): the
+// private channels come from a grouped GEMM over columns hs..h-1, the shared channels from ONE GEMM whose contraction
+// index runs over all T ranks' inputs and weight rows, so the sum over ranks is taken in the accumulator and no partial
+// sum ever reaches memory.
+int rowpar_pcr(const caat_desc* d, const bf16_t* a, long long kdim, const bf16_t* w, const bf16_t* resid, bf16_t* out,
+               hipStream_t s) {
+  const long long T = d->T, n = d->tokens, h = d->h;
+  const int hs = d->hs;
+  hipError_t e = hipSuccess;
+  GemmParams q;
+  if (d->reduce_in_gemm && hs % 8 == 0) {
+    if (hs < h) {
+      std::memset(&q, 0, sizeof(q));
+      q.a = a; q.lda = kdim; q.stride_a = n * kdim;
+      q.b = w + (long long)hs * kdim; q.ldb = kdim; q.stride_b = h * kdim;
+      q.c = out + hs; q.ldc = h; q.stride_c = n * h;
+      q.aux = resid + hs; q.ldaux = h; q.stride_aux = n * h;
+      q.G = (int)T; q.M = (int)n; q.N = (int)(h - hs); q.K = (int)kdim;
+      q.hs = 0; q.scale = d->private_scale;
+      {
+        ProfScope ps(s, "gemm_nt_rowpar_private");
+        e = launch_gemm(q, 0, EPI_ROWPAR, s);
+      }
+      if (e != hipSuccess) return CAAT_EHIP;
+    }
+    if (hs > 0) {
+      std::memset(&q, 0, sizeof(q));
+      q.a = a; q.lda = kdim; q.kstride_a = n * kdim;
+      q.b = w; q.ldb = kdim; q.kstride_b = h * kdim;
+      q.c = out; q.ldc = h; q.stride_c = n * h;
+      q.aux = resid; q.ldaux = h; q.stride_aux = n * h;
+      q.G = 1; q.M = (int)n; q.N = hs; q.K = (int)kdim; q.kcat = (int)T; q.bcast = (int)T;
+      {
+        ProfScope ps(s, "gemm_nt_shared_kcat");
+        e = launch_gemm(q, 0, EPI_SHARED_BCAST, s);
+      }
+      if (e != hipSuccess) return CAAT_EHIP;
+    }
+    return CAAT_OK;
+  }
+  std::memset(&q, 0, sizeof(q));
+  q.a = a; q.lda = kdim; q.stride_a = n * kdim;
+  q.b = w; q.ldb = kdim; q.stride_b = h * kdim;
+  q.c = out; q.ldc = h; q.stride_c = n * h;
+  q.aux = resid; q.ldaux = h; q.stride_aux = n * h;
+  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)kdim;
+  q.hs = hs; q.scale = d->private_scale;
+  {
+    ProfScope ps(s, "gemm_nt_rowpar");
+    e = launch_gemm(q, 0, EPI_ROWPAR, s);
+  }
+  if (e != hipSuccess) return CAAT_EHIP;
+  if (hs > 0) {
+    ProfScope ps(s, "partial_sync_fwd");
+    e = launch_partial_sync_shared(out, resid, (int)T, n, (int)h, hs, s);
+    if (e != hipSuccess) return CAAT_EHIP;
+  }
+  return CAAT_OK;
+}
+
 // Attention sub-block forward (Eq. A5 + Sec. 4): per rank q,k,v = X_m Wqkv_m^T; RoPE(q,k); causal attention per head;
 // Zt_m = H_m Wo_m^T with the private half of the partial channel-reduce in the epilogue; shared half; norm.
 int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* weights, const void* x, const void* r,
@@ -166,23 +231,9 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
     e = launch_flash_fwd(QKV, H, stats, T * d->batch, d->seq, hpr, kvpr, d->head_dim, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
-  GemmParams g2;
-  std::memset(&g2, 0, sizeof(g2));
-  g2.a = H; g2.lda = hd; g2.stride_a = n * hd;
-  g2.b = (const bf16_t*)wo; g2.ldb = hd; g2.stride_b = h * hd;
-  g2.c = (bf16_t*)r_out; g2.ldc = h; g2.stride_c = n * h;
-  g2.aux = (const bf16_t*)r; g2.ldaux = h; g2.stride_aux = n * h;
-  g2.G = (int)T; g2.M = (int)n; g2.N = (int)h; g2.K = (int)hd;
-  g2.hs = d->hs; g2.scale = d->private_scale;
   {
-    ProfScope ps(s, "gemm_nt_rowpar");
-    e = launch_gemm(g2, 0, EPI_ROWPAR, s);
-  }
-  if (e != hipSuccess) return CAAT_EHIP;
-  if (d->hs > 0) {
-    ProfScope ps(s, "partial_sync_fwd");
-    e = launch_partial_sync_shared((bf16_t*)r_out, (const bf16_t*)r, (int)T, n, (int)h, d->hs, s);
-    if (e != hipSuccess) return CAAT_EHIP;
+    const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, (bf16_t*)r_out, s);
+    if (st != CAAT_OK) return st;
   }
   {
     ProfScope ps(s, "norm_fwd");
@@ -317,15 +368,9 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
     CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)kvpr,
                                                 d->head_dim, d->kv_cap, d->kv_len + 1, s))
   }
-  std::memset(&q, 0, sizeof(q));
-  q.a = H; q.lda = hd; q.stride_a = n * hd;
-  q.b = (const bf16_t*)wo; q.ldb = hd; q.stride_b = h * hd;
-  q.c = R1; q.ldc = h; q.stride_c = n * h;
-  q.aux = (const bf16_t*)r; q.ldaux = h; q.stride_aux = n * h;
-  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)hd; q.hs = d->hs; q.scale = d->private_scale;
-  CAAT_STEP("gemm_nt_rowpar", launch_gemm(q, 0, EPI_ROWPAR, s))
-  if (d->hs > 0) {
-    CAAT_STEP("partial_sync_fwd", launch_partial_sync_shared(R1, (const bf16_t*)r, (int)T, n, (int)h, d->hs, s))
+  {
+    const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, R1, s);
+    if (st != CAAT_OK) return st;
   }
   CAAT_STEP("norm_fwd", launch_norm_fwd(R1, (const bf16_t*)g_mlp, nullptr, X2, nullptr, rstd, CAAT_RMSNORM, (int)T, n, (int)h,
                                         d->eps, s))
@@ -336,15 +381,9 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
   q.c2 = Y; q.ldc2 = fr; q.stride_c2 = n * fr;
   q.G = (int)T; q.M = (int)n; q.N = (int)fr; q.K = (int)h; q.half = (int)fr;
   CAAT_STEP("gemm_nt_swiglu_fwd", launch_gemm(q, 0, EPI_SWIGLU_FWD, s))
-  std::memset(&q, 0, sizeof(q));
-  q.a = Y; q.lda = fr; q.stride_a = n * fr;
-  q.b = (const bf16_t*)wb; q.ldb = fr; q.stride_b = h * fr;
-  q.c = (bf16_t*)r_out; q.ldc = h; q.stride_c = n * h;
-  q.aux = R1; q.ldaux = h; q.stride_aux = n * h;
-  q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)fr; q.hs = d->hs; q.scale = d->private_scale;
-  CAAT_STEP("gemm_nt_rowpar", launch_gemm(q, 0, EPI_ROWPAR, s))
-  if (d->hs > 0) {
-    CAAT_STEP("partial_sync_fwd", launch_partial_sync_shared((bf16_t*)r_out, R1, (int)T, n, (int)h, d->hs, s))
+  {
+    const int st = rowpar_pcr(d, Y, fr, (const bf16_t*)wb, R1, (bf16_t*)r_out, s);
+    if (st != CAAT_OK) return st;
   }
 #undef CAAT_STEP
   return CAAT_OK;
@@ -515,27 +554,12 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
   }
   if (e != hipSuccess) return CAAT_EHIP;
 
-  // a2 + private half of a3/a4: Zt_m = Y_m B_m^T; columns >= hs become scale*Zt + R (final), columns < hs hold
-  // the rank's partial sum inside r_out until the reduce below
-  GemmParams g2;
-  std::memset(&g2, 0, sizeof(g2));
-  g2.a = Y; g2.lda = fr; g2.stride_a = n * fr;
-  g2.b = (const bf16_t*)w1; g2.ldb = fr; g2.stride_b = h * fr;
-  g2.c = (bf16_t*)r_out; g2.ldc = h; g2.stride_c = n * h;
-  g2.aux = (const bf16_t*)r; g2.ldaux = h; g2.stride_aux = n * h;
-  g2.G = (int)T; g2.M = (int)n; g2.N = (int)h; g2.K = (int)fr;
-  g2.hs = d->hs; g2.scale = d->private_scale;
+  // a2 + a3/a4: Zt_m = Y_m B_m^T closed by the partial channel-reduce and the residual.  Default: columns >= hs
+  // become scale*Zt + R in the GEMM epilogue (final), columns < hs hold the rank's partial sum inside r_out until the
+  // reduce kernel sums the T partials on the hs shared channels and adds each rank's residual, in place.
   {
-    ProfScope ps(s, "gemm_nt_rowpar");
-    e = launch_gemm(g2, 0, EPI_ROWPAR, s);
-  }
-  if (e != hipSuccess) return CAAT_EHIP;
-
-  // a3/a4 shared half: sum the T partials on the hs shared channels, add each rank's residual, in place
-  if (d->hs > 0) {
-    ProfScope ps(s, "partial_sync_fwd");
-    e = launch_partial_sync_shared((bf16_t*)r_out, (const bf16_t*)r, (int)T, n, (int)h, d->hs, s);
-    if (e != hipSuccess) return CAAT_EHIP;
+    const int st2 = rowpar_pcr(d, Y, fr, (const bf16_t*)w1, (const bf16_t*)r, (bf16_t*)r_out, s);
+    if (st2 != CAAT_OK) return st2;
   }
   // a5: per-rank norm on the now rank-divergent residual stream
   {

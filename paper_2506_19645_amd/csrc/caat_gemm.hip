@@ -21,6 +21,7 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
       case EPI_GELU_FWD: return launch_one<CfgSkinny, false, false, EPI_GELU_FWD>(p, s);
       case EPI_SWIGLU_FWD: return launch_one<CfgSkinnySwi, false, false, EPI_SWIGLU_FWD>(p, s);
       case EPI_ROWPAR: return launch_one<CfgSkinny, false, false, EPI_ROWPAR>(p, s);
+      case EPI_SHARED_BCAST: return launch_one<CfgSkinny, false, false, EPI_SHARED_BCAST>(p, s);
       default: return hipErrorInvalidValue;
     }
   }
@@ -31,6 +32,7 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
         case EPI_GELU_FWD: return launch_one<CfgBig, false, false, EPI_GELU_FWD>(p, s);
         case EPI_SWIGLU_FWD: return launch_one<CfgBig, false, false, EPI_SWIGLU_FWD>(p, s);
         case EPI_ROWPAR: return launch_one<CfgBig, false, false, EPI_ROWPAR>(p, s);
+        case EPI_SHARED_BCAST: return launch_one<CfgBig, false, false, EPI_SHARED_BCAST>(p, s);
         default: return hipErrorInvalidValue;
       }
     case 1:  // NN

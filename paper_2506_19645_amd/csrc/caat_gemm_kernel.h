@@ -80,8 +80,9 @@ struct KContigOperand {
       voff[it] = (r >= 0) ? (unsigned)((r * ld + kc * 8) * 2) : OOB;
     }
   }
-  __device__ __forceinline__ void issue(int k0, int K, uint4* tile) const {
-    const i32x4_t rs = make_rsrc(origin + k0);
+  // koff: element offset of the K-group the stage belongs to (0 unless the contraction runs over several buffers)
+  __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
+    const i32x4_t rs = make_rsrc(origin + koff + k0);
     const bool kin = (k0 + kc * 8) < K;
 #pragma unroll
     for (int it = 0; it < NI; ++it) dma16(rs, kin ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
@@ -126,8 +127,8 @@ struct RowContigOperand {
       voff[it] = (r >= 0) ? (unsigned)(((long long)k * ld_ + r) * 2) : OOB;
     }
   }
-  __device__ __forceinline__ void issue(int k0, int K, uint4* tile) const {
-    const i32x4_t rs = make_rsrc(origin + (long long)k0 * ld);
+  __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
+    const i32x4_t rs = make_rsrc(origin + koff + (long long)k0 * ld);
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
       const int k = (it * NWAVES + wave) * KPI + klocal;
@@ -217,7 +218,10 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
   OpA la;
   OpB lb;
   int g = 0, m0 = 0, n0 = 0;
+  int ik0 = 0, ikg = 0;  // k position and K-group of the next stage to be copied
   auto setup_tile = [&](int id) {
+    ik0 = 0;
+    ikg = 0;
     g = id / tiles;
     const int t = id - g * tiles;
     constexpr int GROUP = 8;
@@ -249,14 +253,24 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
     }
   };
 
+  // The contraction index may run over kcat buffers of K each (operand g' of both a and b lies kstride elements after
+  // operand g'-1): that is how the sum over ranks of Eq. A3's shared channels is taken inside the accumulator.
   const int K = p.K;
-  const int nk = (K + BKS - 1) / BKS;
+  const int kcat = p.kcat > 1 ? p.kcat : 1;
+  const int nk = ((K + BKS - 1) / BKS) * kcat;
   constexpr int A_CHUNKS = BM * (BKS / 8);
   auto stage_a = [&](int s) -> uint4* { return smem + (s % NSTAGE) * CFG::STAGE_CHUNKS; };
-  auto issue_stage = [&](int s) {  // past the end of K every offset is out of range: zeros land in a slot nobody reads
+  // stages are issued in order; past the end every offset is out of range: zeros land in a slot nobody reads
+  auto issue_stage = [&](int s) {
     uint4* As = stage_a(s);
-    la.issue(s * BKS, K, As);
-    lb.issue(s * BKS, K, As + A_CHUNKS);
+    const int kk = ikg < kcat ? K : 0;
+    la.issue(ik0, kk, As, (long long)ikg * p.kstride_a);
+    lb.issue(ik0, kk, As + A_CHUNKS, (long long)ikg * p.kstride_b);
+    ik0 += BKS;
+    if (ik0 >= K) {
+      ik0 = 0;
+      ++ikg;
+    }
   };
 
   constexpr int SCHED = CFG::SCHED;
@@ -438,6 +452,18 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) 
               *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
             } else {
               *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+            }
+          } else if constexpr (EPI == EPI_SHARED_BCAST) {
+            // Eq. A3, shared channels with the sum over ranks already in the accumulator: every rank's output gets
+            // the same sum plus that rank's residual
+            float v[8];
+            unpack(raw, v);
+            for (int m = 0; m < p.bcast; ++m) {
+              float r[8], o[8];
+              unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)m * p.stride_aux + grow * p.ldaux + gcol), r);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) o[e] = v[e] + r[e];
+              *reinterpret_cast<uint4*>(p.c + (long long)m * p.stride_c + grow * p.ldc + gcol) = pack(o);
             }
           } else if constexpr (EPI == EPI_GELU_BWD) {
             float v[8], pr[8];

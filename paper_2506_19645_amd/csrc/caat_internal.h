@@ -82,7 +82,8 @@ enum GemmEpilogue {
   EPI_SWIGLU_FWD = 2,  // b holds gate rows then up rows; c = [gate|up] pre-activations, c2 = silu(gate)*up
   EPI_ROWPAR = 3,      // col < hs: c = acc (partial sum);  col >= hs: c = scale*acc + resid
   EPI_GELU_BWD = 4,    // c = acc * gelu'(aux)
-  EPI_SWIGLU_BWD = 5   // c[:, col] = acc*up*silu'(gate), c[:, half+col] = acc*silu(gate); aux = [gate|up]
+  EPI_SWIGLU_BWD = 5,  // c[:, col] = acc*up*silu'(gate), c[:, half+col] = acc*silu(gate); aux = [gate|up]
+  EPI_SHARED_BCAST = 6 // for m in [0, bcast): c[m] = round_bf16(acc) + aux[m]   (c, aux advance by stride_c / stride_aux)
 };
 
 struct GemmParams {
@@ -98,6 +99,9 @@ struct GemmParams {
   int half;            // SWIGLU: ffn/T (offset between gate and up columns / rows)
   int hs;              // EPI_ROWPAR
   float scale;         // EPI_ROWPAR private scale
+  int kcat;            // > 1: the contraction runs over kcat operand pairs, K each, kstride_* elements apart
+  long long kstride_a, kstride_b;
+  int bcast;           // EPI_SHARED_BCAST: number of output copies (ranks)
 };
 
 // layout: 0 NT, 1 NN, 2 TN (see caat_gemm_layout).  Returns hipError_t of the launch.

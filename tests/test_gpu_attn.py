@@ -11,9 +11,9 @@ from tests.util import assert_close, bits_to_f64
 pytestmark = pytest.mark.gpu
 
 
-def run_attn_block(cfg, d, backward=False):
+def run_attn_block(cfg, d, backward=False, reduce_in_gemm=False):
     import torch
-    desc = B.make_desc(cfg)
+    desc = B.make_desc(cfg, reduce_in_gemm=reduce_in_gemm)
     ln = cfg.norm == I.NORM_LAYERNORM
     T, n, h, hd = cfg.T, cfg.tokens, cfg.h, cfg.hd_r
     weights = [B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),

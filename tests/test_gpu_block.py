@@ -12,10 +12,10 @@ from tests.util import assert_close, bits_to_f64
 pytestmark = pytest.mark.gpu
 
 
-def run_mlp_block(cfg, d, backward=True):
+def run_mlp_block(cfg, d, backward=True, reduce_in_gemm=False):
     """Marshal the bit patterns in d to the GPU, run fwd (+bwd) through the C ABI, return host arrays."""
     import torch
-    desc = B.make_desc(cfg)
+    desc = B.make_desc(cfg, reduce_in_gemm=reduce_in_gemm)
     swi = cfg.kind == I.KIND_MLP_SWIGLU
     ln = cfg.norm == I.NORM_LAYERNORM
     T, n, h, fr = cfg.T, cfg.tokens, cfg.h, cfg.f_r

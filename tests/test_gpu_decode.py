@@ -10,9 +10,9 @@ from tests.util import assert_close, bits_to_f64
 pytestmark = pytest.mark.gpu
 
 
-def run_decode(cfg, d):
+def run_decode(cfg, d, reduce_in_gemm=False):
     import torch
-    desc = B.make_desc(cfg)
+    desc = B.make_desc(cfg, reduce_in_gemm=reduce_in_gemm)
     T, b, h, hd = cfg.T, cfg.batch, cfg.h, cfg.hd_r
     weights = [B.to_device(d["gamma_attn"]), B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
                B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]

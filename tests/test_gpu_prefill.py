@@ -16,9 +16,9 @@ def layer_weights(d):
             B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]
 
 
-def run_prefill(cfg, d, kv_cap=None, keep=("X1", "H", "R1", "X2")):
+def run_prefill(cfg, d, kv_cap=None, keep=("X1", "H", "R1", "X2"), reduce_in_gemm=False):
     import torch
-    desc = B.make_desc(cfg, kv_cap=kv_cap)
+    desc = B.make_desc(cfg, kv_cap=kv_cap, reduce_in_gemm=reduce_in_gemm)
     T, n, h, hd, hpr = cfg.T, cfg.tokens, cfg.h, cfg.hd_r, cfg.kv_heads // cfg.T     # hpr: key / value heads per rank
     weights = layer_weights(d)
     r = B.to_device(d["R"])

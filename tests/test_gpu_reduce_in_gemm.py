@@ -1,0 +1,68 @@
+"""GPU parity of the single-device serving mode (Sec. 3.2, logical ranks: the partial channel-reduce becomes a local
+summation): with reduce_in_gemm the shared channels come from one GEMM whose contraction runs over all ranks.  The
+oracle is the same as for the default path: the result is the same sum, only accumulated without intermediate rounding."""
+import numpy as np
+import pytest
+
+from oracle import caat_oracle as O
+from paper_2506_19645_amd import inputs as I
+from tests.test_gpu_attn import _cfg as attn_cfg, check_attn, oracle_attn_block, run_attn_block
+from tests.test_gpu_block import _cfg as mlp_cfg, check_mlp_block, oracle_mlp_block, run_mlp_block
+from tests.test_gpu_decode import _cfg as dec_cfg, run_decode
+from tests.test_gpu_prefill import _cfg as pre_cfg, check_prefill, oracle_prefill, run_prefill
+from tests.util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("swi", [False, True])
+@pytest.mark.parametrize("T,n,h,ffn,p,scale", [
+    (2, 40, 64, 256, 0.5, 1.0),                 # hs = 32
+    (3, 300, 264, 3 * 344, 0.5, 1.0),           # hs = 132: not a multiple of 8 -> the default path is taken
+    (3, 300, 256, 3 * 344, 0.25, 1.0),          # T = 3, contraction of 3 x 344 with a ragged last stage per rank
+    (4, 515, 512, 4 * 520, 0.25, 2.0),          # private channel scaling
+    (2, 129, 256, 1024, 1.0, 1.0),              # p = 1: only the shared GEMM runs
+    (2, 129, 256, 1024, 0.0, 1.0),              # p = 0: only the private GEMM runs
+    (8, 300, 1024, 8 * 136, 0.5, 1.0),          # T = 8, 136 columns per rank (4 stages + tail of 8)
+])
+def test_mlp_block_reduce_in_gemm(swi, T, n, h, ffn, p, scale):
+    cfg = mlp_cfg(swi, T, n, h, ffn, p, scale)
+    d = I.make_inputs(cfg, seed=51, weight_std=0.05)
+    got = run_mlp_block(cfg, d, reduce_in_gemm=True)      # backward runs on the forward's saved tensors as usual
+    w, fwd, g = oracle_mlp_block(cfg, d)
+    check_mlp_block(cfg, d, got, w, fwd, g)
+    # against the default path: private channels are computed by the same arithmetic -> same bits
+    ref = run_mlp_block(cfg, d, backward=False)
+    assert np.array_equal(got["Rp_bits"][:, :, cfg.hs:], ref["Rp_bits"][:, :, cfg.hs:])
+
+
+def test_attention_block_reduce_in_gemm():
+    cfg = attn_cfg(2, 2, 200, 4, 0.5)
+    d = I.make_inputs(cfg, seed=52, with_grads=False, weight_std=0.05)
+    got = run_attn_block(cfg, d, reduce_in_gemm=True)
+    w, fwd = oracle_attn_block(cfg, d)
+    check_attn(cfg, d, got, fwd)
+
+
+@pytest.mark.parametrize("kv_heads", [0, 2])
+def test_decode_layer_reduce_in_gemm(kv_heads):
+    cfg = dec_cfg(2, 37, 8, 2 * 344, 150, 0.5, kv_heads)
+    d = I.make_inputs(cfg, seed=53, weight_std=0.05)
+    got = run_decode(cfg, d, reduce_in_gemm=True)
+    w = {k: O.widen_bf16(v) for k, v in d.items()}
+    ref = O.decode_layer_fwd(w["R"], w, w["Kc"], w["Vc"], kv_len=cfg.kv_len, heads_per_rank=cfg.n_heads // cfg.T,
+                             head_dim=128, hs=cfg.hs, kv_heads_per_rank=cfg.kv_heads // cfg.T)
+    for name in ("R1", "X2", "R2"):
+        assert_close(got[name], ref[name], name)
+    for m in range(1, cfg.T):
+        assert np.array_equal(got["R2_bits"][m, :, :cfg.hs], got["R2_bits"][0, :, :cfg.hs])
+
+
+def test_prefill_layer_reduce_in_gemm():
+    cfg = pre_cfg(4, 2, 200, 4, 4 * 344, 0.25)
+    d = I.make_inputs(cfg, seed=54, weight_std=0.05)
+    got = run_prefill(cfg, d, reduce_in_gemm=True)
+    w, ref = oracle_prefill(cfg, d)
+    check_prefill(cfg, d, got, ref)
+    for m in range(1, cfg.T):
+        assert np.array_equal(got["R2_bits"][m, :, :cfg.hs], got["R2_bits"][0, :, :cfg.hs])
