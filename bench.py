@@ -297,7 +297,7 @@ def bench_attention_kinds(args, cfg, base):
         work, unit, peak = kv_bytes + w_bytes, "GB/s", HBM_PEAK_GBS
         workload = "%s decode layer: h=%d ffn=%d heads=%d d=%d batch=%d kv_len=%d T=%d p=%g (hs=%d)" % (
             cfg.name, h, cfg.ffn, cfg.n_heads, cfg.head_dim, cfg.batch, cfg.kv_len, T, cfg.p, cfg.hs)
-    desc = B.make_desc(cfg)
+    desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm)
     ms, wall_ms = bench.time_steps(desc, args.steps, args.warmup)
     prof = bench.profile_steps(desc, max(3, min(args.steps, 10)))
     kernels = {}
@@ -324,7 +324,8 @@ def bench_attention_kinds(args, cfg, base):
     out = {"metric": "partial-sync TP block TFLOP/s (% MFMA peak) + sync GB/s (% HBM) vs p, 1 GPU",
            "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": workload, "work_per_step": work, "frac_peak": value / peak, "wall_ms_per_step": wall_ms},
+           "config": {"workload": workload + (" [reduce in GEMM]" if args.reduce_in_gemm else ""), "work_per_step": work,
+                      "frac_peak": value / peak, "wall_ms_per_step": wall_ms},
            "roofline": roof, "kernels": kernels}
     if args.config in ("C6", "C7"):
         # time to first token of a model made of this layer of this layer, and the paper's analytic model (App. C) next to the
@@ -338,7 +339,7 @@ def bench_attention_kinds(args, cfg, base):
             t = {}
             for p in (1.0, 0.5, 0.25, 0.0):
                 c = base.with_(p=p)
-                t[p], _ = bench.time_steps(B.make_desc(c), max(3, args.steps // 3), 2)
+                t[p], _ = bench.time_steps(B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm), max(3, args.steps // 3), 2)
             s0 = (t[1.0] - t[0.0]) / t[1.0]                       # measured speed-up at p = 0 = 1 / (1 + (12h+2s)/(C r))
             c_fit = (12.0 * h + 2.0 * cfg.seq) / (T * (1.0 / s0 - 1.0)) if 0.0 < s0 < 1.0 else None
             for p in (1.0, 0.5, 0.25, 0.0):
@@ -358,7 +359,7 @@ def bench_attention_kinds(args, cfg, base):
         if not args.no_sweep:
             for p in (1.0, 0.5, 0.25, 0.0):
                 c = base.with_(p=p)
-                ms_p, _ = bench.time_steps(B.make_desc(c), max(3, args.steps // 2), 2)
+                ms_p, _ = bench.time_steps(B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm), max(3, args.steps // 2), 2)
                 sweep.append({"p": p, "hs": c.hs, "ms_per_step": round(ms_p, 5), "GB/s": round(work / ms_p / 1e6, 1),
                               "synced_payload_bytes_per_token_per_reduce": 2 * c.hs})
         out["p_sweep"] = sweep
@@ -375,6 +376,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--fwd-only", action="store_true", help="C4: time the forward alone")
+    ap.add_argument("--reduce-in-gemm", action="store_true",
+                    help="single-device serving mode: the sum over ranks of the shared channels is taken inside one "
+                         "GEMM (no partial sums in HBM, no reduce pass) instead of the default reduce kernel")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known size) so that a rocprofv3 --pmc run can scale "
@@ -396,7 +400,7 @@ def main():
         print(json.dumps(bench_attention_kinds(args, cfg, base)))
         return
     bench = MlpBench(cfg, seed=0)
-    desc = B.make_desc(cfg)
+    desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm)
     k = 3 if cfg.kind == I.KIND_MLP_SWIGLU else 2
     step_flops = 6.0 * cfg.tokens * cfg.h * cfg.ffn * k
 
@@ -436,7 +440,7 @@ def main():
     if not args.no_sweep:
         for p in (1.0, 0.5, 0.25, 0.0):
             c = base.with_(p=p)
-            dsc = B.make_desc(c)
+            dsc = B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm)
             ms_p, _ = bench.time_steps(dsc, max(3, args.steps // 2), 2)
             pr = bench.profile_steps(dsc, 5)
             sa_ms, sa_gbs = standalone_sync(torch, B, c, c.hs)

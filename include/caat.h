@@ -89,7 +89,8 @@ typedef struct caat_desc {
                            serving with logical ranks (Sec. 3.2, the reduce becomes a local summation): the shared
                            channels come from one GEMM whose contraction runs over all T ranks, so the sum is taken in
                            the accumulator, no partial sum reaches memory and no reduce pass runs.  Needs hs % 8 == 0
-                           (otherwise the default path is taken).  Same result up to the rounding of the partials. */
+                           and more than 64 tokens (otherwise the default path is taken: a decode-sized GEMM has too few
+                           tiles once the ranks are folded into the contraction).  Same result up to the rounding of the partials. */
 } caat_desc;
 
 /* Byte offsets of the tensors caat_block_fwd leaves in the workspace (0 size = not present).  For tests

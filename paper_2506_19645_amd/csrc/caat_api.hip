@@ -138,7 +138,9 @@ int rowpar_pcr(const caat_desc* d, const bf16_t* a, long long kdim, const bf16_t
   const int hs = d->hs;
   hipError_t e = hipSuccess;
   GemmParams q;
-  if (d->reduce_in_gemm && hs % 8 == 0) {
+  // (Not for skinny problems: with at most 64 token rows per rank the GEMM is a weight stream whose only parallelism
+  // is the number of tiles, and folding the ranks into the contraction would leave hs/64 workgroups for 256 CUs.)
+  if (d->reduce_in_gemm && hs % 8 == 0 && n > 64) {
     if (hs < h) {
       std::memset(&q, 0, sizeof(q));
       q.a = a; q.lda = kdim; q.stride_a = n * kdim;
