@@ -98,7 +98,7 @@ __device__ __forceinline__ int vswz(int row, int c) { return c ^ ((row & 3) << 2
 // qkv: [T*tokens, (heads + 2*kv_heads)*128] with q | k | v column blocks (q, k already rotated); out: [T*tokens, hd],
 // hd = heads*128.  Query head a reads key / value head a / (heads / kv_heads) (grouped-query attention).
 // stats (may be null): the forward fills the log-sum-exp rows (what the backward needs to rebuild the probabilities).
-__global__ __launch_bounds__(256) void flash_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                         float* __restrict__ stats, int seq, int seq_pad, int hd, int heads,
                                                         int kv_heads, int n_qblk, float scale_log2) {
   __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __rest
 // ---- dQ: a workgroup owns 128 queries of one (sequence, head), a wave 32 of them (lane = query), keys in blocks of 64.
 //   S^T = K q^T and dP^T = V dO^T (A operand = K / V row fragments from LDS, B operand = q / dO registers);
 //   dS^T registers, rounded to bf16, are the B operand of dQ^T += K^T dS^T (A operand = transpose reads of K).
-__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+__global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                            const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
                                                            int seq_pad, int hd, int heads, int kv_heads, int n_qblk,
                                                            float scale_log2, float scale) {

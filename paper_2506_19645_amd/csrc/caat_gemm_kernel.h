@@ -52,6 +52,10 @@ struct TileCfg {
   static_assert(SCRATCH_BYTES <= SMEM_CHUNKS * 16, "epilogue scratch must fit");
   static_assert(!PERSIST || SCRATCH_BYTES <= STAGE_CHUNKS * 16, "persistent tiles keep NSTAGE-1 stages free of the scratch");
   static_assert(SMEM_CHUNKS * 16 <= 160 * 1024, "LDS capacity");
+  // workgroups that fit on one compute unit: LDS (160 KB) and at most 8 waves (2 per SIMD, 256 registers each)
+  static constexpr int WGS_PER_CU = ((160 * 1024) / (SMEM_CHUNKS * 16)) < (8 / NWAVES) ? ((160 * 1024) / (SMEM_CHUNKS * 16))
+                                                                                        : (8 / NWAVES);
+  static constexpr int MIN_WAVES_PER_EU = (NWAVES * WGS_PER_CU) / 4 > 0 ? (NWAVES * WGS_PER_CU) / 4 : 1;
 };
 
 // ---- operand contiguous along K: stage [ROWS][32 k], row = 64 B = 4 chunks; chunk c of row r sits at c ^ ((r>>2)&3).
@@ -179,7 +183,7 @@ struct Pipe {
 };
 
 template <class CFG, bool AT, bool BT, int EPI>
-__global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmParams p) {
+__global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kernel(const GemmParams p) {
   constexpr int BM = CFG::BM, BN = CFG::BN, NSTAGE = CFG::NSTAGE;
   constexpr int TM = CFG::TM, TN = CFG::TN, WTM = CFG::WTM, WTN = CFG::WTN;
   constexpr bool SWI = (EPI == EPI_SWIGLU_FWD);
@@ -505,14 +509,14 @@ static hipError_t launch_one(const GemmParams& p, hipStream_t s) {
   if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   long long blocks = total;
   if (CFG::PERSIST) {
-    static int n_cu = 0;  // one workgroup per compute unit (a workgroup's LDS leaves no room for a second one)
+    static int n_cu = 0;  // as many workgroups as the compute units hold at once
     if (n_cu == 0) {
       int dev = 0, v = 0;
       if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return hipErrorInvalidValue;
       n_cu = v > 0 ? v : 256;
     }
-    if (blocks > n_cu) blocks = n_cu;
+    if (blocks > (long long)n_cu * CFG::WGS_PER_CU) blocks = (long long)n_cu * CFG::WGS_PER_CU;
   }
   hipLaunchKernelGGL((gemm_kernel<CFG, AT, BT, EPI>), dim3((unsigned)blocks), dim3(CFG::THREADS), 0, s, p);
   return hipGetLastError();
