@@ -355,6 +355,131 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
   }
 }
 
+// Wide rows (h > 2048): the per-lane column accumulators of the kernel above would need 64+ registers, so here a whole
+// workgroup owns one row at a time: thread t holds the 16-byte vectors v*256 + t (v < VPL) of the row, the two row
+// sums go wave -> LDS -> all waves (slot chosen by row parity, one barrier per row), and the next row's x and dy are
+// already in flight while the current row is reduced and written.  A thread's dgamma / dbeta columns are its own, so
+// the partial row is written without any cross-wave combination.  Workgroup b walks rows [b*rpb, (b+1)*rpb).
+template <int VPL, bool LN>
+__global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ dres,
+                                                            const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+                                                            const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                            bf16_t* __restrict__ g_out, bf16_t* __restrict__ g_scaled,
+                                                            float* __restrict__ partial, long long rows, int h, int hs,
+                                                            float scale, long long rows_per_block) {
+  __shared__ float red[2][2][4];  // [row parity][c1 | c2][wave]
+  const int tid = threadIdx.x, wave = tid >> 6;
+  const int nvec = h >> 3;
+  const float inv_h = 1.0f / (float)h;
+  float dgam[VPL][8], dbet[LN ? VPL : 1][8];
+  uint4 gam[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int vi = v * 256 + tid;
+    gam[v] = make_uint4(0u, 0u, 0u, 0u);
+    if (vi < nvec) gam[v] = *reinterpret_cast<const uint4*>(gamma + vi * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dgam[v][e] = 0.0f;
+      if constexpr (LN) dbet[v][e] = 0.0f;
+    }
+  }
+  const long long r0 = (long long)blockIdx.x * rows_per_block;
+  long long r1 = r0 + rows_per_block;
+  if (r1 > rows) r1 = rows;
+  uint4 nx[VPL], nd[VPL];
+  auto fetch = [&](long long row) {
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int vi = v * 256 + tid;
+      nx[v] = make_uint4(0u, 0u, 0u, 0u);
+      nd[v] = nx[v];
+      if (vi < nvec && row < r1) {
+        nx[v] = *reinterpret_cast<const uint4*>(x + row * h + vi * 8);
+        nd[v] = *reinterpret_cast<const uint4*>(dy + row * h + vi * 8);
+      }
+    }
+  };
+  if (r0 < r1) fetch(r0);
+  for (long long row = r0; row < r1; ++row) {
+    const int par = (int)((row - r0) & 1);
+    const float mu = LN ? mean[row] : 0.0f;
+    const float rs = rstd[row];
+    uint4 wx[VPL], wd[VPL], wr[VPL];
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      wx[v] = nx[v];
+      wd[v] = nd[v];
+      const int vi = v * 256 + tid;
+      wr[v] = make_uint4(0u, 0u, 0u, 0u);
+      if (dres && vi < nvec) wr[v] = *reinterpret_cast<const uint4*>(dres + row * h + vi * 8);
+    }
+    fetch(row + 1);
+    float c1 = 0.0f, c2 = 0.0f;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      float fx[8], fd[8], g[8];
+      unpack8(wx[v], fx);
+      unpack8(wd[v], fd);
+      unpack8(gam[v], g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xh = (fx[e] - mu) * rs;  // idle threads: fd = 0 and gamma = 0, so they add nothing
+        const float dxh = fd[e] * g[e];
+        c1 += dxh;
+        c2 += dxh * xh;
+        dgam[v][e] += fd[e] * xh;
+        if constexpr (LN) dbet[v][e] += fd[e];
+      }
+    }
+    if constexpr (LN) c1 = wave_sum(c1);
+    c2 = wave_sum(c2);
+    if ((tid & 63) == 0) {
+      red[par][0][wave] = c1;
+      red[par][1][wave] = c2;
+    }
+    __syncthreads();
+    if constexpr (LN) c1 = (((red[par][0][0] + red[par][0][1]) + red[par][0][2]) + red[par][0][3]) * inv_h;
+    c2 = (((red[par][1][0] + red[par][1][1]) + red[par][1][2]) + red[par][1][3]) * inv_h;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      const int vi = v * 256 + tid;
+      if (vi < nvec) {
+        float fx[8], fd[8], g[8], r[8], o[8];
+        unpack8(wx[v], fx);
+        unpack8(wd[v], fd);
+        unpack8(gam[v], g);
+        unpack8(wr[v], r);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (fx[e] - mu) * rs;
+          const float dxh = fd[e] * g[e];
+          o[e] = r[e] + rs * (LN ? (dxh - c1 - xh * c2) : (dxh - xh * c2));
+        }
+        *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
+        if (g_scaled) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (vi * 8 + e >= hs) o[e] *= scale;
+          *reinterpret_cast<uint4*>(g_scaled + row * h + vi * 8) = pack8(o);
+        }
+      }
+    }
+  }
+  float* prow = partial + (long long)blockIdx.x * 2 * h;
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int vi = v * 256 + tid;
+    if (vi < nvec) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        prow[vi * 8 + e] = dgam[v][e];
+        if constexpr (LN) prow[h + vi * 8 + e] = dbet[v][e];
+      }
+    }
+  }
+}
+
 // sums partial[nb][2][h] over nb in a fixed order: a workgroup owns 32 columns, its 8 row groups each add every
 // 8th partial row (4 independent chains), and the 8 group sums are combined in ascending order through LDS
 __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __restrict__ partial, int nb, int h,
@@ -386,15 +511,37 @@ __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __r
   }
 }
 
-static long long norm_bwd_blocks(long long rows) {
-  long long nb = (rows + 3) / 4;
-  if (nb > NORM_BWD_MAX_BLOCKS) nb = NORM_BWD_MAX_BLOCKS;
+static constexpr int NORM_BWD_WIDE_H = 2048;          // rows wider than this take the workgroup-per-row kernel
+static constexpr int NORM_BWD_WIDE_MAX_BLOCKS = 1024;
+static long long norm_bwd_blocks(long long rows, int h) {
+  long long nb;
+  if (h > NORM_BWD_WIDE_H) {
+    nb = (rows + 7) / 8;                             // at least 8 rows per workgroup
+    if (nb > NORM_BWD_WIDE_MAX_BLOCKS) nb = NORM_BWD_WIDE_MAX_BLOCKS;
+  } else {
+    nb = (rows + 3) / 4;
+    if (nb > NORM_BWD_MAX_BLOCKS) nb = NORM_BWD_MAX_BLOCKS;
+  }
   if (nb < 1) nb = 1;
   return nb;
 }
 
 size_t norm_bwd_workspace_bytes(int T, long long tokens, int h) {
-  return (size_t)norm_bwd_blocks((long long)T * tokens) * 2 * (size_t)h * sizeof(float);
+  return (size_t)norm_bwd_blocks((long long)T * tokens, h) * 2 * (size_t)h * sizeof(float);
+}
+
+template <int VPL>
+static hipError_t norm_bwd_wide_dispatch(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
+                                         const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled,
+                                         float* partial, int norm, long long rows, int h, int hs, float scale,
+                                         long long nb, long long rpb, hipStream_t s) {
+  if (norm == 0)
+    hipLaunchKernelGGL((norm_bwd_wide_kernel<VPL, true>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+  else
+    hipLaunchKernelGGL((norm_bwd_wide_kernel<VPL, false>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+  return hipGetLastError();
 }
 
 template <int VPL>
@@ -417,16 +564,20 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
                            void* workspace, hipStream_t s) {
   const long long rows = (long long)T * tokens;
   if (rows == 0) return hipSuccess;
-  const long long nb = norm_bwd_blocks(rows);
+  long long nb = norm_bwd_blocks(rows, h);
   const long long rpb = (rows + nb - 1) / nb;
+  nb = (rows + rpb - 1) / rpb;                       // no empty workgroups: every partial row is written
   float* partial = reinterpret_cast<float*>(workspace);
   const int vpl = (h / 8 + 63) / 64;
   hipError_t e;
-  if (vpl <= 1) e = norm_bwd_dispatch<1>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+  if (h > NORM_BWD_WIDE_H) {
+    const int vw = (h / 8 + 255) / 256;
+    if (vw <= 2) e = norm_bwd_wide_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+    else if (vw <= 4) e = norm_bwd_wide_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+    else return hipErrorInvalidValue;
+  } else if (vpl <= 1) e = norm_bwd_dispatch<1>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
   else if (vpl <= 2) e = norm_bwd_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
   else if (vpl <= 4) e = norm_bwd_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
-  else if (vpl <= 8) e = norm_bwd_dispatch<8>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
-  else if (vpl <= 16) e = norm_bwd_dispatch<16>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 31) / 32)), dim3(256), 0, s, partial, (int)nb,
