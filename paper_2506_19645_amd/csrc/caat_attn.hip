@@ -550,11 +550,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
     const uint4* dot = qt + BQB * KCH;
     const float4* st = reinterpret_cast<const float4*>(qt + 2 * BQB * KCH);
     const int q0 = (qb0 + it % nq) * BQB;
-#pragma unroll
-    for (int j = 0; j < BQB / 32; ++j) {
-      const int qs = q0 + j * 32;
-      if (qs + 31 < kw0) continue;                           // wave-uniform: all 32 queries precede this wave's keys
-      f32x16_t sacc, pacc;
+    // scores and dP of one 32-query tile: 16 MFMAs over the head dim
+    auto scores = [&](int j, f32x16_t& sacc, f32x16_t& pacc) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[r] = 0.0f, pacc[r] = 0.0f;
       const int row = j * 32 + frow;
@@ -563,8 +560,11 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt, row, ks * 2 + hf), kf[ks], sacc, 0, 0, 0);
         pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot, row, ks * 2 + hf), vf[ks], pacc, 0, 0, 0);
       }
-      // register r <-> query qs + 8(r/4) + 4hf + r%4, lane <-> key krow
-      const bool diag = qs < kw0 + 31;                        // wave-uniform: some key exceeds some query
+    };
+    // P = exp2(S*c - lse), dS = P o (dP - D), both rounded to bf16 as the next MFMAs' B operands.
+    // register r <-> query qs + 8(r/4) + 4hf + r%4, lane <-> key krow; masked (key > query) only where MASK
+    auto probs = [&](int j, bool mask, const f32x16_t& sacc, const f32x16_t& pacc, bf16x8_t* pf, bf16x8_t* df) {
+      const int qs = q0 + j * 32;
       float pv[16], ds[16];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -575,7 +575,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * i + e;
           float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - ls[e]);
-          if (diag) {
+          if (mask) {
             const int q = qs + 8 * i + 4 * hf + e;
             p = krow > q ? 0.0f : p;
           }
@@ -583,15 +583,30 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
           ds[r] = p * (pacc[r] - dd[e]);
         }
       }
+      pf[0] = pack8(pv);
+      pf[1] = pack8(pv + 8);
+      df[0] = pack8(ds);
+      df[1] = pack8(ds + 8);
+    };
+    // dV^T += dO^T P and dK^T += Q^T dS for one 32-query tile: 16 MFMAs, A operands by transpose reads
+    auto accumulate = [&](int j, const bf16x8_t* pf, const bf16x8_t* df) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8_t pf = pack8(pv + 8 * t), df = pack8(ds + 8 * t);
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int dt = 0; dt < HD / 32; ++dt) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot, dt, j * 32 + t * 16, lane), pf, dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt, dt, j * 32 + t * 16, lane), df, dk[dt], 0, 0, 0);
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot, dt, j * 32 + t * 16, lane), pf[t], dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt, dt, j * 32 + t * 16, lane), df[t], dk[dt], 0, 0, 0);
         }
-      }
+    };
+#pragma unroll
+    for (int j = 0; j < BQB / 32; ++j) {
+      const int qs = q0 + j * 32;
+      if (qs + 31 < kw0) continue;                           // wave-uniform: all 32 queries precede this wave's keys
+      f32x16_t sacc, pacc;
+      bf16x8_t pf[2], df[2];
+      scores(j, sacc, pacc);
+      probs(j, qs < kw0 + 31, sacc, pacc, pf, df);           // wave-uniform: some key exceeds some query
+      accumulate(j, pf, df);
     }
   }
   // lane holds dK[krow][32dt + 8(r/4) + 4hf + r%4] and dV likewise
