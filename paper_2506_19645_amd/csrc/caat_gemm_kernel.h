@@ -257,23 +257,30 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     }
   };
 
-  // The contraction index may run over kcat buffers of K each (operand g' of both a and b lies kstride elements after
-  // operand g'-1): that is how the sum over ranks of Eq. A3's shared channels is taken inside the accumulator.
+  // With the broadcast epilogue the contraction index runs over kcat buffers of K each (operand g' of both a and b lies
+  // kstride elements after operand g'-1): that is how the sum over ranks of Eq. A3's shared channels is taken inside
+  // the accumulator.  Every other instantiation keeps the single-buffer code (no per-stage bookkeeping).
+  constexpr bool KCAT = (EPI == EPI_SHARED_BCAST);
   const int K = p.K;
-  const int kcat = p.kcat > 1 ? p.kcat : 1;
+  const int kcat = KCAT ? (p.kcat > 1 ? p.kcat : 1) : 1;
   const int nk = ((K + BKS - 1) / BKS) * kcat;
   constexpr int A_CHUNKS = BM * (BKS / 8);
   auto stage_a = [&](int s) -> uint4* { return smem + (s % NSTAGE) * CFG::STAGE_CHUNKS; };
   // stages are issued in order; past the end every offset is out of range: zeros land in a slot nobody reads
   auto issue_stage = [&](int s) {
     uint4* As = stage_a(s);
-    const int kk = ikg < kcat ? K : 0;
-    la.issue(ik0, kk, As, (long long)ikg * p.kstride_a);
-    lb.issue(ik0, kk, As + A_CHUNKS, (long long)ikg * p.kstride_b);
-    ik0 += BKS;
-    if (ik0 >= K) {
-      ik0 = 0;
-      ++ikg;
+    if constexpr (KCAT) {
+      const int kk = ikg < kcat ? K : 0;
+      la.issue(ik0, kk, As, (long long)ikg * p.kstride_a);
+      lb.issue(ik0, kk, As + A_CHUNKS, (long long)ikg * p.kstride_b);
+      ik0 += BKS;
+      if (ik0 >= K) {
+        ik0 = 0;
+        ++ikg;
+      }
+    } else {
+      la.issue(s * BKS, K, As, 0);
+      lb.issue(s * BKS, K, As + A_CHUNKS, 0);
     }
   };
 
