@@ -91,6 +91,11 @@ typedef struct caat_desc {
                            the accumulator, no partial sum reaches memory and no reduce pass runs.  Needs hs % 8 == 0
                            and more than 64 tokens (otherwise the default path is taken: a decode-sized GEMM has too few
                            tiles once the ranks are folded into the contraction).  Same result up to the rounding of the partials. */
+  int dedup_shared;     /* forward only, needs reduce_in_gemm = 1, hs % 8 == 0, more than 64 tokens, not the decode kind
+                           (CAAT_EUNSUPPORTED otherwise).  1: the residual-stream tensors r and r_out (and the layer
+                           kinds' internal residual) store the shared channels ONCE instead of T identical copies:
+                           [tokens, hs] followed by the private channels [T, tokens, h - hs], one contiguous buffer of
+                           tokens*hs + T*tokens*(h-hs) elements.  x / x_out keep the [T, tokens, h] layout. */
 } caat_desc;
 
 /* Byte offsets of the tensors caat_block_fwd leaves in the workspace (0 size = not present).  For tests

@@ -31,7 +31,7 @@ class caat_desc(C.Structure):
     _fields_ = [("kind", C.c_int), ("norm", C.c_int), ("h", C.c_int), ("ffn", C.c_int), ("T", C.c_int),
                 ("hs", C.c_int), ("tokens", C.c_longlong), ("batch", C.c_int), ("seq", C.c_int),
                 ("n_heads", C.c_int), ("head_dim", C.c_int), ("kv_len", C.c_longlong), ("kv_cap", C.c_longlong),
-                ("eps", C.c_float), ("private_scale", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int), ("reduce_in_gemm", C.c_int)]
+                ("eps", C.c_float), ("private_scale", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int), ("reduce_in_gemm", C.c_int), ("dedup_shared", C.c_int)]
 
 
 class caat_ws_layout(C.Structure):
@@ -131,7 +131,8 @@ def to_host_bits(t) -> np.ndarray:
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def make_desc(cfg, hs: Optional[int] = None, kv_cap: Optional[int] = None, reduce_in_gemm: bool = False) -> caat_desc:
+def make_desc(cfg, hs: Optional[int] = None, kv_cap: Optional[int] = None, reduce_in_gemm: bool = False,
+              dedup_shared: bool = False) -> caat_desc:
     """caat_desc from a paper_2506_19645_amd.inputs.BlockConfig (cache capacity: one position more than what the
     call fills, unless given)."""
     if kv_cap is None:
@@ -140,7 +141,7 @@ def make_desc(cfg, hs: Optional[int] = None, kv_cap: Optional[int] = None, reduc
                      hs=cfg.hs if hs is None else hs, tokens=cfg.tokens, batch=cfg.batch, seq=cfg.seq,
                      n_heads=cfg.n_heads, head_dim=cfg.head_dim, kv_len=cfg.kv_len, kv_cap=kv_cap,
                      eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base,
-                     n_kv_heads=getattr(cfg, "n_kv_heads", 0), reduce_in_gemm=1 if reduce_in_gemm else 0)
+                     n_kv_heads=getattr(cfg, "n_kv_heads", 0), reduce_in_gemm=1 if reduce_in_gemm else 0, dedup_shared=1 if dedup_shared else 0)
 
 
 # ------------------------------------------------------------------ entry points (same names as the C ABI)

@@ -48,6 +48,9 @@ bool is_mlp(int kind) { return kind == CAAT_MLP_GELU || kind == CAAT_MLP_SWIGLU;
 bool is_layer(int kind) { return kind == CAAT_ATTN_DECODE || kind == CAAT_LAYER_PREFILL; }
 // key / value heads over all ranks (n_kv_heads = 0 means one per query head) and the width of a rank's fused
 // q | k | v projection
+// the residual stream stores its shared channels once (only together with the reduce inside the GEMM)
+bool dedup_on(const caat_desc* d) { return d->dedup_shared != 0; }
+int dedup_hs(const caat_desc* d) { return dedup_on(d) ? d->hs : 0; }
 int kv_heads_of(const caat_desc* d) { return d->n_kv_heads > 0 ? d->n_kv_heads : d->n_heads; }
 long long qkv_width(const caat_desc* d) {
   return (long long)(d->n_heads / d->T + 2 * (kv_heads_of(d) / d->T)) * d->head_dim;
@@ -60,6 +63,11 @@ int validate_desc(const caat_desc* d) {
   if (d->T < 1 || d->h < 1 || d->tokens < 0) return CAAT_EINVAL;
   if (!(d->eps >= 0.0f) || std::isnan(d->private_scale)) return CAAT_EINVAL;
   if (d->reduce_in_gemm != 0 && d->reduce_in_gemm != 1) return CAAT_EINVAL;
+  if (d->dedup_shared != 0 && d->dedup_shared != 1) return CAAT_EINVAL;
+  // the de-duplicated layout exists only where the shared channels are produced once: reduce inside the GEMM, whole
+  // 16-byte groups of shared channels, more than 64 tokens, and not for the decode step
+  if (d->dedup_shared && (!d->reduce_in_gemm || d->hs % 8 != 0 || d->tokens <= 64 || d->kind == CAAT_ATTN_DECODE))
+    return CAAT_EUNSUPPORTED;
   if (d->hs < 0 || d->hs > d->h) return CAAT_ESHAPE;
   if (d->h % 8 != 0 || d->h > 8192) return CAAT_ESHAPE;
   if (d->tokens > 0x7FFFFFFFLL) return CAAT_ESHAPE;
@@ -141,12 +149,18 @@ int rowpar_pcr(const caat_desc* d, const bf16_t* a, long long kdim, const bf16_t
   // (Not for skinny problems: with at most 64 token rows per rank the GEMM is a weight stream whose only parallelism
   // is the number of tiles, and folding the ranks into the contraction would leave hs/64 workgroups for 256 CUs.)
   if (d->reduce_in_gemm && hs % 8 == 0 && n > 64) {
+    // residual stream layouts: [T,n,h] (shared columns in every rank's rows), or de-duplicated: [n,hs] once, then the
+    // private columns [T,n,h-hs]
+    const bool dd = dedup_on(d);
+    const long long ldp = dd ? h - hs : h, ldsh = dd ? hs : h;
+    const bf16_t* resid_p = dd ? resid + n * hs : resid + hs;
+    bf16_t* out_p = dd ? out + n * hs : out + hs;
     if (hs < h) {
       std::memset(&q, 0, sizeof(q));
       q.a = a; q.lda = kdim; q.stride_a = n * kdim;
       q.b = w + (long long)hs * kdim; q.ldb = kdim; q.stride_b = h * kdim;
-      q.c = out + hs; q.ldc = h; q.stride_c = n * h;
-      q.aux = resid + hs; q.ldaux = h; q.stride_aux = n * h;
+      q.c = out_p; q.ldc = ldp; q.stride_c = n * ldp;
+      q.aux = resid_p; q.ldaux = ldp; q.stride_aux = n * ldp;
       q.G = (int)T; q.M = (int)n; q.N = (int)(h - hs); q.K = (int)kdim;
       q.hs = 0; q.scale = d->private_scale;
       {
@@ -159,9 +173,9 @@ int rowpar_pcr(const caat_desc* d, const bf16_t* a, long long kdim, const bf16_t
       std::memset(&q, 0, sizeof(q));
       q.a = a; q.lda = kdim; q.kstride_a = n * kdim;
       q.b = w; q.ldb = kdim; q.kstride_b = h * kdim;
-      q.c = out; q.ldc = h; q.stride_c = n * h;
-      q.aux = resid; q.ldaux = h; q.stride_aux = n * h;
-      q.G = 1; q.M = (int)n; q.N = hs; q.K = (int)kdim; q.kcat = (int)T; q.bcast = (int)T;
+      q.c = out; q.ldc = ldsh; q.stride_c = n * h;
+      q.aux = resid; q.ldaux = ldsh; q.stride_aux = n * h;
+      q.G = 1; q.M = (int)n; q.N = hs; q.K = (int)kdim; q.kcat = (int)T; q.bcast = dd ? 1 : (int)T;
       {
         ProfScope ps(s, "gemm_nt_shared_kcat");
         e = launch_gemm(q, 0, EPI_SHARED_BCAST, s);
@@ -240,7 +254,7 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   {
     ProfScope ps(s, "norm_fwd");
     e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd, d->norm,
-                        (int)T, n, (int)h, d->eps, s);
+                        (int)T, n, (int)h, d->eps, s, dedup_hs(d));
   }
   return hip_status(e);
 }
@@ -354,7 +368,7 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
   GemmParams q;
 #define CAAT_STEP(name, call) { ProfScope ps(s, name); e = (call); } if (e != hipSuccess) return CAAT_EHIP;
   CAAT_STEP("norm_fwd", launch_norm_fwd((const bf16_t*)r, (const bf16_t*)g_attn, nullptr, X1, nullptr, rstd, CAAT_RMSNORM, (int)T,
-                                        n, (int)h, d->eps, s))
+                                        n, (int)h, d->eps, s, dedup_hs(d)))
   std::memset(&q, 0, sizeof(q));
   q.a = X1; q.lda = h; q.stride_a = n * h;
   q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = qw * h;
@@ -375,7 +389,7 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
     if (st != CAAT_OK) return st;
   }
   CAAT_STEP("norm_fwd", launch_norm_fwd(R1, (const bf16_t*)g_mlp, nullptr, X2, nullptr, rstd, CAAT_RMSNORM, (int)T, n, (int)h,
-                                        d->eps, s))
+                                        d->eps, s, dedup_hs(d)))
   std::memset(&q, 0, sizeof(q));
   q.a = X2; q.lda = h; q.stride_a = n * h;
   q.b = (const bf16_t*)wgu; q.ldb = h; q.stride_b = 2 * fr * h;
@@ -567,7 +581,7 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
   {
     ProfScope ps(s, "norm_fwd");
     e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd,
-                        d->norm, (int)T, n, (int)h, d->eps, s);
+                        d->norm, (int)T, n, (int)h, d->eps, s, dedup_hs(d));
   }
   return hip_status(e);
 }
@@ -580,6 +594,7 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   if (st != CAAT_OK) return st;
   if (!weights || !dweights || !x || !r_out || !workspace || !dx_out || !dr_out || !dx || !dr || !dgamma)
     return CAAT_EINVAL;
+  if (d->dedup_shared) return CAAT_EUNSUPPORTED;   // serving-only layout
   if (d->kind == CAAT_ATTN)
     return attn_block_bwd(d, L, weights, x, r_out, workspace, ws_bytes, dx_out, dr_out, dx, dr, dweights, dgamma, dbeta,
                           hip_stream);

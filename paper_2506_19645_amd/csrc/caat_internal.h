@@ -113,7 +113,8 @@ hipError_t launch_partial_sync(const bf16_t* y, const bf16_t* resid, bf16_t* out
 hipError_t launch_partial_sync_shared(bf16_t* io, const bf16_t* resid, int T, long long tokens, int h, int hs,
                                       hipStream_t s);
 hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
-                           float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s);
+                           float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s,
+                           int dedup_hs = 0);
 size_t norm_bwd_workspace_bytes(int T, long long tokens, int h);
 hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
                            const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,

@@ -148,11 +148,14 @@ hipError_t launch_partial_sync_shared(bf16_t* io, const bf16_t* resid, int T, lo
 // ---------------------------------------------------------------------------------------------------------
 // Norm forward: one wavefront per row, the row stays in registers (VPL 16-byte vectors per lane), statistics
 // by wave reduction in fp32 (two passes over registers: mean, then centred second moment).
+// Split source (xs != null): the first hs_split channels of every rank's row are stored once, xs [tokens, hs_split]
+// (row = rank*tokens + token reads token's shared row), and x holds only the private channels [rows, h - hs_split].
 template <int VPL, bool LN>
 __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
                                                        const bf16_t* __restrict__ beta, bf16_t* __restrict__ y,
                                                        float* __restrict__ mean, float* __restrict__ rstd,
-                                                       long long rows, int h, float eps) {
+                                                       long long rows, int h, float eps, const bf16_t* __restrict__ xs,
+                                                       int hs_split, long long tokens) {
   const int lane = threadIdx.x & 63;
   const long long wave0 = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const long long nwaves = (long long)gridDim.x * 4;
@@ -160,13 +163,18 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
   const float inv_h = 1.0f / (float)h;
   for (long long row = wave0; row < rows; row += nwaves) {
     const bf16_t* xr = x + row * h;
+    const bf16_t* xsr = nullptr;
+    if (xs != nullptr) {
+      xr = x + row * (h - hs_split) - hs_split;       // column c >= hs_split of this row sits at xr[c]
+      xsr = xs + (row % tokens) * hs_split;
+    }
     float f[VPL][8];
     float s = 0.0f;
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       const int vi = v * 64 + lane;
       uint4 w = make_uint4(0u, 0u, 0u, 0u);
-      if (vi < nvec) w = *reinterpret_cast<const uint4*>(xr + vi * 8);
+      if (vi < nvec) w = *reinterpret_cast<const uint4*>((xsr != nullptr && vi * 8 < hs_split ? xsr : xr) + vi * 8);
       unpack8(w, f[v]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) s += LN ? f[v][e] : f[v][e] * f[v][e];
@@ -213,28 +221,38 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
 
 template <int VPL>
 static hipError_t norm_fwd_dispatch(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
-                                    float* rstd, int norm, long long rows, int h, float eps, hipStream_t s) {
+                                    float* rstd, int norm, long long rows, int h, float eps, const bf16_t* xs,
+                                    int hs_split, long long tokens, hipStream_t s) {
   long long blocks = (rows + 3) / 4;
   if (blocks > 65536) blocks = 65536;
   if (blocks == 0) return hipSuccess;
   if (norm == 0)
     hipLaunchKernelGGL((norm_fwd_kernel<VPL, true>), dim3((unsigned)blocks), dim3(256), 0, s, x, gamma, beta, y, mean,
-                       rstd, rows, h, eps);
+                       rstd, rows, h, eps, xs, hs_split, tokens);
   else
     hipLaunchKernelGGL((norm_fwd_kernel<VPL, false>), dim3((unsigned)blocks), dim3(256), 0, s, x, gamma, beta, y, mean,
-                       rstd, rows, h, eps);
+                       rstd, rows, h, eps, xs, hs_split, tokens);
   return hipGetLastError();
 }
 
+// dedup_hs > 0: x is a residual stream that stores its first dedup_hs channels once: [tokens, dedup_hs] followed by the
+// private channels [T, tokens, h - dedup_hs] (dedup_hs a multiple of 8)
 hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
-                           float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s) {
+                           float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s,
+                           int dedup_hs) {
   const long long rows = (long long)T * tokens;
   const int vpl = (h / 8 + 63) / 64;
-  if (vpl <= 1) return norm_fwd_dispatch<1>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
-  if (vpl <= 2) return norm_fwd_dispatch<2>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
-  if (vpl <= 4) return norm_fwd_dispatch<4>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
-  if (vpl <= 8) return norm_fwd_dispatch<8>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
-  if (vpl <= 16) return norm_fwd_dispatch<16>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, s);
+  const bf16_t* xs = nullptr;
+  if (dedup_hs > 0) {
+    if (dedup_hs % 8 != 0 || dedup_hs > h) return hipErrorInvalidValue;
+    xs = x;
+    x = x + tokens * dedup_hs;
+  }
+  if (vpl <= 1) return norm_fwd_dispatch<1>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, xs, dedup_hs, tokens, s);
+  if (vpl <= 2) return norm_fwd_dispatch<2>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, xs, dedup_hs, tokens, s);
+  if (vpl <= 4) return norm_fwd_dispatch<4>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, xs, dedup_hs, tokens, s);
+  if (vpl <= 8) return norm_fwd_dispatch<8>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, xs, dedup_hs, tokens, s);
+  if (vpl <= 16) return norm_fwd_dispatch<16>(x, gamma, beta, y, mean, rstd, norm, rows, h, eps, xs, dedup_hs, tokens, s);
   return hipErrorInvalidValue;  // h > 8192
 }
 

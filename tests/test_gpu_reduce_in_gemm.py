@@ -66,3 +66,75 @@ def test_prefill_layer_reduce_in_gemm():
     check_prefill(cfg, d, got, ref)
     for m in range(1, cfg.T):
         assert np.array_equal(got["R2_bits"][m, :, :cfg.hs], got["R2_bits"][0, :, :cfg.hs])
+
+
+# ---------------------------------------------------------------------------------------------------------
+# De-duplicated residual stream: the shared channels are stored once ([n, hs]) instead of T identical copies.
+def _run_mlp_dedup(cfg, d):
+    import torch
+    from paper_2506_19645_amd import binding as B
+    from tests.util import pack_dedup, unpack_dedup
+    swi = cfg.kind == I.KIND_MLP_SWIGLU
+    desc = B.make_desc(cfg, reduce_in_gemm=True, dedup_shared=True)
+    T, n, h, hs = cfg.T, cfg.tokens, cfg.h, cfg.hs
+    w0 = B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1) if swi else d["A"])
+    weights = [w0, B.to_device(d["B"]), B.to_device(d["gamma"]), B.to_device(d["beta"]) if "beta" in d else None]
+    x = B.to_device(d["X"])
+    r = B.to_device(pack_dedup(d["R"], hs))
+    r_out, x_out = torch.zeros_like(r), torch.empty_like(x)
+    ws = torch.zeros(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    B.block_fwd(desc, weights, x, r, r_out, x_out, ws)
+    torch.cuda.synchronize()
+    return unpack_dedup(B.to_host_bits(r_out), T, n, h, hs), B.to_host_bits(x_out)
+
+
+@pytest.mark.parametrize("swi,T,n,h,ffn,p", [
+    (False, 2, 129, 256, 1024, 0.5),
+    (True, 4, 515, 512, 4 * 520, 0.25),
+    (True, 3, 300, 256, 3 * 344, 1.0),      # everything shared: the private block is empty
+    (False, 2, 200, 256, 1024, 0.0),        # nothing shared: the layout is the ordinary one
+])
+def test_mlp_block_dedup_shared_layout(swi, T, n, h, ffn, p):
+    cfg = mlp_cfg(swi, T, n, h, ffn, p, 1.0)
+    d = I.make_inputs(cfg, seed=55, weight_std=0.05)
+    rp_bits, xp_bits = _run_mlp_dedup(cfg, d)
+    ref = run_mlp_block(cfg, d, backward=False, reduce_in_gemm=True)   # same arithmetic, T copies of the shared columns
+    assert np.array_equal(rp_bits, ref["Rp_bits"])
+    assert np.array_equal(xp_bits, ref["Xp_bits"])
+    w, fwd, _ = oracle_mlp_block(cfg, d, backward=False)
+    from tests.util import bits_to_f64
+    assert_close(bits_to_f64(rp_bits), fwd["Rp"], "Rp")
+    assert_close(bits_to_f64(xp_bits), fwd["Xp"], "Xp")
+
+
+def test_prefill_layer_dedup_shared_layout():
+    import torch
+    from paper_2506_19645_amd import binding as B
+    from tests.test_gpu_prefill import layer_weights
+    from tests.util import bits_to_f64, pack_dedup, unpack_dedup
+    cfg = pre_cfg(4, 2, 200, 8, 4 * 344, 0.25, kv_heads=4)
+    d = I.make_inputs(cfg, seed=56, weight_std=0.05)
+    T, n, h, hs = cfg.T, cfg.tokens, cfg.h, cfg.hs
+    desc = B.make_desc(cfg, reduce_in_gemm=True, dedup_shared=True)
+    r = B.to_device(pack_dedup(d["R"], hs))
+    r_out = torch.zeros_like(r)
+    kc = torch.zeros((T, cfg.batch, cfg.kv_heads // T, desc.kv_cap, 128), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    ws = torch.zeros(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    B.block_fwd(desc, layer_weights(d), None, r, r_out, None, ws, kv_k=kc, kv_v=vc)
+    torch.cuda.synchronize()
+    r2_bits = unpack_dedup(B.to_host_bits(r_out), T, n, h, hs)
+    ref_gpu = run_prefill(cfg, d, reduce_in_gemm=True)
+    assert np.array_equal(r2_bits, ref_gpu["R2_bits"])
+    assert np.array_equal(B.to_host_bits(kc), ref_gpu["Kc_bits"])
+    w, ref = oracle_prefill(cfg, d)
+    assert_close(bits_to_f64(r2_bits), ref["R2"], "R2")
+
+
+def test_dedup_layout_is_refused_where_it_cannot_exist():
+    from paper_2506_19645_amd import binding as B
+    cfg = mlp_cfg(False, 2, 129, 256, 1024, 0.5, 1.0)
+    assert B.workspace_bytes(B.make_desc(cfg, reduce_in_gemm=False, dedup_shared=True)) == 0     # needs the reduce in the GEMM
+    assert B.workspace_bytes(B.make_desc(cfg.with_(p=0.3), reduce_in_gemm=True, dedup_shared=True)) == 0   # hs = 76
+    assert B.workspace_bytes(B.make_desc(cfg.with_(seq=64), reduce_in_gemm=True, dedup_shared=True)) == 0  # 64 tokens
+    assert B.workspace_bytes(B.make_desc(cfg, reduce_in_gemm=True, dedup_shared=True)) > 0

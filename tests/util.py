@@ -38,3 +38,18 @@ def ulp_distance_bf16(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
         u = u.astype(np.int32)
         return np.where(u & 0x8000, -(u & 0x7FFF), u & 0x7FFF)
     return np.abs(key(a_bits) - key(b_bits))
+
+
+def pack_dedup(bits, hs):
+    """[T, n, h] residual-stream bit patterns whose first hs columns are equal on all ranks -> the de-duplicated
+    layout: [n, hs] once, then the private columns [T, n, h - hs], flattened into one buffer."""
+    assert all(np.array_equal(bits[m, :, :hs], bits[0, :, :hs]) for m in range(1, bits.shape[0]))
+    return np.concatenate([np.ascontiguousarray(bits[0, :, :hs]).ravel(), np.ascontiguousarray(bits[:, :, hs:]).ravel()])
+
+
+def unpack_dedup(flat, T, n, h, hs):
+    """Inverse of pack_dedup: the shared block is broadcast to every rank."""
+    out = np.empty((T, n, h), dtype=flat.dtype)
+    out[:, :, :hs] = flat[:n * hs].reshape(1, n, hs)
+    out[:, :, hs:] = flat[n * hs:].reshape(T, n, h - hs)
+    return out
