@@ -224,16 +224,21 @@ class DecodeBench(MlpBench):
 class PrefillBench(MlpBench):
     """Prefill decoder layer (C6): a batch of whole prompts through attention + SwiGLU MLP, KV cache filled."""
 
-    def __init__(self, cfg, seed=0):
+    def __init__(self, cfg, seed=0, dedup=False):
         import numpy as np
         import torch
         from paper_2506_19645_amd import binding as B
         from paper_2506_19645_amd import inputs as I
         self.B, self.torch, self.cfg = B, torch, cfg
-        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.h // 2)
+        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.hs if dedup else cfg.h // 2)
         self.weights = [B.to_device(d["gamma_attn"]), B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
                         B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]
-        self.r = B.to_device(d["R"])
+        if dedup:   # shared channels once [n, hs], then the private channels [T, n, h - hs]; valid for this p only
+            hs = cfg.hs
+            self.r = B.to_device(np.concatenate([np.ascontiguousarray(d["R"][0, :, :hs]).ravel(),
+                                                 np.ascontiguousarray(d["R"][:, :, hs:]).ravel()]))
+        else:
+            self.r = B.to_device(d["R"])
         del d
         desc = B.make_desc(cfg)
         self.kc = torch.zeros((cfg.T, cfg.batch, cfg.kv_heads // cfg.T, desc.kv_cap, cfg.head_dim), dtype=torch.bfloat16,
@@ -271,7 +276,7 @@ def bench_attention_kinds(args, cfg, base):
         workload = "%s attention sub-block %s: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
             cfg.name, "fwd+bwd" if bwd else "fwd", h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, cfg.hs)
     elif args.config in ("C6", "C7"):
-        bench = PrefillBench(cfg)
+        bench = PrefillBench(cfg, dedup=args.dedup_shared)
         s, f = cfg.seq, cfg.ffn
         qkv_cols = T * cfg.qkv_r                    # h + 2 * (key/value width); 3h without grouped-query attention
         kvd = cfg.kvd_r
@@ -297,7 +302,7 @@ def bench_attention_kinds(args, cfg, base):
         work, unit, peak = kv_bytes + w_bytes, "GB/s", HBM_PEAK_GBS
         workload = "%s decode layer: h=%d ffn=%d heads=%d d=%d batch=%d kv_len=%d T=%d p=%g (hs=%d)" % (
             cfg.name, h, cfg.ffn, cfg.n_heads, cfg.head_dim, cfg.batch, cfg.kv_len, T, cfg.p, cfg.hs)
-    desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm)
+    desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm, dedup_shared=args.dedup_shared)
     ms, wall_ms = bench.time_steps(desc, args.steps, args.warmup)
     prof = bench.profile_steps(desc, max(3, min(args.steps, 10)))
     kernels = {}
@@ -324,18 +329,19 @@ def bench_attention_kinds(args, cfg, base):
     out = {"metric": "partial-sync TP block TFLOP/s (% MFMA peak) + sync GB/s (% HBM) vs p, 1 GPU",
            "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": workload + (" [reduce in GEMM]" if args.reduce_in_gemm else ""), "work_per_step": work,
+           "config": {"workload": workload + (" [reduce in GEMM]" if args.reduce_in_gemm else "") +
+                                  (" [shared channels stored once]" if args.dedup_shared else ""), "work_per_step": work,
                       "frac_peak": value / peak, "wall_ms_per_step": wall_ms},
            "roofline": roof, "kernels": kernels}
     if args.config in ("C6", "C7"):
-        # time to first token of a model made of this layer of this layer, and the paper's analytic model (App. C) next to the
+        # time to first token of a model made of this layer, and the paper's analytic model (App. C) next to the
         # measured p sweep.  On one GPU the "communication" is the in-HBM reduce over the T emulated ranks, so the
         # compute / communication capacity ratio C of the model is not a property of this machine; the model's linear
         # dependence on (1 - p) is what can be compared, with C fitted from the two end points p = 1 and p = 0.
         layers = 32 if args.config == "C6" else 80
         out["config"]["ttft_ms_%d_layers" % layers] = ms * layers
         sweep = []
-        if not args.no_sweep:
+        if not args.no_sweep and not args.dedup_shared:
             t = {}
             for p in (1.0, 0.5, 0.25, 0.0):
                 c = base.with_(p=p)
@@ -383,7 +389,14 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known size) so that a rocprofv3 --pmc run can scale "
                          "FETCH_SIZE / WRITE_SIZE against it")
+    ap.add_argument("--dedup-shared", action="store_true",
+                    help="C6 / C7, implies --reduce-in-gemm: the residual stream stores its shared channels once "
+                         "instead of T copies (no p sweep: the layout is tied to p)")
     args = ap.parse_args()
+    if args.dedup_shared:
+        if args.config not in ("C6", "C7"):
+            ap.error("--dedup-shared is for the prefill layer configs C6 / C7")
+        args.reduce_in_gemm = True
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (all T tensor-parallel ranks are emulated on it); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -400,7 +413,7 @@ def main():
         print(json.dumps(bench_attention_kinds(args, cfg, base)))
         return
     bench = MlpBench(cfg, seed=0)
-    desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm)
+    desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm, dedup_shared=args.dedup_shared)
     k = 3 if cfg.kind == I.KIND_MLP_SWIGLU else 2
     step_flops = 6.0 * cfg.tokens * cfg.h * cfg.ffn * k
 
