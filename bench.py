@@ -158,6 +158,12 @@ def cpu_baseline(cfg, host, sample_tokens):
     O.mlp_block_bwd(w["X"], fwd, w, w["gamma"], w["dXo"], w["dRo"], **kw)
     sec = time.perf_counter() - t0
     flops = 6.0 * n * cfg.h * cfg.ffn * (3 if swi else 2)
+    return {"value": flops / sec / 1e12, "unit": "TFLOP/s", "cores": _blas_threads(), "kind": "oracle",
+            "sample": "numpy fp64 oracle, fwd+bwd, first %d of %d tokens of each of the %d ranks (%.1f s)"
+                      % (n, cfg.tokens, cfg.T, sec), "seconds": sec}
+
+
+def _blas_threads():
     threads = len(os.sched_getaffinity(0))
     try:
         from threadpoolctl import threadpool_info
@@ -166,9 +172,48 @@ def cpu_baseline(cfg, host, sample_tokens):
             threads = max(blas)
     except Exception:
         pass
-    return {"value": flops / sec / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-            "sample": "numpy fp64 oracle, fwd+bwd, first %d of %d tokens of each of the %d ranks (%.1f s)"
-                      % (n, cfg.tokens, cfg.T, sec), "seconds": sec}
+    return threads
+
+
+def cpu_baseline_other_kinds(name, cfg, bwd):
+    """The numpy fp64 oracle (as it stands) on a bounded sample of the attention / layer workloads: the same layer
+    dimensions, T and p, fewer or shorter sequences (fresh seeded inputs of that smaller shape)."""
+    from oracle import caat_oracle as O
+    from paper_2506_19645_amd import inputs as I
+    T, h = cfg.T, cfg.h
+    hpr, kvpr = cfg.n_heads // T, cfg.kv_heads // T
+    if name == "C5":
+        small = cfg                       # the whole decode batch: the oracle needs only seconds for it
+    else:
+        small = cfg.with_(batch=1, seq=min(cfg.seq, 1024 if h <= 4096 else 512))
+    d = I.make_inputs(small, seed=0, with_grads=bwd)
+    w = {k: O.widen_bf16(v) for k, v in d.items()}
+    n, s = small.tokens, small.seq
+    kw = dict(heads_per_rank=hpr, head_dim=cfg.head_dim, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale,
+              rope_base=cfg.rope_base, kv_heads_per_rank=kvpr)
+    t0 = time.perf_counter()
+    if name == "C4":
+        fwd = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], None, batch=1, seq=s, norm=O.RMSNORM, **kw)
+        if bwd:
+            O.attn_block_bwd(w["X"], fwd, w["Wqkv"], w["Wo"], w["gamma"], w["dXo"], w["dRo"], batch=1, seq=s,
+                             norm=O.RMSNORM, **kw)
+        work = (24.0 if bwd else 8.0) * n * h * h + (7.0 if bwd else 2.0) * s * s * h
+        unit, scale = "TFLOP/s", 1e12
+    elif name == "C5":
+        O.decode_layer_fwd(w["R"], w, w["Kc"], w["Vc"], kv_len=cfg.kv_len, **kw)
+        fr, hd = cfg.f_r, cfg.hd_r
+        work = (2.0 * T * small.batch * kvpr * (cfg.kv_len + 1) * cfg.head_dim * 2 +
+                2.0 * T * (cfg.qkv_r * h + h * hd + 2 * fr * h + h * fr))        # KV cache of the sample + all weights
+        unit, scale = "GB/s", 1e9
+    else:
+        O.prefill_layer_fwd(w["R"], w, batch=1, seq=s, **kw)
+        work = n * (2.0 * h * T * cfg.qkv_r + 2.0 * h * h + 6.0 * h * cfg.ffn) + 2.0 * s * s * h
+        unit, scale = "TFLOP/s", 1e12
+    sec = time.perf_counter() - t0
+    return {"value": work / sec / scale, "unit": unit, "cores": _blas_threads(), "kind": "oracle",
+            "sample": "numpy fp64 oracle, %s, %d sequence(s) of %d token(s) per rank instead of %d x %d, same layer "
+                      "dimensions, T and p (%.1f s)" % ("fwd+bwd" if bwd else "fwd", small.batch, s, cfg.batch, cfg.seq, sec),
+            "seconds": sec}
 
 
 class AttnBench(MlpBench):
@@ -359,6 +404,9 @@ def bench_attention_kinds(args, cfg, base):
                                      "r": T, "h": h, "s": cfg.seq, "C_fitted_from_p1_and_p0": c_fit,
                                      "p_star_at_fitted_C": None if c_fit is None else min((12.0 * h + 2.0 * cfg.seq) / (c_fit * T), 1.0)}
         out["p_sweep"] = sweep
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline_other_kinds(args.config if args.config != "C7" else "C6", cfg,
+                                                       args.config == "C4" and not args.fwd_only)
     if args.config == "C5":
         out["config"]["latency_us_per_token_step"] = ms * 1e3
         sweep = []
