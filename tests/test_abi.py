@@ -91,3 +91,26 @@ def test_no_fallback_when_library_missing(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError):
         B.lib()
+
+
+def test_descriptor_validation_of_the_attention_and_serving_fields():
+    ok = I.BlockConfig("a", I.KIND_ATTN, I.NORM_RMSNORM, h=1024, T=2, p=0.5, batch=1, seq=256, n_heads=8, head_dim=128,
+                       n_kv_heads=4)
+    assert B.workspace_bytes(B.make_desc(ok)) > 0
+    assert B.workspace_bytes(B.make_desc(ok.with_(n_kv_heads=3))) == 0       # 8 % 3
+    assert B.workspace_bytes(B.make_desc(ok.with_(n_kv_heads=1))) == 0       # fewer key / value heads than ranks
+    assert B.workspace_bytes(B.make_desc(ok.with_(T=3))) == 0                # heads do not divide over the ranks
+    d = B.make_desc(ok)
+    d.reduce_in_gemm = 2
+    assert B.workspace_bytes(d) == 0
+    d = B.make_desc(ok, reduce_in_gemm=True, dedup_shared=True)
+    assert B.workspace_bytes(d) > 0
+    d.reduce_in_gemm = 0
+    assert B.workspace_bytes(d) == 0                                         # stored-once layout needs the reduce in the GEMM
+    L = B.workspace_layout(B.make_desc(ok))
+    qw = (4 + 2 * 2) * 128
+    assert L.bytes_Q == 2 * 256 * qw * 2 and L.bytes_dP == L.bytes_Q and L.bytes_dH == 2 * 256 * 512 * 2
+    assert L.bytes_stats == 2 * 4 * 2 * 256 * 4
+    pre = I.C6
+    assert B.workspace_bytes(B.make_desc(pre)) > 0
+    assert B.workspace_bytes(B.make_desc(pre, kv_cap=pre.seq - 1)) > 0       # capacity is checked at the call, not here
