@@ -4,17 +4,28 @@
 namespace caat {
 
 // Tile choices: 256 x 256 tiles with 8 waves (2 x 4) and 4 LDS stages of 32 k for the block-sized GEMMs of every
-// layout; for decode (at most 64 token rows per rank) the GEMM is a weight stream, so small tiles that put a
-// workgroup on every 64 weight rows (several per CU) with a deep 8-stage prefetch replace the big tile.
+// layout.  For decode (at most 64 token rows per rank) the GEMM is a weight stream, so small tiles that put a
+// workgroup on every 64 (or, for wide outputs, 128) weight rows replace the big tile; their stages are 64 k deep so
+// that a weight row is fetched 128 contiguous bytes at a time (64-byte pieces of rows that lie kilobytes apart cost
+// about a fifth of the HBM rate), 4 stages, two workgroups per CU.
 typedef TileCfg<256, 256, 2, 4, 4> CfgBig;
-typedef TileCfg<64, 64, 2, 2, 8, 2, false> CfgSkinny;
-typedef TileCfg<64, 128, 2, 2, 8, 2, false> CfgSkinnySwi;
+typedef TileCfg<64, 64, 2, 2, 4, 2, false, 64> CfgSkinny;
+typedef TileCfg<64, 128, 2, 2, 4, 2, false, 64> CfgSkinnyWide;
+typedef CfgSkinnyWide CfgSkinnySwi;
 
 hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_t s) {
   // buffer-load offsets are 32-bit and relative to the tile origin: the farthest row a tile touches times the
   // row stride must stay below 2 GiB
   const long long far_rows = (epilogue == EPI_SWIGLU_FWD ? (long long)p.half : 0) + 256 + 64;  // rows or k-rows
   if (far_rows * p.lda * 2 >= 0x7FFFFFFFLL || far_rows * p.ldb * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  if (layout == 0 && p.M <= 64 && p.N >= 2048) {
+    switch (epilogue) {
+      case EPI_PLAIN: return launch_one<CfgSkinnyWide, false, false, EPI_PLAIN>(p, s);
+      case EPI_ROWPAR: return launch_one<CfgSkinnyWide, false, false, EPI_ROWPAR>(p, s);
+      case EPI_SHARED_BCAST: return launch_one<CfgSkinnyWide, false, false, EPI_SHARED_BCAST>(p, s);
+      default: break;
+    }
+  }
   if (layout == 0 && p.M <= 64) {
     switch (epilogue) {
       case EPI_PLAIN: return launch_one<CfgSkinny, false, false, EPI_PLAIN>(p, s);

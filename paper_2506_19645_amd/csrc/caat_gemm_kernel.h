@@ -4,7 +4,8 @@
 // of Eq. A3 (column-parallel X_m A_m with the activation fused, row-parallel Y_m B_m with the private-column
 // half of the partial channel-reduce + residual fused) and their data / weight gradients.
 //
-// Tiling: a workgroup owns a BM x BN tile of C and walks K in stages of BKS = 32.  NSTAGE stages of both
+// Tiling: a workgroup owns a BM x BN tile of C and walks K in stages of BKS (32; 128 for the decode-sized tiles, whose
+// weight rows are then fetched 256 contiguous bytes at a time).  NSTAGE stages of both
 // operand tiles live in LDS and every operand goes global -> LDS directly (buffer_load ... lds, no register
 // staging), NSTAGE-1 stages ahead of the MFMAs, so a global / L2 round trip of several stage times is hidden.
 //   * operand contiguous along K in memory (NT's a and b, NN's a): stage = [rows][32 k], 64-byte rows, fragment
@@ -30,11 +31,12 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
 
-static constexpr int BKS = 32;                // k extent of one LDS stage
+static constexpr int BKS = 32;                // default k extent of one LDS stage
 static constexpr unsigned OOB = 0x80000000u;  // buffer offset that is always out of range -> load returns 0
 
-template <int BM_, int BN_, int WM_, int WN_, int NSTAGE_ = 4, int SCHED_ = 2, bool PERSIST_ = true>
+template <int BM_, int BN_, int WM_, int WN_, int NSTAGE_ = 4, int SCHED_ = 2, bool PERSIST_ = true, int BKS_ = 32>
 struct TileCfg {
+  static constexpr int BKS = BKS_;              // k extent of one LDS stage (multiple of 32; K-contiguous operands only if > 32)
   // PERSIST: one workgroup per CU walks several tiles and fetches the next tile's first stages under the epilogue
   static constexpr bool PERSIST = PERSIST_;
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, NSTAGE = NSTAGE_;
@@ -58,44 +60,56 @@ struct TileCfg {
   static constexpr int MIN_WAVES_PER_EU = (NWAVES * WGS_PER_CU) / 4 > 0 ? (NWAVES * WGS_PER_CU) / 4 : 1;
 };
 
-// ---- operand contiguous along K: stage [ROWS][32 k], row = 64 B = 4 chunks; chunk c of row r sits at c ^ ((r>>2)&3).
-// One wave instruction fills 16 rows (64 lanes x 16 B, lane order).  `origin` points at the tile's first row;
+// ---- operand contiguous along K: stage [ROWS][BKS k], row = BKS*2 bytes = CPR chunks of 16 bytes; 16 chunks make
+// up the 64 LDS banks, so chunk c of row r sits at c ^ ((r >> SWZ_SHIFT) & (CPR-1)) (for 64-byte rows: c ^ ((r>>2)&3)):
+// 16 consecutive rows then read the same logical chunk from 16 different bank groups.
+// One wave instruction fills 64/CPR rows (64 lanes x 16 B, lane order).  `origin` points at the tile's first row;
 // rowmap(rr) gives the row of tile row rr RELATIVE to the origin, or -1 if that row does not exist.
-template <int ROWS, int NWAVES>
+template <int ROWS, int NWAVES, int BKS_ = 32>
 struct KContigOperand {
-  static constexpr int NI = ROWS / 16 / NWAVES;  // copy instructions per wave per stage
+  static constexpr int CPR = BKS_ / 8;           // chunks per row: 4, 8 or 16
+  static constexpr int RPI = 64 / CPR;           // rows per copy instruction
+  static constexpr int SWZ_SHIFT = CPR == 4 ? 2 : (CPR == 8 ? 1 : 0);
+  static constexpr int NI = ROWS / RPI / NWAVES;  // copy instructions per wave per stage
   static constexpr int N_VMEM = NI;
   static constexpr int READS_PER_FRAG = 1;
-  static_assert(ROWS % (16 * NWAVES) == 0, "rows must divide over the waves");
+  static_assert(CPR == 4 || CPR == 8 || CPR == 16, "stage depth must be 32, 64 or 128");
+  static_assert(ROWS % (RPI * NWAVES) == 0, "rows must divide over the waves");
+  static __device__ __forceinline__ int swz(int row) { return (row >> SWZ_SHIFT) & (CPR - 1); }
   const bf16_t* origin;
   unsigned voff[NI];
-  int wave, kc;
+  int wave;
+  int kc[NI];  // logical chunk this lane fetches in copy instruction `it` (the same for all `it` when RPI == 16)
 
   template <class RowMap>
   __device__ __forceinline__ void init(const bf16_t* origin_, long long ld, RowMap rowmap) {
     origin = origin_;
     const int lane = threadIdx.x & 63;
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    kc = (lane & 3) ^ ((lane >> 4) & 3);  // logical chunk this lane fetches: physical slot lane&3, row (..)*16 + lane/4
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
-      const int row = (it * NWAVES + wave) * 16 + (lane >> 2);
+      // physical slot lane % CPR of row (it*NWAVES + wave)*RPI + lane / CPR holds logical chunk slot ^ swz(row); the
+      // swizzle has a period of 16 rows, so with 16 rows per instruction it does not depend on `it`
+      const int row = (it * NWAVES + wave) * RPI + lane / CPR;
+      kc[it] = (lane & (CPR - 1)) ^ swz(RPI == 16 ? lane / CPR : row);
       const long long r = rowmap(row);
-      voff[it] = (r >= 0) ? (unsigned)((r * ld + kc * 8) * 2) : OOB;
+      voff[it] = (r >= 0) ? (unsigned)((r * ld + kc[it] * 8) * 2) : OOB;
     }
   }
   // koff: element offset of the K-group the stage belongs to (0 unless the contraction runs over several buffers)
   __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
     const i32x4_t rs = make_rsrc(origin + koff + k0);
-    const bool kin = (k0 + kc * 8) < K;
 #pragma unroll
-    for (int it = 0; it < NI; ++it) dma16(rs, kin ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
+    for (int it = 0; it < NI; ++it) {
+      const bool kin = (k0 + kc[RPI == 16 ? 0 : it] * 8) < K;
+      dma16(rs, kin ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
+    }
   }
   // fragment for MFMA rows row0 .. row0+31, k sub-step ks (16 wide): lane (row0 + lane%32, k = 16 ks + 8 (lane/32) ..+7)
   static __device__ __forceinline__ bf16x8_t frag(const uint4* tile, int row0, int ks, int lane) {
     const int row = row0 + (lane & 31);
     const int c = ks * 2 + (lane >> 5);
-    return __builtin_bit_cast(bf16x8_t, tile[row * 4 + (c ^ ((row >> 2) & 3))]);
+    return __builtin_bit_cast(bf16x8_t, tile[row * CPR + (c ^ swz(row))]);
   }
 };
 
@@ -156,10 +170,13 @@ struct RowContigOperand {
   }
 };
 
-template <bool ROWCONTIG, int ROWS, int NWAVES>
-struct OperandSel { typedef KContigOperand<ROWS, NWAVES> type; };
-template <int ROWS, int NWAVES>
-struct OperandSel<true, ROWS, NWAVES> { typedef RowContigOperand<ROWS, NWAVES> type; };
+template <bool ROWCONTIG, int ROWS, int NWAVES, int BKS_>
+struct OperandSel { typedef KContigOperand<ROWS, NWAVES, BKS_> type; };
+template <int ROWS, int NWAVES, int BKS_>
+struct OperandSel<true, ROWS, NWAVES, BKS_> {
+  static_assert(BKS_ == 32, "operands that are contiguous along their row index are staged 32 k deep");
+  typedef RowContigOperand<ROWS, NWAVES> type;
+};
 
 template <int TM, int TN>
 struct Frags {
@@ -217,8 +234,10 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     pid_step = (nb - x + 7) >> 3;  // workgroups on this XCD
   }
 
-  typedef typename OperandSel<AT, BM, CFG::NWAVES>::type OpA;
-  typedef typename OperandSel<BT, BN, CFG::NWAVES>::type OpB;
+  constexpr int BKS = CFG::BKS;         // this instantiation's stage depth (hides the namespace default)
+  constexpr int NSUB = BKS / 16;        // 16-wide k sub-steps (one MFMA deep) per stage
+  typedef typename OperandSel<AT, BM, CFG::NWAVES, BKS>::type OpA;
+  typedef typename OperandSel<BT, BN, CFG::NWAVES, BKS>::type OpB;
   OpA la;
   OpB lb;
   int g = 0, m0 = 0, n0 = 0;
@@ -328,33 +347,33 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     // previous tile's epilogue scratch from the copies that will reuse its LDS slot.
     wait_vmcnt<(NSTAGE - 2) * NV>();
     __syncthreads();
-    Frags<TM, TN> f0, f1;
-    load_frags(0, 0, f0);
+    // fragments are double buffered over the NSUB 16-wide k sub-steps of a stage (NSUB is even)
+    Frags<TM, TN> fr[2];
+    load_frags(0, 0, fr[0]);
     fence();
 
     for (int kt = 0; kt < nk; ++kt) {
-      // sub-step 0; the slot of stage kt-1 is free (everyone passed the barrier below in the previous iteration)
+      // the slot of stage kt-1 is free (everyone passed the barrier below in the previous iteration)
       issue_stage(kt + NSTAGE - 1);
-      load_frags(kt, 1, f1);
-      mfma_all(f0);
-      if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
-      if constexpr (SCHED == 3) {
-        __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+#pragma unroll
+      for (int ss = 0; ss < NSUB; ++ss) {
+        if (ss + 1 < NSUB) {
+          load_frags(kt, ss + 1, fr[(ss + 1) & 1]);
+        } else {
+          // last sub-step: stage kt+1 must have landed (the two newest stages may still be in flight) and be visible
+          wait_vmcnt<(NSTAGE - 2) * NV>();
+          __syncthreads();
+          fence();
+          load_frags(kt + 1, 0, fr[0]);
+        }
+        mfma_all(fr[ss & 1]);
+        if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
+        if constexpr (SCHED == 3) {
+          __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+        }
+        fence();
       }
-      fence();
-      // sub-step 1; stage kt+1 must have landed (the two newest stages may still be in flight) and be visible
-      wait_vmcnt<(NSTAGE - 2) * NV>();
-      __syncthreads();
-      fence();
-      load_frags(kt + 1, 0, f0);
-      mfma_all(f1);
-      if constexpr (SCHED == 2) Pipe<0, NM, NR, 0>::run();
-      if constexpr (SCHED == 3) {
-        __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
-      }
-      fence();
     }
     // the zero-filled stages past K still target LDS: let them land, and let every wave finish its fragment reads,
     // before the buffers are reused
