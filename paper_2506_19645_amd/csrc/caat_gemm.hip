@@ -3,12 +3,13 @@
 
 namespace caat {
 
-// Tile choices: 256 x 256 tiles with 8 waves (2 x 4) and 4 LDS stages of 32 k for the block-sized GEMMs of every
-// layout.  For decode (at most 64 token rows per rank) the GEMM is a weight stream, so small tiles that put a
+// Tile choices: 256 x 256 tiles with 8 waves (2 x 4) and 2 LDS stages of 64 k for the block-sized GEMMs of every
+// layout (with 4 stages of 32 k an operand that is contiguous along K was fetched in 64-byte pieces of rows that lie
+// kilobytes apart, which cost the NT GEMMs 12 %; 64-k stages fetch whole 128-byte lines).  For decode (at most 64 token rows per rank) the GEMM is a weight stream, so small tiles that put a
 // workgroup on every 64 (or, for wide outputs, 128) weight rows replace the big tile; their stages are 64 k deep so
 // that a weight row is fetched 128 contiguous bytes at a time (64-byte pieces of rows that lie kilobytes apart cost
 // about a fifth of the HBM rate), 4 stages, two workgroups per CU.
-typedef TileCfg<256, 256, 2, 4, 4> CfgBig;
+typedef TileCfg<256, 256, 2, 4, 2, 2, true, 64> CfgBig;
 typedef TileCfg<64, 64, 2, 2, 4, 2, false, 64> CfgSkinny;
 typedef TileCfg<64, 128, 2, 2, 4, 2, false, 64> CfgSkinnyWide;
 typedef CfgSkinnyWide CfgSkinnySwi;

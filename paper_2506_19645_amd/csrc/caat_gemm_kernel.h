@@ -113,17 +113,17 @@ struct KContigOperand {
   }
 };
 
-// ---- operand contiguous along its row index ([K][rows] in memory): stage [32 k][ROWS] as in memory, k-row =
+// ---- operand contiguous along its row index ([K][rows] in memory): stage [BKS k][ROWS] as in memory, k-row =
 // ROWS*2 bytes; chunk c of k-row k sits at c ^ ((k&3)<<2).  One wave instruction fills 512/ROWS k-rows.
 // `origin` points at (k = 0, first row of the tile); rows_valid = rows of the tile that exist (multiple of 8).
-template <int ROWS, int NWAVES>
+template <int ROWS, int NWAVES, int BKS_ = 32>
 struct RowContigOperand {
   static constexpr int CPR = ROWS / 8;       // chunks per k-row
   static constexpr int KPI = 64 / CPR;       // k-rows per copy instruction
-  static constexpr int NI = BKS / KPI / NWAVES;
+  static constexpr int NI = BKS_ / KPI / NWAVES;
   static constexpr int N_VMEM = NI;
   static constexpr int READS_PER_FRAG = 2;
-  static_assert(ROWS >= 128 && ROWS <= 512 && BKS % (KPI * NWAVES) == 0, "unsupported tile shape for a transposed operand");
+  static_assert(ROWS >= 128 && ROWS <= 512 && BKS_ % (KPI * NWAVES) == 0, "unsupported tile shape for a transposed operand");
   const bf16_t* origin;
   long long ld;
   unsigned voff[NI];
@@ -173,10 +173,7 @@ struct RowContigOperand {
 template <bool ROWCONTIG, int ROWS, int NWAVES, int BKS_>
 struct OperandSel { typedef KContigOperand<ROWS, NWAVES, BKS_> type; };
 template <int ROWS, int NWAVES, int BKS_>
-struct OperandSel<true, ROWS, NWAVES, BKS_> {
-  static_assert(BKS_ == 32, "operands that are contiguous along their row index are staged 32 k deep");
-  typedef RowContigOperand<ROWS, NWAVES> type;
-};
+struct OperandSel<true, ROWS, NWAVES, BKS_> { typedef RowContigOperand<ROWS, NWAVES, BKS_> type; };
 
 template <int TM, int TN>
 struct Frags {
