@@ -405,6 +405,30 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     };
     bf16_t* cg = p.c + (long long)eg * p.stride_c;
     const int M = p.M;
+    // epilogues that read a second tensor (residual, saved pre-activations) fetch it one 32-row slab ahead, so that the
+    // load latency hides behind the previous slab's conversion, LDS round trip and stores
+    constexpr bool HAS_AUX = (EPI == EPI_ROWPAR || EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD);
+    constexpr int AUXV = (EPI == EPI_SWIGLU_BWD) ? 2 : 1;
+    constexpr int ASTEPS = 32 * CHW / 64;
+    uint4 auxbuf[2][HAS_AUX ? ASTEPS * AUXV : 1];
+    auto aux_fetch = [&](int i, uint4* buf) {
+      const long long rb = (long long)em0 + wm * WTM + i * 32;
+#pragma unroll
+      for (int st = 0; st < ASTEPS; ++st) {
+        const int idx = st * 64 + lane;
+        const int row = idx / CHW, c = idx - row * CHW;
+        const long long grow = rb + row;
+        const int gcol = en0 + wn * WTN + c * 8;
+#pragma unroll
+        for (int v = 0; v < AUXV; ++v) buf[st * AUXV + v] = make_uint4(0u, 0u, 0u, 0u);
+        if (grow < M && gcol < p.N && (EPI != EPI_ROWPAR || gcol + 7 >= p.hs)) {
+          const bf16_t* ap = p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol;
+          buf[st * AUXV] = *reinterpret_cast<const uint4*>(ap);
+          if constexpr (AUXV == 2) buf[st * AUXV + 1] = *reinterpret_cast<const uint4*>(ap + p.half);
+        }
+      }
+    };
+    if constexpr (HAS_AUX) aux_fetch(0, auxbuf[0]);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -417,6 +441,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
           w.y = pack2bf(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
           *reinterpret_cast<uint2*>(scratch + ((frow * CHW + (c ^ (frow & (CHW - 1)))) * 16 + fk * 8)) = w;
         }
+      if constexpr (HAS_AUX) {
+        if (i + 1 < TM) aux_fetch(i + 1, auxbuf[(i + 1) & 1]);
+      }
       // the wave reads back what its other lanes wrote: LDS executes a wave's operations in order; the compiler
       // must not reorder across this point either
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -472,7 +499,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
             if (gcol + 7 >= p.hs) {
               float v[8], r[8];
               unpack(raw, v);
-              unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol), r);
+              unpack(auxbuf[i & 1][st], r);
 #pragma unroll
               for (int e = 0; e < 8; ++e)
                 if (gcol + e >= p.hs) v[e] = p.scale * v[e] + r[e];
@@ -495,16 +522,15 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
           } else if constexpr (EPI == EPI_GELU_BWD) {
             float v[8], pr[8];
             unpack(raw, v);
-            unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol), pr);
+            unpack(auxbuf[i & 1][st], pr);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
             *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
           } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-            const bf16_t* pg = p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol;
             float v[8], gt[8], up[8], dg[8], du[8];
             unpack(raw, v);
-            unpack(*reinterpret_cast<const uint4*>(pg), gt);
-            unpack(*reinterpret_cast<const uint4*>(pg + p.half), up);
+            unpack(auxbuf[i & 1][st * AUXV], gt);
+            unpack(auxbuf[i & 1][st * AUXV + (AUXV - 1)], up);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
               const float sg = sigmoid_f(gt[e]);
