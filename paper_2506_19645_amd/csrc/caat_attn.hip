@@ -95,20 +95,45 @@ size_t attn_stats_bytes(long long n_seq, int heads, int seq) { return (size_t)(n
 __device__ __forceinline__ int kswz(int row, int c) { return c ^ (row & 15); }
 __device__ __forceinline__ int vswz(int row, int c) { return c ^ ((row & 3) << 2); }
 
+// Workgroup order of the attention kernels.  A launch covers n_bh (sequence, head) pairs x n_blk blocks whose cost grows
+// with the block index (causal).  Heaviest blocks should start first, but the blocks of one head re-read that head's
+// K / V (or Q / dO) rows, so all blocks of a head should also run close together in time: heads are taken in chunks of
+// `chunk` (a multiple of 8, so that a head's blocks also land on one XCD and share its L2: workgroup b runs on XCD
+// b % 8), and inside a chunk the order is heaviest block first, heads innermost.
+// Returns the head index; `rank` = 0 for the heaviest block .. n_blk-1 for the lightest.
+__device__ __forceinline__ int attn_block_order(int bid, int n_bh, int n_blk, int chunk, int& rank) {
+  const int per_chunk = chunk * n_blk;
+  const int c = bid / per_chunk;
+  const int r = bid - c * per_chunk;
+  const int first = c * chunk;
+  const int size = min(chunk, n_bh - first);      // the last chunk may hold fewer heads
+  rank = r / size;
+  return first + (r - rank * size);
+}
+// chunk size: about 32 MB of K + V rows (seq x 512 bytes per head) per chunk, a multiple of 8, at least 8
+static int attn_chunk_heads(int seq) {
+  long long c = (32LL << 20) / ((long long)seq * 512);
+  c = c / 8 * 8;
+  if (c < 8) c = 8;
+  if (c > 1024) c = 1024;
+  return (int)c;
+}
+
 // qkv: [T*tokens, (heads + 2*kv_heads)*128] with q | k | v column blocks (q, k already rotated); out: [T*tokens, hd],
 // hd = heads*128.  Query head a reads key / value head a / (heads / kv_heads) (grouped-query attention).
 // stats (may be null): the forward fills the log-sum-exp rows (what the backward needs to rebuild the probabilities).
 __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                         float* __restrict__ stats, int seq, int seq_pad, int hd, int heads,
-                                                        int kv_heads, int n_qblk, float scale_log2) {
+                                                        int kv_heads, int n_qblk, float scale_log2, int chunk) {
   __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, hf = lane >> 5;
   // longest-first over the whole launch: the last (heaviest, causal) query blocks of every head come first
   const int n_bh = gridDim.x / n_qblk;
-  const int qb = n_qblk - 1 - (int)(blockIdx.x / n_bh);
-  const int bh = blockIdx.x % n_bh;              // (rank*batch + b) * heads + head
+  int lpt_rank;
+  const int bh = attn_block_order(blockIdx.x, n_bh, n_qblk, chunk, lpt_rank);   // (rank*batch + b) * heads + head
+  const int qb = n_qblk - 1 - lpt_rank;          // the last (heaviest, causal) query blocks first
   const int head = bh % heads;
   const long long seq_row0 = (long long)(bh / heads) * seq;   // first row of this sequence in qkv
   const long long ld = (long long)(heads + 2 * kv_heads) * HD;
@@ -284,7 +309,7 @@ hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, float* stats, long l
     return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)d);
   hipLaunchKernelGGL(flash_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, out, stats, seq, (int)attn_seq_pad(seq), hd,
-                     heads, kv_heads, n_qblk, scale_log2);
+                     heads, kv_heads, n_qblk, scale_log2, attn_chunk_heads(seq));
   return hipGetLastError();
 }
 
@@ -382,14 +407,15 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __rest
 __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                            const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
                                                            int seq_pad, int hd, int heads, int kv_heads, int n_qblk,
-                                                           float scale_log2, float scale) {
+                                                           float scale_log2, float scale, int chunk) {
   __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, hf = lane >> 5;
   const int n_bh = gridDim.x / n_qblk;
-  const int qb = n_qblk - 1 - (int)(blockIdx.x / n_bh);      // heaviest (last) query blocks first
-  const int bh = blockIdx.x % n_bh;
+  int lpt_rank;
+  const int bh = attn_block_order(blockIdx.x, n_bh, n_qblk, chunk, lpt_rank);
+  const int qb = n_qblk - 1 - lpt_rank;                      // heaviest (last) query blocks first
   const int head = bh % heads;
   const long long seq_row0 = (long long)(bh / heads) * seq;
   const long long ld = (long long)(heads + 2 * kv_heads) * HD;
@@ -489,14 +515,14 @@ static constexpr int DKV_STAGE = 2 * BQB * KCH + 64;        // uint4 per stage: 
 __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
                                                             const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
                                                             int seq_pad, int hd, int heads, int kv_heads, int n_kblk,
-                                                            float scale_log2, float scale) {
+                                                            float scale_log2, float scale, int chunk) {
   __shared__ uint4 smem[2 * DKV_STAGE];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, hf = lane >> 5;
   const int n_bh = gridDim.x / n_kblk;                        // sequences x key/value heads
-  const int kb = (int)(blockIdx.x / n_bh);                    // heaviest (first) key blocks first
-  const int bh = blockIdx.x % n_bh;
+  int kb;                                                     // heaviest (first) key blocks first
+  const int bh = attn_block_order(blockIdx.x, n_bh, n_kblk, chunk, kb);
   const int kvh = bh % kv_heads;
   const int grp = heads / kv_heads;                           // query heads that read this key / value head
   const long long sq = bh / kv_heads;
@@ -650,11 +676,11 @@ hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(flash_bwd_dkv_kernel, dim3((unsigned)(n_seq * kv_heads * n_qblk)), dim3(256), 0, s, qkv, dout, stats, dqkv,
-                     seq, seq_pad, hd, heads, kv_heads, n_qblk, scale_log2, inv_sqrt_d);
+                     seq, seq_pad, hd, heads, kv_heads, n_qblk, scale_log2, inv_sqrt_d, attn_chunk_heads(seq));
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(flash_bwd_dq_kernel, dim3((unsigned)(n_bh * n_qblk)), dim3(256), 0, s, qkv, dout, stats, dqkv, seq, seq_pad,
-                     hd, heads, kv_heads, n_qblk, scale_log2, inv_sqrt_d);
+                     hd, heads, kv_heads, n_qblk, scale_log2, inv_sqrt_d, attn_chunk_heads(seq));
   return hipGetLastError();
 }
 
