@@ -169,6 +169,25 @@ def test_gemm_layouts(layout, G, M, N, K):
     assert_close(bits_to_f64(B.to_host_bits(c)), want, "gemm layout %d" % layout, tol=5e-3)
 
 
+def _random_gemm_shapes(count, seed):
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        G = int(r.integers(1, 4))
+        M = int(r.choice([8, 40, 64, 72, 200, 256, 264, 520, 776]))
+        N = int(r.choice([8, 32, 64, 136, 256, 264, 512, 600]))
+        K = int(r.choice([8, 24, 56, 64, 72, 128, 136, 200, 328, 1032]))
+        out.append((int(r.integers(0, 3)), G, M, N, K))
+    return out
+
+
+@pytest.mark.parametrize("layout,G,M,N,K", _random_gemm_shapes(36, seed=2024))
+def test_gemm_random_shapes(layout, G, M, N, K):
+    """Seeded random mixes of tile-ragged M, N and stage-ragged K (64-k stages, 16-byte k granularity) in every layout,
+    including the decode-sized tiles (M <= 64)."""
+    test_gemm_layouts(layout, G, M, N, K)
+
+
 def test_gemm_strided_output_and_operands():
     """Leading dimensions larger than the logical extents (sub-matrix views) and untouched padding."""
     torch = _torch()
