@@ -390,7 +390,7 @@ def bench_attention_kinds(args, cfg, base):
             t = {}
             for p in (1.0, 0.5, 0.25, 0.0):
                 c = base.with_(p=p)
-                t[p], _ = bench.time_steps(B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm), max(3, args.steps // 3), 2)
+                t[p], _ = bench.time_steps(B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm), max(3, args.steps // 2), max(2, args.warmup // 2))
             s0 = (t[1.0] - t[0.0]) / t[1.0]                       # measured speed-up at p = 0 = 1 / (1 + (12h+2s)/(C r))
             c_fit = (12.0 * h + 2.0 * cfg.seq) / (T * (1.0 / s0 - 1.0)) if 0.0 < s0 < 1.0 else None
             for p in (1.0, 0.5, 0.25, 0.0):
@@ -413,7 +413,7 @@ def bench_attention_kinds(args, cfg, base):
         if not args.no_sweep:
             for p in (1.0, 0.5, 0.25, 0.0):
                 c = base.with_(p=p)
-                ms_p, _ = bench.time_steps(B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm), max(3, args.steps // 2), 2)
+                ms_p, _ = bench.time_steps(B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm), args.steps, args.warmup)
                 sweep.append({"p": p, "hs": c.hs, "ms_per_step": round(ms_p, 5), "GB/s": round(work / ms_p / 1e6, 1),
                               "synced_payload_bytes_per_token_per_reduce": 2 * c.hs})
         out["p_sweep"] = sweep
@@ -502,7 +502,7 @@ def main():
         for p in (1.0, 0.5, 0.25, 0.0):
             c = base.with_(p=p)
             dsc = B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm)
-            ms_p, _ = bench.time_steps(dsc, max(3, args.steps // 2), 2)
+            ms_p, _ = bench.time_steps(dsc, args.steps, args.warmup)   # same warm-up as the headline: the clocks ramp
             pr = bench.profile_steps(dsc, 5)
             sa_ms, sa_gbs = standalone_sync(torch, B, c, c.hs)
             e = {"p": p, "hs": c.hs, "ms_per_step": round(ms_p, 4), "TFLOP/s": round(step_flops / ms_p / 1e9, 1),
