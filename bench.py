@@ -90,16 +90,30 @@ class MlpBench:
         B.block_bwd(desc, self.weights, self.x, self.r_out, self.ws, self.dxo, self.dro, self.dx, self.dr,
                     [self.dw0, self.dw1], self.dgamma, self.dbeta)
 
+    use_graph = False   # --graph: one step is recorded into a HIP graph and the timed region replays it
+
     def time_steps(self, desc, steps, warmup):
         torch = self.torch
+        run = lambda: self.step(desc)
+        if self.use_graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                self.step(desc)
+                torch.cuda.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    self.step(desc)
+            torch.cuda.current_stream().wait_stream(side)
+            run = graph.replay
         for _ in range(warmup):
-            self.step(desc)
+            run()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         e0.record()
         for _ in range(steps):
-            self.step(desc)
+            run()
         e1.record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
@@ -375,7 +389,8 @@ def bench_attention_kinds(args, cfg, base):
            "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": workload + (" [reduce in GEMM]" if args.reduce_in_gemm else "") +
-                                  (" [shared channels stored once]" if args.dedup_shared else ""), "work_per_step": work,
+                                  (" [shared channels stored once]" if args.dedup_shared else "") +
+                                  (" [HIP graph replay]" if args.graph else ""), "work_per_step": work,
                       "frac_peak": value / peak, "wall_ms_per_step": wall_ms},
            "roofline": roof, "kernels": kernels}
     if args.config in ("C6", "C7"):
@@ -440,7 +455,10 @@ def main():
     ap.add_argument("--dedup-shared", action="store_true",
                     help="C6 / C7, implies --reduce-in-gemm: the residual stream stores its shared channels once "
                          "instead of T copies (no p sweep: the layout is tied to p)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph and time its replays (launch-bound small configs)")
     args = ap.parse_args()
+    MlpBench.use_graph = args.graph
     if args.dedup_shared:
         if args.config not in ("C6", "C7"):
             ap.error("--dedup-shared is for the prefill layer configs C6 / C7")
