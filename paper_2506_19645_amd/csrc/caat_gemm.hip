@@ -10,9 +10,48 @@ namespace caat {
 // that a weight row is fetched 128 contiguous bytes at a time (64-byte pieces of rows that lie kilobytes apart cost
 // about a fifth of the HBM rate), 4 stages, two workgroups per CU.
 typedef TileCfg<256, 256, 2, 4, 2, 2, true, 64> CfgBig;
+typedef TileCfg<128, 128, 2, 2, 2, 2, false, 64> CfgMid;   // problems with too few 256 x 256 tiles to fill the chip
 typedef TileCfg<64, 64, 2, 2, 4, 2, false, 64> CfgSkinny;
 typedef TileCfg<64, 128, 2, 2, 4, 2, false, 64> CfgSkinnyWide;
 typedef CfgSkinnyWide CfgSkinnySwi;
+
+// every (layout, epilogue) pair that exists, for one block-sized tile shape
+template <class CFG>
+static hipError_t launch_block_sized(const GemmParams& p, int layout, int epilogue, hipStream_t s) {
+  switch (layout) {
+    case 0:  // NT
+      switch (epilogue) {
+        case EPI_PLAIN: return launch_one<CFG, false, false, EPI_PLAIN>(p, s);
+        case EPI_GELU_FWD: return launch_one<CFG, false, false, EPI_GELU_FWD>(p, s);
+        case EPI_SWIGLU_FWD: return launch_one<CFG, false, false, EPI_SWIGLU_FWD>(p, s);
+        case EPI_ROWPAR: return launch_one<CFG, false, false, EPI_ROWPAR>(p, s);
+        case EPI_SHARED_BCAST: return launch_one<CFG, false, false, EPI_SHARED_BCAST>(p, s);
+        default: return hipErrorInvalidValue;
+      }
+    case 1:  // NN
+      switch (epilogue) {
+        case EPI_PLAIN: return launch_one<CFG, false, true, EPI_PLAIN>(p, s);
+        case EPI_GELU_BWD: return launch_one<CFG, false, true, EPI_GELU_BWD>(p, s);
+        case EPI_SWIGLU_BWD: return launch_one<CFG, false, true, EPI_SWIGLU_BWD>(p, s);
+        default: return hipErrorInvalidValue;
+      }
+    case 2:  // TN
+      if (epilogue == EPI_PLAIN) return launch_one<CFG, true, true, EPI_PLAIN>(p, s);
+      return hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
+
+static int compute_units() {
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+      n_cu = v;
+    if (n_cu <= 0) n_cu = 256;
+  }
+  return n_cu;
+}
 
 hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_t s) {
   // buffer-load offsets are 32-bit and relative to the tile origin: the farthest row a tile touches times the
@@ -37,28 +76,18 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
       default: return hipErrorInvalidValue;
     }
   }
-  switch (layout) {
-    case 0:  // NT
-      switch (epilogue) {
-        case EPI_PLAIN: return launch_one<CfgBig, false, false, EPI_PLAIN>(p, s);
-        case EPI_GELU_FWD: return launch_one<CfgBig, false, false, EPI_GELU_FWD>(p, s);
-        case EPI_SWIGLU_FWD: return launch_one<CfgBig, false, false, EPI_SWIGLU_FWD>(p, s);
-        case EPI_ROWPAR: return launch_one<CfgBig, false, false, EPI_ROWPAR>(p, s);
-        case EPI_SHARED_BCAST: return launch_one<CfgBig, false, false, EPI_SHARED_BCAST>(p, s);
-        default: return hipErrorInvalidValue;
-      }
-    case 1:  // NN
-      switch (epilogue) {
-        case EPI_PLAIN: return launch_one<CfgBig, false, true, EPI_PLAIN>(p, s);
-        case EPI_GELU_BWD: return launch_one<CfgBig, false, true, EPI_GELU_BWD>(p, s);
-        case EPI_SWIGLU_BWD: return launch_one<CfgBig, false, true, EPI_SWIGLU_BWD>(p, s);
-        default: return hipErrorInvalidValue;
-      }
-    case 2:  // TN
-      if (epilogue == EPI_PLAIN) return launch_one<CfgBig, true, true, EPI_PLAIN>(p, s);
-      return hipErrorInvalidValue;
-    default: return hipErrorInvalidValue;
-  }
+  // 256 x 256 tiles (one workgroup per CU) unless they would leave much of the chip idle: then 128 x 128 tiles, two
+  // workgroups per CU (measured about 15 % less efficient per tile, hence the factor).  Occupancy of a launch =
+  // tiles / (rounds x slots).
+  const int n_cu = compute_units();
+  auto occupancy = [&](long long bm, long long bn, long long slots) {
+    const long long bn_out = epilogue == EPI_SWIGLU_FWD ? bn / 2 : bn;
+    const long long tiles = ((p.M + bm - 1) / bm) * ((p.N + bn_out - 1) / bn_out) * p.G;
+    const long long rounds = (tiles + slots - 1) / slots;
+    return (double)tiles / (double)(rounds * slots);
+  };
+  if (0.85 * occupancy(128, 128, 2LL * n_cu) > occupancy(256, 256, n_cu)) return launch_block_sized<CfgMid>(p, layout, epilogue, s);
+  return launch_block_sized<CfgBig>(p, layout, epilogue, s);
 }
 
 }  // namespace caat
