@@ -78,13 +78,15 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
   }
   // 256 x 256 tiles (one workgroup per CU) unless they would leave much of the chip idle: then 128 x 128 tiles, two
   // workgroups per CU (measured about 15 % less efficient per tile, hence the factor).  Occupancy of a launch =
-  // tiles / (rounds x slots).
+  // tiles / (rounds x slots), times the fraction of the tiles' area that lies inside the matrix.
   const int n_cu = compute_units();
   auto occupancy = [&](long long bm, long long bn, long long slots) {
     const long long bn_out = epilogue == EPI_SWIGLU_FWD ? bn / 2 : bn;
-    const long long tiles = ((p.M + bm - 1) / bm) * ((p.N + bn_out - 1) / bn_out) * p.G;
+    const long long tm = (p.M + bm - 1) / bm, tn = (p.N + bn_out - 1) / bn_out;
+    const long long tiles = tm * tn * p.G;
     const long long rounds = (tiles + slots - 1) / slots;
-    return (double)tiles / (double)(rounds * slots);
+    const double filled = ((double)p.M * (double)p.N) / ((double)(tm * bm) * (double)(tn * bn_out));  // ragged edge tiles
+    return filled * (double)tiles / (double)(rounds * slots);
   };
   if (0.85 * occupancy(128, 128, 2LL * n_cu) > occupancy(256, 256, n_cu)) return launch_block_sized<CfgMid>(p, layout, epilogue, s);
   return launch_block_sized<CfgBig>(p, layout, epilogue, s);
