@@ -77,7 +77,7 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
     }
   }
   // 256 x 256 tiles (one workgroup per CU) unless they would leave much of the chip idle: then 128 x 128 tiles, two
-  // workgroups per CU (measured about 15 % less efficient per tile, hence the factor).  Occupancy of a launch =
+  // workgroups per CU (measured 17 % less efficient per tile at full occupancy, hence the factor).  Occupancy of a launch =
   // tiles / (rounds x slots), times the fraction of the tiles' area that lies inside the matrix.
   const int n_cu = compute_units();
   auto occupancy = [&](long long bm, long long bn, long long slots) {
@@ -88,7 +88,7 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
     const double filled = ((double)p.M * (double)p.N) / ((double)(tm * bm) * (double)(tn * bn_out));  // ragged edge tiles
     return filled * (double)tiles / (double)(rounds * slots);
   };
-  if (0.85 * occupancy(128, 128, 2LL * n_cu) > occupancy(256, 256, n_cu)) return launch_block_sized<CfgMid>(p, layout, epilogue, s);
+  if (0.83 * occupancy(128, 128, 2LL * n_cu) > occupancy(256, 256, n_cu)) return launch_block_sized<CfgMid>(p, layout, epilogue, s);
   return launch_block_sized<CfgBig>(p, layout, epilogue, s);
 }
 
