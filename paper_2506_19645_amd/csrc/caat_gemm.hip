@@ -1,4 +1,5 @@
 // Instantiations and launch dispatch of the grouped bf16 shard GEMM (kernel template in caat_gemm_kernel.h).
+#include <algorithm>
 #include "caat_gemm_kernel.h"
 
 namespace caat {
@@ -58,6 +59,9 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
   // row stride must stay below 2 GiB
   const long long far_rows = (epilogue == EPI_SWIGLU_FWD ? (long long)p.half : 0) + 256 + 64;  // rows or k-rows
   if (far_rows * p.lda * 2 >= 0x7FFFFFFFLL || far_rows * p.ldb * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  // the epilogue's buffer offsets are relative to a wave's first row: up to 256 rows of any output / second operand
+  const long long ldmax = std::max(std::max(p.ldc, p.ldc2), p.ldaux);
+  if ((256 * ldmax + 2 * (long long)p.half + (long long)p.N) * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
   if (layout == 0 && p.M <= 64 && p.N >= 2048) {
     switch (epilogue) {
       case EPI_PLAIN: return launch_one<CfgSkinnyWide, false, false, EPI_PLAIN>(p, s);

@@ -308,6 +308,14 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     if constexpr (SCHED >= 1) __builtin_amdgcn_sched_barrier(0);
   };
 
+  // epilogue stores per wave and tile (known at compile time except for the broadcast epilogue's loop over ranks)
+  constexpr int EPI_STORES =
+      (EPI == EPI_SHARED_BCAST)
+          ? 1000
+          : TM * (32 * (SWI ? WTN / 16 : WTN / 8) / 64) *
+                (EPI == EPI_SWIGLU_FWD ? 3 : ((EPI == EPI_GELU_FWD || EPI == EPI_SWIGLU_BWD) ? 2 : 1));
+  bool first_tile = true;
+
   if (pid >= pid_end) return;
   setup_tile(pid);
 #pragma unroll
@@ -339,10 +347,15 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
     };
 
-    // copies complete in order: with at most the two newest stages outstanding, stage 0 has landed.  (Younger
-    // epilogue loads / stores of the previous tile only make this wait stricter.)  The barrier also separates the
-    // previous tile's epilogue scratch from the copies that will reuse its LDS slot.
-    wait_vmcnt<(NSTAGE - 2) * NV>();
+    // copies complete in order: with at most the two newest stages outstanding, stage 0 has landed.  After a
+    // previous tile, the wave's newest vector-memory instructions are that tile's epilogue stores (a fixed number,
+    // all issued after this tile's first copies): they may stay in flight under the first stage's MFMAs.  The
+    // barrier also separates the previous tile's epilogue scratch from the copies that will reuse its LDS slot.
+    if (first_tile || EPI_STORES + (NSTAGE - 2) * NV > 63)
+      wait_vmcnt<(NSTAGE - 2) * NV>();
+    else
+      wait_vmcnt<(EPI_STORES + (NSTAGE - 2) * NV > 63) ? 0 : EPI_STORES + (NSTAGE - 2) * NV>();
+    first_tile = false;
     __syncthreads();
     // fragments are double buffered over the NSUB 16-wide k sub-steps of a stage (NSUB is even)
     Frags<TM, TN> fr[2];
@@ -392,6 +405,12 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     // wave rounds 32 rows x WTN columns to bf16 into its own LDS scratch (chunk index XOR-swizzled by the row) and
     // reads them back row-wise: 16 bytes per lane, consecutive lanes = consecutive columns.  The fused element-wise
     // work (activation, its derivative, the private half of the partial channel-reduce + residual) happens there.
+    //
+    // Every global access of the epilogue is a raw buffer load / store whose offset is replaced by an out-of-range
+    // one where the row or column does not exist (the load then returns zero, the store is dropped): the code has no
+    // branch, so the number of vector-memory instructions per tile is fixed (the wait at the top of the next tile
+    // counts on it) and the compiler's own waits for the prefetched second operand stay exact (vmcnt(n), not
+    // vmcnt(0), which would also wait for the stores and the prefetch issued just before).
     constexpr int CHW = WTN / 8;  // 16-byte chunks per scratch row
     char* scratch = reinterpret_cast<char*>(smem) + (CFG::SMEM_CHUNKS * 16 - CFG::SCRATCH_BYTES) + wave * (32 * WTN * 2);
     const uint4* scr4 = reinterpret_cast<const uint4*>(scratch);
@@ -403,32 +422,67 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     auto pack = [](const float* f) -> uint4 {
       return make_uint4(pack2bf(f[0], f[1]), pack2bf(f[2], f[3]), pack2bf(f[4], f[5]), pack2bf(f[6], f[7]));
     };
-    bf16_t* cg = p.c + (long long)eg * p.stride_c;
-    const int M = p.M;
-    // epilogues that read a second tensor (residual, saved pre-activations) fetch it one 32-row slab ahead, so that the
-    // load latency hides behind the previous slab's conversion, LDS round trip and stores
+    constexpr int OCW = SWI ? CHW / 2 : CHW;      // 16-byte chunks per output row of the wave
+    constexpr int STEPS = 32 * OCW / 64;          // vectors per lane per 32-row slab
+    static_assert(STEPS >= 1, "a slab must give every lane at least one vector");
     constexpr bool HAS_AUX = (EPI == EPI_ROWPAR || EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD);
     constexpr int AUXV = (EPI == EPI_SWIGLU_BWD) ? 2 : 1;
-    constexpr int ASTEPS = 32 * CHW / 64;
-    uint4 auxbuf[2][HAS_AUX ? ASTEPS * AUXV : 1];
-    auto aux_fetch = [&](int i, uint4* buf) {
-      const long long rb = (long long)em0 + wm * WTM + i * 32;
+    const int wrow0 = em0 + wm * WTM;             // first row of the wave's sub-tile
+    const int wcol0 = en0 + wn * (SWI ? WTN / 2 : WTN);  // first output column of the wave's sub-tile
+    const int ncols = SWI ? p.half : p.N;
+    // buffer windows start at the wave's first row, so that offsets stay small: (row in slab) * ld + column, in
+    // bytes; the slab's 32 * i rows go into the scalar offset
+    const rsrc_t rc = make_rsrc_t(p.c + (long long)eg * p.stride_c + (long long)wrow0 * p.ldc);
+    const rsrc_t rc2 = make_rsrc_t((EPI == EPI_GELU_FWD || SWI) ? p.c2 + (long long)eg * p.stride_c2 + (long long)wrow0 * p.ldc2 : p.c);
+    const rsrc_t raux = make_rsrc_t(HAS_AUX ? p.aux + (long long)eg * p.stride_aux + (long long)wrow0 * p.ldaux : p.c);
+    int erow[STEPS], ecol[STEPS];                 // slab row and output column of the lane's vector in step st
+    unsigned voff_c[STEPS], voff_c2[STEPS], voff_aux[STEPS];
 #pragma unroll
-      for (int st = 0; st < ASTEPS; ++st) {
-        const int idx = st * 64 + lane;
-        const int row = idx / CHW, c = idx - row * CHW;
-        const long long grow = rb + row;
-        const int gcol = en0 + wn * WTN + c * 8;
+    for (int st = 0; st < STEPS; ++st) {
+      const int idx = st * 64 + lane;
+      erow[st] = idx / OCW;
+      const int oc = idx - erow[st] * OCW;
+      ecol[st] = wcol0 + oc * 8;
+      const bool colok = ecol[st] < ncols;
+      voff_c[st] = colok ? (unsigned)((erow[st] * p.ldc + ecol[st]) * 2) : OOB;
+      voff_c2[st] = colok ? (unsigned)((erow[st] * p.ldc2 + ecol[st]) * 2) : OOB;
+      // the residual is only needed where the vector has a private channel (Eq. A3)
+      const bool auxok = colok && (EPI != EPI_ROWPAR || ecol[st] + 7 >= p.hs);
+      voff_aux[st] = auxok ? (unsigned)((erow[st] * p.ldaux + ecol[st]) * 2) : OOB;
+    }
+    auto rows_left = [&](int i) { return p.M - wrow0 - i * 32; };
+    // epilogues that read a second tensor (residual, saved pre-activations) fetch it AUXD 32-row slabs ahead: a slab's
+    // conversion, LDS round trip and stores take less time than one trip to memory.  The residual epilogue, light on
+    // registers, fetches all of the wave's slabs at once; the activation-derivative epilogues (whose NN main loop
+    // already needs nearly every register) measured faster with two.
+    constexpr int AUXD = !HAS_AUX ? 1 : (TM < 2 ? 1 : (EPI == EPI_ROWPAR && STEPS * 4 * TM <= 64 ? TM : 2));
+    u32x4_t auxbuf[AUXD][HAS_AUX ? STEPS * AUXV : 1];
+    auto aux_fetch = [&](int i, u32x4_t* buf) {
+      const int rl = rows_left(i);
+      const int so = i * 32 * (int)p.ldaux * 2;
 #pragma unroll
-        for (int v = 0; v < AUXV; ++v) buf[st * AUXV + v] = make_uint4(0u, 0u, 0u, 0u);
-        if (grow < M && gcol < p.N && (EPI != EPI_ROWPAR || gcol + 7 >= p.hs)) {
-          const bf16_t* ap = p.aux + (long long)eg * p.stride_aux + grow * p.ldaux + gcol;
-          buf[st * AUXV] = *reinterpret_cast<const uint4*>(ap);
-          if constexpr (AUXV == 2) buf[st * AUXV + 1] = *reinterpret_cast<const uint4*>(ap + p.half);
-        }
+      for (int st = 0; st < STEPS; ++st) {
+        const unsigned vo = erow[st] < rl ? voff_aux[st] : OOB;
+        buf[st * AUXV] = __builtin_amdgcn_raw_buffer_load_b128(raux, vo, so, 0);
+        if constexpr (AUXV == 2) buf[st * AUXV + 1] = __builtin_amdgcn_raw_buffer_load_b128(raux, vo, so + p.half * 2, 0);
       }
     };
-    if constexpr (HAS_AUX) aux_fetch(0, auxbuf[0]);
+    auto to_u4 = [](const u32x4_t& v) -> uint4 { return make_uint4(v[0], v[1], v[2], v[3]); };
+    // Stores keep the slab offset in the vector offset and pass no scalar offset register: the 16-byte store reads
+    // its data registers a few cycles after it issues, and the compiler only keeps the following instructions from
+    // overwriting them (the documented store-data hazard) for the form without a scalar offset register; with one,
+    // the first data register was now and then overwritten by the next vector's arithmetic before the store had
+    // read it (seen as a wrong first dword in a few lanes at full problem sizes).  The two idle cycles after the
+    // store restate that requirement where the store is issued.
+    auto put = [&](const rsrc_t& r, const uint4& v, bool ok, unsigned vo, int so) {
+      const u32x4_t w = {v.x, v.y, v.z, v.w};
+      __builtin_amdgcn_raw_buffer_store_b128(w, r, ok ? vo + (unsigned)so : OOB, 0, 0);
+      asm volatile("s_nop 1" ::: "memory");
+    };
+    if constexpr (HAS_AUX) {
+#pragma unroll
+      for (int i = 0; i < AUXD && i < TM; ++i) aux_fetch(i, auxbuf[i]);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -441,108 +495,93 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
           w.y = pack2bf(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
           *reinterpret_cast<uint2*>(scratch + ((frow * CHW + (c ^ (frow & (CHW - 1)))) * 16 + fk * 8)) = w;
         }
-      if constexpr (HAS_AUX) {
-        if (i + 1 < TM) aux_fetch(i + 1, auxbuf[(i + 1) & 1]);
-      }
       // the wave reads back what its other lanes wrote: LDS executes a wave's operations in order; the compiler
       // must not reorder across this point either
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      const long long row_base = (long long)em0 + wm * WTM + i * 32;
-      if constexpr (SWI) {
-        // scratch columns: [gate 32 | up 32] pairs; output chunk oc -> gate chunk (oc/4)*8 + oc%4, up chunk = +4
-        constexpr int OCW = CHW / 2;
-        constexpr int STEPS = 32 * OCW / 64;
-        bf16_t* yg = p.c2 + (long long)eg * p.stride_c2;
+      const int rl = rows_left(i);
+      const int so_c = i * 32 * (int)p.ldc * 2;
 #pragma unroll
-        for (int st = 0; st < STEPS; ++st) {
-          const int idx = st * 64 + lane;
-          const int row = idx / OCW, oc = idx - row * OCW;
-          const long long grow = row_base + row;
-          const int gcol = en0 + (wn * (TN / 2) + (oc >> 2)) * 32 + (oc & 3) * 8;
-          if (grow >= M || gcol >= p.half) continue;
+      for (int st = 0; st < STEPS; ++st) {
+        const bool rowok = erow[st] < rl;
+        const unsigned vo = voff_c[st];
+        if constexpr (SWI) {
+          // scratch columns: [gate 32 | up 32] pairs; output chunk oc -> gate chunk (oc/4)*8 + oc%4, up chunk = +4
+          const int oc = (st * 64 + lane) - erow[st] * OCW;
           const int gc = (oc >> 2) * 8 + (oc & 3);
-          const uint4 gw = staged(row, gc), uw = staged(row, gc + 4);
+          const uint4 gw = staged(erow[st], gc), uw = staged(erow[st], gc + 4);
           float gt[8], up[8], y[8];
           unpack(gw, gt);
           unpack(uw, up);
 #pragma unroll
           for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
-          *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = gw;
-          *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = uw;
-          *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
-        }
-      } else {
-        constexpr int STEPS = 32 * CHW / 64;
-#pragma unroll
-        for (int st = 0; st < STEPS; ++st) {
-          const int idx = st * 64 + lane;
-          const int row = idx / CHW, c = idx - row * CHW;
-          const long long grow = row_base + row;
-          const int gcol = en0 + wn * WTN + c * 8;
-          if (grow >= M || gcol >= p.N) continue;
-          const uint4 raw = staged(row, c);
+          put(rc, gw, rowok, vo, so_c);
+          put(rc, uw, rowok, vo, so_c + p.half * 2);
+          put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
+        } else {
+          const int c = (st * 64 + lane) - erow[st] * CHW;
+          const uint4 raw = staged(erow[st], c);
           if constexpr (EPI == EPI_PLAIN) {
-            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
+            put(rc, raw, rowok, vo, so_c);
           } else if constexpr (EPI == EPI_GELU_FWD) {
             // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
             float v[8], y[8];
             unpack(raw, v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
-            bf16_t* yg = p.c2 + (long long)eg * p.stride_c2;
-            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
-            *reinterpret_cast<uint4*>(yg + grow * p.ldc2 + gcol) = pack(y);
+            put(rc, raw, rowok, vo, so_c);
+            put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
           } else if constexpr (EPI == EPI_ROWPAR) {
             // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual); columns < hs are
-            // stored as this rank's partial sum for the reduce kernel.  The private value is scaled from the
-            // bf16-rounded partial.
-            if (gcol + 7 >= p.hs) {
-              float v[8], r[8];
-              unpack(raw, v);
-              unpack(auxbuf[i & 1][st], r);
+            // stored as this rank's partial sum for the reduce kernel (rounding a bf16 value to bf16 again leaves
+            // its bits as they are).  The private value is scaled from the bf16-rounded partial.
+            float v[8], r[8];
+            unpack(raw, v);
+            unpack(to_u4(auxbuf[i % AUXD][st]), r);
 #pragma unroll
-              for (int e = 0; e < 8; ++e)
-                if (gcol + e >= p.hs) v[e] = p.scale * v[e] + r[e];
-              *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
-            } else {
-              *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = raw;
-            }
+            for (int e = 0; e < 8; ++e) v[e] = (ecol[st] + e >= p.hs) ? p.scale * v[e] + r[e] : v[e];
+            put(rc, pack(v), rowok, vo, so_c);
           } else if constexpr (EPI == EPI_SHARED_BCAST) {
             // Eq. A3, shared channels with the sum over ranks already in the accumulator: every rank's output gets
             // the same sum plus that rank's residual
             float v[8];
             unpack(raw, v);
             for (int m = 0; m < p.bcast; ++m) {
+              const rsrc_t rr = make_rsrc_t(p.aux + (long long)m * p.stride_aux + (long long)wrow0 * p.ldaux);
+              const rsrc_t rw = make_rsrc_t(p.c + (long long)m * p.stride_c + (long long)wrow0 * p.ldc);
+              const unsigned va = (rowok && ecol[st] < ncols) ? (unsigned)((erow[st] * p.ldaux + ecol[st]) * 2) : OOB;
               float r[8], o[8];
-              unpack(*reinterpret_cast<const uint4*>(p.aux + (long long)m * p.stride_aux + grow * p.ldaux + gcol), r);
+              unpack(to_u4(__builtin_amdgcn_raw_buffer_load_b128(rr, va, i * 32 * (int)p.ldaux * 2, 0)), r);
 #pragma unroll
               for (int e = 0; e < 8; ++e) o[e] = v[e] + r[e];
-              *reinterpret_cast<uint4*>(p.c + (long long)m * p.stride_c + grow * p.ldc + gcol) = pack(o);
+              put(rw, pack(o), rowok, vo, so_c);
             }
           } else if constexpr (EPI == EPI_GELU_BWD) {
             float v[8], pr[8];
             unpack(raw, v);
-            unpack(auxbuf[i & 1][st], pr);
+            unpack(to_u4(auxbuf[i % AUXD][st]), pr);
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
-            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(v);
+            put(rc, pack(v), rowok, vo, so_c);
           } else if constexpr (EPI == EPI_SWIGLU_BWD) {
             float v[8], gt[8], up[8], dg[8], du[8];
             unpack(raw, v);
-            unpack(auxbuf[i & 1][st * AUXV], gt);
-            unpack(auxbuf[i & 1][st * AUXV + (AUXV - 1)], up);
+            unpack(to_u4(auxbuf[i % AUXD][st * AUXV]), gt);
+            unpack(to_u4(auxbuf[i % AUXD][st * AUXV + (AUXV - 1)]), up);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
               const float sg = sigmoid_f(gt[e]);
               dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
               du[e] = v[e] * gt[e] * sg;
             }
-            *reinterpret_cast<uint4*>(cg + grow * p.ldc + gcol) = pack(dg);
-            *reinterpret_cast<uint4*>(cg + grow * p.ldc + p.half + gcol) = pack(du);
+            put(rc, pack(dg), rowok, vo, so_c);
+            put(rc, pack(du), rowok, vo, so_c + p.half * 2);
           }
         }
       }
       asm volatile("" ::: "memory");  // keep the next 32 rows' scratch writes behind these reads
+      if constexpr (HAS_AUX) {
+        if (i + AUXD < TM) aux_fetch(i + AUXD, auxbuf[i % AUXD]);  // this slab's registers are free again
+      }
     }
     if (!has_next) break;
     pid = next;

@@ -205,3 +205,64 @@ def test_gemm_strided_output_and_operands():
     want = np.einsum("gmk,gnk->gmn", O.widen_bf16(d["a"]), O.widen_bf16(d["b"]))
     assert_close(got[:, :, :N], want, "gemm strided", tol=5e-3)
     assert np.all(got[:, :, N:] == 0.0)
+
+
+# ------------------------------------------------------------------------------------------ activation, exhaustive
+def test_gelu_and_derivative_on_every_bf16_input():
+    """The fused epilogues evaluate GELU and its derivative on the bf16-rounded pre-activation, so both are functions
+    of a 16-bit input: run all 65 280 finite bf16 values through the block (one rank, no sync, X = value in channel
+    0, A = e_0 rows so that P = value; dR' = e_0, dX' = 0, B row 0 = 1 so that dY = 1 and dP = gelu'(P)) and compare
+    element by element with the oracle's erf forms."""
+    torch = _torch()
+    h, fr = 8, 8
+    bits = np.arange(65536, dtype=np.uint32)
+    finite = ((bits >> 7) & 0xFF) != 0xFF
+    vals = bits[finite].astype(np.uint16)
+    n = vals.size
+    cfg = I.BlockConfig("act", I.KIND_MLP_GELU, I.NORM_LAYERNORM, h=h, T=1, p=0.0, batch=1, seq=n, ffn=fr)
+    one = int(I.f32_to_bf16_bits(np.array([1.0], dtype=np.float32))[0])
+    X = np.zeros((1, n, h), dtype=np.uint16)
+    X[0, :, 0] = vals
+    A = np.zeros((1, fr, h), dtype=np.uint16)
+    A[0, :, 0] = one
+    Bw = np.zeros((1, h, fr), dtype=np.uint16)
+    Bw[0, 0, :] = one
+    gamma = np.full(h, one, dtype=np.uint16)
+    beta = np.zeros(h, dtype=np.uint16)
+    R = np.zeros((1, n, h), dtype=np.uint16)
+    dXo = np.zeros((1, n, h), dtype=np.uint16)
+    dRo = np.zeros((1, n, h), dtype=np.uint16)
+    dRo[0, :, 0] = one
+    desc = B.make_desc(cfg)
+    w0, w1, g, b = B.to_device(A), B.to_device(Bw), B.to_device(gamma), B.to_device(beta)
+    x, r = B.to_device(X), B.to_device(R)
+    r_out, x_out = torch.empty_like(x), torch.empty_like(x)
+    ws = torch.zeros(B.workspace_bytes(desc), dtype=torch.uint8, device="cuda")
+    B.block_fwd(desc, [w0, w1, g, b], x, r, r_out, x_out, ws)
+    dx, dr = torch.empty_like(x), torch.empty_like(x)
+    dw0, dw1 = torch.empty_like(w0), torch.empty_like(w1)
+    dgamma = torch.empty(h, dtype=torch.float32, device="cuda")
+    dbeta = torch.empty(h, dtype=torch.float32, device="cuda")
+    B.block_bwd(desc, [w0, w1, g, b], x, r_out, ws, B.to_device(dXo), B.to_device(dRo), dx, dr, [dw0, dw1], dgamma, dbeta)
+    torch.cuda.synchronize()
+    L = B.workspace_layout(desc)
+
+    def ws_bits(off, nbytes):
+        return ws[off:off + nbytes].view(torch.int16).cpu().numpy().view(np.uint16).reshape(n, fr)
+
+    P, Y, dP = ws_bits(L.off_P, L.bytes_P), ws_bits(L.off_Y, L.bytes_Y), ws_bits(L.off_dP, L.bytes_dP)
+    v = bits_to_f64(vals)
+    # -0.0 * 1 + 0 * 0 ... accumulates to +0.0: compare values, not bits, for the zero inputs
+    assert np.array_equal(bits_to_f64(P[:, 0]), v), "pre-activation must be the input value itself"
+    for j in range(1, fr):
+        assert np.array_equal(P[:, j], P[:, 0]) and np.array_equal(Y[:, j], Y[:, 0]) and np.array_equal(dP[:, j], dP[:, 0])
+    y, want = bits_to_f64(Y[:, 0]), O.gelu(v)
+    # bf16 rounding of the result (2^-9 relative) + the evaluation's own error (2.5e-4 relative in the lower tail
+    # down to |x| = 5.5, below 1e-7 absolute beyond)
+    bound = 2.0 ** -8 * np.abs(want) + 1e-7
+    bad = np.abs(y - want) > bound
+    assert not bad.any(), "gelu: %d inputs off, worst at x = %r" % (bad.sum(), v[np.argmax(np.abs(y - want) - bound)])
+    dy, dwant = bits_to_f64(dP[:, 0]), O.gelu_grad(v)
+    dbound = 2.0 ** -8 * np.abs(dwant) + 3e-5
+    dbad = np.abs(dy - dwant) > dbound
+    assert not dbad.any(), "gelu': %d inputs off, worst at x = %r" % (dbad.sum(), v[np.argmax(np.abs(dy - dwant) - dbound)])
