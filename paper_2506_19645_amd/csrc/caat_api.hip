@@ -375,9 +375,8 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
   q.c = QKV; q.ldc = qw; q.stride_c = n * qw;
   q.G = (int)T; q.M = (int)n; q.N = (int)qw; q.K = (int)h;
   CAAT_STEP("gemm_nt_qkv", launch_gemm(q, 0, EPI_PLAIN, s))
-  CAAT_STEP("rope", launch_rope(QKV, T * n, d->seq, (int)qw, (int)(hpr + kvpr), d->head_dim, d->rope_base, d->kv_len, false, s))
-  CAAT_STEP("kv_append", launch_kv_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * d->batch, d->seq, (int)hpr, (int)kvpr,
-                                          d->kv_cap, d->kv_len, s))
+  CAAT_STEP("rope_kv_append", launch_rope_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * d->batch, d->seq, (int)hpr, (int)kvpr,
+                                                 d->head_dim, d->rope_base, d->kv_cap, d->kv_len, s))
   if (prefill) {
     CAAT_STEP("flash_attn_fwd", launch_flash_fwd(QKV, H, nullptr, T * d->batch, d->seq, (int)hpr, (int)kvpr, d->head_dim, s))
   } else {

@@ -78,6 +78,75 @@ hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int ld, int n_rot, 
   return hipGetLastError();
 }
 
+// RoPE on q and k in place and, in the same pass, the store of the rotated k and of v into the KV caches
+// [n_seq][kvpr][cap][128] at positions pos0 .. pos0+seq-1 (decode: seq = 1; prefill: the whole prompt).  One thread
+// rotates 8 pairs (j, j + d/2) of one q or k head of one token; the threads of a k head also write their two rotated
+// chunks to the key cache and copy the matching two chunks of v to the value cache, so a k / v head is covered by
+// its 8 threads.  d = 128 only (the cache rows are 128 wide).
+__global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* qkv, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
+                                                          long long rows, int seq, int hpr, int kvpr, float log2_base,
+                                                          long long cap, long long pos0) {
+  constexpr int d = 128, half = 64, groups_per_head = 8;
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long per_row = (long long)(hpr + kvpr) * groups_per_head;
+  if (idx >= rows * per_row) return;
+  const long long row = idx / per_row;                 // sequence * seq + token
+  const int rem = (int)(idx - row * per_row);
+  const int head = rem / groups_per_head, grp = rem - head * groups_per_head;
+  const long long sq = row / seq;
+  const long long t = row - sq * seq;
+  const float pos = (float)(pos0 + t);
+  const long long ld = (long long)(hpr + 2 * kvpr) * d;
+  bf16_t* p = qkv + row * ld + (long long)head * d + grp * 8;   // q heads first, k heads right after them
+  const uint4 lo = *reinterpret_cast<const uint4*>(p);
+  const uint4 hi = *reinterpret_cast<const uint4*>(p + half);
+  const bool is_k = head >= hpr;
+  uint4 vlo = make_uint4(0u, 0u, 0u, 0u), vhi = vlo;
+  if (is_k) {                                                   // the v head sits kvpr heads after its k head
+    vlo = *reinterpret_cast<const uint4*>(p + (long long)kvpr * d);
+    vhi = *reinterpret_cast<const uint4*>(p + (long long)kvpr * d + half);
+  }
+  const unsigned lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+  unsigned ol[4], oh[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    float x1[2] = {lo_bf(lw[w]), hi_bf(lw[w])}, x2[2] = {lo_bf(hw[w]), hi_bf(hw[w])}, y1[2], y2[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const int j = grp * 8 + w * 2 + e;
+      const float inv = exp2f(-2.0f * (float)j / (float)d * log2_base);
+      float sn, cs;
+      sincosf(pos * inv, &sn, &cs);
+      y1[e] = x1[e] * cs - x2[e] * sn;
+      y2[e] = x2[e] * cs + x1[e] * sn;
+    }
+    ol[w] = pack2bf(y1[0], y1[1]);
+    oh[w] = pack2bf(y2[0], y2[1]);
+  }
+  const uint4 rlo = make_uint4(ol[0], ol[1], ol[2], ol[3]), rhi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+  *reinterpret_cast<uint4*>(p) = rlo;
+  *reinterpret_cast<uint4*>(p + half) = rhi;
+  if (is_k) {
+    const long long dst = ((sq * kvpr + (head - hpr)) * cap + pos0 + t) * d + grp * 8;
+    *reinterpret_cast<uint4*>(kc + dst) = rlo;
+    *reinterpret_cast<uint4*>(kc + dst + half) = rhi;
+    *reinterpret_cast<uint4*>(vc + dst) = vlo;
+    *reinterpret_cast<uint4*>(vc + dst + half) = vhi;
+  }
+}
+
+hipError_t launch_rope_append(bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int seq, int hpr, int kvpr, int d,
+                              float base, long long cap, long long pos0, hipStream_t s) {
+  if (d != 128 || pos0 < 0 || pos0 + seq > cap) return hipErrorInvalidValue;
+  const long long work = n_seq * seq * (long long)(hpr + kvpr) * 8;
+  if (work == 0) return hipSuccess;
+  const long long blocks = (work + 255) / 256;
+  if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, kc, vc, n_seq * seq, seq, hpr, kvpr,
+                     log2f(base), cap, pos0);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------------------
 static constexpr int HD = 128;    // head dim
 static constexpr int BQ = 128;    // queries per workgroup (32 per wave)
@@ -686,29 +755,11 @@ hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* 
 
 
 // ---------------------------------------------------------------------------------------------------------
-// Decode: one new token per sequence.  (a) append the token's rotated k and its v to the caches at position
-// kv_len (the same kernel stores a whole prompt's k and v at positions 0 .. seq-1 after a prefill); (b) attention of the single query over kv_len + 1 cached keys.  Both are pure streaming (the KV read is
+// Decode: one new token per sequence, whose rotated k and v the RoPE kernel above has appended to the caches at
+// position kv_len: attention of the single query over kv_len + 1 cached keys.  Pure streaming (the KV read is
 // the layer's dominant HBM traffic), so there is no MFMA here: a workgroup owns one (rank, sequence, head);
 // 16 lanes own one key row (256 B), a wave takes 4 consecutive keys per step, the 4 waves 16; every 16-lane group
 // runs its own online softmax and the 16 partial results are merged through LDS in a fixed order.
-__global__ __launch_bounds__(256) void kv_append_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ kc,
-                                                        bf16_t* __restrict__ vc, long long n_seq, int seq, int hpr, int kvpr,
-                                                        long long cap, long long pos) {
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;   // ((sequence, token), key/value head, chunk of 8)
-  if (idx >= n_seq * seq * kvpr * 16) return;
-  const int c = (int)(idx & 15);
-  const long long rh = idx >> 4;                                      // row * kvpr + head
-  const long long row = rh / kvpr;                                    // sequence * seq + token
-  const int head = (int)(rh - row * kvpr);
-  const long long sq = row / seq;
-  const long long t = row - sq * seq;
-  const long long ld = (long long)(hpr + 2 * kvpr) * 128;
-  const bf16_t* src = qkv + row * ld + (long long)(hpr + head) * 128 + c * 8;   // k heads follow the q heads
-  const long long dst = ((sq * kvpr + head) * cap + pos + t) * 128 + c * 8;
-  *reinterpret_cast<uint4*>(kc + dst) = *reinterpret_cast<const uint4*>(src);
-  *reinterpret_cast<uint4*>(vc + dst) = *reinterpret_cast<const uint4*>(src + kvpr * 128);
-}
-
 __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kc,
                                                           const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, int hpr,
                                                           int kvpr, long long cap, int nkeys, float scale_log2) {
@@ -784,18 +835,6 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restri
     }
     out[sh * 128 + tid] = f2bf(num / den);
   }
-}
-
-// rotated k and v of `seq` consecutive tokens per sequence (rows of qkv) -> cache positions pos .. pos+seq-1 of
-// caches [n_seq][kvpr][cap][128]
-hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int seq, int hpr, int kvpr,
-                            long long cap, long long pos, hipStream_t s) {
-  const long long work = n_seq * seq * kvpr * 16;
-  if (work == 0) return hipSuccess;
-  if (pos < 0 || pos + seq > cap || (work + 255) / 256 > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, qkv, kc, vc, n_seq, seq, hpr,
-                     kvpr, cap, pos);
-  return hipGetLastError();
 }
 
 // out [n_seq, hpr*128] = softmax(q K^T / sqrt(d)) V over keys 0 .. nkeys-1 of caches [n_seq][kvpr][cap][128]

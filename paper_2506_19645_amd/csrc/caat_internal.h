@@ -142,13 +142,13 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
 // kv_heads < heads; heads, kv_heads are per rank); ld = (heads + 2*kv_heads)*128.
 hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int ld, int n_rot, int d, float base, long long pos0,
                        bool inverse, hipStream_t s);
+hipError_t launch_rope_append(bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int seq, int hpr, int kvpr, int d,
+                              float base, long long cap, long long pos0, hipStream_t s);   // RoPE + KV cache store in one pass
 size_t attn_stats_bytes(long long n_seq, int heads, int seq);   // fp32 [n_seq*heads][2][seq rounded up to 64]: lse, D
 hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, float* stats, long long n_seq, int seq, int heads, int kv_heads,
                             int d, hipStream_t s);
 hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, float* stats, bf16_t* dqkv,
                             long long n_seq, int seq, int heads, int kv_heads, int d, hipStream_t s);
-hipError_t launch_kv_append(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, long long n_seq, int seq, int hpr, int kvpr,
-                            long long cap, long long pos, hipStream_t s);
 hipError_t launch_decode_attn(const bf16_t* qkv, const bf16_t* kc, const bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
                               int kvpr, int d, long long cap, long long nkeys, hipStream_t s);
 

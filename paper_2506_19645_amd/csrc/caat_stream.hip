@@ -295,16 +295,20 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
   for (long long row = r0 + wave; row < r1; row += 4) {
     const float mu = LN ? mean[row] : 0.0f;
     const float rs = rstd[row];
-    uint4 wx[VPL], wd[VPL];
+    // all three inputs of the row are requested together: fetching the residual gradient only after the row sums
+    // put a second trip to memory into every row
+    uint4 wx[VPL], wd[VPL], wr[VPL];
     float c1 = 0.0f, c2 = 0.0f;
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       const int vi = v * 64 + lane;
       wx[v] = make_uint4(0u, 0u, 0u, 0u);
       wd[v] = wx[v];
+      wr[v] = wx[v];
       if (vi < nvec) {
         wx[v] = *reinterpret_cast<const uint4*>(x + row * h + vi * 8);
         wd[v] = *reinterpret_cast<const uint4*>(dy + row * h + vi * 8);
+        if (dres) wr[v] = *reinterpret_cast<const uint4*>(dres + row * h + vi * 8);
       }
     }
 #pragma unroll
@@ -333,12 +337,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
         unpack8(wx[v], fx);
         unpack8(wd[v], fd);
         unpack8(gam[v], g);
-        if (dres) {
-          unpack8(*reinterpret_cast<const uint4*>(dres + row * h + vi * 8), r);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) r[e] = 0.0f;
-        }
+        unpack8(wr[v], r);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float xh = (fx[e] - mu) * rs;
