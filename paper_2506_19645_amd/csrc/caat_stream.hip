@@ -374,9 +374,10 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
 
 // Wide rows (h > 2048): the per-lane column accumulators of the kernel above would need 64+ registers, so here a whole
 // workgroup owns one row at a time: thread t holds the 16-byte vectors v*256 + t (v < VPL) of the row, the two row
-// sums go wave -> LDS -> all waves (slot chosen by row parity, one barrier per row), and the next row's x and dy are
-// already in flight while the current row is reduced and written.  A thread's dgamma / dbeta columns are its own, so
-// the partial row is written without any cross-wave combination.  Workgroup b walks rows [b*rpb, (b+1)*rpb).
+// sums go wave -> LDS -> all waves (slot chosen by row parity, one barrier per row), and the next row's x, dy and
+// residual gradient are already in flight while the current row is reduced and written.  A thread's dgamma / dbeta
+// columns are its own, so the partial row is written without any cross-wave combination.  Workgroup b walks rows
+// [b*rpb, (b+1)*rpb).
 template <int VPL, bool LN>
 __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ dres,
                                                             const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
@@ -404,16 +405,18 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
   const long long r0 = (long long)blockIdx.x * rows_per_block;
   long long r1 = r0 + rows_per_block;
   if (r1 > rows) r1 = rows;
-  uint4 nx[VPL], nd[VPL];
+  uint4 nx[VPL], nd[VPL], nr[VPL];
   auto fetch = [&](long long row) {
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
       const int vi = v * 256 + tid;
       nx[v] = make_uint4(0u, 0u, 0u, 0u);
       nd[v] = nx[v];
+      nr[v] = nx[v];
       if (vi < nvec && row < r1) {
         nx[v] = *reinterpret_cast<const uint4*>(x + row * h + vi * 8);
         nd[v] = *reinterpret_cast<const uint4*>(dy + row * h + vi * 8);
+        if (dres) nr[v] = *reinterpret_cast<const uint4*>(dres + row * h + vi * 8);
       }
     }
   };
@@ -427,9 +430,7 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
     for (int v = 0; v < VPL; ++v) {
       wx[v] = nx[v];
       wd[v] = nd[v];
-      const int vi = v * 256 + tid;
-      wr[v] = make_uint4(0u, 0u, 0u, 0u);
-      if (dres && vi < nvec) wr[v] = *reinterpret_cast<const uint4*>(dres + row * h + vi * 8);
+      wr[v] = nr[v];
     }
     fetch(row + 1);
     float c1 = 0.0f, c2 = 0.0f;
