@@ -56,6 +56,31 @@ def sync_bytes(name: str, cfg, hs: int) -> float:
     return 0.0
 
 
+def gemm_power_check(torch, B, bench, cfg, iters=40):
+    """The dominant GEMM family's shape class (TN, M = N = h, K = tokens, all T ranks) timed stand-alone twice: on the
+    step's own N(0,1) operands and on all-zero operands.  The instruction stream is identical; on zeros the
+    matrix units toggle almost nothing, so the gap shows how far the chip's power management (not the kernel's
+    schedule) holds the clock down on real data."""
+    T, n, h = cfg.T, cfg.tokens, cfg.h
+    c = torch.empty(T, h, h, dtype=torch.bfloat16, device="cuda")
+    out = {}
+    for name, a, b in (("random", bench.x, bench.dxo), ("zeros", torch.zeros_like(bench.x), torch.zeros_like(bench.dxo))):
+        run = lambda: B.gemm_bf16(a, b, c, B.GEMM_TN, T, h, h, n, h, h, h, n * h, n * h, h * h)
+        for _ in range(15):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        out[name + "_operands_TFLOP/s"] = round(2.0 * T * h * h * n / ms / 1e9, 1)
+    out["shape"] = "TN G=%d M=N=%d K=%d, plain epilogue, stand-alone" % (T, h, n)
+    return out
+
+
 class MlpBench:
     def __init__(self, cfg, seed=0):
         import numpy as np
@@ -504,6 +529,8 @@ def main():
                 "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": PMC_TRAFFIC_BYTES.get((args.config, args.p), {}).get(dom),
                 "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": dom_flops}
+    if not args.no_sweep:
+        roofline["power_check"] = gemm_power_check(torch, B, bench, cfg)
     kernels = {}
     for name, v in prof.items():
         e = {"avg_ms": round(v["avg_ms"], 5), "launches_per_step": v["launches_per_step"]}
