@@ -51,8 +51,8 @@ def sync_bytes(name: str, cfg, hs: int) -> float:
         return 2.0 * T * n * hs * 2
     if name == "norm_fwd":
         return 2.0 * T * n * h * 2 + T * n * 8
-    if name == "norm_bwd":               # read dy, dres, x; write g and scaled g
-        return 5.0 * T * n * h * 2 + T * n * 8
+    if name == "norm_bwd":               # read dy, dres, x; write g and scaled g (whose shared channels the reduce writes)
+        return 5.0 * T * n * h * 2 - (T * n * hs * 2 if hs % 8 == 0 else 0) + T * n * 8
     return 0.0
 
 
@@ -354,7 +354,7 @@ def bench_attention_kinds(args, cfg, base):
             fl.update({"flash_attn_bwd": 5.0 * cfg.batch * s * s * h, "gemm_nn_dgrad": 4.0 * n * h * h,
                        "gemm_tn_wgrad": 4.0 * n * h * h})
             by.update({"rope_bwd": 2.0 * T * n * 2 * hd * 2, "partial_sync_bwd": 2.0 * T * n * cfg.hs * 2,
-                       "norm_bwd": 5.0 * T * n * h * 2})
+                       "norm_bwd": 5.0 * T * n * h * 2 - (T * n * cfg.hs * 2 if cfg.hs % 8 == 0 else 0)})
             work += 5.0 * cfg.batch * s * s * h + 16.0 * n * h * h
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
         workload = "%s attention sub-block %s: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
@@ -564,6 +564,24 @@ def main():
                     e[nm + "_ms"] = 0.0
             sweep.append(e)
 
+    # time to sync against p: least-squares line through the four sweep points (slope = time per unit of p, i.e. the
+    # part that scales with the synced volume; intercept = what a launch costs when nothing is synced)
+    sync_fit = None
+    if len(sweep) >= 3:
+        ps = [e["p"] for e in sweep]
+        fit = {}
+        for key in ("partial_sync_fwd_ms", "partial_sync_bwd_ms", "standalone_sync_ms"):
+            ts = [e[key] for e in sweep]
+            pm, tm = sum(ps) / len(ps), sum(ts) / len(ts)
+            sxx = sum((a - pm) ** 2 for a in ps)
+            slope = sum((a - pm) * (b - tm) for a, b in zip(ps, ts)) / sxx
+            icpt = tm - slope * pm
+            ss_res = sum((b - (icpt + slope * a)) ** 2 for a, b in zip(ps, ts))
+            ss_tot = sum((b - tm) ** 2 for b in ts)
+            fit[key] = {"slope_ms_per_unit_p": round(slope, 5), "intercept_ms": round(icpt, 5),
+                        "r2": round(1.0 - ss_res / ss_tot, 4) if ss_tot > 0 else None}
+        sync_fit = fit
+
     out = {
         "metric": "partial-sync TP block TFLOP/s (% MFMA peak) + sync GB/s (% HBM) vs p, 1 GPU",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -575,7 +593,7 @@ def main():
                                                             cfg.hs, cfg.tokens),
                    "flops_per_step": step_flops, "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,
                    "wall_ms_per_step": wall_ms},
-        "roofline": roofline, "kernels": kernels, "p_sweep": sweep,
+        "roofline": roofline, "kernels": kernels, "p_sweep": sweep, "sync_time_vs_p_fit": sync_fit,
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, bench.host, args.cpu_sample_tokens)

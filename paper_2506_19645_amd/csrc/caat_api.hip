@@ -292,8 +292,12 @@ int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
 #define CAAT_STEP(name, call) { ProfScope ps(s, name); e = (call); } if (e != hipSuccess) return CAAT_EHIP;
   CAAT_STEP("norm_bwd", launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
                                         mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
-                                        d->private_scale, ws + L.off_scratch, s))
-  CAAT_STEP("partial_sync_bwd", launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s))
+                                        d->private_scale, ws + L.off_scratch, s, true))
+  // when no 8-channel vector straddles hs, the norm backward leaves the shared channels of dZt to the reduce, which
+  // reads them from dr (the same values) instead of reading them back from dZt: one write of T*n*hs values less
+  CAAT_STEP("partial_sync_bwd", d->hs % 8 == 0
+                                    ? launch_partial_sync_shared_from((const bf16_t*)dr, dZt, (int)T, n, (int)h, d->hs, s)
+                                    : launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s))
   // dH_m = dZt_m Wo_m (NN): [n,h] x [h,hd]
   std::memset(&q, 0, sizeof(q));
   q.a = dZt; q.lda = h; q.stride_a = n * h;
@@ -626,13 +630,16 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
     ProfScope ps(s, "norm_bwd");
     e = launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
                                  mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
-                                 d->private_scale, ws + L.off_scratch, s);
+                                 d->private_scale, ws + L.off_scratch, s, true);
   }
   if (e != hipSuccess) return CAAT_EHIP;
-  // a8: the same partial channel-reduce on the gradients, in place on the shared channels, fp32 accumulation
+  // a8: the same partial channel-reduce on the gradients, shared channels only, fp32 accumulation.  When no 8-channel
+  // vector straddles hs, the norm backward has left dZt's shared channels unwritten and the reduce reads them from dr
+  // (the same values) and writes the sums into dZt; otherwise it runs in place on dZt.
   {
     ProfScope ps(s, "partial_sync_bwd");
-    e = launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s);
+    e = d->hs % 8 == 0 ? launch_partial_sync_shared_from((const bf16_t*)dr, dZt, (int)T, n, (int)h, d->hs, s)
+                       : launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
 

@@ -135,7 +135,10 @@ size_t norm_bwd_workspace_bytes(int T, long long tokens, int h);
 hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
                            const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,
                            float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
-                           void* workspace, hipStream_t s);
+                           void* workspace, hipStream_t s, bool skip_shared_scaled = false);
+// shared channels of dst = sum over ranks of src's; dst's other channels are not touched (hs % 8 == 0)
+hipError_t launch_partial_sync_shared_from(const bf16_t* src, bf16_t* dst, int T, long long tokens, int h, int hs,
+                                           hipStream_t s);
 
 // ---------------------------------------------------------------- attention core
 // Projections of one rank-row: [heads*128 q | kv_heads*128 k | kv_heads*128 v] (grouped-query attention when

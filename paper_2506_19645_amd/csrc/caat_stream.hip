@@ -145,6 +145,14 @@ hipError_t launch_partial_sync_shared(bf16_t* io, const bf16_t* resid, int T, lo
   return sync_any(io, resid, io, T, tokens, h, hs, 1.0f, 1, s);
 }
 
+// The reduce of the backward pass, shared channels only, from one buffer into another: dst[m][:, l < hs] = sum over
+// ranks of src[m'][:, l]; nothing else of dst is touched.  hs must be a multiple of 8 (no vector straddles it).
+hipError_t launch_partial_sync_shared_from(const bf16_t* src, bf16_t* dst, int T, long long tokens, int h, int hs,
+                                           hipStream_t s) {
+  if (hs % 8 != 0) return hipErrorInvalidValue;
+  return sync_any(src, nullptr, dst, T, tokens, h, hs, 1.0f, 1, s);
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Norm forward: one wavefront per row, the row stays in registers (VPL 16-byte vectors per lane), statistics
 // by wave reduction in fp32 (two passes over registers: mean, then centred second moment).
@@ -269,7 +277,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
                                                        bf16_t* __restrict__ g_out, bf16_t* __restrict__ g_scaled,
                                                        float* __restrict__ partial, long long rows, int h, int hs,
-                                                       float scale, long long rows_per_block) {
+                                                       float scale, long long rows_per_block, int skip_shared) {
   __shared__ float red[4][64 * 8];  // one vector column group at a time
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -345,7 +353,8 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
           o[e] = r[e] + rs * (LN ? (dxh - c1 - xh * c2) : (dxh - xh * c2));
         }
         *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
-        if (g_scaled) {
+        // skip_shared: the reduce that follows writes the shared channels of g_scaled itself (from g_out)
+        if (g_scaled && !(skip_shared && vi * 8 + 8 <= hs)) {
 #pragma unroll
           for (int e = 0; e < 8; ++e)
             if (vi * 8 + e >= hs) o[e] *= scale;
@@ -384,7 +393,7 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
                                                             const float* __restrict__ mean, const float* __restrict__ rstd,
                                                             bf16_t* __restrict__ g_out, bf16_t* __restrict__ g_scaled,
                                                             float* __restrict__ partial, long long rows, int h, int hs,
-                                                            float scale, long long rows_per_block) {
+                                                            float scale, long long rows_per_block, int skip_shared) {
   __shared__ float red[2][2][4];  // [row parity][c1 | c2][wave]
   const int tid = threadIdx.x, wave = tid >> 6;
   const int nvec = h >> 3;
@@ -475,7 +484,8 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
           o[e] = r[e] + rs * (LN ? (dxh - c1 - xh * c2) : (dxh - xh * c2));
         }
         *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
-        if (g_scaled) {
+        // skip_shared: the reduce that follows writes the shared channels of g_scaled itself (from g_out)
+        if (g_scaled && !(skip_shared && vi * 8 + 8 <= hs)) {
 #pragma unroll
           for (int e = 0; e < 8; ++e)
             if (vi * 8 + e >= hs) o[e] *= scale;
@@ -552,13 +562,13 @@ template <int VPL>
 static hipError_t norm_bwd_wide_dispatch(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
                                          const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled,
                                          float* partial, int norm, long long rows, int h, int hs, float scale,
-                                         long long nb, long long rpb, hipStream_t s) {
+                                         long long nb, long long rpb, int skip_shared, hipStream_t s) {
   if (norm == 0)
     hipLaunchKernelGGL((norm_bwd_wide_kernel<VPL, true>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
-                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb, skip_shared);
   else
     hipLaunchKernelGGL((norm_bwd_wide_kernel<VPL, false>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
-                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb, skip_shared);
   return hipGetLastError();
 }
 
@@ -566,21 +576,22 @@ template <int VPL>
 static hipError_t norm_bwd_dispatch(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
                                     const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled,
                                     float* partial, int norm, long long rows, int h, int hs, float scale, long long nb,
-                                    long long rpb, hipStream_t s) {
+                                    long long rpb, int skip_shared, hipStream_t s) {
   if (norm == 0)
     hipLaunchKernelGGL((norm_bwd_kernel<VPL, true>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
-                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb, skip_shared);
   else
     hipLaunchKernelGGL((norm_bwd_kernel<VPL, false>), dim3((unsigned)nb), dim3(256), 0, s, dy, dres, x, gamma, mean,
-                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb);
+                       rstd, g_out, g_scaled, partial, rows, h, hs, scale, rpb, skip_shared);
   return hipGetLastError();
 }
 
 hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
                            const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,
                            float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
-                           void* workspace, hipStream_t s) {
+                           void* workspace, hipStream_t s, bool skip_shared_scaled) {
   const long long rows = (long long)T * tokens;
+  const int skip_shared = (skip_shared_scaled && g_scaled != nullptr && hs % 8 == 0) ? 1 : 0;
   if (rows == 0) return hipSuccess;
   long long nb = norm_bwd_blocks(rows, h);
   const long long rpb = (rows + nb - 1) / nb;
@@ -590,12 +601,12 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
   hipError_t e;
   if (h > NORM_BWD_WIDE_H) {
     const int vw = (h / 8 + 255) / 256;
-    if (vw <= 2) e = norm_bwd_wide_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
-    else if (vw <= 4) e = norm_bwd_wide_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+    if (vw <= 2) e = norm_bwd_wide_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
+    else if (vw <= 4) e = norm_bwd_wide_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
     else return hipErrorInvalidValue;
-  } else if (vpl <= 1) e = norm_bwd_dispatch<1>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
-  else if (vpl <= 2) e = norm_bwd_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
-  else if (vpl <= 4) e = norm_bwd_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, s);
+  } else if (vpl <= 1) e = norm_bwd_dispatch<1>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
+  else if (vpl <= 2) e = norm_bwd_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
+  else if (vpl <= 4) e = norm_bwd_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 31) / 32)), dim3(256), 0, s, partial, (int)nb,
