@@ -109,3 +109,18 @@ def test_config7_llama70b_gqa_prefill_layer_sampled_sequence():
     check_prefill(one, d, got, ref, rows=rows)
     assert_close(bits_to_f64(got["Kc_bits"][:, sq:sq + 1, :, :cfg.seq]), ref["K"], "K cache")
     assert_close(bits_to_f64(got["Vc_bits"][:, sq:sq + 1, :, :cfg.seq]), ref["V"], "V cache")
+
+
+@pytest.mark.parametrize("swi,p", [(False, 0.3), (True, 0.301)])
+def test_ragged_shapes_on_the_big_persistent_tiles(swi, p):
+    """Dimensions just past multiples of 256 (8264 tokens, h = 2056, 2056 columns per rank), large enough that the
+    GEMMs take the 256 x 256 persistent tiles with several tiles per workgroup: every fused epilogue then meets edge
+    tiles (rows and columns that do not exist) and, with hs = 616 (a multiple of 8) resp. 618 (not), both routes of
+    the backward reduce.  Forward + backward against the whole oracle."""
+    cfg = I.BlockConfig("ragged-big", I.KIND_MLP_SWIGLU if swi else I.KIND_MLP_GELU,
+                        I.NORM_RMSNORM if swi else I.NORM_LAYERNORM, h=2056, T=4, p=p, batch=1, seq=8264, ffn=4 * 2056)
+    assert cfg.hs == (618 if swi else 616)
+    d = I.make_inputs(cfg, seed=3)
+    got = run_mlp_block(cfg, d)
+    w, fwd, g = oracle_mlp_block(cfg, d)
+    check_mlp_block(cfg, d, got, w, fwd, g)
