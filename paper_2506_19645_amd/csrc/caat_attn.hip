@@ -789,8 +789,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restri
     for (int u = 0; u < UN; ++u) {
       const int key = key0 + 16 * u;
       const unsigned off = key < nkeys ? (unsigned)key * 256u + c * 16 : OOB_OFF;
-      kv[u] = __builtin_amdgcn_raw_buffer_load_b128(rk, (int)off, 0, 0);
-      vv[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)off, 0, 0);
+      // read-once stream: the non-temporal hint (cache policy bit 1) measured 7.1 TB/s against 6.2 TB/s for plain
+      // loads on a 2 GiB read with this access pattern
+      kv[u] = __builtin_amdgcn_raw_buffer_load_b128(rk, (int)off, 0, 2);
+      vv[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)off, 0, 2);
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {

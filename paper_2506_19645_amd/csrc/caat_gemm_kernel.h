@@ -97,12 +97,13 @@ struct KContigOperand {
     }
   }
   // koff: element offset of the K-group the stage belongs to (0 unless the contraction runs over several buffers)
+  template <bool STREAM = false>
   __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
     const i32x4_t rs = make_rsrc(origin + koff + k0);
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
       const bool kin = (k0 + kc[RPI == 16 ? 0 : it] * 8) < K;
-      dma16(rs, kin ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
+      dma16<STREAM>(rs, kin ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
     }
   }
   // fragment for MFMA rows row0 .. row0+31, k sub-step ks (16 wide): lane (row0 + lane%32, k = 16 ks + 8 (lane/32) ..+7)
@@ -145,12 +146,13 @@ struct RowContigOperand {
       voff[it] = (r >= 0) ? (unsigned)(((long long)k * ld_ + r) * 2) : OOB;
     }
   }
+  template <bool STREAM = false>
   __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
     const i32x4_t rs = make_rsrc(origin + koff + (long long)k0 * ld);
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
       const int k = (it * NWAVES + wave) * KPI + klocal;
-      dma16(rs, (k0 + k < K) ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
+      dma16<STREAM>(rs, (k0 + k < K) ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
     }
   }
   // same fragment as KContigOperand::frag, gathered by two transpose reads of 4 k each
@@ -281,6 +283,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
   const int kcat = KCAT ? (p.kcat > 1 ? p.kcat : 1) : 1;
   const int nk = ((K + BKS - 1) / BKS) * kcat;
   constexpr int A_CHUNKS = BM * (BKS / 8);
+  // decode-sized tiles (at most 64 token rows per rank: one tile row) read every weight row exactly once
+  constexpr bool B_STREAM = (BM <= 64);
   auto stage_a = [&](int s) -> uint4* { return smem + (s % NSTAGE) * CFG::STAGE_CHUNKS; };
   // stages are issued in order; past the end every offset is out of range: zeros land in a slot nobody reads
   auto issue_stage = [&](int s) {
@@ -288,7 +292,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     if constexpr (KCAT) {
       const int kk = ikg < kcat ? K : 0;
       la.issue(ik0, kk, As, (long long)ikg * p.kstride_a);
-      lb.issue(ik0, kk, As + A_CHUNKS, (long long)ikg * p.kstride_b);
+      lb.template issue<B_STREAM>(ik0, kk, As + A_CHUNKS, (long long)ikg * p.kstride_b);
       ik0 += BKS;
       if (ik0 >= K) {
         ik0 = 0;
@@ -296,7 +300,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
       }
     } else {
       la.issue(s * BKS, K, As, 0);
-      lb.issue(s * BKS, K, As + A_CHUNKS, 0);
+      lb.template issue<B_STREAM>(s * BKS, K, As + A_CHUNKS, 0);
     }
   };
 

@@ -26,6 +26,9 @@ __device__ __forceinline__ float wave_sum(float v) {
 // reads every input of its group before it writes, out may alias y.  `ncg` = number of 8-channel groups per
 // row that are processed: ceil(hs/8) when the private channels need no work, h/8 otherwise.
 // TT > 0: compile-time rank count (loads fully unrolled and in flight together); TT == 0: any T.
+// The partial sums were written by the kernel just before and mostly still sit in the caches: plain loads.  The
+// residual is older data read once: non-temporal loads (with the hint on both, small problems whose partials are
+// cache-resident lost 7 %, large ones gained 14 %).
 template <int TT, bool HAS_RES>
 __global__ __launch_bounds__(256) void partial_sync_kernel(const bf16_t* y, const bf16_t* resid,
                                                            bf16_t* out, int T_, long long n, int h, int hs,
@@ -63,7 +66,7 @@ __global__ __launch_bounds__(256) void partial_sync_kernel(const bf16_t* y, cons
 #pragma unroll 4
       for (int m = 0; m < T; ++m) {
         float r[8], o[8];
-        unpack8(*reinterpret_cast<const uint4*>(resid + m * plane + off), r);
+        unpack8(ld_stream(resid + m * plane + off), r);
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = sum[e] + r[e];
         *reinterpret_cast<uint4*>(out + m * plane + off) = pack8(o);
@@ -90,7 +93,7 @@ __global__ __launch_bounds__(256) void partial_sync_kernel(const bf16_t* y, cons
     float f[8], r[8], o[8];
     unpack8(*reinterpret_cast<const uint4*>(y + m * plane + off), f);  // rank m's own values (not yet overwritten)
     if constexpr (HAS_RES) {
-      unpack8(*reinterpret_cast<const uint4*>(resid + m * plane + off), r);
+      unpack8(ld_stream(resid + m * plane + off), r);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) r[e] = 0.0f;
@@ -158,7 +161,7 @@ hipError_t launch_partial_sync_shared_from(const bf16_t* src, bf16_t* dst, int T
 // by wave reduction in fp32 (two passes over registers: mean, then centred second moment).
 // Split source (xs != null): the first hs_split channels of every rank's row are stored once, xs [tokens, hs_split]
 // (row = rank*tokens + token reads token's shared row), and x holds only the private channels [rows, h - hs_split].
-template <int VPL, bool LN>
+template <int VPL, bool LN, bool STREAM>
 __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
                                                        const bf16_t* __restrict__ beta, bf16_t* __restrict__ y,
                                                        float* __restrict__ mean, float* __restrict__ rstd,
@@ -182,7 +185,10 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
     for (int v = 0; v < VPL; ++v) {
       const int vi = v * 64 + lane;
       uint4 w = make_uint4(0u, 0u, 0u, 0u);
-      if (vi < nvec) w = *reinterpret_cast<const uint4*>((xsr != nullptr && vi * 8 < hs_split ? xsr : xr) + vi * 8);
+      if (vi < nvec) {
+        const bf16_t* src = (xsr != nullptr && vi * 8 < hs_split ? xsr : xr) + vi * 8;
+        w = STREAM ? ld_stream(src) : *reinterpret_cast<const uint4*>(src);
+      }
       unpack8(w, f[v]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) s += LN ? f[v][e] : f[v][e] * f[v][e];
@@ -234,12 +240,17 @@ static hipError_t norm_fwd_dispatch(const bf16_t* x, const bf16_t* gamma, const 
   long long blocks = (rows + 3) / 4;
   if (blocks > 65536) blocks = 65536;
   if (blocks == 0) return hipSuccess;
-  if (norm == 0)
-    hipLaunchKernelGGL((norm_fwd_kernel<VPL, true>), dim3((unsigned)blocks), dim3(256), 0, s, x, gamma, beta, y, mean,
-                       rstd, rows, h, eps, xs, hs_split, tokens);
-  else
-    hipLaunchKernelGGL((norm_fwd_kernel<VPL, false>), dim3((unsigned)blocks), dim3(256), 0, s, x, gamma, beta, y, mean,
-                       rstd, rows, h, eps, xs, hs_split, tokens);
+  // An input of about the size of the 256 MB memory-side cache or more cannot still be there from the kernel that wrote it: it is
+  // read with the non-temporal hint (h = 4096, T = 8, 4096 tokens: -15 %); a smaller one mostly is, and the hint cost
+  // 4 % there.
+  const bool stream = (double)rows * h * 2.0 > 192.0 * 1048576.0;
+#define CAAT_NORM_FWD(LN_, ST_) hipLaunchKernelGGL((norm_fwd_kernel<VPL, LN_, ST_>), dim3((unsigned)blocks), dim3(256), 0, s, x, gamma, beta, y, mean, rstd, rows, h, eps, xs, hs_split, tokens)
+  if (norm == 0) {
+    if (stream) CAAT_NORM_FWD(true, true); else CAAT_NORM_FWD(true, false);
+  } else {
+    if (stream) CAAT_NORM_FWD(false, true); else CAAT_NORM_FWD(false, false);
+  }
+#undef CAAT_NORM_FWD
   return hipGetLastError();
 }
 
@@ -304,7 +315,8 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
     const float mu = LN ? mean[row] : 0.0f;
     const float rs = rstd[row];
     // all three inputs of the row are requested together: fetching the residual gradient only after the row sums
-    // put a second trip to memory into every row
+    // put a second trip to memory into every row.  They are read once: non-temporal loads (-10 % at h = 2048; in the
+    // wide-row kernel below the hint gained 3 % and cost the reduce kernel that follows more than that)
     uint4 wx[VPL], wd[VPL], wr[VPL];
     float c1 = 0.0f, c2 = 0.0f;
 #pragma unroll
@@ -314,9 +326,9 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
       wd[v] = wx[v];
       wr[v] = wx[v];
       if (vi < nvec) {
-        wx[v] = *reinterpret_cast<const uint4*>(x + row * h + vi * 8);
-        wd[v] = *reinterpret_cast<const uint4*>(dy + row * h + vi * 8);
-        if (dres) wr[v] = *reinterpret_cast<const uint4*>(dres + row * h + vi * 8);
+        wx[v] = ld_stream(x + row * h + vi * 8);
+        wd[v] = ld_stream(dy + row * h + vi * 8);
+        if (dres) wr[v] = ld_stream(dres + row * h + vi * 8);
       }
     }
 #pragma unroll
