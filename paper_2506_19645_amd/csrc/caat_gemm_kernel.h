@@ -467,8 +467,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
 #pragma unroll
       for (int st = 0; st < STEPS; ++st) {
         const unsigned vo = erow[st] < rl ? voff_aux[st] : OOB;
-        buf[st * AUXV] = __builtin_amdgcn_raw_buffer_load_b128(raux, vo, so, 0);
-        if constexpr (AUXV == 2) buf[st * AUXV + 1] = __builtin_amdgcn_raw_buffer_load_b128(raux, vo, so + p.half * 2, 0);
+        // read once by this tile only: non-temporal hint (cache policy bit 1)
+        buf[st * AUXV] = __builtin_amdgcn_raw_buffer_load_b128(raux, vo, so, 2);
+        if constexpr (AUXV == 2) buf[st * AUXV + 1] = __builtin_amdgcn_raw_buffer_load_b128(raux, vo, so + p.half * 2, 2);
       }
     };
     auto to_u4 = [](const u32x4_t& v) -> uint4 { return make_uint4(v[0], v[1], v[2], v[3]); };
@@ -481,6 +482,13 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     auto put = [&](const rsrc_t& r, const uint4& v, bool ok, unsigned vo, int so) {
       const u32x4_t w = {v.x, v.y, v.z, v.w};
       __builtin_amdgcn_raw_buffer_store_b128(w, r, ok ? vo + (unsigned)so : OOB, 0, 0);
+      asm volatile("s_nop 1" ::: "memory");
+    };
+    // the same for a tensor that nothing reads before the backward pass (saved pre-activations): non-temporal hint,
+    // so that it does not push the activation the next GEMM is about to read out of the caches
+    auto put_late = [&](const rsrc_t& r, const uint4& v, bool ok, unsigned vo, int so) {
+      const u32x4_t w = {v.x, v.y, v.z, v.w};
+      __builtin_amdgcn_raw_buffer_store_b128(w, r, ok ? vo + (unsigned)so : OOB, 0, 2);
       asm volatile("s_nop 1" ::: "memory");
     };
     if constexpr (HAS_AUX) {
@@ -518,8 +526,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
           unpack(uw, up);
 #pragma unroll
           for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
-          put(rc, gw, rowok, vo, so_c);
-          put(rc, uw, rowok, vo, so_c + p.half * 2);
+          put_late(rc, gw, rowok, vo, so_c);
+          put_late(rc, uw, rowok, vo, so_c + p.half * 2);
           put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
         } else {
           const int c = (st * 64 + lane) - erow[st] * CHW;
@@ -532,7 +540,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
             unpack(raw, v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
-            put(rc, raw, rowok, vo, so_c);
+            put_late(rc, raw, rowok, vo, so_c);
             put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
           } else if constexpr (EPI == EPI_ROWPAR) {
             // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual); columns < hs are
