@@ -309,7 +309,7 @@ int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   std::memset(&q, 0, sizeof(q));
   q.a = dZt; q.lda = h; q.stride_a = n * h;
   q.b = H; q.ldb = hd; q.stride_b = n * hd;
-  q.c = (bf16_t*)dwo; q.ldc = hd; q.stride_c = h * hd;
+  q.c = (bf16_t*)dwo; q.ldc = hd; q.stride_c = h * hd; q.late_c = 1;   // gradients leave the block: not read again here
   q.G = (int)T; q.M = (int)h; q.N = (int)hd; q.K = (int)n;
   CAAT_STEP("gemm_tn_wgrad", launch_gemm(q, 2, EPI_PLAIN, s))
   CAAT_STEP("flash_attn_bwd", launch_flash_bwd(QKV, H, dH, stats, dQKV, T * d->batch, d->seq, hpr, kvpr, d->head_dim, s))
@@ -318,14 +318,14 @@ int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   std::memset(&q, 0, sizeof(q));
   q.a = dQKV; q.lda = qw; q.stride_a = n * qw;
   q.b = (const bf16_t*)wqkv; q.ldb = h; q.stride_b = qw * h;
-  q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h;
+  q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h; q.late_c = 1;
   q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)qw;
   CAAT_STEP("gemm_nn_dgrad", launch_gemm(q, 1, EPI_PLAIN, s))
   // dWqkv_m [qw,h] = dqkv_m^T X_m (TN)
   std::memset(&q, 0, sizeof(q));
   q.a = dQKV; q.lda = qw; q.stride_a = n * qw;
   q.b = (const bf16_t*)x; q.ldb = h; q.stride_b = n * h;
-  q.c = (bf16_t*)dwqkv; q.ldc = h; q.stride_c = qw * h;
+  q.c = (bf16_t*)dwqkv; q.ldc = h; q.stride_c = qw * h; q.late_c = 1;
   q.G = (int)T; q.M = (int)qw; q.N = (int)h; q.K = (int)n;
   CAAT_STEP("gemm_tn_wgrad", launch_gemm(q, 2, EPI_PLAIN, s))
 #undef CAAT_STEP
@@ -661,7 +661,7 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   std::memset(&q, 0, sizeof(q));
   q.a = dZt; q.lda = h; q.stride_a = n * h;
   q.b = Y; q.ldb = fr; q.stride_b = n * fr;
-  q.c = (bf16_t*)dw1; q.ldc = fr; q.stride_c = h * fr;
+  q.c = (bf16_t*)dw1; q.ldc = fr; q.stride_c = h * fr; q.late_c = 1;   // gradients leave the block: not read again here
   q.G = (int)T; q.M = (int)h; q.N = (int)fr; q.K = (int)n;
   {
     ProfScope ps(s, "gemm_tn_wgrad");
@@ -673,7 +673,7 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   std::memset(&q, 0, sizeof(q));
   q.a = dP; q.lda = pw; q.stride_a = n * pw;
   q.b = (const bf16_t*)w0; q.ldb = h; q.stride_b = pw * h;
-  q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h;
+  q.c = (bf16_t*)dx; q.ldc = h; q.stride_c = n * h; q.late_c = 1;
   q.G = (int)T; q.M = (int)n; q.N = (int)h; q.K = (int)pw;
   {
     ProfScope ps(s, "gemm_nn_dgrad");
@@ -685,7 +685,7 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   std::memset(&q, 0, sizeof(q));
   q.a = dP; q.lda = pw; q.stride_a = n * pw;
   q.b = (const bf16_t*)x; q.ldb = h; q.stride_b = n * h;
-  q.c = (bf16_t*)dw0; q.ldc = h; q.stride_c = pw * h;
+  q.c = (bf16_t*)dw0; q.ldc = h; q.stride_c = pw * h; q.late_c = 1;
   q.G = (int)T; q.M = (int)pw; q.N = (int)h; q.K = (int)n;
   {
     ProfScope ps(s, "gemm_tn_wgrad");

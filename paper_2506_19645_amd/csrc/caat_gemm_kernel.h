@@ -533,7 +533,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
           const int c = (st * 64 + lane) - erow[st] * CHW;
           const uint4 raw = staged(erow[st], c);
           if constexpr (EPI == EPI_PLAIN) {
-            put(rc, raw, rowok, vo, so_c);
+            if (p.late_c) put_late(rc, raw, rowok, vo, so_c);
+            else put(rc, raw, rowok, vo, so_c);
           } else if constexpr (EPI == EPI_GELU_FWD) {
             // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
             float v[8], y[8];

@@ -133,6 +133,7 @@ struct GemmParams {
   int kcat;            // > 1: the contraction runs over kcat operand pairs, K each, kstride_* elements apart
   long long kstride_a, kstride_b;
   int bcast;           // EPI_SHARED_BCAST: number of output copies (ranks)
+  int late_c;          // EPI_PLAIN: c is not read again soon (weight / input gradients): store it with the non-temporal hint
 };
 
 // layout: 0 NT, 1 NN, 2 TN (see caat_gemm_layout).  Returns hipError_t of the launch.
