@@ -128,10 +128,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(bf16_t* qkv, bf16_t* _
   *reinterpret_cast<uint4*>(p + half) = rhi;
   if (is_k) {
     const long long dst = ((sq * kvpr + (head - hpr)) * cap + pos0 + t) * d + grp * 8;
-    *reinterpret_cast<uint4*>(kc + dst) = rlo;
-    *reinterpret_cast<uint4*>(kc + dst + half) = rhi;
-    *reinterpret_cast<uint4*>(vc + dst) = vlo;
-    *reinterpret_cast<uint4*>(vc + dst + half) = vhi;
+    // the caches are read by later decode steps, not by this layer's attention (which reads qkv): non-temporal stores
+    st_stream(kc + dst, rlo);
+    st_stream(kc + dst + half, rhi);
+    st_stream(vc + dst, vlo);
+    st_stream(vc + dst + half, vhi);
   }
 }
 

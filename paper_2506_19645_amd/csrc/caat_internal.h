@@ -101,6 +101,12 @@ __device__ __forceinline__ uint4 ld_stream(const void* p) {
   return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
+// 16-byte store of data that nothing reads again soon
+__device__ __forceinline__ void st_stream(void* p, const uint4& v) {
+  const u32x4_t w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(p));
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");

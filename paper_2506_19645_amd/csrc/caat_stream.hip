@@ -227,7 +227,8 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const bf16_t* __restrict_
         if constexpr (LN) unpack8(*reinterpret_cast<const uint4*>(beta + vi * 8), b);
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = LN ? ((f[v][e] - mu) * rs * g[e] + b[e]) : (f[v][e] * rs * g[e]);
-        *reinterpret_cast<uint4*>(yr + vi * 8) = pack8(o);
+        if (STREAM) st_stream(yr + vi * 8, pack8(o));   // an output this large is out of the caches before it is read
+        else *reinterpret_cast<uint4*>(yr + vi * 8) = pack8(o);
       }
     }
   }
