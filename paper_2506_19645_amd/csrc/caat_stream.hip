@@ -28,11 +28,12 @@ __device__ __forceinline__ float wave_sum(float v) {
 // TT > 0: compile-time rank count (loads fully unrolled and in flight together); TT == 0: any T.
 // The partial sums were written by the kernel just before and mostly still sit in the caches: plain loads.  The
 // residual is older data read once: non-temporal loads (with the hint on both, small problems whose partials are
-// cache-resident lost 7 %, large ones gained 14 %).
+// cache-resident lost 7 %, large ones gained 14 %).  `big`: the shared part of one tensor is too large to stay in the
+// caches between kernels (more than 96 MiB): its partial sums are streamed too, and so are the results.
 template <int TT, bool HAS_RES>
 __global__ __launch_bounds__(256) void partial_sync_kernel(const bf16_t* y, const bf16_t* resid,
                                                            bf16_t* out, int T_, long long n, int h, int hs,
-                                                           float scale, int ncg, int shared_only) {
+                                                           float scale, int ncg, int shared_only, int big) {
   const int T = TT > 0 ? TT : T_;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= n * (long long)ncg) return;
@@ -46,7 +47,8 @@ __global__ __launch_bounds__(256) void partial_sync_kernel(const bf16_t* y, cons
     if constexpr (TT > 0) {
       uint4 v[TT > 0 ? TT : 1];
 #pragma unroll
-      for (int m = 0; m < TT; ++m) v[m] = *reinterpret_cast<const uint4*>(y + m * plane + off);
+      for (int m = 0; m < TT; ++m)
+        v[m] = big ? ld_stream(y + m * plane + off) : *reinterpret_cast<const uint4*>(y + m * plane + off);
 #pragma unroll
       for (int m = 0; m < TT; ++m) {
         float f[8];
@@ -69,12 +71,16 @@ __global__ __launch_bounds__(256) void partial_sync_kernel(const bf16_t* y, cons
         unpack8(ld_stream(resid + m * plane + off), r);
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = sum[e] + r[e];
-        *reinterpret_cast<uint4*>(out + m * plane + off) = pack8(o);
+        if (big) st_stream(out + m * plane + off, pack8(o));
+        else *reinterpret_cast<uint4*>(out + m * plane + off) = pack8(o);
       }
     } else {
       const uint4 o = pack8(sum);  // one rounding, the same bits on every rank
 #pragma unroll 4
-      for (int m = 0; m < T; ++m) *reinterpret_cast<uint4*>(out + m * plane + off) = o;
+      for (int m = 0; m < T; ++m) {
+        if (big) st_stream(out + m * plane + off, o);
+        else *reinterpret_cast<uint4*>(out + m * plane + off) = o;
+      }
     }
     return;
   }
@@ -113,12 +119,13 @@ static hipError_t sync_dispatch(const bf16_t* y, const bf16_t* resid, bf16_t* ou
   const long long work = n * (long long)ncg;
   const long long blocks = (work + 255) / 256;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  const int big = ((double)T * (double)n * (double)hs * 2.0 > 96.0 * 1048576.0) ? 1 : 0;
   if (resid)
     hipLaunchKernelGGL((partial_sync_kernel<TT, true>), dim3((unsigned)blocks), dim3(256), 0, s, y, resid, out, T, n,
-                       h, hs, scale, ncg, shared_only);
+                       h, hs, scale, ncg, shared_only, big);
   else
     hipLaunchKernelGGL((partial_sync_kernel<TT, false>), dim3((unsigned)blocks), dim3(256), 0, s, y, resid, out, T, n,
-                       h, hs, scale, ncg, shared_only);
+                       h, hs, scale, ncg, shared_only, big);
   return hipGetLastError();
 }
 
