@@ -383,7 +383,10 @@ def bench_attention_kinds(args, cfg, base):
         fl = {}
         by = {"decode_attn": kv_bytes, "gemm_nt_qkv": 2.0 * T * 3 * hd * h, "gemm_nt_swiglu_fwd": 2.0 * T * 2 * fr * h,
               "gemm_nt_rowpar": 2.0 * T * (h * hd + h * fr) / 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
-              "norm_fwd": 2.0 * T * n * h * 2}
+              "norm_fwd": 2.0 * T * n * h * 2,
+              # reduce + residual + RMSNorm in one launch: T partials and T residual slices and the private columns read,
+              # R' shared columns and the whole normalised copy written
+              "partial_sync_norm_fwd": (3.0 * T * n * cfg.hs + T * n * (h - cfg.hs) + T * n * h) * 2}
         work, unit, peak = kv_bytes + w_bytes, "GB/s", HBM_PEAK_GBS
         workload = "%s decode layer: h=%d ffn=%d heads=%d d=%d batch=%d kv_len=%d T=%d p=%g (hs=%d)" % (
             cfg.name, h, cfg.ffn, cfg.n_heads, cfg.head_dim, cfg.batch, cfg.kv_len, T, cfg.p, cfg.hs)

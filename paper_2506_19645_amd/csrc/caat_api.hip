@@ -141,7 +141,7 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
 // index runs over all T ranks' inputs and weight rows, so the sum over ranks is taken in the accumulator and no partial
 // sum ever reaches memory.
 int rowpar_pcr(const caat_desc* d, const bf16_t* a, long long kdim, const bf16_t* w, const bf16_t* resid, bf16_t* out,
-               hipStream_t s) {
+               hipStream_t s, bool leave_reduce_to_caller = false) {
   const long long T = d->T, n = d->tokens, h = d->h;
   const int hs = d->hs;
   hipError_t e = hipSuccess;
@@ -196,7 +196,7 @@ int rowpar_pcr(const caat_desc* d, const bf16_t* a, long long kdim, const bf16_t
     e = launch_gemm(q, 0, EPI_ROWPAR, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
-  if (hs > 0) {
+  if (hs > 0 && !leave_reduce_to_caller) {
     ProfScope ps(s, "partial_sync_fwd");
     e = launch_partial_sync_shared(out, resid, (int)T, n, (int)h, hs, s);
     if (e != hipSuccess) return CAAT_EHIP;
@@ -387,12 +387,21 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
     CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)kvpr,
                                                 d->head_dim, d->kv_cap, d->kv_len + 1, s))
   }
+  // decode-sized batches: the reduce after o_proj and the RMSNorm in front of the MLP run as one launch (both are
+  // start-up latency at this size); everything else keeps the two kernels
+  const bool fuse_mid = !prefill && n <= 64 && d->hs > 0 && d->hs % 8 == 0 && (T == 2 || T == 4 || T == 8) && h <= 8192 &&
+                        !d->reduce_in_gemm && dedup_hs(d) == 0;
   {
-    const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, R1, s);
+    const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, R1, s, fuse_mid);
     if (st != CAAT_OK) return st;
   }
-  CAAT_STEP("norm_fwd", launch_norm_fwd(R1, (const bf16_t*)g_mlp, nullptr, X2, nullptr, rstd, CAAT_RMSNORM, (int)T, n, (int)h,
-                                        d->eps, s, dedup_hs(d)))
+  if (fuse_mid) {
+    CAAT_STEP("partial_sync_norm_fwd", launch_sync_rmsnorm(R1, (const bf16_t*)r, (const bf16_t*)g_mlp, X2, rstd, (int)T, n, (int)h,
+                                                           d->hs, d->eps, s))
+  } else {
+    CAAT_STEP("norm_fwd", launch_norm_fwd(R1, (const bf16_t*)g_mlp, nullptr, X2, nullptr, rstd, CAAT_RMSNORM, (int)T, n, (int)h,
+                                          d->eps, s, dedup_hs(d)))
+  }
   std::memset(&q, 0, sizeof(q));
   q.a = X2; q.lda = h; q.stride_a = n * h;
   q.b = (const bf16_t*)wgu; q.ldb = h; q.stride_b = 2 * fr * h;

@@ -153,6 +153,10 @@ hipError_t launch_partial_sync_shared(bf16_t* io, const bf16_t* resid, int T, lo
 hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
                            float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s,
                            int dedup_hs = 0);
+// reduce on the shared channels + residual + RMSNorm in one launch for decode-sized batches (T in {2,4,8}, hs % 8 == 0,
+// h <= 8192); hipErrorInvalidValue if the shape is not taken
+hipError_t launch_sync_rmsnorm(bf16_t* io, const bf16_t* resid, const bf16_t* gamma, bf16_t* xout, float* rstd, int T,
+                               long long tokens, int h, int hs, float eps, hipStream_t s);
 size_t norm_bwd_workspace_bytes(int T, long long tokens, int h);
 hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
                            const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,

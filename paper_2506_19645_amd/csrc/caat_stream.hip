@@ -284,6 +284,122 @@ hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* b
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// Decode-sized batches (a few dozen tokens): the reduce and the RMSNorm that follows it are two launches whose
+// duration is start-up latency, not traffic.  Here one workgroup owns one token of ALL ranks: it sums the T
+// partial vectors of the shared channels in ascending rank order, adds each rank's residual, rounds once and
+// stores R' (exactly what partial_sync_kernel does), keeps every rank's row (rounded values, packed) in registers,
+// and then normalises each rank's row with its own statistics (what norm_fwd_kernel does on R').  hs % 8 == 0,
+// h <= 8192, RMSNorm only.
+template <int TT>
+__global__ __launch_bounds__(256) void sync_rmsnorm_kernel(bf16_t* io, const bf16_t* __restrict__ resid,
+                                                           const bf16_t* __restrict__ gamma, bf16_t* __restrict__ xout,
+                                                           float* __restrict__ rstd, long long n, int h, int hs,
+                                                           float eps) {
+  constexpr int NG = 4;                                  // 16-byte column groups per thread: h <= 8192
+  __shared__ float red[4][TT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long long i = blockIdx.x;                        // token
+  const long long plane = n * (long long)h;
+  const int nvec = h >> 3;
+  uint4 val[NG][TT];
+  float ss[TT];
+#pragma unroll
+  for (int m = 0; m < TT; ++m) ss[m] = 0.0f;
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int vi = g * 256 + tid;
+    if (vi < nvec) {
+      const int col = vi * 8;
+      const long long off = i * h + col;
+      if (col < hs) {                                     // shared channels (hs is a multiple of 8)
+        uint4 pv[TT], rv[TT];
+#pragma unroll
+        for (int m = 0; m < TT; ++m) {
+          pv[m] = *reinterpret_cast<const uint4*>(io + m * plane + off);
+          rv[m] = *reinterpret_cast<const uint4*>(resid + m * plane + off);
+        }
+        float sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int m = 0; m < TT; ++m) {
+          float f[8];
+          unpack8(pv[m], f);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) sum[e] += f[e];
+        }
+#pragma unroll
+        for (int m = 0; m < TT; ++m) {
+          float r[8], o[8];
+          unpack8(rv[m], r);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = sum[e] + r[e];
+          val[g][m] = pack8(o);
+          *reinterpret_cast<uint4*>(io + m * plane + off) = val[g][m];
+        }
+      } else {                                            // private channels: final since the GEMM epilogue
+#pragma unroll
+        for (int m = 0; m < TT; ++m) val[g][m] = *reinterpret_cast<const uint4*>(io + m * plane + off);
+      }
+#pragma unroll
+      for (int m = 0; m < TT; ++m) {
+        float f[8];
+        unpack8(val[g][m], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss[m] += f[e] * f[e];
+      }
+    } else {
+#pragma unroll
+      for (int m = 0; m < TT; ++m) val[g][m] = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < TT; ++m) {
+    const float w = wave_sum(ss[m]);
+    if (lane == 0) red[wave][m] = w;
+  }
+  __syncthreads();
+  float rs[TT];
+  const float inv_h = 1.0f / (float)h;
+#pragma unroll
+  for (int m = 0; m < TT; ++m) {
+    const float tot = ((red[0][m] + red[1][m]) + red[2][m]) + red[3][m];
+    rs[m] = rsqrtf(tot * inv_h + eps);
+  }
+  if (tid < TT) rstd[tid * n + i] = rsqrtf((((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid]) * inv_h + eps);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int vi = g * 256 + tid;
+    if (vi < nvec) {
+      float gm[8];
+      unpack8(*reinterpret_cast<const uint4*>(gamma + vi * 8), gm);
+      const long long off = i * h + vi * 8;
+#pragma unroll
+      for (int m = 0; m < TT; ++m) {
+        float f[8], o[8];
+        unpack8(val[g][m], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = f[e] * rs[m] * gm[e];
+        *reinterpret_cast<uint4*>(xout + m * plane + off) = pack8(o);
+      }
+    }
+  }
+}
+
+// io [T,n,h]: partial sums on the shared channels, final values on the private ones -> R' in place; xout = RMSNorm(R');
+// returns hipErrorInvalidValue for shapes the fused kernel does not take (the caller then runs the two kernels)
+hipError_t launch_sync_rmsnorm(bf16_t* io, const bf16_t* resid, const bf16_t* gamma, bf16_t* xout, float* rstd, int T,
+                               long long tokens, int h, int hs, float eps, hipStream_t s) {
+  if (hs <= 0 || hs % 8 != 0 || hs > h || h % 8 != 0 || h > 8192 || tokens <= 0 || tokens > 0x7FFFFFFFLL)
+    return hipErrorInvalidValue;
+  switch (T) {
+    case 2: hipLaunchKernelGGL((sync_rmsnorm_kernel<2>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, xout, rstd, tokens, h, hs, eps); break;
+    case 4: hipLaunchKernelGGL((sync_rmsnorm_kernel<4>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, xout, rstd, tokens, h, hs, eps); break;
+    case 8: hipLaunchKernelGGL((sync_rmsnorm_kernel<8>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, xout, rstd, tokens, h, hs, eps); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // Norm backward, placed before the reduce (Fig. 2b): g = dres + NormBwd(dy).  Each wave walks a contiguous
 // range of rows and keeps its lanes' columns of dgamma / dbeta in registers; a workgroup combines its 4 waves
 // through LDS and writes one partial row [2][h] to the workspace; a second kernel sums the partials in order.
