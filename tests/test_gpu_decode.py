@@ -30,6 +30,7 @@ def run_decode(cfg, d, reduce_in_gemm=False):
     return {"R2": bits_to_f64(B.to_host_bits(r_out)), "R2_bits": B.to_host_bits(r_out),
             "X1": ws_bf16(L.off_X1, L.bytes_X1, (T, b, h)), "H": ws_bf16(L.off_H, L.bytes_H, (T, b, hd)),
             "R1": ws_bf16(L.off_R1, L.bytes_R1, (T, b, h)), "X2": ws_bf16(L.off_X2, L.bytes_X2, (T, b, h)),
+            "R1_bits": ws[L.off_R1:L.off_R1 + L.bytes_R1].view(torch.int16).cpu().numpy().view(np.uint16).reshape(T, b, h),
             "Kc_bits": B.to_host_bits(kc), "Vc_bits": B.to_host_bits(vc)}
 
 
@@ -45,6 +46,8 @@ def _cfg(T, b, heads, ffn, L, p, kv_heads=0):
     (1, 2, 2, 256, 129, 0.0, 0),
     (2, 5, 8, 2 * 256, 200, 0.5, 2),     # grouped-query attention: 4 query heads per key / value head
     (2, 3, 8, 2 * 256, 70, 0.5, 4),      # two groups per rank
+    (2, 4, 4, 2 * 256, 50, 0.3, 0),      # hs = 153: not a multiple of 8, so the reduce and the norm stay two kernels
+    (8, 6, 8, 8 * 128, 90, 0.5, 0),      # tensor-parallel degree 8 through the one-launch reduce + norm
 ])
 def test_decode_layer(T, b, heads, ffn, L, p, kv_heads):
     cfg = _cfg(T, b, heads, ffn, L, p, kv_heads)
@@ -68,3 +71,4 @@ def test_decode_layer(T, b, heads, ffn, L, p, kv_heads):
     if hs > 0 and T > 1 and np.array_equal(d["R"][0, :, :hs], d["R"][-1, :, :hs]):
         for m in range(1, T):
             assert np.array_equal(got["R2_bits"][m, :, :hs], got["R2_bits"][0, :, :hs])
+            assert np.array_equal(got["R1_bits"][m, :, :hs], got["R1_bits"][0, :, :hs])
