@@ -484,10 +484,37 @@ def main():
     ap.add_argument("--dedup-shared", action="store_true",
                     help="C6 / C7, implies --reduce-in-gemm: the residual stream stores its shared channels once "
                          "instead of T copies (no p sweep: the layout is tied to p)")
+    ap.add_argument("--probe-hbm", action="store_true",
+                    help="no workload: time the library's HBM streaming probe (read / copy, access pattern, "
+                         "non-temporal hint) on a 2 GiB buffer and print one JSON line")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph and time its replays (launch-bound small configs)")
     args = ap.parse_args()
     MlpBench.use_graph = args.graph
+    if args.probe_hbm:
+        import torch
+        from paper_2506_19645_amd import binding as B
+        nbytes = 1 << 31
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        names = ["read_chunk_per_workgroup", "read_chunk_per_workgroup_nontemporal", "read_grid_stride",
+                 "copy_chunk_per_workgroup", "copy_chunk_per_workgroup_nontemporal"]
+        res = {}
+        for mode, name in enumerate(names):
+            for _ in range(3):
+                B.hbm_probe(src, dst, nbytes, mode)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                B.hbm_probe(src, dst, nbytes, mode)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            moved = nbytes * (2 if mode >= 3 else 1)
+            res[name] = {"ms": round(ms, 4), "GB/s": round(moved / ms / 1e6, 1), "frac_hbm_peak": round(moved / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        print(json.dumps({"probe": "hbm streaming, 2 GiB buffer, 16-byte accesses", "results": res}))
+        return
     if args.dedup_shared:
         if args.config not in ("C6", "C7"):
             ap.error("--dedup-shared is for the prefill layer configs C6 / C7")

@@ -230,6 +230,21 @@ int caat_profile_reset(void);
 int caat_profile_count(void);
 int caat_profile_get(int index, const char** name, float* ms);
 
+/*
+ * HBM streaming probe (a measuring tool, not part of the method): enqueues one kernel that reads `bytes` bytes of
+ * the device buffer `src` (16-byte aligned, bytes % 16 == 0) and, for the copy modes, writes them to `dst`.
+ *   mode 0: read, every workgroup walks its own contiguous piece, plain loads
+ *   mode 1: the same with the non-temporal hint on the loads
+ *   mode 2: read, the whole grid sweeps one window (grid-stride), plain loads
+ *   mode 3: copy src -> dst, contiguous piece per workgroup, plain loads and stores
+ *   mode 4: the same with the non-temporal hint on loads and stores
+ * dst may be NULL for the read modes (a result is only stored if the data hash to one particular value, which
+ * keeps the loads alive; pass a buffer of at least 16 bytes to be safe).  The caller times it with events on
+ * `hip_stream`; bench.py --probe-hbm does.  This is where the cache-policy choices of the streaming kernels
+ * (which accesses carry the hint) were measured.
+ */
+int caat_hbm_probe(const void* src, void* dst, size_t bytes, int mode, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

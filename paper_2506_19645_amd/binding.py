@@ -44,7 +44,7 @@ class caat_ws_layout(C.Structure):
 EXPORTS = ["caat_shared_channels", "caat_status_string", "caat_workspace_bytes", "caat_workspace_layout",
            "caat_partial_sync", "caat_norm_fwd", "caat_norm_bwd_workspace_bytes", "caat_norm_bwd", "caat_gemm_bf16",
            "caat_block_fwd", "caat_block_bwd", "caat_profile_enable", "caat_profile_reset", "caat_profile_count",
-           "caat_profile_get"]
+           "caat_profile_get", "caat_hbm_probe"]
 
 _lib = None
 
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
         L.caat_profile_count.restype = i
         L.caat_profile_get.argtypes = [i, C.POINTER(C.c_char_p), C.POINTER(f)]
         L.caat_profile_get.restype = i
+        L.caat_hbm_probe.argtypes = [vp, vp, C.c_size_t, i, vp]
+        L.caat_hbm_probe.restype = i
         _lib = L
     return _lib
 
@@ -230,6 +232,10 @@ def block_bwd(desc: caat_desc, weights: Sequence, x, r_out, workspace, dx_out, d
     if check:
         _check(st, "caat_block_bwd")
     return st
+
+
+def hbm_probe(src, dst, nbytes: int, mode: int, stream=None) -> None:
+    _check(lib().caat_hbm_probe(_ptr(src), _ptr(dst), nbytes, mode, _stream(stream)), "caat_hbm_probe")
 
 
 def profile_enable(on: bool) -> None:

@@ -453,6 +453,13 @@ int caat_workspace_layout(const caat_desc* d, caat_ws_layout* out) {
   return layout_of(d, out);
 }
 
+int caat_hbm_probe(const void* src, void* dst, size_t bytes, int mode, void* hip_stream) {
+  if (!src || mode < 0 || mode > 4 || (mode >= 3 && !dst)) return CAAT_EINVAL;
+  if (bytes % 16 != 0) return CAAT_ESHAPE;
+  if (misaligned(src) || (dst && misaligned(dst))) return CAAT_EALIGN;
+  return hip_status(launch_hbm_probe(src, dst, bytes, mode, (hipStream_t)hip_stream));
+}
+
 int caat_profile_enable(int on) {
   g_prof_on = on != 0;
   return CAAT_OK;

@@ -166,6 +166,8 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
 hipError_t launch_partial_sync_shared_from(const bf16_t* src, bf16_t* dst, int T, long long tokens, int h, int hs,
                                            hipStream_t s);
 
+hipError_t launch_hbm_probe(const void* src, void* dst, size_t bytes, int mode, hipStream_t s);   // measuring tool
+
 // ---------------------------------------------------------------- attention core
 // Projections of one rank-row: [heads*128 q | kv_heads*128 k | kv_heads*128 v] (grouped-query attention when
 // kv_heads < heads; heads, kv_heads are per rank); ld = (heads + 2*kv_heads)*128.

@@ -133,3 +133,21 @@ def test_profile_records_every_launch():
     assert all(ms > 0.0 for _, ms in rec)
     B.profile_reset()
     assert B.profile_records() == []
+
+
+def test_hbm_probe_modes():
+    """The measuring tool: every mode runs, the copy modes copy, bad arguments are refused before any launch."""
+    import torch
+    n = (1 << 20) + 4096                      # not a multiple of the per-workgroup piece
+    src = torch.arange(n, dtype=torch.int64, device="cuda").to(torch.uint8)
+    for mode in (0, 1, 2):
+        B.hbm_probe(src, torch.zeros(16, dtype=torch.uint8, device="cuda"), n, mode)
+    for mode in (3, 4):
+        dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        B.hbm_probe(src, dst, n, mode)
+        torch.cuda.synchronize()
+        assert torch.equal(dst, src), mode
+    L = B.lib()
+    assert L.caat_hbm_probe(B._ptr(src), None, n, 3, None) == 1        # copy without a destination
+    assert L.caat_hbm_probe(B._ptr(src), None, n, 7, None) == 1        # unknown mode
+    assert L.caat_hbm_probe(B._ptr(src), None, n - 8, 0, None) == 2    # size not a multiple of 16
