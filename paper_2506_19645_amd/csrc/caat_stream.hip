@@ -488,7 +488,9 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
           const float dxh = fd[e] * g[e];
           o[e] = r[e] + rs * (LN ? (dxh - c1 - xh * c2) : (dxh - xh * c2));
         }
-        *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
+        // the private channels of g_out are not read again by the backward pass (the reduce reads the shared ones)
+        if (skip_shared && vi * 8 >= hs) st_stream(g_out + row * h + vi * 8, pack8(o));
+        else *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
         // skip_shared: the reduce that follows writes the shared channels of g_scaled itself (from g_out)
         if (g_scaled && !(skip_shared && vi * 8 + 8 <= hs)) {
 #pragma unroll
@@ -619,7 +621,9 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
           const float dxh = fd[e] * g[e];
           o[e] = r[e] + rs * (LN ? (dxh - c1 - xh * c2) : (dxh - xh * c2));
         }
-        *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
+        // the private channels of g_out are not read again by the backward pass (the reduce reads the shared ones)
+        if (skip_shared && vi * 8 >= hs) st_stream(g_out + row * h + vi * 8, pack8(o));
+        else *reinterpret_cast<uint4*>(g_out + row * h + vi * 8) = pack8(o);
         // skip_shared: the reduce that follows writes the shared channels of g_scaled itself (from g_out)
         if (g_scaled && !(skip_shared && vi * 8 + 8 <= hs)) {
 #pragma unroll
