@@ -177,6 +177,24 @@ struct OperandSel { typedef KContigOperand<ROWS, NWAVES, BKS_> type; };
 template <int ROWS, int NWAVES, int BKS_>
 struct OperandSel<true, ROWS, NWAVES, BKS_> { typedef RowContigOperand<ROWS, NWAVES, BKS_> type; };
 
+// Which weight row (relative to the tile's first row n0) lies in row rr of the B tile in LDS, or -1 for none.  Plain
+// epilogues: rows in order, as many as the tile covers (bn_out) and the matrix has.  SwiGLU: each wave's WTN tile rows
+// are 32 gate rows, then the 32 up rows of the same output columns (`half` rows further down), and so on, so that an
+// accumulator pair of a wave holds gate and up of the same 32 outputs.
+template <class CFG, bool SWI>
+__device__ __forceinline__ long long b_tile_row(int rr, int n0, int bn_out, int N, int half) {
+  if constexpr (SWI) {
+    const int w = rr / CFG::WTN, rw = rr - w * CFG::WTN;
+    const int j = rw >> 5, c = rw & 31;
+    const int col = (w * (CFG::TN / 2) + (j >> 1)) * 32 + c;  // output column relative to n0
+    if (col >= bn_out || n0 + col >= half) return -1;
+    return (long long)col + ((j & 1) ? half : 0);
+  } else {
+    const int nrem = (N - n0) < bn_out ? (N - n0) : bn_out;
+    return rr < nrem ? (long long)rr : -1;
+  }
+}
+
 template <int TM, int TN>
 struct Frags {
   bf16x8_t a[TM], b[TN];
@@ -219,8 +237,13 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
   // ---- tiles of this workgroup.  Tile ids are cut into 8 contiguous ranges, one per XCD (workgroup b runs on XCD
   // b % 8), so that the workgroups sharing an L2 work on neighbouring tiles; inside a range the workgroups of the XCD
   // take tiles round-robin.  A tile id maps to (rank g, tile row, tile column) in a grouped (8 tile rows) order.
+  // Decode-sized tiles may be told to cover fewer output columns than the MFMA tile is wide (bn_out, a multiple of
+  // 8): the kernel is then a weight stream, and what counts is that every compute unit gets the same number of weight
+  // rows.  The rows beyond bn_out are not fetched (out-of-range copy offsets) and their columns are not stored.
+  constexpr bool NARROW = (BM <= 64);
+  const int bn_out = (NARROW && p.bn_out > 0) ? p.bn_out : BN_OUT;
   const int tiles_m = (p.M + BM - 1) / BM;
-  const int tiles_n = (p.N + BN_OUT - 1) / BN_OUT;
+  const int tiles_n = (p.N + bn_out - 1) / bn_out;
   const int tiles = tiles_m * tiles_n;
   const int total = tiles * p.G;
   int pid, pid_end, pid_step;
@@ -253,25 +276,19 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     const int gsize = (tiles_m - first) < GROUP ? (tiles_m - first) : GROUP;
     const int r = t - grp * width;
     m0 = (first + r % gsize) * BM;
-    n0 = (r / gsize) * BN_OUT;
+    n0 = (r / gsize) * bn_out;
     const bf16_t* ag = p.a + (long long)g * p.stride_a;
     const bf16_t* bg = p.b + (long long)g * p.stride_b;
     const int mrem = p.M - m0;
     la.init(AT ? ag + m0 : ag + (long long)m0 * p.lda, p.lda,
             [=](int rr) -> long long { return (rr < mrem) ? (long long)rr : -1; });
-    if constexpr (SWI) {
-      const int half = p.half, n0c = n0;
-      lb.init(bg + (long long)n0 * p.ldb, p.ldb, [=](int rr) -> long long {
-        const int w = rr / WTN, rw = rr - w * WTN;
-        const int j = rw >> 5, c = rw & 31;
-        const int col = (w * (TN / 2) + (j >> 1)) * 32 + c;  // output column relative to n0
-        if (n0c + col >= half) return -1;
-        return (long long)col + ((j & 1) ? half : 0);
-      });
+    if constexpr (!BT) {
+      const int n0c = n0, bnc = bn_out, Nc = p.N, halfc = p.half;
+      auto rowmap = [=](int rr) -> long long { return b_tile_row<CFG, SWI>(rr, n0c, bnc, Nc, halfc); };
+      lb.init(bg + (long long)n0 * p.ldb, p.ldb, rowmap);
     } else {
       const int nrem = p.N - n0;
-      lb.init(BT ? bg + n0 : bg + (long long)n0 * p.ldb, p.ldb,
-              [=](int rr) -> long long { return (rr < nrem) ? (long long)rr : -1; });
+      lb.init(bg + n0, p.ldb, [=](int rr) -> long long { return (rr < nrem) ? (long long)rr : -1; });
     }
   };
 
@@ -447,7 +464,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
       erow[st] = idx / OCW;
       const int oc = idx - erow[st] * OCW;
       ecol[st] = wcol0 + oc * 8;
-      const bool colok = ecol[st] < ncols;
+      const bool colok = ecol[st] < ncols && ecol[st] - en0 < bn_out;
       voff_c[st] = colok ? (unsigned)((erow[st] * p.ldc + ecol[st]) * 2) : OOB;
       voff_c2[st] = colok ? (unsigned)((erow[st] * p.ldc2 + ecol[st]) * 2) : OOB;
       // the residual is only needed where the vector has a private channel (Eq. A3)
@@ -604,8 +621,10 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
 template <class CFG, bool AT, bool BT, int EPI>
 static hipError_t launch_one(const GemmParams& p, hipStream_t s) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU_FWD) ? CFG::BN / 2 : CFG::BN;
+  if (p.bn_out < 0 || p.bn_out > BN_OUT || (p.bn_out & 7)) return hipErrorInvalidValue;
+  const long long bn_out = (CFG::BM <= 64 && p.bn_out > 0) ? p.bn_out : BN_OUT;  // as in the kernel
   const long long tiles_m = (p.M + CFG::BM - 1) / CFG::BM;
-  const long long tiles_n = (p.N + BN_OUT - 1) / BN_OUT;
+  const long long tiles_n = (p.N + bn_out - 1) / bn_out;
   const long long total = tiles_m * tiles_n * p.G;
   if (total <= 0 || total > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   long long blocks = total;

@@ -140,6 +140,7 @@ struct GemmParams {
   long long kstride_a, kstride_b;
   int bcast;           // EPI_SHARED_BCAST: number of output copies (ranks)
   int late_c;          // EPI_PLAIN: c is not read again soon (weight / input gradients): store it with the non-temporal hint
+  int bn_out;          // decode-sized tiles: output columns one tile covers (0 = the tile's full width); set by launch_gemm
 };
 
 // layout: 0 NT, 1 NN, 2 TN (see caat_gemm_layout).  Returns hipError_t of the launch.
