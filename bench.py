@@ -23,7 +23,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per launch read off the rocprofv3 --pmc runs of this same command (FETCH_SIZE x 2.00 calibration factor
 # + WRITE_SIZE x 1.00), summarised in profiles/mlp_block_c2_fwd_bwd.md; valid for the default workload only
-PMC_TRAFFIC_BYTES = {("C2", 0.5): {"gemm_tn_wgrad": 403e6 + 34e6, "gemm_nt_gelu_fwd": 404e6 + 268e6,
+PMC_TRAFFIC_BYTES = {("C2", 0.5): {"gemm_tn_wgrad": 403e6 + 34e6, "gemm_nt_gelu_fwd": 408e6 + 268e6,
                                    "gemm_nt_rowpar": 471e6 + 134e6, "gemm_nn_gelu_bwd": 537e6 + 134e6,
                                    "gemm_nn_dgrad": 403e6 + 134e6}}
 
