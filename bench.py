@@ -21,11 +21,20 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
-# HBM bytes per launch read off the rocprofv3 --pmc runs of this same command (FETCH_SIZE x 2.00 calibration factor
-# + WRITE_SIZE x 1.00), summarised in profiles/mlp_block_c2_fwd_bwd.md; valid for the default workload only
+# HBM bytes per launch read off the rocprofv3 --pmc runs of these same commands (FETCH_SIZE x 2.00 calibration factor
+# + WRITE_SIZE x 1.00), summarised in the profiles/ file of each configuration; valid for the default p only.  A kernel
+# family with several launches or kernels per step (the two weight-gradient GEMMs, the three kernels of the attention
+# backward) carries the mean per launch, respectively the sum over its kernels, like its time.
 PMC_TRAFFIC_BYTES = {("C2", 0.5): {"gemm_tn_wgrad": 403e6 + 34e6, "gemm_nt_gelu_fwd": 408e6 + 268e6,
                                    "gemm_nt_rowpar": 471e6 + 134e6, "gemm_nn_gelu_bwd": 537e6 + 134e6,
-                                   "gemm_nn_dgrad": 403e6 + 134e6}}
+                                   "gemm_nn_dgrad": 403e6 + 134e6},
+                     ("C3", 0.5): {"gemm_tn_wgrad": 1010e6 + 140e6, "gemm_nt_swiglu_fwd": 1370e6 + 304e6,
+                                   "gemm_nt_rowpar": 691e6 + 268e6, "gemm_nn_swiglu_bwd": 1048e6 + 182e6,
+                                   "gemm_nn_dgrad": 1084e6 + 269e6},
+                     ("C4", 0.5): {"flash_attn_bwd": (136e6 + 67e6) + (182e6 + 34e6) + (67e6 + 1e6),
+                                   "flash_attn_fwd": 116e6 + 34e6},
+                     ("C5", 0.5): {"decode_attn": 2149e6 + 1e6},
+                     ("C6", 0.5): {"gemm_nt_swiglu_fwd": 12660e6 + 2465e6}}
 
 
 def flops_per_launch(name: str, cfg, which: int = 0) -> float:
@@ -408,12 +417,14 @@ def bench_attention_kinds(args, cfg, base):
         value = work / ms / 1e9
         ach = fl.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e9
         roof = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-                "traffic": None, "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": fl.get(dom, 0.0)}
+                "traffic": PMC_TRAFFIC_BYTES.get((args.config, args.p), {}).get(dom),
+                "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": fl.get(dom, 0.0)}
     else:
         value = work / ms / 1e6
         ach = by.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e6
         roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-                "traffic": None, "avg_launch_ms": prof[dom]["avg_ms"], "bytes_per_launch": by.get(dom, 0.0)}
+                "traffic": PMC_TRAFFIC_BYTES.get((args.config, args.p), {}).get(dom),
+                "avg_launch_ms": prof[dom]["avg_ms"], "bytes_per_launch": by.get(dom, 0.0)}
     out = {"metric": "partial-sync TP block TFLOP/s (% MFMA peak) + sync GB/s (% HBM) vs p, 1 GPU",
            "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
