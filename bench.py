@@ -378,7 +378,9 @@ def bench_attention_kinds(args, cfg, base):
               "gemm_nt_rowpar": n * h * h + n * h * f, "gemm_nt_swiglu_fwd": 4.0 * n * h * f}
         # RoPE rewrites q and k in place and the same kernel stores k and v into the caches: read q, k, v; write q, k, K, V
         by = {"rope_kv_append": T * n * (2.0 * hd + 5.0 * kvd) * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
-              "norm_fwd": 2.0 * T * n * h * 2}
+              "norm_fwd": 2.0 * T * n * h * 2,
+              # reduce + residual + RMSNorm in one launch (as in the decode layer)
+              "partial_sync_norm_fwd": (3.0 * T * n * cfg.hs + T * n * (h - cfg.hs) + T * n * h) * 2}
         work = n * (2.0 * h * qkv_cols + 2.0 * h * h + 6.0 * h * f) + 2.0 * cfg.batch * s * s * h
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
         workload = ("%s prefill decoder layer fwd: h=%d ffn=%d heads=%d kv_heads=%d d=%d RoPE causal, %d prompts x %d tokens, "

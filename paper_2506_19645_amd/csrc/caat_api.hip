@@ -387,9 +387,10 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
     CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)kvpr,
                                                 d->head_dim, d->kv_cap, d->kv_len + 1, s))
   }
-  // decode-sized batches: the reduce after o_proj and the RMSNorm in front of the MLP run as one launch (both are
-  // start-up latency at this size); everything else keeps the two kernels
-  const bool fuse_mid = !prefill && n <= 64 && d->hs > 0 && d->hs % 8 == 0 && (T == 2 || T == 4 || T == 8) && h <= 8192 &&
+  // the reduce after o_proj and the RMSNorm in front of the MLP run as one launch where the fused kernel takes the
+  // shape: for decode-sized batches both are start-up latency, for prompts the fused kernel does not read the
+  // reduced shared channels back from memory (measured 1.28 ms instead of 0.61 + 0.78 ms on 16 prompts of 2048)
+  const bool fuse_mid = d->hs > 0 && d->hs % 8 == 0 && (T == 2 || T == 4 || T == 8) && h <= 8192 &&
                         !d->reduce_in_gemm && dedup_hs(d) == 0;
   {
     const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, R1, s, fuse_mid);

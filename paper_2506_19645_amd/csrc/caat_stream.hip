@@ -284,8 +284,9 @@ hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* b
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Decode-sized batches (a few dozen tokens): the reduce and the RMSNorm that follows it are two launches whose
-// duration is start-up latency, not traffic.  Here one workgroup owns one token of ALL ranks: it sums the T
+// Serving layers: the reduce and the RMSNorm that follows it in one launch.  For decode-sized batches (a few dozen
+// tokens) the two launches are start-up latency, not traffic; for prompts the fused kernel saves reading the reduced
+// shared channels back.  One workgroup owns one token of ALL ranks: it sums the T
 // partial vectors of the shared channels in ascending rank order, adds each rank's residual, rounds once and
 // stores R' (exactly what partial_sync_kernel does), keeps every rank's row (rounded values, packed) in registers,
 // and then normalises each rank's row with its own statistics (what norm_fwd_kernel does on R').  hs % 8 == 0,
