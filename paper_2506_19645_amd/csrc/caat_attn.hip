@@ -27,49 +27,55 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t attn_rsrc(const void* p) {
 // ---------------------------------------------------------------------------------------------------------
 // RoPE in place on the q and k column blocks of qkv [rows, ld] (row = rank*tokens + batch*seq + pos; the first
 // n_rot heads of a row, i.e. the q heads then the k heads, are rotated, the v heads after them are not):
-// pairs (j, j + d/2), angle pos * base^(-2j/d).  One thread rotates 8 pairs of one head of one row.
+// pairs (j, j + d/2), angle pos * base^(-2j/d).  One thread owns 8 pairs (j = 8 grp .. 8 grp + 7) of one row and
+// rotates them in every head: the angles depend on the position and on j, not on the head, so the 8 sines and cosines
+// are computed once per thread (with a thread per head they were what the kernel spent its time on).
 // sign = +1 rotates forward; sign = -1 applies the transpose of that rotation (its inverse), which is what the
 // gradients of the rotated q and k need on their way back to the projection outputs.
 __global__ __launch_bounds__(256) void rope_kernel(bf16_t* qkv, long long rows, int seq, int ld, int n_rot, int d,
                                                    float log2_base, long long pos0, float sign) {
   const int half = d >> 1;
-  const int groups_per_head = half >> 3;            // 8 pairs per thread
-  const int heads2 = n_rot;                         // q heads then k heads
+  const int groups = half >> 3;                     // 8 pairs per thread
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long per_row = (long long)heads2 * groups_per_head;
-  if (idx >= rows * per_row) return;
-  const long long row = idx / per_row;
-  const int rem = (int)(idx - row * per_row);
-  const int head = rem / groups_per_head, grp = rem - head * groups_per_head;
+  if (idx >= rows * groups) return;
+  const long long row = idx / groups;
+  const int grp = (int)(idx - row * groups);
   const float pos = (float)(pos0 + row % seq);
-  bf16_t* p = qkv + row * (long long)ld + (long long)head * d + grp * 8;   // q heads first, k heads right after them
-  const uint4 lo = *reinterpret_cast<const uint4*>(p);
-  const uint4 hi = *reinterpret_cast<const uint4*>(p + half);
-  const unsigned lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
-  unsigned ol[4], oh[4];
+  float sn[8], cs[8];
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    float x1[2] = {lo_bf(lw[w]), hi_bf(lw[w])}, x2[2] = {lo_bf(hw[w]), hi_bf(hw[w])}, y1[2], y2[2];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int j = grp * 8 + w * 2 + e;
-      const float inv = exp2f(-2.0f * (float)j / (float)d * log2_base);
-      float s, c;
-      sincosf(pos * inv, &s, &c);
-      s *= sign;
-      y1[e] = x1[e] * c - x2[e] * s;
-      y2[e] = x2[e] * c + x1[e] * s;
-    }
-    ol[w] = pack2bf(y1[0], y1[1]);
-    oh[w] = pack2bf(y2[0], y2[1]);
+  for (int e = 0; e < 8; ++e) {
+    const int j = grp * 8 + e;
+    const float inv = exp2f(-2.0f * (float)j / (float)d * log2_base);
+    sincosf(pos * inv, &sn[e], &cs[e]);
+    sn[e] *= sign;
   }
-  *reinterpret_cast<uint4*>(p) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
-  *reinterpret_cast<uint4*>(p + half) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+  bf16_t* p = qkv + row * (long long)ld + grp * 8;  // q heads first, k heads right after them
+  for (int head = 0; head < n_rot; ++head, p += d) {
+    const uint4 lo = *reinterpret_cast<const uint4*>(p);
+    const uint4 hi = *reinterpret_cast<const uint4*>(p + half);
+    const unsigned lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+    unsigned ol[4], oh[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float x1[2] = {lo_bf(lw[w]), hi_bf(lw[w])}, x2[2] = {lo_bf(hw[w]), hi_bf(hw[w])};
+      float y1[2], y2[2];
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        y1[e] = x1[e] * cs[w * 2 + e] - x2[e] * sn[w * 2 + e];
+        y2[e] = x2[e] * cs[w * 2 + e] + x1[e] * sn[w * 2 + e];
+      }
+      ol[w] = pack2bf(y1[0], y1[1]);
+      oh[w] = pack2bf(y2[0], y2[1]);
+    }
+    *reinterpret_cast<uint4*>(p) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+    *reinterpret_cast<uint4*>(p + half) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+  }
 }
 
 hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int ld, int n_rot, int d, float base, long long pos0,
                        bool inverse, hipStream_t s) {
-  const long long work = rows * (long long)n_rot * (d / 16);
+  if (n_rot == 0) return hipSuccess;
+  const long long work = rows * (long long)(d / 16);
   if (work == 0) return hipSuccess;
   const long long blocks = (work + 255) / 256;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
