@@ -649,34 +649,46 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
   }
 }
 
-// sums partial[nb][2][h] over nb in a fixed order: a workgroup owns 32 columns, its 8 row groups each add every
-// 8th partial row (4 independent chains), and the 8 group sums are combined in ascending order through LDS
+// sums partial[nb][2][h] over nb in a fixed order: a workgroup owns 64 columns (a thread 4 of them, one 16-byte
+// load per partial row), its 16 row groups each add every 16th partial row (4 independent chains), and the 16 group
+// sums are combined in ascending order through LDS.  h % 8 == 0, so 2h is a multiple of 4.
 __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __restrict__ partial, int nb, int h,
                                                                 float* __restrict__ dgamma,
                                                                 float* __restrict__ dbeta) {
-  __shared__ float red[8][32];
-  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
-  const int c = blockIdx.x * 32 + cl;
+  __shared__ float4 red[16][16];
+  const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
+  const int c = (blockIdx.x * 16 + cl) * 4;
   const long long w = 2LL * h;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  float4 s[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) s[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto add = [](float4& a, const float4& b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; };
   if (c < 2 * h) {
     int b = rg;
-    for (; b + 24 < nb; b += 32) {
-      s0 += partial[(long long)b * w + c];
-      s1 += partial[(long long)(b + 8) * w + c];
-      s2 += partial[(long long)(b + 16) * w + c];
-      s3 += partial[(long long)(b + 24) * w + c];
+    for (; b + 48 < nb; b += 64) {
+      float4 v[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const float4*>(partial + (long long)(b + 16 * k) * w + c);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) add(s[k], v[k]);
     }
-    for (; b < nb; b += 8) s0 += partial[(long long)b * w + c];
+    for (; b < nb; b += 16) add(s[0], *reinterpret_cast<const float4*>(partial + (long long)b * w + c));
   }
-  red[rg][cl] = (s0 + s1) + (s2 + s3);
+  add(s[0], s[1]);
+  add(s[2], s[3]);
+  add(s[0], s[2]);
+  red[rg][cl] = s[0];
   __syncthreads();
   if (rg == 0 && c < 2 * h) {
-    float s = red[0][cl];
+    float4 t = red[0][cl];
 #pragma unroll
-    for (int k = 1; k < 8; ++k) s += red[k][cl];
-    if (c < h) dgamma[c] = s;
-    else if (dbeta) dbeta[c - h] = s;
+    for (int k = 1; k < 16; ++k) add(t, red[k][cl]);
+    const float o[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (c + e < h) dgamma[c + e] = o[e];
+      else if (dbeta) dbeta[c + e - h] = o[e];
+    }
   }
 }
 
@@ -750,7 +762,7 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
   else if (vpl <= 4) e = norm_bwd_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 31) / 32)), dim3(256), 0, s, partial, (int)nb,
+  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 63) / 64)), dim3(256), 0, s, partial, (int)nb,
                      h, dgamma, dbeta);
   return hipGetLastError();
 }
