@@ -520,7 +520,8 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const bf16_t* __restrict_
   }
 }
 
-// Wide rows (h > 2048): the per-lane column accumulators of the kernel above would need 64+ registers, so here a whole
+// Wide rows (h > 4096; up to there the kernel above, at h = 4096 with every register of a one-wave-per-SIMD
+// budget, measured 8 % faster than this one): the per-lane column accumulators would not fit, so here a whole
 // workgroup owns one row at a time: thread t holds the 16-byte vectors v*256 + t (v < VPL) of the row, the two row
 // sums go wave -> LDS -> all waves (slot chosen by row parity, one barrier per row), and the next row's x, dy and
 // residual gradient are already in flight while the current row is reduced and written.  A thread's dgamma / dbeta
@@ -692,7 +693,7 @@ __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __r
   }
 }
 
-static constexpr int NORM_BWD_WIDE_H = 2048;          // rows wider than this take the workgroup-per-row kernel
+static constexpr int NORM_BWD_WIDE_H = 4096;          // rows wider than this take the workgroup-per-row kernel
 static constexpr int NORM_BWD_WIDE_MAX_BLOCKS = 1024;
 static long long norm_bwd_blocks(long long rows, int h) {
   long long nb;
@@ -760,6 +761,7 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
   } else if (vpl <= 1) e = norm_bwd_dispatch<1>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
   else if (vpl <= 2) e = norm_bwd_dispatch<2>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
   else if (vpl <= 4) e = norm_bwd_dispatch<4>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
+  else if (vpl <= 8) e = norm_bwd_dispatch<8>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 63) / 64)), dim3(256), 0, s, partial, (int)nb,
