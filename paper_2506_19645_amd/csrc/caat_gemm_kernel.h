@@ -22,6 +22,7 @@
 // private LDS scratch and stores row segments of 16 bytes per lane (no workgroup barrier).  With PERSIST a workgroup
 // walks several tiles and the first NSTAGE-1 stages of the next tile are already in flight during the epilogue.
 #pragma once
+#include <type_traits>
 #include "caat_internal.h"
 
 namespace caat {
@@ -508,110 +509,125 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
       __builtin_amdgcn_raw_buffer_store_b128(w, r, ok ? vo + (unsigned)so : OOB, 0, 2);
       asm volatile("s_nop 1" ::: "memory");
     };
-    if constexpr (HAS_AUX) {
-#pragma unroll
-      for (int i = 0; i < AUXD && i < TM; ++i) aux_fetch(i, auxbuf[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int c = j * 4 + q;
-          uint2 w;
-          w.x = pack2bf(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
-          w.y = pack2bf(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-          *reinterpret_cast<uint2*>(scratch + ((frow * CHW + (c ^ (frow & (CHW - 1)))) * 16 + fk * 8)) = w;
-        }
-      // the wave reads back what its other lanes wrote: LDS executes a wave's operations in order; the compiler
-      // must not reorder across this point either
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      const int rl = rows_left(i);
-      const int so_c = i * 32 * (int)p.ldc * 2;
-#pragma unroll
-      for (int st = 0; st < STEPS; ++st) {
-        const bool rowok = erow[st] < rl;
-        const unsigned vo = voff_c[st];
-        if constexpr (SWI) {
-          // scratch columns: [gate 32 | up 32] pairs; output chunk oc -> gate chunk (oc/4)*8 + oc%4, up chunk = +4
-          const int oc = (st * 64 + lane) - erow[st] * OCW;
-          const int gc = (oc >> 2) * 8 + (oc & 3);
-          const uint4 gw = staged(erow[st], gc), uw = staged(erow[st], gc + 4);
-          float gt[8], up[8], y[8];
-          unpack(gw, gt);
-          unpack(uw, up);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
-          put_late(rc, gw, rowok, vo, so_c);
-          put_late(rc, uw, rowok, vo, so_c + p.half * 2);
-          put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
-        } else {
-          const int c = (st * 64 + lane) - erow[st] * CHW;
-          const uint4 raw = staged(erow[st], c);
-          if constexpr (EPI == EPI_PLAIN) {
-            if (p.late_c) put_late(rc, raw, rowok, vo, so_c);
-            else put(rc, raw, rowok, vo, so_c);
-          } else if constexpr (EPI == EPI_GELU_FWD) {
-            // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
-            float v[8], y[8];
-            unpack(raw, v);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
-            put_late(rc, raw, rowok, vo, so_c);
+    // The slab loop exists twice for the row-parallel epilogue: a tile that lies entirely left of hs holds shared
+    // channels only (Eq. A3: every rank's partial sum goes out as it is, the reduce adds the residual), so it needs
+    // neither the residual fetch nor the case split and runs the plain store path; both versions issue the same number
+    // of stores, and each is free of branches in itself.
+    auto slabs = [&](auto shared_tile) {
+      constexpr bool SH = decltype(shared_tile)::value;
+      if constexpr (HAS_AUX && !SH) {
+  #pragma unroll
+        for (int i = 0; i < AUXD && i < TM; ++i) aux_fetch(i, auxbuf[i]);
+      }
+  #pragma unroll
+      for (int i = 0; i < TM; ++i) {
+  #pragma unroll
+        for (int j = 0; j < TN; ++j)
+  #pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int c = j * 4 + q;
+            uint2 w;
+            w.x = pack2bf(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1]);
+            w.y = pack2bf(acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+            *reinterpret_cast<uint2*>(scratch + ((frow * CHW + (c ^ (frow & (CHW - 1)))) * 16 + fk * 8)) = w;
+          }
+        // the wave reads back what its other lanes wrote: LDS executes a wave's operations in order; the compiler
+        // must not reorder across this point either
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const int rl = rows_left(i);
+        const int so_c = i * 32 * (int)p.ldc * 2;
+  #pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+          const bool rowok = erow[st] < rl;
+          const unsigned vo = voff_c[st];
+          if constexpr (SWI) {
+            // scratch columns: [gate 32 | up 32] pairs; output chunk oc -> gate chunk (oc/4)*8 + oc%4, up chunk = +4
+            const int oc = (st * 64 + lane) - erow[st] * OCW;
+            const int gc = (oc >> 2) * 8 + (oc & 3);
+            const uint4 gw = staged(erow[st], gc), uw = staged(erow[st], gc + 4);
+            float gt[8], up[8], y[8];
+            unpack(gw, gt);
+            unpack(uw, up);
+  #pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
+            put_late(rc, gw, rowok, vo, so_c);
+            put_late(rc, uw, rowok, vo, so_c + p.half * 2);
             put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
-          } else if constexpr (EPI == EPI_ROWPAR) {
-            // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual); columns < hs are
-            // stored as this rank's partial sum for the reduce kernel (rounding a bf16 value to bf16 again leaves
-            // its bits as they are).  The private value is scaled from the bf16-rounded partial.
-            float v[8], r[8];
-            unpack(raw, v);
-            unpack(to_u4(auxbuf[i % AUXD][st]), r);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = (ecol[st] + e >= p.hs) ? p.scale * v[e] + r[e] : v[e];
-            put(rc, pack(v), rowok, vo, so_c);
-          } else if constexpr (EPI == EPI_SHARED_BCAST) {
-            // Eq. A3, shared channels with the sum over ranks already in the accumulator: every rank's output gets
-            // the same sum plus that rank's residual
-            float v[8];
-            unpack(raw, v);
-            for (int m = 0; m < p.bcast; ++m) {
-              const rsrc_t rr = make_rsrc_t(p.aux + (long long)m * p.stride_aux + (long long)wrow0 * p.ldaux);
-              const rsrc_t rw = make_rsrc_t(p.c + (long long)m * p.stride_c + (long long)wrow0 * p.ldc);
-              const unsigned va = (rowok && ecol[st] < ncols) ? (unsigned)((erow[st] * p.ldaux + ecol[st]) * 2) : OOB;
-              float r[8], o[8];
-              unpack(to_u4(__builtin_amdgcn_raw_buffer_load_b128(rr, va, i * 32 * (int)p.ldaux * 2, 0)), r);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) o[e] = v[e] + r[e];
-              put(rw, pack(o), rowok, vo, so_c);
+          } else {
+            const int c = (st * 64 + lane) - erow[st] * CHW;
+            const uint4 raw = staged(erow[st], c);
+            if constexpr (EPI == EPI_PLAIN) {
+              if (p.late_c) put_late(rc, raw, rowok, vo, so_c);
+              else put(rc, raw, rowok, vo, so_c);
+            } else if constexpr (EPI == EPI_GELU_FWD) {
+              // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
+              float v[8], y[8];
+              unpack(raw, v);
+  #pragma unroll
+              for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
+              put_late(rc, raw, rowok, vo, so_c);
+              put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
+            } else if constexpr (EPI == EPI_ROWPAR && SH) {
+              put(rc, raw, rowok, vo, so_c);  // a tile of shared channels only: this rank's partial sums as they are
+            } else if constexpr (EPI == EPI_ROWPAR) {
+              // Eq. A3 case split, private side: columns >= hs are final here (scale, + residual); columns < hs are
+              // stored as this rank's partial sum for the reduce kernel (rounding a bf16 value to bf16 again leaves
+              // its bits as they are).  The private value is scaled from the bf16-rounded partial.
+              float v[8], r[8];
+              unpack(raw, v);
+              unpack(to_u4(auxbuf[i % AUXD][st]), r);
+  #pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] = (ecol[st] + e >= p.hs) ? p.scale * v[e] + r[e] : v[e];
+              put(rc, pack(v), rowok, vo, so_c);
+            } else if constexpr (EPI == EPI_SHARED_BCAST) {
+              // Eq. A3, shared channels with the sum over ranks already in the accumulator: every rank's output gets
+              // the same sum plus that rank's residual
+              float v[8];
+              unpack(raw, v);
+              for (int m = 0; m < p.bcast; ++m) {
+                const rsrc_t rr = make_rsrc_t(p.aux + (long long)m * p.stride_aux + (long long)wrow0 * p.ldaux);
+                const rsrc_t rw = make_rsrc_t(p.c + (long long)m * p.stride_c + (long long)wrow0 * p.ldc);
+                const unsigned va = (rowok && ecol[st] < ncols) ? (unsigned)((erow[st] * p.ldaux + ecol[st]) * 2) : OOB;
+                float r[8], o[8];
+                unpack(to_u4(__builtin_amdgcn_raw_buffer_load_b128(rr, va, i * 32 * (int)p.ldaux * 2, 0)), r);
+  #pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = v[e] + r[e];
+                put(rw, pack(o), rowok, vo, so_c);
+              }
+            } else if constexpr (EPI == EPI_GELU_BWD) {
+              float v[8], pr[8];
+              unpack(raw, v);
+              unpack(to_u4(auxbuf[i % AUXD][st]), pr);
+  #pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
+              put(rc, pack(v), rowok, vo, so_c);
+            } else if constexpr (EPI == EPI_SWIGLU_BWD) {
+              float v[8], gt[8], up[8], dg[8], du[8];
+              unpack(raw, v);
+              unpack(to_u4(auxbuf[i % AUXD][st * AUXV]), gt);
+              unpack(to_u4(auxbuf[i % AUXD][st * AUXV + (AUXV - 1)]), up);
+  #pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const float sg = sigmoid_f(gt[e]);
+                dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
+                du[e] = v[e] * gt[e] * sg;
+              }
+              put(rc, pack(dg), rowok, vo, so_c);
+              put(rc, pack(du), rowok, vo, so_c + p.half * 2);
             }
-          } else if constexpr (EPI == EPI_GELU_BWD) {
-            float v[8], pr[8];
-            unpack(raw, v);
-            unpack(to_u4(auxbuf[i % AUXD][st]), pr);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
-            put(rc, pack(v), rowok, vo, so_c);
-          } else if constexpr (EPI == EPI_SWIGLU_BWD) {
-            float v[8], gt[8], up[8], dg[8], du[8];
-            unpack(raw, v);
-            unpack(to_u4(auxbuf[i % AUXD][st * AUXV]), gt);
-            unpack(to_u4(auxbuf[i % AUXD][st * AUXV + (AUXV - 1)]), up);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              const float sg = sigmoid_f(gt[e]);
-              dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
-              du[e] = v[e] * gt[e] * sg;
-            }
-            put(rc, pack(dg), rowok, vo, so_c);
-            put(rc, pack(du), rowok, vo, so_c + p.half * 2);
           }
         }
+        asm volatile("" ::: "memory");  // keep the next 32 rows' scratch writes behind these reads
+        if constexpr (HAS_AUX && !SH) {
+          if (i + AUXD < TM) aux_fetch(i + AUXD, auxbuf[i % AUXD]);  // this slab's registers are free again
+        }
       }
-      asm volatile("" ::: "memory");  // keep the next 32 rows' scratch writes behind these reads
-      if constexpr (HAS_AUX) {
-        if (i + AUXD < TM) aux_fetch(i + AUXD, auxbuf[i % AUXD]);  // this slab's registers are free again
-      }
+    };
+    if constexpr (EPI == EPI_ROWPAR) {
+      if (en0 + bn_out <= p.hs) slabs(std::true_type{});
+      else slabs(std::false_type{});
+    } else {
+      slabs(std::false_type{});
     }
     if (!has_next) break;
     pid = next;
