@@ -509,12 +509,14 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
       __builtin_amdgcn_raw_buffer_store_b128(w, r, ok ? vo + (unsigned)so : OOB, 0, 2);
       asm volatile("s_nop 1" ::: "memory");
     };
-    // The slab loop exists twice for the row-parallel epilogue: a tile that lies entirely left of hs holds shared
-    // channels only (Eq. A3: every rank's partial sum goes out as it is, the reduce adds the residual), so it needs
-    // neither the residual fetch nor the case split and runs the plain store path; both versions issue the same number
+    // The slab loop exists three times for the row-parallel epilogue: a tile that lies entirely left of hs holds
+    // shared channels only (Eq. A3: every rank's partial sum goes out as it is, the reduce adds the residual), so it
+    // needs neither the residual fetch nor the case split and runs the plain store path; a tile entirely right of hs
+    // needs no case split; only a tile that contains hs takes the general code.  All versions issue the same number
     // of stores, and each is free of branches in itself.
-    auto slabs = [&](auto shared_tile) {
-      constexpr bool SH = decltype(shared_tile)::value;
+    auto slabs = [&](auto tile_kind) {
+      constexpr bool SH = decltype(tile_kind)::value == 1;    // shared channels only
+      constexpr bool PRIV = decltype(tile_kind)::value == 2;  // private channels only
       if constexpr (HAS_AUX && !SH) {
   #pragma unroll
         for (int i = 0; i < AUXD && i < TM; ++i) aux_fetch(i, auxbuf[i]);
@@ -577,7 +579,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
               unpack(raw, v);
               unpack(to_u4(auxbuf[i % AUXD][st]), r);
   #pragma unroll
-              for (int e = 0; e < 8; ++e) v[e] = (ecol[st] + e >= p.hs) ? p.scale * v[e] + r[e] : v[e];
+              for (int e = 0; e < 8; ++e) v[e] = (PRIV || ecol[st] + e >= p.hs) ? p.scale * v[e] + r[e] : v[e];
               put(rc, pack(v), rowok, vo, so_c);
             } else if constexpr (EPI == EPI_SHARED_BCAST) {
               // Eq. A3, shared channels with the sum over ranks already in the accumulator: every rank's output gets
@@ -624,10 +626,11 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
       }
     };
     if constexpr (EPI == EPI_ROWPAR) {
-      if (en0 + bn_out <= p.hs) slabs(std::true_type{});
-      else slabs(std::false_type{});
+      if (en0 + bn_out <= p.hs) slabs(std::integral_constant<int, 1>{});
+      else if (en0 >= p.hs) slabs(std::integral_constant<int, 2>{});
+      else slabs(std::integral_constant<int, 0>{});
     } else {
-      slabs(std::false_type{});
+      slabs(std::integral_constant<int, 0>{});
     }
     if (!has_next) break;
     pid = next;
