@@ -24,8 +24,10 @@ __device__ __forceinline__ float hi_bf(unsigned w) { return __uint_as_float(w & 
 // and a short polynomial each (the activation runs in the GEMM epilogues, where every VALU cycle is exposed).
 // With a = |x|: the lower tail is Phi(-a) = 2^r(a), r a degree-5 minimax fit of log2 Phi(-a) on [0, 5.5]
 // (relative error of the tail <= 2.5e-4, an eighth of bf16's rounding step, also where the tail is tiny);
-// gelu(x) = x*Phi(-a) for x <= 0 and x - x*Phi(-a) for x > 0.  Beyond 5.5 the polynomial keeps falling (its
-// leading coefficient is negative), so the tail runs smoothly into 0 (absolute error of gelu there < 1e-7).
+// gelu(x) = x*Phi(-a) for x <= 0 and x - x*Phi(-a) for x > 0, i.e. max(x, 0) - a*Phi(-a) for both signs (one
+// maximum and one fused multiply-add instead of a product, a difference, a comparison and a select).  Beyond 5.5
+// the polynomial keeps falling (its leading coefficient is negative), so the tail runs smoothly into 0 (absolute
+// error of gelu there < 1e-7).
 __device__ __forceinline__ float gelu_f(float x) {
   const float a = fabsf(x);
   float r = -0.000233251485f;
@@ -34,8 +36,7 @@ __device__ __forceinline__ float gelu_f(float x) {
   r = r * a - 0.469681203f;
   r = r * a - 1.14626062f;
   r = r * a - 1.00035918f;
-  const float xt = x * __builtin_amdgcn_exp2f(r);
-  return x > 0.0f ? x - xt : xt;
+  return __builtin_fmaf(-a, __builtin_amdgcn_exp2f(r), fmaxf(x, 0.0f));
 }
 // The derivative on the negative side is u(a) = Phi(-a) - a*phi(a) = phi(a)*(m(a) - a) with Mills' ratio
 // m = Phi(-a)/phi(a); (m(a) - a)/sqrt(2 pi) is a smooth function fitted by a degree-6 polynomial weighted with
