@@ -518,14 +518,14 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
       constexpr bool SH = decltype(tile_kind)::value == 1;    // shared channels only
       constexpr bool PRIV = decltype(tile_kind)::value == 2;  // private channels only
       if constexpr (HAS_AUX && !SH) {
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < AUXD && i < TM; ++i) aux_fetch(i, auxbuf[i]);
       }
-  #pragma unroll
+#pragma unroll
       for (int i = 0; i < TM; ++i) {
-  #pragma unroll
+#pragma unroll
         for (int j = 0; j < TN; ++j)
-  #pragma unroll
+#pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int c = j * 4 + q;
             uint2 w;
@@ -538,7 +538,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         const int rl = rows_left(i);
         const int so_c = i * 32 * (int)p.ldc * 2;
-  #pragma unroll
+#pragma unroll
         for (int st = 0; st < STEPS; ++st) {
           const bool rowok = erow[st] < rl;
           const unsigned vo = voff_c[st];
@@ -550,7 +550,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
             float gt[8], up[8], y[8];
             unpack(gw, gt);
             unpack(uw, up);
-  #pragma unroll
+#pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = gt[e] * sigmoid_f(gt[e]) * up[e];
             put_late(rc, gw, rowok, vo, so_c);
             put_late(rc, uw, rowok, vo, so_c + p.half * 2);
@@ -565,7 +565,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
               // the activation is taken of the bf16-rounded pre-activation, the value the backward pass sees too
               float v[8], y[8];
               unpack(raw, v);
-  #pragma unroll
+#pragma unroll
               for (int e = 0; e < 8; ++e) y[e] = gelu_f(v[e]);
               put_late(rc, raw, rowok, vo, so_c);
               put(rc2, pack(y), rowok, voff_c2[st], i * 32 * (int)p.ldc2 * 2);
@@ -578,7 +578,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
               float v[8], r[8];
               unpack(raw, v);
               unpack(to_u4(auxbuf[i % AUXD][st]), r);
-  #pragma unroll
+#pragma unroll
               for (int e = 0; e < 8; ++e) v[e] = (PRIV || ecol[st] + e >= p.hs) ? p.scale * v[e] + r[e] : v[e];
               put(rc, pack(v), rowok, vo, so_c);
             } else if constexpr (EPI == EPI_SHARED_BCAST) {
@@ -592,7 +592,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
                 const unsigned va = (rowok && ecol[st] < ncols) ? (unsigned)((erow[st] * p.ldaux + ecol[st]) * 2) : OOB;
                 float r[8], o[8];
                 unpack(to_u4(__builtin_amdgcn_raw_buffer_load_b128(rr, va, i * 32 * (int)p.ldaux * 2, 0)), r);
-  #pragma unroll
+#pragma unroll
                 for (int e = 0; e < 8; ++e) o[e] = v[e] + r[e];
                 put(rw, pack(o), rowok, vo, so_c);
               }
@@ -600,7 +600,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
               float v[8], pr[8];
               unpack(raw, v);
               unpack(to_u4(auxbuf[i % AUXD][st]), pr);
-  #pragma unroll
+#pragma unroll
               for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(pr[e]);
               put(rc, pack(v), rowok, vo, so_c);
             } else if constexpr (EPI == EPI_SWIGLU_BWD) {
@@ -608,7 +608,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
               unpack(raw, v);
               unpack(to_u4(auxbuf[i % AUXD][st * AUXV]), gt);
               unpack(to_u4(auxbuf[i % AUXD][st * AUXV + (AUXV - 1)]), up);
-  #pragma unroll
+#pragma unroll
               for (int e = 0; e < 8; ++e) {
                 const float sg = sigmoid_f(gt[e]);
                 dg[e] = v[e] * up[e] * sg * (1.0f + gt[e] * (1.0f - sg));
