@@ -259,8 +259,15 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
 
   constexpr int BKS = CFG::BKS;         // this instantiation's stage depth (hides the namespace default)
   constexpr int NSUB = BKS / 16;        // 16-wide k sub-steps (one MFMA deep) per stage
-  typedef typename OperandSel<AT, BM, CFG::NWAVES, BKS>::type OpA;
-  typedef typename OperandSel<BT, BN, CFG::NWAVES, BKS>::type OpB;
+  // Waves that issue the global -> LDS copies.  A wave's copies and its epilogue stores complete in issue order on one
+  // counter, so a wave that copies has to let its stores drain before it can wait for the next tile's second stage;
+  // with several outputs per tile (the fused forward epilogues) those stores are a chip-wide burst that takes several
+  // k steps.  There only the first four waves copy (twice the instructions each): the other four never wait on that
+  // counter in the main loop, and their half of the stores drains under the next tile.
+  constexpr int NLOAD = (CFG::PERSIST && CFG::NWAVES == 8 && (EPI == EPI_GELU_FWD || EPI == EPI_SWIGLU_FWD)) ? 4 : CFG::NWAVES;
+  const bool loader = wave < NLOAD;
+  typedef typename OperandSel<AT, BM, NLOAD, BKS>::type OpA;
+  typedef typename OperandSel<BT, BN, NLOAD, BKS>::type OpB;
   OpA la;
   OpB lb;
   int g = 0, m0 = 0, n0 = 0;
@@ -306,6 +313,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
   auto stage_a = [&](int s) -> uint4* { return smem + (s % NSTAGE) * CFG::STAGE_CHUNKS; };
   // stages are issued in order; past the end every offset is out of range: zeros land in a slot nobody reads
   auto issue_stage = [&](int s) {
+    if (!loader) return;
     uint4* As = stage_a(s);
     if constexpr (KCAT) {
       const int kk = ikg < kcat ? K : 0;
@@ -373,10 +381,12 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     // previous tile, the wave's newest vector-memory instructions are that tile's epilogue stores (a fixed number,
     // all issued after this tile's first copies): they may stay in flight under the first stage's MFMAs.  The
     // barrier also separates the previous tile's epilogue scratch from the copies that will reuse its LDS slot.
-    if (first_tile || EPI_STORES + (NSTAGE - 2) * NV > 63)
-      wait_vmcnt<(NSTAGE - 2) * NV>();
-    else
-      wait_vmcnt<(EPI_STORES + (NSTAGE - 2) * NV > 63) ? 0 : EPI_STORES + (NSTAGE - 2) * NV>();
+    if (loader) {
+      if (first_tile || EPI_STORES + (NSTAGE - 2) * NV > 63)
+        wait_vmcnt<(NSTAGE - 2) * NV>();
+      else
+        wait_vmcnt<(EPI_STORES + (NSTAGE - 2) * NV > 63) ? 0 : EPI_STORES + (NSTAGE - 2) * NV>();
+    }
     first_tile = false;
     __syncthreads();
     // fragments are double buffered over the NSUB 16-wide k sub-steps of a stage (NSUB is even)
@@ -393,7 +403,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
           load_frags(kt, ss + 1, fr[(ss + 1) & 1]);
         } else {
           // last sub-step: stage kt+1 must have landed (the two newest stages may still be in flight) and be visible
-          wait_vmcnt<(NSTAGE - 2) * NV>();
+          if (loader) wait_vmcnt<(NSTAGE - 2) * NV>();
           __syncthreads();
           fence();
           load_frags(kt + 1, 0, fr[0]);
@@ -409,7 +419,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
     }
     // the zero-filled stages past K still target LDS: let them land, and let every wave finish its fragment reads,
     // before the buffers are reused
-    wait_vmcnt<0>();
+    if (loader) wait_vmcnt<0>();
     __syncthreads();
 
     // ---- the finished tile's coordinates; then start on the next tile's data before the epilogue
