@@ -264,7 +264,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::MIN_WAVES_PER_EU) void gemm_kern
   // with several outputs per tile (the fused forward epilogues) those stores are a chip-wide burst that takes several
   // k steps.  There only the first four waves copy (twice the instructions each): the other four never wait on that
   // counter in the main loop, and their half of the stores drains under the next tile.
-  constexpr int NLOAD = (CFG::PERSIST && CFG::NWAVES == 8 && (EPI == EPI_GELU_FWD || EPI == EPI_SWIGLU_FWD)) ? 4 : CFG::NWAVES;
+  constexpr int NLOAD = (CFG::PERSIST && CFG::NWAVES == 8 && (EPI == EPI_GELU_FWD || EPI == EPI_SWIGLU_FWD || EPI == EPI_PLAIN)) ? 4 : CFG::NWAVES;
   const bool loader = wave < NLOAD;
   typedef typename OperandSel<AT, BM, NLOAD, BKS>::type OpA;
   typedef typename OperandSel<BT, BN, NLOAD, BKS>::type OpB;
