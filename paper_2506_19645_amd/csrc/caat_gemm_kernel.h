@@ -101,6 +101,11 @@ struct KContigOperand {
   template <bool STREAM = false>
   __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
     const i32x4_t rs = make_rsrc(origin + koff + k0);
+    if (k0 + BKS_ <= K) {  // a whole stage inside the contraction (all but the last one or two): no per-lane test
+#pragma unroll
+      for (int it = 0; it < NI; ++it) dma16<STREAM>(rs, voff[it], tile + (it * NWAVES + wave) * 64);
+      return;
+    }
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
       const bool kin = (k0 + kc[RPI == 16 ? 0 : it] * 8) < K;
@@ -150,6 +155,11 @@ struct RowContigOperand {
   template <bool STREAM = false>
   __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
     const i32x4_t rs = make_rsrc(origin + koff + (long long)k0 * ld);
+    if (k0 + BKS_ <= K) {  // a whole stage inside the contraction: no per-lane test
+#pragma unroll
+      for (int it = 0; it < NI; ++it) dma16<STREAM>(rs, voff[it], tile + (it * NWAVES + wave) * 64);
+      return;
+    }
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
       const int k = (it * NWAVES + wave) * KPI + klocal;
