@@ -4,23 +4,24 @@
 // of Eq. A3 (column-parallel X_m A_m with the activation fused, row-parallel Y_m B_m with the private-column
 // half of the partial channel-reduce + residual fused) and their data / weight gradients.
 //
-// Tiling: a workgroup owns a BM x BN tile of C and walks K in stages of BKS (32; 128 for the decode-sized tiles, whose
-// weight rows are then fetched 256 contiguous bytes at a time).  NSTAGE stages of both
-// operand tiles live in LDS and every operand goes global -> LDS directly (buffer_load ... lds, no register
-// staging), NSTAGE-1 stages ahead of the MFMAs, so a global / L2 round trip of several stage times is hidden.
-//   * operand contiguous along K in memory (NT's a and b, NN's a): stage = [rows][32 k], 64-byte rows, fragment
-//     reads are ds_read_b128 (32 consecutive rows x one 16-byte chunk);
-//   * operand contiguous along its row index in memory (NN's b, TN's a and b): stage = [32 k][rows], the memory
+// Tiling: a workgroup owns a BM x BN tile of C and walks K in stages of BKS (64 in every tile shape in use).  NSTAGE
+// stages of both operand tiles live in LDS and every operand goes global -> LDS directly (buffer_load ... lds, no
+// register staging), NSTAGE-1 stages ahead of the MFMAs, so a global / L2 round trip is hidden.
+//   * operand contiguous along K in memory (NT's a and b, NN's a): stage = [rows][BKS k], fragment reads are
+//     ds_read_b128 (32 consecutive rows x one 16-byte chunk);
+//   * operand contiguous along its row index in memory (NN's b, TN's a and b): stage = [BKS k][rows], the memory
 //     layout as it is, and the MFMA fragments (8 consecutive k of one row per lane) are gathered by the LDS
 //     transpose read ds_read_b64_tr_b16 (16 lanes fetch 4 k-rows x 16 rows and lane j receives row j's 4 k).
 // 16-byte chunks are XOR-swizzled (applied on the global side of the copy) so that both kinds of reads are
 // bank-conflict free.  Rows / k outside the matrix get an out-of-range buffer offset and arrive as zeros, so
-// the main loop has no branch.  MFMA fragments are double buffered over the two 16-wide k sub-steps of a stage.
+// the main loop has no branch.  MFMA fragments are double buffered over the 16-wide k sub-steps of a stage.
 //
 // The accumulator is computed transposed (operands swapped in the MFMA) so that each lane ends up with 4
 // consecutive columns of one row of C; in the epilogue every wave passes its sub-tile, 32 rows at a time, through a
 // private LDS scratch and stores row segments of 16 bytes per lane (no workgroup barrier).  With PERSIST a workgroup
-// walks several tiles and the first NSTAGE-1 stages of the next tile are already in flight during the epilogue.
+// walks several tiles, the first NSTAGE-1 stages of the next tile are already in flight during the epilogue, and
+// only half of its waves issue copies (NLOAD below), so that the other half's stores can drain under the next tile.
+// Decode-sized tiles (BM <= 64) may cover fewer output columns than the MFMA tile is wide (bn_out).
 #pragma once
 #include <type_traits>
 #include "caat_internal.h"
