@@ -86,7 +86,7 @@ hipError_t launch_gemm(const GemmParams& p, int layout, int epilogue, hipStream_
   // buffer-load offsets are 32-bit and relative to the tile origin: the farthest row a tile touches times the
   // row stride must stay below 2 GiB
   const long long far_rows = (epilogue == EPI_SWIGLU_FWD ? (long long)p.half : 0) + 256 + 64;  // rows or k-rows
-  if (far_rows * p.lda * 2 >= 0x7FFFFFFFLL || far_rows * p.ldb * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  if (far_rows * p.lda * 2 >= 0x7FFFF000LL || far_rows * p.ldb * 2 >= 0x7FFFF000LL) return hipErrorInvalidValue;
   // the epilogue's buffer offsets are relative to a wave's first row: up to 256 rows of any output / second operand
   const long long ldmax = std::max(std::max(p.ldc, p.ldc2), p.ldaux);
   if ((256 * ldmax + 2 * (long long)p.half + (long long)p.N) * 2 >= 0x7FFFFFFFLL) return hipErrorInvalidValue;

@@ -35,6 +35,7 @@ typedef short short8_t __attribute__((ext_vector_type(8)));
 
 static constexpr int BKS = 32;                // default k extent of one LDS stage
 static constexpr unsigned OOB = 0x80000000u;  // buffer offset that is always out of range -> load returns 0
+static constexpr int DMA_SHIFT = 3072;        // operand windows start this many bytes early (see dma16_group's offsets)
 
 template <int BM_, int BN_, int WM_, int WN_, int NSTAGE_ = 4, int SCHED_ = 2, bool PERSIST_ = true, int BKS_ = 32>
 struct TileCfg {
@@ -73,8 +74,10 @@ struct KContigOperand {
   static constexpr int RPI = 64 / CPR;           // rows per copy instruction
   static constexpr int SWZ_SHIFT = CPR == 4 ? 2 : (CPR == 8 ? 1 : 0);
   static constexpr int NI = ROWS / RPI / NWAVES;  // copy instructions per wave per stage
+  static constexpr int GRP = NI >= 4 ? 4 : NI;    // copies that share one LDS base (see dma16_group)
   static constexpr int N_VMEM = NI;
   static constexpr int READS_PER_FRAG = 1;
+  static_assert(NI % GRP == 0, "whole groups of copies");
   static_assert(CPR == 4 || CPR == 8 || CPR == 16, "stage depth must be 32, 64 or 128");
   static_assert(ROWS % (RPI * NWAVES) == 0, "rows must divide over the waves");
   static __device__ __forceinline__ int swz(int row) { return (row >> SWZ_SHIFT) & (CPR - 1); }
@@ -90,27 +93,32 @@ struct KContigOperand {
     wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
-      // physical slot lane % CPR of row (it*NWAVES + wave)*RPI + lane / CPR holds logical chunk slot ^ swz(row); the
-      // swizzle has a period of 16 rows, so with 16 rows per instruction it does not depend on `it`
-      const int row = (it * NWAVES + wave) * RPI + lane / CPR;
+      // a wave's NI copies fill consecutive groups of RPI rows (1 KB of LDS each).  Physical slot lane % CPR of row
+      // (wave*NI + it)*RPI + lane / CPR holds logical chunk slot ^ swz(row); the swizzle has a period of 16 rows, so
+      // with 16 rows per instruction it does not depend on `it`
+      const int row = (wave * NI + it) * RPI + lane / CPR;
       kc[it] = (lane & (CPR - 1)) ^ swz(RPI == 16 ? lane / CPR : row);
       const long long r = rowmap(row);
-      voff[it] = (r >= 0) ? (unsigned)((r * ld + kc[it] * 8) * 2) : OOB;
+      // memory-side offsets are relative to a base DMA_SHIFT bytes in front of the operand, less the immediate offset
+      // the copy carries as member it % GRP of its group (dma16_group)
+      voff[it] = (r >= 0) ? (unsigned)((r * ld + kc[it] * 8) * 2 + DMA_SHIFT - (it % GRP) * 1024) : OOB;
     }
   }
   // koff: element offset of the K-group the stage belongs to (0 unless the contraction runs over several buffers)
   template <bool STREAM = false>
   __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
-    const i32x4_t rs = make_rsrc(origin + koff + k0);
+    const i32x4_t rs = make_rsrc(reinterpret_cast<const char*>(origin + koff + k0) - DMA_SHIFT);
     if (k0 + BKS_ <= K) {  // a whole stage inside the contraction (all but the last one or two): no per-lane test
 #pragma unroll
-      for (int it = 0; it < NI; ++it) dma16<STREAM>(rs, voff[it], tile + (it * NWAVES + wave) * 64);
+      for (int gi = 0; gi < NI / GRP; ++gi) dma16_group<STREAM, GRP>(rs, voff + gi * GRP, tile + (wave * NI + gi * GRP) * 64);
       return;
     }
 #pragma unroll
-    for (int it = 0; it < NI; ++it) {
-      const bool kin = (k0 + kc[RPI == 16 ? 0 : it] * 8) < K;
-      dma16<STREAM>(rs, kin ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
+    for (int gi = 0; gi < NI / GRP; ++gi) {
+      unsigned v[GRP];
+#pragma unroll
+      for (int j = 0; j < GRP; ++j) v[j] = (k0 + kc[RPI == 16 ? 0 : gi * GRP + j] * 8) < K ? voff[gi * GRP + j] : OOB;
+      dma16_group<STREAM, GRP>(rs, v, tile + (wave * NI + gi * GRP) * 64);
     }
   }
   // fragment for MFMA rows row0 .. row0+31, k sub-step ks (16 wide): lane (row0 + lane%32, k = 16 ks + 8 (lane/32) ..+7)
@@ -129,8 +137,10 @@ struct RowContigOperand {
   static constexpr int CPR = ROWS / 8;       // chunks per k-row
   static constexpr int KPI = 64 / CPR;       // k-rows per copy instruction
   static constexpr int NI = BKS_ / KPI / NWAVES;
+  static constexpr int GRP = NI >= 4 ? 4 : NI;  // copies that share one LDS base (see dma16_group)
   static constexpr int N_VMEM = NI;
   static constexpr int READS_PER_FRAG = 2;
+  static_assert(NI % GRP == 0, "whole groups of copies");
   static_assert(ROWS >= 128 && ROWS <= 512 && BKS_ % (KPI * NWAVES) == 0, "unsupported tile shape for a transposed operand");
   const bf16_t* origin;
   long long ld;
@@ -147,24 +157,29 @@ struct RowContigOperand {
     const int phys = lane % CPR;
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
-      const int k = (it * NWAVES + wave) * KPI + klocal;
+      const int k = (wave * NI + it) * KPI + klocal;  // a wave's NI copies fill consecutive 1 KB groups of k-rows
       const int c = phys ^ ((k & 3) << 2);
       const long long r = rowmap(c * 8);  // 8 consecutive rows share validity (dims % 8 == 0)
-      voff[it] = (r >= 0) ? (unsigned)(((long long)k * ld_ + r) * 2) : OOB;
+      voff[it] = (r >= 0) ? (unsigned)(((long long)k * ld_ + r) * 2 + DMA_SHIFT - (it % GRP) * 1024) : OOB;
     }
   }
   template <bool STREAM = false>
   __device__ __forceinline__ void issue(int k0, int K, uint4* tile, long long koff) const {
-    const i32x4_t rs = make_rsrc(origin + koff + (long long)k0 * ld);
+    const i32x4_t rs = make_rsrc(reinterpret_cast<const char*>(origin + koff + (long long)k0 * ld) - DMA_SHIFT);
     if (k0 + BKS_ <= K) {  // a whole stage inside the contraction: no per-lane test
 #pragma unroll
-      for (int it = 0; it < NI; ++it) dma16<STREAM>(rs, voff[it], tile + (it * NWAVES + wave) * 64);
+      for (int gi = 0; gi < NI / GRP; ++gi) dma16_group<STREAM, GRP>(rs, voff + gi * GRP, tile + (wave * NI + gi * GRP) * 64);
       return;
     }
 #pragma unroll
-    for (int it = 0; it < NI; ++it) {
-      const int k = (it * NWAVES + wave) * KPI + klocal;
-      dma16<STREAM>(rs, (k0 + k < K) ? voff[it] : OOB, tile + (it * NWAVES + wave) * 64);
+    for (int gi = 0; gi < NI / GRP; ++gi) {
+      unsigned v[GRP];
+#pragma unroll
+      for (int j = 0; j < GRP; ++j) {
+        const int k = (wave * NI + gi * GRP + j) * KPI + klocal;
+        v[j] = (k0 + k < K) ? voff[gi * GRP + j] : OOB;
+      }
+      dma16_group<STREAM, GRP>(rs, v, tile + (wave * NI + gi * GRP) * 64);
     }
   }
   // same fragment as KContigOperand::frag, gathered by two transpose reads of 4 k each

@@ -96,6 +96,48 @@ __device__ __forceinline__ void dma16(i32x4_t rs, unsigned voff, const uint4* ld
                  : "memory");
 }
 
+// G copies (1, 2 or 4) whose LDS destinations lie 1 KB apart, written with one LDS base: the instruction's immediate
+// offset o moves BOTH sides of a copy (memory address and LDS address) by o bytes, so copy number i of the group
+// takes offset 1024 i, and its memory-side offset v[i] must have those 1024 i bytes taken off beforehand.  Saves
+// the M0 write and its wait state on all but the first copy of a group.
+template <bool STREAM, int G>
+__device__ __forceinline__ void dma16_group(i32x4_t rs, const unsigned* v, const uint4* lds_wave_uniform) {
+  static_assert(G == 1 || G == 2 || G == 4, "group of 1, 2 or 4 copies");
+  if constexpr (G == 1) {
+    dma16<STREAM>(rs, v[0], lds_wave_uniform);
+  } else if constexpr (G == 2) {
+    if constexpr (STREAM)
+      asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %2, 0 offen nt lds\n\t"
+                   "buffer_load_dwordx4 %1, %2, 0 offen offset:1024 nt lds"
+                   :
+                   : "v"(v[0]), "v"(v[1]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
+                   : "memory");
+    else
+      asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %2, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %1, %2, 0 offen offset:1024 lds"
+                   :
+                   : "v"(v[0]), "v"(v[1]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
+                   : "memory");
+  } else {
+    if constexpr (STREAM)
+      asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %4, 0 offen nt lds\n\t"
+                   "buffer_load_dwordx4 %1, %4, 0 offen offset:1024 nt lds\n\t"
+                   "buffer_load_dwordx4 %2, %4, 0 offen offset:2048 nt lds\n\t"
+                   "buffer_load_dwordx4 %3, %4, 0 offen offset:3072 nt lds"
+                   :
+                   : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
+                   : "memory");
+    else
+      asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %4, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %1, %4, 0 offen offset:1024 lds\n\t"
+                   "buffer_load_dwordx4 %2, %4, 0 offen offset:2048 lds\n\t"
+                   "buffer_load_dwordx4 %3, %4, 0 offen offset:3072 lds"
+                   :
+                   : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
+                   : "memory");
+  }
+}
+
 // 16-byte load of data that this kernel reads once (non-temporal hint: see dma16)
 __device__ __forceinline__ uint4 ld_stream(const void* p) {
   const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
