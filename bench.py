@@ -37,6 +37,12 @@ PMC_TRAFFIC_BYTES = {("C2", 0.5): {"gemm_tn_wgrad": 403e6 + 34e6, "gemm_nt_gelu_
                      ("C6", 0.5): {"gemm_nt_swiglu_fwd": 12660e6 + 2465e6}}
 
 
+def hs_of(cfg) -> int:
+    """Shared channels of a configuration as the library counts them (caat_shared_channels, Eq. A3)."""
+    from paper_2506_19645_amd import binding as B
+    return B.shared_channels(cfg.h, float(cfg.p))
+
+
 def flops_per_launch(name: str, cfg, which: int = 0) -> float:
     """Algorithmic FLOPs of one launch (all T ranks) of a kernel family of the MLP block."""
     n, h, f = cfg.tokens, cfg.h, cfg.ffn
@@ -200,7 +206,7 @@ def cpu_baseline(cfg, host, sample_tokens):
     w = {k: O.widen_bf16(v) for k, v in sub.items()}
     swi = cfg.kind == 1
     norm = O.LAYERNORM if cfg.norm == 0 else O.RMSNORM
-    kw = dict(swiglu=swi, norm=norm, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale)
+    kw = dict(swiglu=swi, norm=norm, hs=O.shared_channels(cfg.h, cfg.p), eps=cfg.eps, private_scale=cfg.private_scale)
     t0 = time.perf_counter()
     fwd = O.mlp_block_fwd(w["X"], w["R"], w, w["gamma"], w.get("beta"), **kw)
     O.mlp_block_bwd(w["X"], fwd, w, w["gamma"], w["dXo"], w["dRo"], **kw)
@@ -234,10 +240,10 @@ def cpu_baseline_other_kinds(name, cfg, bwd):
         small = cfg                       # the whole decode batch: the oracle needs only seconds for it
     else:
         small = cfg.with_(batch=1, seq=min(cfg.seq, 1024 if h <= 4096 else 512))
-    d = I.make_inputs(small, seed=0, with_grads=bwd)
+    d = I.make_inputs(small, seed=0, with_grads=bwd, hs_struct=cfg.h // 2)
     w = {k: O.widen_bf16(v) for k, v in d.items()}
     n, s = small.tokens, small.seq
-    kw = dict(heads_per_rank=hpr, head_dim=cfg.head_dim, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale,
+    kw = dict(heads_per_rank=hpr, head_dim=cfg.head_dim, hs=O.shared_channels(cfg.h, cfg.p), eps=cfg.eps, private_scale=cfg.private_scale,
               rope_base=cfg.rope_base, kv_heads_per_rank=kvpr)
     t0 = time.perf_counter()
     if name == "C4":
@@ -323,11 +329,11 @@ class PrefillBench(MlpBench):
         from paper_2506_19645_amd import binding as B
         from paper_2506_19645_amd import inputs as I
         self.B, self.torch, self.cfg = B, torch, cfg
-        d = I.make_inputs(cfg, seed=seed, hs_struct=cfg.hs if dedup else cfg.h // 2)
+        d = I.make_inputs(cfg, seed=seed, hs_struct=hs_of(cfg) if dedup else cfg.h // 2)
         self.weights = [B.to_device(d["gamma_attn"]), B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
                         B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]
         if dedup:   # shared channels once [n, hs], then the private channels [T, n, h - hs]; valid for this p only
-            hs = cfg.hs
+            hs = hs_of(cfg)
             self.r = B.to_device(np.concatenate([np.ascontiguousarray(d["R"][0, :, :hs]).ravel(),
                                                  np.ascontiguousarray(d["R"][:, :, hs:]).ravel()]))
         else:
@@ -354,7 +360,7 @@ def bench_attention_kinds(args, cfg, base):
         s = cfg.seq
         fl = {"gemm_nt_qkv": 2.0 * n * h * 3 * h, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,   # causal half of 4 s^2 h
               "gemm_nt_rowpar": 2.0 * n * h * h}
-        by = {"rope": 2.0 * T * n * 2 * hd * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
+        by = {"rope": 2.0 * T * n * 2 * hd * 2, "partial_sync_fwd": 3.0 * T * n * hs_of(cfg) * 2,
               "norm_fwd": 2.0 * T * n * h * 2}
         work = sum(fl.values())
         if bwd:
@@ -362,12 +368,12 @@ def bench_attention_kinds(args, cfg, base):
             # (o_proj: 2nh^2, qkv: 6nh^2) share a kernel family, so the per-launch figure is their mean
             fl.update({"flash_attn_bwd": 5.0 * cfg.batch * s * s * h, "gemm_nn_dgrad": 4.0 * n * h * h,
                        "gemm_tn_wgrad": 4.0 * n * h * h})
-            by.update({"rope_bwd": 2.0 * T * n * 2 * hd * 2, "partial_sync_bwd": 2.0 * T * n * cfg.hs * 2,
-                       "norm_bwd": 5.0 * T * n * h * 2 - (T * n * cfg.hs * 2 if cfg.hs % 8 == 0 else 0)})
+            by.update({"rope_bwd": 2.0 * T * n * 2 * hd * 2, "partial_sync_bwd": 2.0 * T * n * hs_of(cfg) * 2,
+                       "norm_bwd": 5.0 * T * n * h * 2 - (T * n * hs_of(cfg) * 2 if hs_of(cfg) % 8 == 0 else 0)})
             work += 5.0 * cfg.batch * s * s * h + 16.0 * n * h * h
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
         workload = "%s attention sub-block %s: h=%d heads=%d d=%d RoPE causal seq=%d batch=%d T=%d p=%g (hs=%d)" % (
-            cfg.name, "fwd+bwd" if bwd else "fwd", h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, cfg.hs)
+            cfg.name, "fwd+bwd" if bwd else "fwd", h, cfg.n_heads, cfg.head_dim, s, cfg.batch, T, cfg.p, hs_of(cfg))
     elif args.config in ("C6", "C7"):
         bench = PrefillBench(cfg, dedup=args.dedup_shared)
         s, f = cfg.seq, cfg.ffn
@@ -377,15 +383,15 @@ def bench_attention_kinds(args, cfg, base):
         fl = {"gemm_nt_qkv": 2.0 * n * h * qkv_cols, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,
               "gemm_nt_rowpar": n * h * h + n * h * f, "gemm_nt_swiglu_fwd": 4.0 * n * h * f}
         # RoPE rewrites q and k in place and the same kernel stores k and v into the caches: read q, k, v; write q, k, K, V
-        by = {"rope_kv_append": T * n * (2.0 * hd + 5.0 * kvd) * 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
+        by = {"rope_kv_append": T * n * (2.0 * hd + 5.0 * kvd) * 2, "partial_sync_fwd": 3.0 * T * n * hs_of(cfg) * 2,
               "norm_fwd": 2.0 * T * n * h * 2,
               # reduce + residual + RMSNorm in one launch (as in the decode layer)
-              "partial_sync_norm_fwd": (3.0 * T * n * cfg.hs + T * n * (h - cfg.hs) + T * n * h) * 2}
+              "partial_sync_norm_fwd": (3.0 * T * n * hs_of(cfg) + T * n * (h - hs_of(cfg)) + T * n * h) * 2}
         work = n * (2.0 * h * qkv_cols + 2.0 * h * h + 6.0 * h * f) + 2.0 * cfg.batch * s * s * h
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS
         workload = ("%s prefill decoder layer fwd: h=%d ffn=%d heads=%d kv_heads=%d d=%d RoPE causal, %d prompts x %d tokens, "
                     "T=%d p=%g (hs=%d)" % (cfg.name, h, f, cfg.n_heads, cfg.kv_heads, cfg.head_dim, cfg.batch, s, T, cfg.p,
-                                           cfg.hs))
+                                           hs_of(cfg)))
     else:
         bench = DecodeBench(cfg)
         fr = cfg.f_r
@@ -393,14 +399,14 @@ def bench_attention_kinds(args, cfg, base):
         w_bytes = 2.0 * T * (3 * hd * h + h * hd + 2 * fr * h + h * fr)
         fl = {}
         by = {"decode_attn": kv_bytes, "gemm_nt_qkv": 2.0 * T * 3 * hd * h, "gemm_nt_swiglu_fwd": 2.0 * T * 2 * fr * h,
-              "gemm_nt_rowpar": 2.0 * T * (h * hd + h * fr) / 2, "partial_sync_fwd": 3.0 * T * n * cfg.hs * 2,
+              "gemm_nt_rowpar": 2.0 * T * (h * hd + h * fr) / 2, "partial_sync_fwd": 3.0 * T * n * hs_of(cfg) * 2,
               "norm_fwd": 2.0 * T * n * h * 2,
               # reduce + residual + RMSNorm in one launch: T partials and T residual slices and the private columns read,
               # R' shared columns and the whole normalised copy written
-              "partial_sync_norm_fwd": (3.0 * T * n * cfg.hs + T * n * (h - cfg.hs) + T * n * h) * 2}
+              "partial_sync_norm_fwd": (3.0 * T * n * hs_of(cfg) + T * n * (h - hs_of(cfg)) + T * n * h) * 2}
         work, unit, peak = kv_bytes + w_bytes, "GB/s", HBM_PEAK_GBS
         workload = "%s decode layer: h=%d ffn=%d heads=%d d=%d batch=%d kv_len=%d T=%d p=%g (hs=%d)" % (
-            cfg.name, h, cfg.ffn, cfg.n_heads, cfg.head_dim, cfg.batch, cfg.kv_len, T, cfg.p, cfg.hs)
+            cfg.name, h, cfg.ffn, cfg.n_heads, cfg.head_dim, cfg.batch, cfg.kv_len, T, cfg.p, hs_of(cfg))
     desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm, dedup_shared=args.dedup_shared)
     ms, wall_ms = bench.time_steps(desc, args.steps, args.warmup)
     prof = bench.profile_steps(desc, max(3, min(args.steps, 10)))
@@ -452,11 +458,11 @@ def bench_attention_kinds(args, cfg, base):
             c_fit = (12.0 * h + 2.0 * cfg.seq) / (T * (1.0 / s0 - 1.0)) if 0.0 < s0 < 1.0 else None
             for p in (1.0, 0.5, 0.25, 0.0):
                 c = base.with_(p=p)
-                sweep.append({"p": p, "hs": c.hs, "ms_per_layer": round(t[p], 4), "ttft_ms_%d_layers" % layers: round(t[p] * layers, 2),
+                sweep.append({"p": p, "hs": hs_of(c), "ms_per_layer": round(t[p], 4), "ttft_ms_%d_layers" % layers: round(t[p] * layers, 2),
                               "TFLOP/s": round(work / t[p] / 1e9, 1),
                               "speedup_vs_p1_measured": round((t[1.0] - t[p]) / t[1.0], 5),
                               "speedup_vs_p1_model": round((1.0 - p) * s0, 5),
-                              "synced_payload_bytes_per_token_per_layer": 2 * 2 * c.hs})
+                              "synced_payload_bytes_per_token_per_layer": 2 * 2 * hs_of(c)})
             out["analytic_model"] = {"form": "(T(1)-T(p))/T(1) = (1-p) / (1 + (12h+2s)/(C r)), G = (24sh^2+4s^2h)/r, P(p) = 2shp",
                                      "r": T, "h": h, "s": cfg.seq, "C_fitted_from_p1_and_p0": c_fit,
                                      "p_star_at_fitted_C": None if c_fit is None else min((12.0 * h + 2.0 * cfg.seq) / (c_fit * T), 1.0)}
@@ -471,8 +477,8 @@ def bench_attention_kinds(args, cfg, base):
             for p in (1.0, 0.5, 0.25, 0.0):
                 c = base.with_(p=p)
                 ms_p, _ = bench.time_steps(B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm), args.steps, args.warmup)
-                sweep.append({"p": p, "hs": c.hs, "ms_per_step": round(ms_p, 5), "GB/s": round(work / ms_p / 1e6, 1),
-                              "synced_payload_bytes_per_token_per_reduce": 2 * c.hs})
+                sweep.append({"p": p, "hs": hs_of(c), "ms_per_step": round(ms_p, 5), "GB/s": round(work / ms_p / 1e6, 1),
+                              "synced_payload_bytes_per_token_per_reduce": 2 * hs_of(c)})
         out["p_sweep"] = sweep
     return out
 
@@ -577,7 +583,7 @@ def main():
     kernels = {}
     for name, v in prof.items():
         e = {"avg_ms": round(v["avg_ms"], 5), "launches_per_step": v["launches_per_step"]}
-        fl, by = flops_per_launch(name, cfg), sync_bytes(name, cfg, cfg.hs)
+        fl, by = flops_per_launch(name, cfg), sync_bytes(name, cfg, hs_of(cfg))
         if fl:
             e["TFLOP/s"] = round(fl / v["avg_ms"] / 1e9, 1)
             e["frac_mfma_peak"] = round(fl / v["avg_ms"] / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)
@@ -593,16 +599,16 @@ def main():
             dsc = B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm)
             ms_p, _ = bench.time_steps(dsc, args.steps, args.warmup)   # same warm-up as the headline: the clocks ramp
             pr = bench.profile_steps(dsc, 5)
-            sa_ms, sa_gbs = standalone_sync(torch, B, c, c.hs)
-            e = {"p": p, "hs": c.hs, "ms_per_step": round(ms_p, 4), "TFLOP/s": round(step_flops / ms_p / 1e9, 1),
-                 "synced_payload_bytes_per_token_per_reduce": 2 * c.hs,
-                 "in_hbm_sync_bytes_per_token_fwd": 6 * c.T * c.hs, "in_hbm_sync_bytes_per_token_bwd": 4 * c.T * c.hs,
+            sa_ms, sa_gbs = standalone_sync(torch, B, c, hs_of(c))
+            e = {"p": p, "hs": hs_of(c), "ms_per_step": round(ms_p, 4), "TFLOP/s": round(step_flops / ms_p / 1e9, 1),
+                 "synced_payload_bytes_per_token_per_reduce": 2 * hs_of(c),
+                 "in_hbm_sync_bytes_per_token_fwd": 6 * c.T * hs_of(c), "in_hbm_sync_bytes_per_token_bwd": 4 * c.T * hs_of(c),
                  "standalone_sync_ms": round(sa_ms, 5), "standalone_sync_GB/s": round(sa_gbs, 1),
                  "standalone_sync_frac_hbm": round(sa_gbs / HBM_PEAK_GBS, 4)}
             for nm in ("partial_sync_fwd", "partial_sync_bwd"):
                 if nm in pr:
                     e[nm + "_ms"] = round(pr[nm]["avg_ms"], 5)
-                    e[nm + "_GB/s"] = round(sync_bytes(nm, c, c.hs) / pr[nm]["avg_ms"] / 1e6, 1)
+                    e[nm + "_GB/s"] = round(sync_bytes(nm, c, hs_of(c)) / pr[nm]["avg_ms"] / 1e6, 1)
                 else:
                     e[nm + "_ms"] = 0.0
             sweep.append(e)
@@ -633,7 +639,7 @@ def main():
         "config": {"workload": "%s MLP block fwd+bwd: h=%d ffn=%d %s %s T=%d p=%g (hs=%d) tokens=%d, seed 0, "
                                "x~N(0,1) w~N(0,0.02^2)" % (cfg.name, cfg.h, cfg.ffn, "SwiGLU" if k == 3 else "GELU",
                                                             "LayerNorm" if cfg.norm == 0 else "RMSNorm", cfg.T, cfg.p,
-                                                            cfg.hs, cfg.tokens),
+                                                            hs_of(cfg), cfg.tokens),
                    "flops_per_step": step_flops, "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,
                    "wall_ms_per_step": wall_ms},
         "roofline": roofline, "kernels": kernels, "p_sweep": sweep, "sync_time_vs_p_fit": sync_fit,

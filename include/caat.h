@@ -96,6 +96,11 @@ typedef struct caat_desc {
                            kinds' internal residual) store the shared channels ONCE instead of T identical copies:
                            [tokens, hs] followed by the private channels [T, tokens, h - hs], one contiguous buffer of
                            tokens*hs + T*tokens*(h-hs) elements.  x / x_out keep the [T, tokens, h] layout. */
+  int separate_reduce;  /* 0: where the shape allows (see caat_partial_sync_norm_fwd) the reduce over ranks, the residual
+                           add and the norm that follows run as ONE kernel, which does not read the reduced channels
+                           back from memory.  1: the reduce stays a kernel of its own (caat_partial_sync's kernel, the
+                           in-HBM stand-in for the tensor-parallel collective, whose time against p is what the
+                           benchmark's sweep reports) followed by the norm kernel.  Same values either way. */
 } caat_desc;
 
 /* Byte offsets of the tensors caat_block_fwd leaves in the workspace (0 size = not present).  For tests
@@ -157,13 +162,30 @@ int caat_norm_fwd(const void* x, const void* gamma, const void* beta, void* y, f
                   int norm, int T, long long tokens, int h, float eps, void* hip_stream);
 
 /*
+ * The shared half of the partial channel-reduce, the residual add and the norm in one launch (Eq. A3 / A5 second
+ * line + Sec. 4: X'_m = Norm(R_m + Z_m)), the unit the block calls use after a row-parallel GEMM whose epilogue has
+ * already finished the private channels:
+ *   io [T,tokens,h] on entry : channels l <  hs: rank m's partial sum Zt_m[:,l];  l >= hs: the final R'_m[:,l]
+ *   io on return             : R'_m everywhere: for l < hs  sum_{m'} Zt_m'[:,l] + resid[m,:,l] (fp32 sum in ascending
+ *                              rank order, residual added, rounded once)
+ *   x_out [T,tokens,h]       : Norm(R'_m) with gamma (and beta for LayerNorm, NULL for RMSNorm)
+ *   mean (LayerNorm; may be NULL), rstd : [T,tokens] fp32
+ * resid [T,tokens,h] is read on the shared channels only.  Shapes taken: hs > 0 and hs % 8 == 0, T in {2,4,8} with
+ * h <= 8192, or T = 16 with h <= 4096 (a thread keeps its columns of all T rows in registers); anything else
+ * returns CAAT_EUNSUPPORTED and the caller runs caat_partial_sync and caat_norm_fwd instead.
+ */
+int caat_partial_sync_norm_fwd(void* io, const void* resid, const void* gamma, const void* beta, void* x_out,
+                               float* mean, float* rstd, int norm, int T, long long tokens, int h, int hs, float eps,
+                               void* hip_stream);
+
+/*
  * Backward of the norm placed BEFORE the reduce (Sec. 4, Fig. 2b):
  *   g[m] = dres[m] + NormBwd(dy[m]; x[m], gamma)                (dres may be NULL)
  * g is written to `g_out` (the un-reduced residual gradient, App. B) and, if `g_scaled` is not NULL,
  * also to `g_scaled` with its private columns (l >= hs) multiplied by private_scale -- the buffer the
  * backward partial channel-reduce then runs on in place.  dgamma/dbeta: [h] fp32, summed over tokens AND
  * over ranks in a fixed order (Sec. 4: norm parameters are replicated, their gradients reduced).
- * dbeta may be NULL for RMSNorm.  workspace: at least caat_norm_bwd_workspace_bytes() bytes.
+ * dbeta is neither read nor written for RMSNorm (may be NULL).  workspace: at least caat_norm_bwd_workspace_bytes() bytes.
  */
 size_t caat_norm_bwd_workspace_bytes(int T, long long tokens, int h);
 int caat_norm_bwd(const void* dy, const void* dres, const void* x, const void* gamma, const float* mean,
@@ -217,33 +239,6 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
 int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x, const void* r_out,
                    void* workspace, size_t ws_bytes, const void* dx_out, const void* dr_out, void* dx, void* dr,
                    void* const* dweights, float* dgamma, float* dbeta, void* hip_stream);
-
-/*
- * Per-launch timing of the block calls (a host-side measuring tool, not part of the method): while enabled,
- * caat_block_fwd / caat_block_bwd bracket every kernel they enqueue with a pair of HIP events on the caller's
- * stream.  caat_profile_get waits for record `index` (in launch order since the last reset) and returns a
- * static kernel-family name (host pointer to a NUL-terminated string) and the elapsed milliseconds.  Events
- * are created on first use and reused after a reset.  Not thread-safe; off by default.
- */
-int caat_profile_enable(int on);
-int caat_profile_reset(void);
-int caat_profile_count(void);
-int caat_profile_get(int index, const char** name, float* ms);
-
-/*
- * HBM streaming probe (a measuring tool, not part of the method): enqueues one kernel that reads `bytes` bytes of
- * the device buffer `src` (16-byte aligned, bytes % 16 == 0) and, for the copy modes, writes them to `dst`.
- *   mode 0: read, every workgroup walks its own contiguous piece, plain loads
- *   mode 1: the same with the non-temporal hint on the loads
- *   mode 2: read, the whole grid sweeps one window (grid-stride), plain loads
- *   mode 3: copy src -> dst, contiguous piece per workgroup, plain loads and stores
- *   mode 4: the same with the non-temporal hint on loads and stores
- * dst may be NULL for the read modes (a result is only stored if the data hash to one particular value, which
- * keeps the loads alive; pass a buffer of at least 16 bytes to be safe).  The caller times it with events on
- * `hip_stream`; bench.py --probe-hbm does.  This is where the cache-policy choices of the streaming kernels
- * (which accesses carry the hint) were measured.
- */
-int caat_hbm_probe(const void* src, void* dst, size_t bytes, int mode, void* hip_stream);
 
 #ifdef __cplusplus
 }

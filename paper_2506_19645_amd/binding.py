@@ -31,7 +31,8 @@ class caat_desc(C.Structure):
     _fields_ = [("kind", C.c_int), ("norm", C.c_int), ("h", C.c_int), ("ffn", C.c_int), ("T", C.c_int),
                 ("hs", C.c_int), ("tokens", C.c_longlong), ("batch", C.c_int), ("seq", C.c_int),
                 ("n_heads", C.c_int), ("head_dim", C.c_int), ("kv_len", C.c_longlong), ("kv_cap", C.c_longlong),
-                ("eps", C.c_float), ("private_scale", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int), ("reduce_in_gemm", C.c_int), ("dedup_shared", C.c_int)]
+                ("eps", C.c_float), ("private_scale", C.c_float), ("rope_base", C.c_float), ("n_kv_heads", C.c_int),
+                ("reduce_in_gemm", C.c_int), ("dedup_shared", C.c_int), ("separate_reduce", C.c_int)]
 
 
 class caat_ws_layout(C.Structure):
@@ -41,10 +42,11 @@ class caat_ws_layout(C.Structure):
         "off_X1", "bytes_X1", "off_R1", "bytes_R1", "off_X2", "bytes_X2", "off_stats", "bytes_stats", "off_dH", "bytes_dH")]
 
 
+# the method's C ABI (include/caat.h) and the measuring tools the library exports beside it (csrc/caat_tools.h)
 EXPORTS = ["caat_shared_channels", "caat_status_string", "caat_workspace_bytes", "caat_workspace_layout",
-           "caat_partial_sync", "caat_norm_fwd", "caat_norm_bwd_workspace_bytes", "caat_norm_bwd", "caat_gemm_bf16",
-           "caat_block_fwd", "caat_block_bwd", "caat_profile_enable", "caat_profile_reset", "caat_profile_count",
-           "caat_profile_get", "caat_hbm_probe"]
+           "caat_partial_sync", "caat_norm_fwd", "caat_partial_sync_norm_fwd", "caat_norm_bwd_workspace_bytes",
+           "caat_norm_bwd", "caat_gemm_bf16", "caat_block_fwd", "caat_block_bwd"]
+TOOL_EXPORTS = ["caat_profile_enable", "caat_profile_reset", "caat_profile_count", "caat_profile_get", "caat_hbm_probe"]
 
 _lib = None
 
@@ -69,6 +71,8 @@ def lib() -> C.CDLL:
         L.caat_partial_sync.restype = i
         L.caat_norm_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, ll, i, f, vp]
         L.caat_norm_fwd.restype = i
+        L.caat_partial_sync_norm_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, ll, i, i, f, vp]
+        L.caat_partial_sync_norm_fwd.restype = i
         L.caat_norm_bwd_workspace_bytes.argtypes = [i, ll, i]
         L.caat_norm_bwd_workspace_bytes.restype = sz
         L.caat_norm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, ll, i, i, f, vp, sz, vp]
@@ -134,16 +138,19 @@ def to_host_bits(t) -> np.ndarray:
 
 
 def make_desc(cfg, hs: Optional[int] = None, kv_cap: Optional[int] = None, reduce_in_gemm: bool = False,
-              dedup_shared: bool = False) -> caat_desc:
+              dedup_shared: bool = False, separate_reduce: bool = False) -> caat_desc:
     """caat_desc from a paper_2506_19645_amd.inputs.BlockConfig (cache capacity: one position more than what the
-    call fills, unless given)."""
+    call fills, unless given; shared-channel count from caat_shared_channels(h, p), unless given)."""
     if kv_cap is None:
         kv_cap = cfg.seq + 1 if cfg.kind == LAYER_PREFILL else cfg.kv_len + 1
+    if hs is None:
+        hs = shared_channels(cfg.h, float(cfg.p))     # the library's own floor(h*p), Eq. A3
     return caat_desc(kind=cfg.kind, norm=cfg.norm, h=cfg.h, ffn=cfg.ffn, T=cfg.T,
-                     hs=cfg.hs if hs is None else hs, tokens=cfg.tokens, batch=cfg.batch, seq=cfg.seq,
+                     hs=hs, tokens=cfg.tokens, batch=cfg.batch, seq=cfg.seq,
                      n_heads=cfg.n_heads, head_dim=cfg.head_dim, kv_len=cfg.kv_len, kv_cap=kv_cap,
                      eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base,
-                     n_kv_heads=getattr(cfg, "n_kv_heads", 0), reduce_in_gemm=1 if reduce_in_gemm else 0, dedup_shared=1 if dedup_shared else 0)
+                     n_kv_heads=getattr(cfg, "n_kv_heads", 0), reduce_in_gemm=1 if reduce_in_gemm else 0,
+                     dedup_shared=1 if dedup_shared else 0, separate_reduce=1 if separate_reduce else 0)
 
 
 # ------------------------------------------------------------------ entry points (same names as the C ABI)
@@ -179,6 +186,15 @@ def norm_fwd(x, gamma, beta, y, mean, rstd, norm: int, T: int, tokens: int, h: i
                              eps, _stream(stream))
     if check:
         _check(st, "caat_norm_fwd")
+    return st
+
+
+def partial_sync_norm_fwd(io, resid, gamma, beta, x_out, mean, rstd, norm: int, T: int, tokens: int, h: int, hs: int,
+                          eps: float, stream=None, check: bool = True) -> int:
+    st = lib().caat_partial_sync_norm_fwd(_ptr(io), _ptr(resid), _ptr(gamma), _ptr(beta), _ptr(x_out), _ptr(mean),
+                                          _ptr(rstd), norm, T, tokens, h, hs, eps, _stream(stream))
+    if check:
+        _check(st, "caat_partial_sync_norm_fwd")
     return st
 
 

@@ -1,6 +1,7 @@
 // C ABI of libcaat: host-side argument validation and the launch sequences of the block forward / backward.
 // No device memory is allocated here; everything is enqueued on the caller's stream.
 #include "../../include/caat.h"
+#include "caat_tools.h"
 #include "caat_internal.h"
 
 #include <cmath>
@@ -64,6 +65,7 @@ int validate_desc(const caat_desc* d) {
   if (!(d->eps >= 0.0f) || std::isnan(d->private_scale)) return CAAT_EINVAL;
   if (d->reduce_in_gemm != 0 && d->reduce_in_gemm != 1) return CAAT_EINVAL;
   if (d->dedup_shared != 0 && d->dedup_shared != 1) return CAAT_EINVAL;
+  if (d->separate_reduce != 0 && d->separate_reduce != 1) return CAAT_EINVAL;
   // the de-duplicated layout exists only where the shared channels are produced once: reduce inside the GEMM, whole
   // 16-byte groups of shared channels, more than 64 tokens, and not for the decode step
   if (d->dedup_shared && (!d->reduce_in_gemm || d->hs % 8 != 0 || d->tokens <= 64 || d->kind == CAAT_ATTN_DECODE))
@@ -130,6 +132,12 @@ int layout_of(const caat_desc* d, caat_ws_layout* L) {
   }
   L->total_bytes = off;
   return CAAT_OK;
+}
+
+// The reduce over ranks, the residual add and the norm run as one kernel where its shape is taken and the caller has
+// not asked for the reduce as a kernel of its own; the folded-into-the-GEMM serving modes have no reduce pass at all.
+bool fuse_reduce_norm(const caat_desc* d) {
+  return !d->separate_reduce && !d->reduce_in_gemm && !d->dedup_shared && sync_norm_takes(d->T, d->tokens, d->h, d->hs);
 }
 
 // Row-parallel projection closed by the partial channel-reduce and the residual add (Eq. A3 / A5, second line + Sec. 4):
@@ -247,11 +255,16 @@ int attn_block_fwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
     e = launch_flash_fwd(QKV, H, stats, T * d->batch, d->seq, hpr, kvpr, d->head_dim, s);
   }
   if (e != hipSuccess) return CAAT_EHIP;
+  const bool fuse = fuse_reduce_norm(d);
   {
-    const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, (bf16_t*)r_out, s);
+    const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, (bf16_t*)r_out, s, fuse);
     if (st != CAAT_OK) return st;
   }
-  {
+  if (fuse) {
+    ProfScope ps(s, "partial_sync_norm_fwd");
+    e = launch_sync_norm((bf16_t*)r_out, (const bf16_t*)r, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd,
+                         d->norm, (int)T, n, (int)h, d->hs, d->eps, s);
+  } else {
     ProfScope ps(s, "norm_fwd");
     e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd, d->norm,
                         (int)T, n, (int)h, d->eps, s, dedup_hs(d));
@@ -390,15 +403,14 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
   // the reduce after o_proj and the RMSNorm in front of the MLP run as one launch where the fused kernel takes the
   // shape: for decode-sized batches both are start-up latency, for prompts the fused kernel does not read the
   // reduced shared channels back from memory (measured 1.28 ms instead of 0.61 + 0.78 ms on 16 prompts of 2048)
-  const bool fuse_mid = d->hs > 0 && d->hs % 8 == 0 && (T == 2 || T == 4 || T == 8) && h <= 8192 &&
-                        !d->reduce_in_gemm && dedup_hs(d) == 0;
+  const bool fuse_mid = fuse_reduce_norm(d);
   {
     const int st = rowpar_pcr(d, H, hd, (const bf16_t*)wo, (const bf16_t*)r, R1, s, fuse_mid);
     if (st != CAAT_OK) return st;
   }
   if (fuse_mid) {
-    CAAT_STEP("partial_sync_norm_fwd", launch_sync_rmsnorm(R1, (const bf16_t*)r, (const bf16_t*)g_mlp, X2, rstd, (int)T, n, (int)h,
-                                                           d->hs, d->eps, s))
+    CAAT_STEP("partial_sync_norm_fwd", launch_sync_norm(R1, (const bf16_t*)r, (const bf16_t*)g_mlp, nullptr, X2, nullptr, rstd,
+                                                        CAAT_RMSNORM, (int)T, n, (int)h, d->hs, d->eps, s))
   } else {
     CAAT_STEP("norm_fwd", launch_norm_fwd(R1, (const bf16_t*)g_mlp, nullptr, X2, nullptr, rstd, CAAT_RMSNORM, (int)T, n, (int)h,
                                           d->eps, s, dedup_hs(d)))
@@ -502,6 +514,20 @@ int caat_norm_fwd(const void* x, const void* gamma, const void* beta, void* y, f
                                     norm, T, tokens, h, eps, (hipStream_t)hip_stream));
 }
 
+int caat_partial_sync_norm_fwd(void* io, const void* resid, const void* gamma, const void* beta, void* x_out, float* mean,
+                               float* rstd, int norm, int T, long long tokens, int h, int hs, float eps, void* hip_stream) {
+  if (!io || !resid || !gamma || !x_out || !rstd || T < 1 || tokens < 0 || h < 1 || !(eps >= 0.0f)) return CAAT_EINVAL;
+  if (norm != CAAT_LAYERNORM && norm != CAAT_RMSNORM) return CAAT_EINVAL;
+  if (norm == CAAT_LAYERNORM && !beta) return CAAT_EINVAL;
+  if (h % 8 != 0 || h > 8192 || hs < 0 || hs > h) return CAAT_ESHAPE;
+  if (misaligned(io) || misaligned(resid) || misaligned(gamma) || misaligned(x_out) || (beta && misaligned(beta)))
+    return CAAT_EALIGN;
+  if (tokens == 0) return CAAT_OK;
+  if (!sync_norm_takes(T, tokens, h, hs)) return CAAT_EUNSUPPORTED;
+  return hip_status(launch_sync_norm((bf16_t*)io, (const bf16_t*)resid, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out,
+                                     mean, rstd, norm, T, tokens, h, hs, eps, (hipStream_t)hip_stream));
+}
+
 size_t caat_norm_bwd_workspace_bytes(int T, long long tokens, int h) {
   if (T < 1 || tokens < 0 || h < 1) return 0;
   return norm_bwd_workspace_bytes(T, tokens, h);
@@ -593,12 +619,18 @@ int caat_block_fwd(const caat_desc* d, const void* const* weights, const void* x
   // a2 + a3/a4: Zt_m = Y_m B_m^T closed by the partial channel-reduce and the residual.  Default: columns >= hs
   // become scale*Zt + R in the GEMM epilogue (final), columns < hs hold the rank's partial sum inside r_out until the
   // reduce kernel sums the T partials on the hs shared channels and adds each rank's residual, in place.
+  // a5: per-rank norm on the now rank-divergent residual stream; where the shape allows (and unless the caller wants
+  // the reduce as a kernel of its own) the shared half of the reduce, the residual add and the norm are one launch
+  const bool fuse = fuse_reduce_norm(d);
   {
-    const int st2 = rowpar_pcr(d, Y, fr, (const bf16_t*)w1, (const bf16_t*)r, (bf16_t*)r_out, s);
+    const int st2 = rowpar_pcr(d, Y, fr, (const bf16_t*)w1, (const bf16_t*)r, (bf16_t*)r_out, s, fuse);
     if (st2 != CAAT_OK) return st2;
   }
-  // a5: per-rank norm on the now rank-divergent residual stream
-  {
+  if (fuse) {
+    ProfScope ps(s, "partial_sync_norm_fwd");
+    e = launch_sync_norm((bf16_t*)r_out, (const bf16_t*)r, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd,
+                         d->norm, (int)T, n, (int)h, d->hs, d->eps, s);
+  } else {
     ProfScope ps(s, "norm_fwd");
     e = launch_norm_fwd((const bf16_t*)r_out, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)x_out, mean, rstd,
                         d->norm, (int)T, n, (int)h, d->eps, s, dedup_hs(d));

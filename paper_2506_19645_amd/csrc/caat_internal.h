@@ -80,18 +80,25 @@ __device__ __forceinline__ unsigned lds_addr(const void* p) {
 // Written as inline assembly on purpose: the compiler then does not know that LDS is written by a vector-memory
 // operation and does not force "wait for every outstanding copy" in front of each later LDS read; the kernel
 // orders copies and reads itself (wait_vmcnt + barrier), which is what lets NSTAGE-1 stages stay in flight.
+// The copy takes its LDS base from M0.  M0 is a reserved register for this compiler (it cannot be named in a clobber
+// list), so every statement saves M0 into a scalar temporary first and puts it back after its last copy: from the
+// compiler's point of view M0 is unchanged, whatever it keeps there (indirect register indexing, lane reads).  The
+// copies read M0 when they issue, in order, so the restoring move right behind them is safe.
 // STREAM: non-temporal hint, for bytes that no other workgroup will ask for (a read-once stream keeps 7.1 TB/s
 // against 6.2 TB/s without the hint); operands that several workgroups share stay cacheable.
 template <bool STREAM = false>
 __device__ __forceinline__ void dma16(i32x4_t rs, unsigned voff, const uint4* lds_wave_uniform) {
+  unsigned keep;  // M0 as the compiler left it
   if constexpr (STREAM)
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen nt lds"
-                 :
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen nt lds\n\t"
+                 "s_mov_b32 m0, %0"
+                 : "=&s"(keep)
                  : "v"(voff), "s"(rs), "s"(lds_addr(lds_wave_uniform))
                  : "memory");
   else
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
-                 :
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds\n\t"
+                 "s_mov_b32 m0, %0"
+                 : "=&s"(keep)
                  : "v"(voff), "s"(rs), "s"(lds_addr(lds_wave_uniform))
                  : "memory");
 }
@@ -103,36 +110,41 @@ __device__ __forceinline__ void dma16(i32x4_t rs, unsigned voff, const uint4* ld
 template <bool STREAM, int G>
 __device__ __forceinline__ void dma16_group(i32x4_t rs, const unsigned* v, const uint4* lds_wave_uniform) {
   static_assert(G == 1 || G == 2 || G == 4, "group of 1, 2 or 4 copies");
+  unsigned keep;
   if constexpr (G == 1) {
     dma16<STREAM>(rs, v[0], lds_wave_uniform);
   } else if constexpr (G == 2) {
     if constexpr (STREAM)
-      asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %2, 0 offen nt lds\n\t"
-                   "buffer_load_dwordx4 %1, %2, 0 offen offset:1024 nt lds"
-                   :
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %4\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %3, 0 offen nt lds\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 nt lds\n\t"
+                   "s_mov_b32 m0, %0"
+                   : "=&s"(keep)
                    : "v"(v[0]), "v"(v[1]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
                    : "memory");
     else
-      asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %2, 0 offen lds\n\t"
-                   "buffer_load_dwordx4 %1, %2, 0 offen offset:1024 lds"
-                   :
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %4\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %3, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %2, %3, 0 offen offset:1024 lds\n\t"
+                   "s_mov_b32 m0, %0"
+                   : "=&s"(keep)
                    : "v"(v[0]), "v"(v[1]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
                    : "memory");
   } else {
     if constexpr (STREAM)
-      asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %4, 0 offen nt lds\n\t"
-                   "buffer_load_dwordx4 %1, %4, 0 offen offset:1024 nt lds\n\t"
-                   "buffer_load_dwordx4 %2, %4, 0 offen offset:2048 nt lds\n\t"
-                   "buffer_load_dwordx4 %3, %4, 0 offen offset:3072 nt lds"
-                   :
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %6\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %5, 0 offen nt lds\n\t"
+                   "buffer_load_dwordx4 %2, %5, 0 offen offset:1024 nt lds\n\t"
+                   "buffer_load_dwordx4 %3, %5, 0 offen offset:2048 nt lds\n\t"
+                   "buffer_load_dwordx4 %4, %5, 0 offen offset:3072 nt lds\n\t"
+                   "s_mov_b32 m0, %0"
+                   : "=&s"(keep)
                    : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
                    : "memory");
     else
-      asm volatile("s_mov_b32 m0, %5\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %4, 0 offen lds\n\t"
-                   "buffer_load_dwordx4 %1, %4, 0 offen offset:1024 lds\n\t"
-                   "buffer_load_dwordx4 %2, %4, 0 offen offset:2048 lds\n\t"
-                   "buffer_load_dwordx4 %3, %4, 0 offen offset:3072 lds"
-                   :
+      asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %6\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %5, 0 offen lds\n\t"
+                   "buffer_load_dwordx4 %2, %5, 0 offen offset:1024 lds\n\t"
+                   "buffer_load_dwordx4 %3, %5, 0 offen offset:2048 lds\n\t"
+                   "buffer_load_dwordx4 %4, %5, 0 offen offset:3072 lds\n\t"
+                   "s_mov_b32 m0, %0"
+                   : "=&s"(keep)
                    : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "s"(rs), "s"(lds_addr(lds_wave_uniform))
                    : "memory");
   }
@@ -197,10 +209,12 @@ hipError_t launch_partial_sync_shared(bf16_t* io, const bf16_t* resid, int T, lo
 hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* beta, bf16_t* y, float* mean,
                            float* rstd, int norm, int T, long long tokens, int h, float eps, hipStream_t s,
                            int dedup_hs = 0);
-// reduce on the shared channels + residual + RMSNorm in one launch for decode-sized batches (T in {2,4,8}, hs % 8 == 0,
-// h <= 8192); hipErrorInvalidValue if the shape is not taken
-hipError_t launch_sync_rmsnorm(bf16_t* io, const bf16_t* resid, const bf16_t* gamma, bf16_t* xout, float* rstd, int T,
-                               long long tokens, int h, int hs, float eps, hipStream_t s);
+// reduce on the shared channels + residual + norm in one launch (hs % 8 == 0; T in {2,4,8} with h <= 8192, T = 16 with
+// h <= 4096: sync_norm_takes); hipErrorInvalidValue if the shape is not taken
+bool sync_norm_takes(int T, long long tokens, int h, int hs);
+hipError_t launch_sync_norm(bf16_t* io, const bf16_t* resid, const bf16_t* gamma, const bf16_t* beta, bf16_t* xout,
+                            float* mean, float* rstd, int norm, int T, long long tokens, int h, int hs, float eps,
+                            hipStream_t s);
 size_t norm_bwd_workspace_bytes(int T, long long tokens, int h);
 hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
                            const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,

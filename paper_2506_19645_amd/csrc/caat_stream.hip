@@ -284,20 +284,21 @@ hipError_t launch_norm_fwd(const bf16_t* x, const bf16_t* gamma, const bf16_t* b
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Serving layers: the reduce and the RMSNorm that follows it in one launch.  For decode-sized batches (a few dozen
-// tokens) the two launches are start-up latency, not traffic; for prompts the fused kernel saves reading the reduced
-// shared channels back.  One workgroup owns one token of ALL ranks: it sums the T
-// partial vectors of the shared channels in ascending rank order, adds each rank's residual, rounds once and
-// stores R' (exactly what partial_sync_kernel does), keeps every rank's row (rounded values, packed) in registers,
-// and then normalises each rank's row with its own statistics (what norm_fwd_kernel does on R').  hs % 8 == 0,
-// h <= 8192, RMSNorm only.
-template <int TT>
-__global__ __launch_bounds__(256) void sync_rmsnorm_kernel(bf16_t* io, const bf16_t* __restrict__ resid,
-                                                           const bf16_t* __restrict__ gamma, bf16_t* __restrict__ xout,
-                                                           float* __restrict__ rstd, long long n, int h, int hs,
-                                                           float eps) {
-  constexpr int NG = 4;                                  // 16-byte column groups per thread: h <= 8192
-  __shared__ float red[4][TT];
+// The reduce and the norm that follows it in one launch (Eq. A3 / A5 second line + Sec. 4: X'_m = Norm(R_m + Z_m)).
+// For decode-sized batches (a few dozen tokens) the two launches are start-up latency, not traffic; for prompts and
+// training batches the fused kernel saves reading the reduced shared channels back.  One workgroup owns one token of
+// ALL ranks: it sums the T partial vectors of the shared channels in ascending rank order, adds each rank's residual,
+// rounds once and stores R' (exactly what partial_sync_kernel does), keeps every rank's row (rounded values, packed)
+// in registers, and then normalises each rank's row with its own statistics (what norm_fwd_kernel does on R':
+// RMSNorm, or LayerNorm with the two-pass variance).  hs % 8 == 0; a thread holds NG 16-byte column groups of every
+// rank's row (h <= 2048 NG), so the register budget is NG*TT*4: T = 16 is taken up to h = 4096.
+template <int TT, int NG, bool LN>
+__global__ __launch_bounds__(256) void sync_norm_kernel(bf16_t* io, const bf16_t* __restrict__ resid,
+                                                        const bf16_t* __restrict__ gamma,
+                                                        const bf16_t* __restrict__ beta, bf16_t* __restrict__ xout,
+                                                        float* __restrict__ mean, float* __restrict__ rstd,
+                                                        long long n, int h, int hs, float eps) {
+  __shared__ float red[2][4][TT];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long i = blockIdx.x;                        // token
   const long long plane = n * (long long)h;
@@ -313,24 +314,26 @@ __global__ __launch_bounds__(256) void sync_rmsnorm_kernel(bf16_t* io, const bf1
       const int col = vi * 8;
       const long long off = i * h + col;
       if (col < hs) {                                     // shared channels (hs is a multiple of 8)
-        uint4 pv[TT], rv[TT];
-#pragma unroll
-        for (int m = 0; m < TT; ++m) {
-          pv[m] = *reinterpret_cast<const uint4*>(io + m * plane + off);
-          rv[m] = *reinterpret_cast<const uint4*>(resid + m * plane + off);
-        }
         float sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        {
+          uint4 pv[TT];   // the T partials and the T residual vectors are requested together
 #pragma unroll
-        for (int m = 0; m < TT; ++m) {
-          float f[8];
-          unpack8(pv[m], f);
+          for (int m = 0; m < TT; ++m) {
+            pv[m] = *reinterpret_cast<const uint4*>(io + m * plane + off);
+            val[g][m] = *reinterpret_cast<const uint4*>(resid + m * plane + off);
+          }
 #pragma unroll
-          for (int e = 0; e < 8; ++e) sum[e] += f[e];
+          for (int m = 0; m < TT; ++m) {
+            float f[8];
+            unpack8(pv[m], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[e] += f[e];
+          }
         }
 #pragma unroll
         for (int m = 0; m < TT; ++m) {
           float r[8], o[8];
-          unpack8(rv[m], r);
+          unpack8(val[g][m], r);
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = sum[e] + r[e];
           val[g][m] = pack8(o);
@@ -345,59 +348,130 @@ __global__ __launch_bounds__(256) void sync_rmsnorm_kernel(bf16_t* io, const bf1
         float f[8];
         unpack8(val[g][m], f);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ss[m] += f[e] * f[e];
+        for (int e = 0; e < 8; ++e) ss[m] += LN ? f[e] : f[e] * f[e];
       }
     } else {
 #pragma unroll
       for (int m = 0; m < TT; ++m) val[g][m] = make_uint4(0u, 0u, 0u, 0u);
     }
   }
+  // workgroup sums of the T rows: wave sums, then the four waves in a fixed order
+  auto block_sums = [&](float* v, int slot) {
 #pragma unroll
-  for (int m = 0; m < TT; ++m) {
-    const float w = wave_sum(ss[m]);
-    if (lane == 0) red[wave][m] = w;
-  }
-  __syncthreads();
-  float rs[TT];
+    for (int m = 0; m < TT; ++m) {
+      const float w = wave_sum(v[m]);
+      if (lane == 0) red[slot][wave][m] = w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < TT; ++m) v[m] = ((red[slot][0][m] + red[slot][1][m]) + red[slot][2][m]) + red[slot][3][m];
+  };
   const float inv_h = 1.0f / (float)h;
+  block_sums(ss, 0);
+  float mu[TT], rs[TT];
+  if constexpr (LN) {
+    float q[TT];
 #pragma unroll
-  for (int m = 0; m < TT; ++m) {
-    const float tot = ((red[0][m] + red[1][m]) + red[2][m]) + red[3][m];
-    rs[m] = rsqrtf(tot * inv_h + eps);
+    for (int m = 0; m < TT; ++m) {
+      mu[m] = ss[m] * inv_h;
+      q[m] = 0.0f;
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      if (g * 256 + tid < nvec) {
+#pragma unroll
+        for (int m = 0; m < TT; ++m) {
+          float f[8];
+          unpack8(val[g][m], f);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float d = f[e] - mu[m];
+            q[m] += d * d;
+          }
+        }
+      }
+    }
+    block_sums(q, 1);
+#pragma unroll
+    for (int m = 0; m < TT; ++m) rs[m] = rsqrtf(q[m] * inv_h + eps);
+  } else {
+#pragma unroll
+    for (int m = 0; m < TT; ++m) {
+      mu[m] = 0.0f;
+      rs[m] = rsqrtf(ss[m] * inv_h + eps);
+    }
   }
-  if (tid < TT) rstd[tid * n + i] = rsqrtf((((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid]) * inv_h + eps);
+  if (tid == 0) {
+#pragma unroll
+    for (int m = 0; m < TT; ++m) {
+      if (LN && mean) mean[m * n + i] = mu[m];
+      rstd[m * n + i] = rs[m];
+    }
+  }
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     const int vi = g * 256 + tid;
     if (vi < nvec) {
-      float gm[8];
+      float gm[8], bt[8];
       unpack8(*reinterpret_cast<const uint4*>(gamma + vi * 8), gm);
+      if constexpr (LN) unpack8(*reinterpret_cast<const uint4*>(beta + vi * 8), bt);
       const long long off = i * h + vi * 8;
 #pragma unroll
       for (int m = 0; m < TT; ++m) {
         float f[8], o[8];
         unpack8(val[g][m], f);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = f[e] * rs[m] * gm[e];
+        for (int e = 0; e < 8; ++e) o[e] = LN ? ((f[e] - mu[m]) * rs[m] * gm[e] + bt[e]) : (f[e] * rs[m] * gm[e]);
         *reinterpret_cast<uint4*>(xout + m * plane + off) = pack8(o);
       }
     }
   }
 }
 
-// io [T,n,h]: partial sums on the shared channels, final values on the private ones -> R' in place; xout = RMSNorm(R');
+template <int TT, int NG>
+static hipError_t sync_norm_dispatch(bf16_t* io, const bf16_t* resid, const bf16_t* gamma, const bf16_t* beta, bf16_t* xout,
+                                     float* mean, float* rstd, int norm, long long tokens, int h, int hs, float eps,
+                                     hipStream_t s) {
+  if (norm == 0)
+    hipLaunchKernelGGL((sync_norm_kernel<TT, NG, true>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, beta, xout,
+                       mean, rstd, tokens, h, hs, eps);
+  else
+    hipLaunchKernelGGL((sync_norm_kernel<TT, NG, false>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, beta, xout,
+                       mean, rstd, tokens, h, hs, eps);
+  return hipGetLastError();
+}
+
+// shapes the fused reduce + norm kernel takes: whole 16-byte groups of shared channels, T in {2, 4, 8} up to h = 8192 and
+// T = 16 up to h = 4096 (a thread keeps its columns of all T rows in registers)
+bool sync_norm_takes(int T, long long tokens, int h, int hs) {
+  if (hs <= 0 || hs % 8 != 0 || hs > h || h % 8 != 0 || h > 8192 || tokens <= 0 || tokens > 0x7FFFFFFFLL) return false;
+  if (T == 2 || T == 4 || T == 8) return true;
+  return T == 16 && h <= 4096;
+}
+
+// io [T,n,h]: partial sums on the shared channels, final values on the private ones -> R' in place; xout = Norm(R');
 // returns hipErrorInvalidValue for shapes the fused kernel does not take (the caller then runs the two kernels)
-hipError_t launch_sync_rmsnorm(bf16_t* io, const bf16_t* resid, const bf16_t* gamma, bf16_t* xout, float* rstd, int T,
-                               long long tokens, int h, int hs, float eps, hipStream_t s) {
-  if (hs <= 0 || hs % 8 != 0 || hs > h || h % 8 != 0 || h > 8192 || tokens <= 0 || tokens > 0x7FFFFFFFLL)
-    return hipErrorInvalidValue;
+hipError_t launch_sync_norm(bf16_t* io, const bf16_t* resid, const bf16_t* gamma, const bf16_t* beta, bf16_t* xout,
+                            float* mean, float* rstd, int norm, int T, long long tokens, int h, int hs, float eps,
+                            hipStream_t s) {
+  if (!sync_norm_takes(T, tokens, h, hs)) return hipErrorInvalidValue;
+  const int ng = (h / 8 + 255) / 256;   // 1 .. 4
+#define CAAT_SN(TT_, NG_) return sync_norm_dispatch<TT_, NG_>(io, resid, gamma, beta, xout, mean, rstd, norm, tokens, h, hs, eps, s)
+#define CAAT_SN_T(TT_) \
+  if (ng <= 1) CAAT_SN(TT_, 1); \
+  if (ng <= 2) CAAT_SN(TT_, 2); \
+  CAAT_SN(TT_, 4);
   switch (T) {
-    case 2: hipLaunchKernelGGL((sync_rmsnorm_kernel<2>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, xout, rstd, tokens, h, hs, eps); break;
-    case 4: hipLaunchKernelGGL((sync_rmsnorm_kernel<4>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, xout, rstd, tokens, h, hs, eps); break;
-    case 8: hipLaunchKernelGGL((sync_rmsnorm_kernel<8>), dim3((unsigned)tokens), dim3(256), 0, s, io, resid, gamma, xout, rstd, tokens, h, hs, eps); break;
+    case 2: CAAT_SN_T(2)
+    case 4: CAAT_SN_T(4)
+    case 8: CAAT_SN_T(8)
+    case 16:
+      if (ng <= 1) CAAT_SN(16, 1);
+      CAAT_SN(16, 2);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
+#undef CAAT_SN_T
+#undef CAAT_SN
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -652,9 +726,11 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
 
 // sums partial[nb][2][h] over nb in a fixed order: a workgroup owns 64 columns (a thread 4 of them, one 16-byte
 // load per partial row), its 16 row groups each add every 16th partial row (4 independent chains), and the 16 group
-// sums are combined in ascending order through LDS.  h % 8 == 0, so 2h is a multiple of 4.
+// sums are combined in ascending order through LDS.  h % 8 == 0, so 2h is a multiple of 4.  Only the first `ncols`
+// columns of a partial row are read and reduced: 2h for LayerNorm (dgamma | dbeta), h for RMSNorm, whose backward
+// kernels never write the dbeta half of a partial row (and whose dbeta is never stored).
 __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __restrict__ partial, int nb, int h,
-                                                                float* __restrict__ dgamma,
+                                                                int ncols, float* __restrict__ dgamma,
                                                                 float* __restrict__ dbeta) {
   __shared__ float4 red[16][16];
   const int cl = threadIdx.x & 15, rg = threadIdx.x >> 4;
@@ -664,7 +740,7 @@ __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __r
 #pragma unroll
   for (int k = 0; k < 4; ++k) s[k] = make_float4(0.f, 0.f, 0.f, 0.f);
   auto add = [](float4& a, const float4& b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; };
-  if (c < 2 * h) {
+  if (c < ncols) {
     int b = rg;
     for (; b + 48 < nb; b += 64) {
       float4 v[4];
@@ -680,7 +756,7 @@ __global__ __launch_bounds__(256) void norm_bwd_finalize_kernel(const float* __r
   add(s[0], s[2]);
   red[rg][cl] = s[0];
   __syncthreads();
-  if (rg == 0 && c < 2 * h) {
+  if (rg == 0 && c < ncols) {
     float4 t = red[0][cl];
 #pragma unroll
     for (int k = 1; k < 16; ++k) add(t, red[k][cl]);
@@ -764,8 +840,9 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
   else if (vpl <= 8) e = norm_bwd_dispatch<8>(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, partial, norm, rows, h, hs, private_scale, nb, rpb, skip_shared, s);
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((2 * h + 63) / 64)), dim3(256), 0, s, partial, (int)nb,
-                     h, dgamma, dbeta);
+  const int ncols = norm == 0 ? 2 * h : h;           // RMSNorm has no dbeta: that half of a partial row is never written
+  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((ncols + 63) / 64)), dim3(256), 0, s, partial, (int)nb,
+                     h, ncols, dgamma, norm == 0 ? dbeta : nullptr);
   return hipGetLastError();
 }
 

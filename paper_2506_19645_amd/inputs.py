@@ -18,7 +18,6 @@ dX', dR', then the KV cache.  Changing the order changes every stored value.
 from __future__ import annotations
 
 import dataclasses
-import math
 from typing import Dict, Optional
 
 import numpy as np
@@ -56,11 +55,6 @@ class BlockConfig:
     @property
     def tokens(self) -> int:
         return self.batch * self.seq
-
-    @property
-    def hs(self) -> int:
-        # number of shared channels; the floor is taken in IEEE double, like the C entry point
-        return int(math.floor(self.h * float(self.p)))
 
     @property
     def f_r(self) -> int:
@@ -150,7 +144,9 @@ def _activations(rng, cfg: BlockConfig, n: int, mode: str, hs_struct: Optional[i
             X[1:] = X[0]
         R[1:] = R[0]
     elif mode == "divergent":
-        k = cfg.hs if hs_struct is None else hs_struct
+        if hs_struct is None:
+            raise ValueError("divergent inputs need hs_struct: how many leading residual columns are rank-equal")
+        k = int(hs_struct)
         if k > 0:
             R[1:, :, :k] = R[0:1, :, :k]
     else:
@@ -166,8 +162,10 @@ def make_inputs(cfg: BlockConfig, seed: int = 0, mode: str = "divergent", with_g
     point, Sec. 3.1); the residual's shared columns are copied from rank 0 and
     its private columns are independent.  mode='replicated': X_m = X_0 and
     R_m = R_0, the vanilla-TP special case used by the p=1 dense-equivalence check.
-    hs_struct overrides how many residual columns are made rank-equal (used by
-    p sweeps so that the same tensors serve every p).
+    hs_struct: how many leading residual columns are made rank-equal (required
+    for mode='divergent').  It is a property of the data, chosen by the caller
+    (tests pass the oracle's shared-channel count, the benchmark h/2 so that the
+    same tensors serve every p); this module does not derive it from p.
     """
     rng = np.random.default_rng(seed)
     T, h, n = cfg.T, cfg.h, cfg.tokens

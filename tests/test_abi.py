@@ -12,17 +12,19 @@ from paper_2506_19645_amd import inputs as I
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    txt = open(os.path.join(ROOT, "include", "caat.h")).read()
+def _declared(path):
+    txt = open(os.path.join(ROOT, *path)).read()
     txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
     return sorted(set(re.findall(r"\b(caat_[a-z0-9_]+)\s*\(", txt)))
 
 
 def test_library_exports_every_declared_symbol():
-    names = _declared()
+    names = _declared(("include", "caat.h"))
     assert set(names) == set(B.EXPORTS)
+    tools = _declared(("paper_2506_19645_amd", "csrc", "caat_tools.h"))     # measuring tools, outside the method's ABI
+    assert set(tools) == set(B.TOOL_EXPORTS) and not set(tools) & set(names)
     L = B.lib()
-    for n in names:
+    for n in names + tools:
         assert getattr(L, n) is not None
 
 
@@ -34,9 +36,12 @@ def test_shared_channels_matches_floor():
     assert B.shared_channels(4096, 1.0) == 4096 and B.shared_channels(4096, 0.0) == 0
     for bad in (-0.01, 1.01, float("nan")):
         assert B.shared_channels(16, bad) == -1
+    # the library's count (what the GPU descriptor gets) against the oracle's (what the oracle calls get): two
+    # independent implementations of Eq. A3's floor(h*p), over the benchmark shapes and a sweep of awkward p
+    from oracle import caat_oracle as O
     for cfg in I.CONFIGS.values():
-        for p in (1.0, 0.5, 0.25, 0.0):
-            assert B.shared_channels(cfg.h, p) == cfg.with_(p=p).hs
+        for p in (1.0, 0.5, 0.25, 0.0, 0.3, 0.301, 0.7, 1.0 / 3.0, 90.0 / 128.0, 1e-9, 1.0 - 1e-12):
+            assert B.shared_channels(cfg.h, p) == O.shared_channels(cfg.h, p)
 
 
 def test_status_strings():

@@ -6,14 +6,14 @@ import pytest
 from oracle import caat_oracle as O
 from paper_2506_19645_amd import binding as B
 from paper_2506_19645_amd import inputs as I
-from tests.util import assert_close, bits_to_f64
+from tests.util import assert_close, bits_to_f64, make_inputs, hs_of
 
 pytestmark = pytest.mark.gpu
 
 
-def run_attn_block(cfg, d, backward=False, reduce_in_gemm=False):
+def run_attn_block(cfg, d, backward=False, reduce_in_gemm=False, separate_reduce=False):
     import torch
-    desc = B.make_desc(cfg, reduce_in_gemm=reduce_in_gemm)
+    desc = B.make_desc(cfg, reduce_in_gemm=reduce_in_gemm, separate_reduce=separate_reduce)
     ln = cfg.norm == I.NORM_LAYERNORM
     T, n, h, hd = cfg.T, cfg.tokens, cfg.h, cfg.hd_r
     weights = [B.to_device(d["Wqkv"]), B.to_device(d["Wo"]), B.to_device(d["gamma"]),
@@ -54,7 +54,7 @@ def run_attn_block(cfg, d, backward=False, reduce_in_gemm=False):
 def _oracle_kw(cfg):
     norm = O.LAYERNORM if cfg.norm == I.NORM_LAYERNORM else O.RMSNORM
     return dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim, norm=norm,
-                hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base,
+                hs=hs_of(cfg), eps=cfg.eps, private_scale=cfg.private_scale, rope_base=cfg.rope_base,
                 kv_heads_per_rank=cfg.kv_heads // cfg.T)
 
 
@@ -83,7 +83,7 @@ def check_attn(cfg, d, got, fwd):
     assert_close(got["H"], fwd["H"], "H")
     assert_close(got["Rp"], fwd["Rp"], "Rp")
     assert_close(got["Xp"], fwd["Xp"], "Xp")
-    hs = cfg.hs
+    hs = hs_of(cfg)
     if hs > 0 and np.array_equal(d["R"][0, :, :hs], d["R"][-1, :, :hs]):
         for m in range(1, T):
             assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
@@ -103,7 +103,7 @@ def _cfg(T, batch, seq, heads, p, norm=I.NORM_RMSNORM, scale=1.0, kv_heads=0):
 ])
 def test_attn_block_fwd(T, batch, seq, heads, p, norm):
     cfg = _cfg(T, batch, seq, heads, p, norm)
-    d = I.make_inputs(cfg, seed=21, with_grads=False, weight_std=0.05)
+    d = make_inputs(cfg, seed=21, with_grads=False, weight_std=0.05)
     got = run_attn_block(cfg, d)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
@@ -115,7 +115,7 @@ def test_attn_block_fwd(T, batch, seq, heads, p, norm):
 def test_attn_causal_on_gpu():
     """Perturbing the tokens after position i must not change any output row <= i (bitwise)."""
     cfg = _cfg(2, 1, 192, 2, 0.5)
-    d = I.make_inputs(cfg, seed=22, with_grads=False, weight_std=0.05)
+    d = make_inputs(cfg, seed=22, with_grads=False, weight_std=0.05)
     a = run_attn_block(cfg, d)
     d2 = {k: v.copy() for k, v in d.items()}
     d2["X"][:, 100:] = d2["X"][:, 100:][:, ::-1].copy()
@@ -131,10 +131,12 @@ def test_attn_causal_on_gpu():
     (4, 1, 130, 4, 0.0, I.NORM_RMSNORM, 2.0),        # p = 0 with private-channel scaling sqrt(T), just past one block
     (2, 3, 1, 2, 0.25, I.NORM_RMSNORM, 1.0),         # seq = 1: P = 1, dS = 0, so dq = dk = 0 and dv = dH
     (2, 1, 450, 2, 0.3, I.NORM_RMSNORM, 1.0),        # hs not a multiple of 8, 4 key blocks, tail of 2
+    (16, 1, 130, 32, 0.5, I.NORM_RMSNORM, 1.0),      # tensor-parallel degree 16 (Sec. 5's largest): 32 heads, 2 per rank
+    (16, 2, 70, 32, 0.25, I.NORM_LAYERNORM, 4.0),    # T = 16, LayerNorm, private channel scaling sqrt(T)
 ])
 def test_attn_block_bwd(T, batch, seq, heads, p, norm, scale):
     cfg = _cfg(T, batch, seq, heads, p, norm, scale)
-    d = I.make_inputs(cfg, seed=23, with_grads=True, weight_std=0.05)
+    d = make_inputs(cfg, seed=23, with_grads=True, weight_std=0.05)
     got = run_attn_block(cfg, d, backward=True)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
@@ -152,7 +154,7 @@ def test_attn_bwd_causal_on_gpu():
     """An upstream gradient that is zero at positions < i gives dq rows < i that are exactly zero, while the keys and
     values before i still receive gradient from the later queries: gradients flow from queries to earlier keys."""
     cfg = _cfg(2, 1, 192, 2, 0.5)
-    d = I.make_inputs(cfg, seed=24, with_grads=True, weight_std=0.05)
+    d = make_inputs(cfg, seed=24, with_grads=True, weight_std=0.05)
     d["dXo"][:, :100] = 0
     d["dRo"][:, :100] = 0
     got = run_attn_block(cfg, d, backward=True)
@@ -171,7 +173,7 @@ def test_attn_bwd_causal_on_gpu():
 def test_gqa_attn_block_fwd_bwd(T, batch, seq, heads, kv_heads, p):
     """Grouped-query attention (the 34B / 70B shapes of the paper's additional speed-up results), forward + backward."""
     cfg = _cfg(T, batch, seq, heads, p, kv_heads=kv_heads)
-    d = I.make_inputs(cfg, seed=25, with_grads=True, weight_std=0.05)
+    d = make_inputs(cfg, seed=25, with_grads=True, weight_std=0.05)
     got = run_attn_block(cfg, d, backward=True)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
@@ -185,7 +187,7 @@ def test_attn_peaked_softmax_stays_a_convex_combination(weight_std):
     oracle's output by 6e-2), so an element-wise comparison is ill-conditioned; what must hold for any rounding is that
     every output row is a convex combination of the visible value rows: finite, and inside their per-column range."""
     cfg = _cfg(2, 1, 300, 4, 0.5)
-    d = I.make_inputs(cfg, seed=27, with_grads=False, weight_std=weight_std)
+    d = make_inputs(cfg, seed=27, with_grads=False, weight_std=weight_std)
     got = run_attn_block(cfg, d)
     T, s_, hd = cfg.T, cfg.seq, cfg.hd_r
     assert np.isfinite(got["H"]).all() and np.isfinite(got["Rp"]).all() and np.isfinite(got["Xp"]).all()
@@ -196,3 +198,21 @@ def test_attn_peaked_softmax_stays_a_convex_combination(weight_std):
     slack = 2.0 ** -7 * np.maximum(np.abs(lo), np.abs(hi)) + 1e-30                   # one bf16 rounding of the result
     assert (got["H"] >= lo - slack).all() and (got["H"] <= hi + slack).all()
     assert np.array_equal(got["H"][:, 0], v[:, 0])                                   # the first token sees only itself
+
+
+@pytest.mark.parametrize("separate", [False, True])
+@pytest.mark.parametrize("norm", [I.NORM_RMSNORM, I.NORM_LAYERNORM])
+def test_attn_block_z_alone_with_zero_residual(norm, separate):
+    """With R = 0 the residual stream IS Z: the reduced attention output is checked without R ~ N(0,1) masking its
+    error; through the one-launch reduce + norm and through the reduce as a kernel of its own."""
+    cfg = _cfg(4, 2, 150, 8, 0.5, norm)
+    d = make_inputs(cfg, seed=28, with_grads=False, weight_std=0.05)
+    d["R"][:] = 0
+    got = run_attn_block(cfg, d, separate_reduce=separate)
+    w, fwd = oracle_attn_block(cfg, d)
+    assert_close(got["Rp"], fwd["Z"], "Z")
+    assert_close(got["Xp"], fwd["Xp"], "Xp")
+    hs = hs_of(cfg)
+    for m in range(1, cfg.T):
+        assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
+    assert not np.array_equal(got["Rp_bits"][1, :, hs:], got["Rp_bits"][0, :, hs:])

@@ -7,15 +7,15 @@ import pytest
 from oracle import caat_oracle as O
 from paper_2506_19645_amd import binding as B
 from paper_2506_19645_amd import inputs as I
-from tests.util import assert_close, bits_to_f64
+from tests.util import assert_close, bits_to_f64, make_inputs, hs_of, ulp_distance_bf16
 
 pytestmark = pytest.mark.gpu
 
 
-def run_mlp_block(cfg, d, backward=True, reduce_in_gemm=False):
+def run_mlp_block(cfg, d, backward=True, reduce_in_gemm=False, separate_reduce=False):
     """Marshal the bit patterns in d to the GPU, run fwd (+bwd) through the C ABI, return host arrays."""
     import torch
-    desc = B.make_desc(cfg, reduce_in_gemm=reduce_in_gemm)
+    desc = B.make_desc(cfg, reduce_in_gemm=reduce_in_gemm, separate_reduce=separate_reduce)
     swi = cfg.kind == I.KIND_MLP_SWIGLU
     ln = cfg.norm == I.NORM_LAYERNORM
     T, n, h, fr = cfg.T, cfg.tokens, cfg.h, cfg.f_r
@@ -61,7 +61,7 @@ def oracle_mlp_block(cfg, d, backward=True):
     w = {k: O.widen_bf16(v) for k, v in d.items()}
     swi = cfg.kind == I.KIND_MLP_SWIGLU
     norm = O.LAYERNORM if cfg.norm == I.NORM_LAYERNORM else O.RMSNORM
-    kw = dict(swiglu=swi, norm=norm, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale)
+    kw = dict(swiglu=swi, norm=norm, hs=hs_of(cfg), eps=cfg.eps, private_scale=cfg.private_scale)
     fwd = O.mlp_block_fwd(w["X"], w["R"], w, w["gamma"], w.get("beta"), **kw)
     g = O.mlp_block_bwd(w["X"], fwd, w, w["gamma"], w["dXo"], w["dRo"], **kw) if backward else {}
     return w, fwd, g
@@ -69,7 +69,7 @@ def oracle_mlp_block(cfg, d, backward=True):
 
 def check_mlp_block(cfg, d, got, w, fwd, g, backward=True):
     swi = cfg.kind == I.KIND_MLP_SWIGLU
-    hs = cfg.hs
+    hs = hs_of(cfg)
     Pfull = np.concatenate([fwd["P"], fwd["Pu"]], axis=-1) if swi else fwd["P"]
     assert_close(got["P"], Pfull, "P")
     assert_close(got["Y"], fwd["Y"], "Y")
@@ -111,7 +111,7 @@ def _cfg(swi, T, n, h, ffn, p, scale=1.0):
 ])
 def test_mlp_block_fwd_bwd(swi, T, n, h, ffn, p, scale):
     cfg = _cfg(swi, T, n, h, ffn, p, scale)
-    d = I.make_inputs(cfg, seed=7, weight_std=0.05)
+    d = make_inputs(cfg, seed=7, weight_std=0.05)
     got = run_mlp_block(cfg, d)
     w, fwd, g = oracle_mlp_block(cfg, d)
     check_mlp_block(cfg, d, got, w, fwd, g)
@@ -120,7 +120,7 @@ def test_mlp_block_fwd_bwd(swi, T, n, h, ffn, p, scale):
 def test_mlp_block_config1_seed0():
     """The small benchmark configuration, exactly as specified (h=768, ffn=3072, T=2, p=0.5, 256 tokens, seed 0)."""
     cfg = I.C1
-    d = I.make_inputs(cfg, seed=0)
+    d = make_inputs(cfg, seed=0)
     got = run_mlp_block(cfg, d)
     w, fwd, g = oracle_mlp_block(cfg, d)
     check_mlp_block(cfg, d, got, w, fwd, g)
@@ -129,12 +129,12 @@ def test_mlp_block_config1_seed0():
 def test_mlp_block_z_alone_with_zero_residual():
     """With R = 0 the residual stream IS Z: checks the reduce output without R ~ N(0,1) masking its error."""
     cfg = _cfg(False, 4, 200, 256, 1024, 0.5)
-    d = I.make_inputs(cfg, seed=9, weight_std=0.05)
+    d = make_inputs(cfg, seed=9, weight_std=0.05)
     d["R"][:] = 0
     got = run_mlp_block(cfg, d, backward=False)
     w, fwd, _ = oracle_mlp_block(cfg, d, backward=False)
     assert_close(got["Rp"], fwd["Z"], "Z")
-    hs = cfg.hs
+    hs = hs_of(cfg)
     for m in range(1, cfg.T):
         assert np.array_equal(got["Rp_bits"][m, :, :hs], got["Rp_bits"][0, :, :hs])
     assert not np.array_equal(got["Rp_bits"][1, :, hs:], got["Rp_bits"][0, :, hs:])
@@ -143,7 +143,7 @@ def test_mlp_block_z_alone_with_zero_residual():
 def test_mlp_block_p1_replicated_all_ranks_identical():
     """p = 1 with replicated inputs is the vanilla transformer: every rank ends with the same bits (Sec. 3)."""
     cfg = _cfg(True, 4, 100, 256, 1024, 1.0)
-    d = I.make_inputs(cfg, seed=11, mode="replicated", weight_std=0.05)
+    d = make_inputs(cfg, seed=11, mode="replicated", weight_std=0.05)
     got = run_mlp_block(cfg, d, backward=False)
     for m in range(1, cfg.T):
         assert np.array_equal(got["Rp_bits"][m], got["Rp_bits"][0])
@@ -155,10 +155,28 @@ def test_mlp_block_p1_replicated_all_ranks_identical():
 def test_mlp_block_p0_is_local():
     """p = 0: rank m's output depends on rank m's data only (ensemble limit)."""
     cfg = _cfg(False, 2, 64, 128, 512, 0.0)
-    d = I.make_inputs(cfg, seed=12, weight_std=0.05)
+    d = make_inputs(cfg, seed=12, weight_std=0.05)
     a = run_mlp_block(cfg, d, backward=False)
     d2 = {k: v.copy() for k, v in d.items()}
     d2["X"][1] = d2["X"][1][::-1].copy()
     b = run_mlp_block(cfg, d2, backward=False)
     assert np.array_equal(a["Rp_bits"][0], b["Rp_bits"][0])
     assert not np.array_equal(a["Rp_bits"][1], b["Rp_bits"][1])
+
+
+@pytest.mark.parametrize("swi", [False, True])
+@pytest.mark.parametrize("T,n,h,ffn,p", [(4, 300, 512, 4 * 256, 0.5), (8, 130, 1024, 8 * 128, 0.25), (16, 70, 512, 16 * 136, 0.5)])
+def test_mlp_block_reduce_as_its_own_kernel_gives_the_same_bits(swi, T, n, h, ffn, p):
+    """separate_reduce = 1 keeps the reduce a kernel of its own (the stand-in for the collective) followed by the norm;
+    the default runs them as one launch.  Both sum the same rounded partials in the same order and round once, so
+    R' must agree bit for bit (X' to one bf16 step), and both match the oracle."""
+    cfg = _cfg(swi, T, n, h, ffn, p)
+    d = make_inputs(cfg, seed=14, weight_std=0.05)
+    a = run_mlp_block(cfg, d, backward=False)
+    b = run_mlp_block(cfg, d, backward=False, separate_reduce=True)
+    assert np.array_equal(a["Rp_bits"], b["Rp_bits"])
+    # the two norm kernels add a row's squares in different orders: the statistics agree to fp32 rounding, the
+    # normalised values to one bf16 step
+    assert ulp_distance_bf16(a["Xp_bits"], b["Xp_bits"]).max() <= 1
+    w, fwd, _ = oracle_mlp_block(cfg, d, backward=False)
+    check_mlp_block(cfg, d, a, w, fwd, {}, backward=False)

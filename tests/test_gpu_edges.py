@@ -7,6 +7,7 @@ from paper_2506_19645_amd import binding as B
 from paper_2506_19645_amd import inputs as I
 from tests.test_gpu_attn import _cfg as attn_cfg, check_attn, check_attn_bwd, oracle_attn_block, oracle_attn_bwd, run_attn_block
 from tests.test_gpu_block import _cfg as mlp_cfg, check_mlp_block, oracle_mlp_block, run_mlp_block
+from tests.util import make_inputs, hs_of
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +23,7 @@ def _mlp_buffers(cfg, d, sentinel=0x7FC0):
 def test_zero_tokens_is_a_no_op():
     import torch
     cfg = mlp_cfg(False, 2, 8, 64, 256, 0.5)
-    d = I.make_inputs(cfg, seed=61)
+    d = make_inputs(cfg, seed=61)
     w, x, r, r_out, x_out = _mlp_buffers(cfg, d)
     desc = B.make_desc(cfg)
     desc.tokens, desc.seq = 0, 0
@@ -39,7 +40,7 @@ def test_zero_tokens_is_a_no_op():
 def test_errors_leave_outputs_untouched():
     import torch
     cfg = mlp_cfg(False, 2, 40, 64, 256, 0.5)
-    d = I.make_inputs(cfg, seed=62)
+    d = make_inputs(cfg, seed=62)
     w, x, r, r_out, x_out = _mlp_buffers(cfg, d)
     desc = B.make_desc(cfg)
     need = B.workspace_bytes(desc)
@@ -81,8 +82,8 @@ def test_unsupported_requests_are_refused():
 def test_extreme_shared_channel_counts(hs):
     """One shared channel, a partial first group, all but one channel shared: the case split of Eq. A3 at its edges."""
     cfg = mlp_cfg(False, 2, 70, 2048, 512, hs / 2048.0)
-    assert cfg.hs == hs
-    d = I.make_inputs(cfg, seed=63, weight_std=0.05)
+    assert hs_of(cfg) == hs
+    d = make_inputs(cfg, seed=63, weight_std=0.05)
     got = run_mlp_block(cfg, d)
     w, fwd, g = oracle_mlp_block(cfg, d)
     check_mlp_block(cfg, d, got, w, fwd, g)
@@ -92,7 +93,7 @@ def test_extreme_shared_channel_counts(hs):
 def test_widest_hidden_size(swi):
     """h = 8192 is the widest row the norm kernels take; T = 2, ragged token count."""
     cfg = mlp_cfg(swi, 2, 77, 8192, 2 * 264, 0.5)
-    d = I.make_inputs(cfg, seed=64, weight_std=0.02)
+    d = make_inputs(cfg, seed=64, weight_std=0.02)
     got = run_mlp_block(cfg, d)
     w, fwd, g = oracle_mlp_block(cfg, d)
     check_mlp_block(cfg, d, got, w, fwd, g)
@@ -100,7 +101,7 @@ def test_widest_hidden_size(swi):
 
 def test_single_rank_partial_sync_is_identity_plus_residual():
     cfg = mlp_cfg(True, 1, 129, 256, 512, 0.5)
-    d = I.make_inputs(cfg, seed=65, weight_std=0.05)
+    d = make_inputs(cfg, seed=65, weight_std=0.05)
     got = run_mlp_block(cfg, d)
     w, fwd, g = oracle_mlp_block(cfg, d)
     check_mlp_block(cfg, d, got, w, fwd, g)
@@ -110,7 +111,7 @@ def test_single_rank_partial_sync_is_identity_plus_residual():
 
 def test_attention_one_past_a_block_boundary():
     cfg = attn_cfg(2, 2, 129, 2, 0.5)
-    d = I.make_inputs(cfg, seed=66, with_grads=True, weight_std=0.05)
+    d = make_inputs(cfg, seed=66, with_grads=True, weight_std=0.05)
     got = run_attn_block(cfg, d, backward=True)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
@@ -119,7 +120,7 @@ def test_attention_one_past_a_block_boundary():
 
 def test_profile_records_every_launch():
     cfg = mlp_cfg(False, 2, 40, 64, 256, 0.5)
-    d = I.make_inputs(cfg, seed=67)
+    d = make_inputs(cfg, seed=67)
     B.profile_reset()
     B.profile_enable(True)
     try:

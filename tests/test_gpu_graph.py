@@ -5,6 +5,7 @@ import pytest
 
 from paper_2506_19645_amd import binding as B
 from paper_2506_19645_amd import inputs as I
+from tests.util import make_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -12,7 +13,7 @@ pytestmark = pytest.mark.gpu
 def test_block_fwd_bwd_graph_replay_matches_eager():
     import torch
     cfg = I.C1
-    d = I.make_inputs(cfg, seed=3)
+    d = make_inputs(cfg, seed=3)
     desc = B.make_desc(cfg)
     w = [B.to_device(d["A"]), B.to_device(d["B"]), B.to_device(d["gamma"]), B.to_device(d["beta"])]
     x, r = B.to_device(d["X"]), B.to_device(d["R"])

@@ -94,6 +94,56 @@ def test_partial_sync_empty():
     torch.cuda.synchronize()
 
 
+# ------------------------------------------------------------------------------------------ fused reduce + norm
+@pytest.mark.parametrize("layernorm", [False, True])
+@pytest.mark.parametrize("T,n,h,hs", [(2, 37, 40, 8), (4, 9, 2048, 1024), (8, 5, 4096, 2048), (8, 3, 8192, 4096),
+                                        (16, 6, 4096, 2048), (16, 4, 264, 264), (4, 3, 520, 512)])
+def test_partial_sync_norm_fwd_integer_bit_exact(layernorm, T, n, h, hs):
+    """The one-launch reduce + residual + norm: with small-integer partial sums and residuals every sum is exact, so
+    the shared channels of R' must carry exactly the oracle's bits on every rank and the private channels must keep
+    theirs; the normalised copy is compared with the oracle's norm of that R'."""
+    torch = _torch()
+    kind = O.LAYERNORM if layernorm else O.RMSNORM
+    d = I.make_sync_inputs(T, n, h, seed=70 + T, integer=True)
+    dn = I.make_norm_inputs(T, n, h, layernorm, seed=71 + T)
+    io_bits = d["Zt"].copy()
+    io_bits[:, :, hs:] = dn["R"][:, :, hs:]                   # private channels: already final, arbitrary values
+    Zt, R = O.widen_bf16(d["Zt"]), O.widen_bf16(d["R"])
+    want_rp = O.widen_bf16(io_bits)
+    want_rp[:, :, :hs] = O.partial_channel_reduce(Zt, hs)[:, :, :hs] + R[:, :, :hs]
+    gam, bet = O.widen_bf16(dn["gamma"]), (O.widen_bf16(dn["beta"]) if layernorm else None)
+    want_x, _, want_rstd = O.norm_fwd(want_rp, gam, bet, kind, 1e-5)
+    io, res = B.to_device(io_bits), B.to_device(d["R"])
+    x_out = torch.full_like(io, float("nan"))
+    mean = torch.empty(T * n, dtype=torch.float32, device="cuda") if layernorm else None
+    rstd = torch.empty(T * n, dtype=torch.float32, device="cuda")
+    B.partial_sync_norm_fwd(io, res, B.to_device(dn["gamma"]), B.to_device(dn["beta"]) if layernorm else None, x_out,
+                            mean, rstd, kind, T, n, h, hs, 1e-5)
+    torch.cuda.synchronize()
+    got = B.to_host_bits(io)
+    assert np.array_equal(got[:, :, :hs], f64_to_bits(want_rp[:, :, :hs]))      # exact sums + residual, every rank
+    assert np.array_equal(got[:, :, hs:], io_bits[:, :, hs:])                   # private channels: bits untouched
+    assert_close(bits_to_f64(B.to_host_bits(x_out)), want_x, "fused norm output")
+    assert_close(rstd.cpu().numpy().reshape(T, n, 1), want_rstd, "rstd", tol=1e-4)
+    if layernorm:
+        assert_close(mean.cpu().numpy().reshape(T, n), want_rp.mean(-1), "mean", tol=1e-4)
+
+
+def test_partial_sync_norm_fwd_shapes_not_taken():
+    torch = _torch()
+    buf = torch.zeros(16 * 2 * 8192, dtype=torch.bfloat16, device="cuda")
+    rstd = torch.zeros(64, dtype=torch.float32, device="cuda")
+    call = lambda T, n, h, hs: B.partial_sync_norm_fwd(buf, buf, buf, None, buf, None, rstd, B.RMSNORM, T, n, h, hs, 1e-5,
+                                                       check=False)
+    assert call(2, 2, 64, 12) == B.EUNSUPPORTED       # a 16-byte group straddles hs
+    assert call(2, 2, 64, 0) == B.EUNSUPPORTED        # nothing shared
+    assert call(3, 2, 64, 32) == B.EUNSUPPORTED       # rank counts without an instantiation
+    assert call(16, 2, 8192, 4096) == B.EUNSUPPORTED  # T = 16 is taken up to h = 4096
+    assert call(2, 2, 64, 72) == B.ESHAPE
+    assert call(2, 0, 64, 32) == B.OK
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------------------------------ norms
 @pytest.mark.parametrize("layernorm", [True, False])
 @pytest.mark.parametrize("T,n,h", [(2, 33, 64), (2, 256, 768), (3, 70, 520), (4, 65, 2048), (2, 40, 4096), (1, 9, 8192)])

@@ -6,7 +6,7 @@ import pytest
 from oracle import caat_oracle as O
 from paper_2506_19645_amd import binding as B
 from paper_2506_19645_amd import inputs as I
-from tests.util import assert_close, bits_to_f64
+from tests.util import assert_close, bits_to_f64, make_inputs, hs_of
 
 pytestmark = pytest.mark.gpu
 
@@ -16,9 +16,9 @@ def layer_weights(d):
             B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1)), B.to_device(d["B"])]
 
 
-def run_prefill(cfg, d, kv_cap=None, keep=("X1", "H", "R1", "X2"), reduce_in_gemm=False):
+def run_prefill(cfg, d, kv_cap=None, keep=("X1", "H", "R1", "X2"), reduce_in_gemm=False, separate_reduce=False):
     import torch
-    desc = B.make_desc(cfg, kv_cap=kv_cap, reduce_in_gemm=reduce_in_gemm)
+    desc = B.make_desc(cfg, kv_cap=kv_cap, reduce_in_gemm=reduce_in_gemm, separate_reduce=separate_reduce)
     T, n, h, hd, hpr = cfg.T, cfg.tokens, cfg.h, cfg.hd_r, cfg.kv_heads // cfg.T     # hpr: key / value heads per rank
     weights = layer_weights(d)
     r = B.to_device(d["R"])
@@ -46,7 +46,7 @@ def run_prefill(cfg, d, kv_cap=None, keep=("X1", "H", "R1", "X2"), reduce_in_gem
 def oracle_prefill(cfg, d):
     w = {k: O.widen_bf16(v) for k, v in d.items()}
     return w, O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T,
-                                  head_dim=cfg.head_dim, hs=cfg.hs, eps=cfg.eps, private_scale=cfg.private_scale,
+                                  head_dim=cfg.head_dim, hs=hs_of(cfg), eps=cfg.eps, private_scale=cfg.private_scale,
                                   rope_base=cfg.rope_base, kv_heads_per_rank=cfg.kv_heads // cfg.T)
 
 
@@ -71,10 +71,12 @@ def _cfg(T, batch, seq, heads, ffn, p, scale=1.0, kv_heads=0):
     (1, 1, 333, 2, 512, 1.0, 1.0, 0),            # T = 1
     (2, 2, 70, 2, 2 * 256, 0.0, 1.0, 0),         # p = 0
     (2, 2, 200, 8, 2 * 256, 0.5, 1.0, 2),        # grouped-query attention
+    (16, 1, 100, 32, 16 * 128, 0.5, 1.0, 0),     # tensor-parallel degree 16 (Sec. 5's largest): 32 heads, 2 per rank
+    (16, 2, 70, 32, 16 * 136, 0.25, 4.0, 16),    # T = 16 with grouped-query attention (one key / value head per rank), sqrt(T)
 ])
 def test_prefill_layer(T, batch, seq, heads, ffn, p, scale, kv_heads):
     cfg = _cfg(T, batch, seq, heads, ffn, p, scale, kv_heads)
-    d = I.make_inputs(cfg, seed=41, weight_std=0.05)
+    d = make_inputs(cfg, seed=41, weight_std=0.05)
     got = run_prefill(cfg, d, kv_cap=seq + 3)
     w, ref = oracle_prefill(cfg, d)
     check_prefill(cfg, d, got, ref)
@@ -82,7 +84,7 @@ def test_prefill_layer(T, batch, seq, heads, ffn, p, scale, kv_heads):
     assert_close(bits_to_f64(got["Kc_bits"][:, :, :, :seq]), ref["K"], "K cache")
     assert_close(bits_to_f64(got["Vc_bits"][:, :, :, :seq]), ref["V"], "V cache")
     assert not got["Kc_bits"][:, :, :, seq:].any() and not got["Vc_bits"][:, :, :, seq:].any()
-    hs = cfg.hs
+    hs = hs_of(cfg)
     if hs > 0 and T > 1:
         for m in range(1, T):
             assert np.array_equal(got["R2_bits"][m, :, :hs], got["R2_bits"][0, :, :hs])
@@ -94,7 +96,7 @@ def test_prefill_then_decode_matches_longer_prefill():
     import torch
     T, b, heads, ffn, L = 2, 3, 4, 2 * 256, 150
     full = _cfg(T, b, L + 1, heads, ffn, 0.5)
-    d = I.make_inputs(full, seed=42, weight_std=0.05)
+    d = make_inputs(full, seed=42, weight_std=0.05)
     w, ref = oracle_prefill(full, d)
     R = d["R"].reshape(T, b, L + 1, full.h)
     pre_cfg = _cfg(T, b, L, heads, ffn, 0.5)
@@ -114,3 +116,16 @@ def test_prefill_then_decode_matches_longer_prefill():
     vc = bits_to_f64(B.to_host_bits(got["vc_dev"]))
     assert_close(kc, ref["K"], "K cache after prefill + decode")
     assert_close(vc, ref["V"], "V cache after prefill + decode")
+
+
+@pytest.mark.parametrize("separate", [False, True])
+def test_prefill_layer_outputs_alone_with_a_tiny_residual(separate):
+    """Residual stream scaled by 2^-10: R1 and R2 are then the reduced sub-layer outputs Z up to a negligible term, so
+    the error bound is relative to Z (at full size with 0.02-std weights |Z| << |R| would hide an error in Z)."""
+    cfg = _cfg(4, 2, 150, 8, 4 * 256, 0.5)
+    d = make_inputs(cfg, seed=43, weight_std=0.05)
+    d["R"] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(d["R"]) * np.float32(2.0 ** -10))
+    got = run_prefill(cfg, d, separate_reduce=separate)
+    w, ref = oracle_prefill(cfg, d)
+    assert np.abs(ref["R1"] - w["R"]).max() > 50 * np.abs(w["R"]).max()
+    check_prefill(cfg, d, got, ref)

@@ -10,7 +10,7 @@ from tests.test_gpu_attn import _cfg as attn_cfg, check_attn, oracle_attn_block,
 from tests.test_gpu_block import _cfg as mlp_cfg, check_mlp_block, oracle_mlp_block, run_mlp_block
 from tests.test_gpu_decode import _cfg as dec_cfg, run_decode
 from tests.test_gpu_prefill import _cfg as pre_cfg, check_prefill, oracle_prefill, run_prefill
-from tests.util import assert_close
+from tests.util import assert_close, make_inputs, hs_of
 
 pytestmark = pytest.mark.gpu
 
@@ -27,18 +27,18 @@ pytestmark = pytest.mark.gpu
 ])
 def test_mlp_block_reduce_in_gemm(swi, T, n, h, ffn, p, scale):
     cfg = mlp_cfg(swi, T, n, h, ffn, p, scale)
-    d = I.make_inputs(cfg, seed=51, weight_std=0.05)
+    d = make_inputs(cfg, seed=51, weight_std=0.05)
     got = run_mlp_block(cfg, d, reduce_in_gemm=True)      # backward runs on the forward's saved tensors as usual
     w, fwd, g = oracle_mlp_block(cfg, d)
     check_mlp_block(cfg, d, got, w, fwd, g)
     # against the default path: private channels are computed by the same arithmetic -> same bits
     ref = run_mlp_block(cfg, d, backward=False)
-    assert np.array_equal(got["Rp_bits"][:, :, cfg.hs:], ref["Rp_bits"][:, :, cfg.hs:])
+    assert np.array_equal(got["Rp_bits"][:, :, hs_of(cfg):], ref["Rp_bits"][:, :, hs_of(cfg):])
 
 
 def test_attention_block_reduce_in_gemm():
     cfg = attn_cfg(2, 2, 200, 4, 0.5)
-    d = I.make_inputs(cfg, seed=52, with_grads=False, weight_std=0.05)
+    d = make_inputs(cfg, seed=52, with_grads=False, weight_std=0.05)
     got = run_attn_block(cfg, d, reduce_in_gemm=True)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
@@ -47,25 +47,25 @@ def test_attention_block_reduce_in_gemm():
 @pytest.mark.parametrize("kv_heads", [0, 2])
 def test_decode_layer_reduce_in_gemm(kv_heads):
     cfg = dec_cfg(2, 37, 8, 2 * 344, 150, 0.5, kv_heads)
-    d = I.make_inputs(cfg, seed=53, weight_std=0.05)
+    d = make_inputs(cfg, seed=53, weight_std=0.05)
     got = run_decode(cfg, d, reduce_in_gemm=True)
     w = {k: O.widen_bf16(v) for k, v in d.items()}
     ref = O.decode_layer_fwd(w["R"], w, w["Kc"], w["Vc"], kv_len=cfg.kv_len, heads_per_rank=cfg.n_heads // cfg.T,
-                             head_dim=128, hs=cfg.hs, kv_heads_per_rank=cfg.kv_heads // cfg.T)
+                             head_dim=128, hs=hs_of(cfg), kv_heads_per_rank=cfg.kv_heads // cfg.T)
     for name in ("R1", "X2", "R2"):
         assert_close(got[name], ref[name], name)
     for m in range(1, cfg.T):
-        assert np.array_equal(got["R2_bits"][m, :, :cfg.hs], got["R2_bits"][0, :, :cfg.hs])
+        assert np.array_equal(got["R2_bits"][m, :, :hs_of(cfg)], got["R2_bits"][0, :, :hs_of(cfg)])
 
 
 def test_prefill_layer_reduce_in_gemm():
     cfg = pre_cfg(4, 2, 200, 4, 4 * 344, 0.25)
-    d = I.make_inputs(cfg, seed=54, weight_std=0.05)
+    d = make_inputs(cfg, seed=54, weight_std=0.05)
     got = run_prefill(cfg, d, reduce_in_gemm=True)
     w, ref = oracle_prefill(cfg, d)
     check_prefill(cfg, d, got, ref)
     for m in range(1, cfg.T):
-        assert np.array_equal(got["R2_bits"][m, :, :cfg.hs], got["R2_bits"][0, :, :cfg.hs])
+        assert np.array_equal(got["R2_bits"][m, :, :hs_of(cfg)], got["R2_bits"][0, :, :hs_of(cfg)])
 
 
 # ---------------------------------------------------------------------------------------------------------
@@ -76,7 +76,7 @@ def _run_mlp_dedup(cfg, d):
     from tests.util import pack_dedup, unpack_dedup
     swi = cfg.kind == I.KIND_MLP_SWIGLU
     desc = B.make_desc(cfg, reduce_in_gemm=True, dedup_shared=True)
-    T, n, h, hs = cfg.T, cfg.tokens, cfg.h, cfg.hs
+    T, n, h, hs = cfg.T, cfg.tokens, cfg.h, hs_of(cfg)
     w0 = B.to_device(np.concatenate([d["Wg"], d["Wu"]], axis=1) if swi else d["A"])
     weights = [w0, B.to_device(d["B"]), B.to_device(d["gamma"]), B.to_device(d["beta"]) if "beta" in d else None]
     x = B.to_device(d["X"])
@@ -96,7 +96,7 @@ def _run_mlp_dedup(cfg, d):
 ])
 def test_mlp_block_dedup_shared_layout(swi, T, n, h, ffn, p):
     cfg = mlp_cfg(swi, T, n, h, ffn, p, 1.0)
-    d = I.make_inputs(cfg, seed=55, weight_std=0.05)
+    d = make_inputs(cfg, seed=55, weight_std=0.05)
     rp_bits, xp_bits = _run_mlp_dedup(cfg, d)
     ref = run_mlp_block(cfg, d, backward=False, reduce_in_gemm=True)   # same arithmetic, T copies of the shared columns
     assert np.array_equal(rp_bits, ref["Rp_bits"])
@@ -113,8 +113,8 @@ def test_prefill_layer_dedup_shared_layout():
     from tests.test_gpu_prefill import layer_weights
     from tests.util import bits_to_f64, pack_dedup, unpack_dedup
     cfg = pre_cfg(4, 2, 200, 8, 4 * 344, 0.25, kv_heads=4)
-    d = I.make_inputs(cfg, seed=56, weight_std=0.05)
-    T, n, h, hs = cfg.T, cfg.tokens, cfg.h, cfg.hs
+    d = make_inputs(cfg, seed=56, weight_std=0.05)
+    T, n, h, hs = cfg.T, cfg.tokens, cfg.h, hs_of(cfg)
     desc = B.make_desc(cfg, reduce_in_gemm=True, dedup_shared=True)
     r = B.to_device(pack_dedup(d["R"], hs))
     r_out = torch.zeros_like(r)

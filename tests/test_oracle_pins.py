@@ -9,6 +9,7 @@ import pytest
 
 from oracle import caat_oracle as O
 from paper_2506_19645_amd import inputs as I
+from tests.util import make_inputs, hs_of
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -207,7 +208,7 @@ def test_norm_bwd_fd(kind):
 def _tiny_mlp(swiglu, T=2, n=4, h=16, f=32, seed=0, mode="divergent", p=0.5):
     cfg = I.BlockConfig("tiny", I.KIND_MLP_SWIGLU if swiglu else I.KIND_MLP_GELU,
                         I.NORM_RMSNORM if swiglu else I.NORM_LAYERNORM, h=h, T=T, p=p, batch=1, seq=n, ffn=f)
-    d = I.make_inputs(cfg, seed=seed, mode=mode, weight_std=0.3)
+    d = make_inputs(cfg, seed=seed, mode=mode, weight_std=0.3)
     w = {k: O.widen_bf16(v) for k, v in d.items()}
     return cfg, w
 
@@ -260,7 +261,7 @@ def test_mlp_p1_replicated_equals_dense_block(swiglu):
 def test_mlp_two_rank_block_formula():
     """Eq. 8: Z_1 = [Y_1 B_11 + Y_2 B_12, Y_1 B_21], Z_2 = [same, Y_2 B_22] with explicit sub-blocks of B."""
     cfg, w = _tiny_mlp(False, T=2, n=3, h=8, f=12, p=0.5)
-    hs = cfg.hs
+    hs = hs_of(cfg)
     out = O.mlp_block_fwd(w["X"], w["R"], w, w["gamma"], w["beta"], swiglu=False, norm=O.LAYERNORM, hs=hs)
     Y1, Y2 = out["Y"]
     B1, B2 = w["B"][0].T, w["B"][1].T           # [f/2, h] row blocks of B held by device 1 and 2
@@ -405,7 +406,7 @@ def test_rope_properties():
 def _tiny_attn(T=2, batch=2, seq=5, heads=4, d=4, p=0.5, seed=0):
     cfg = I.BlockConfig("tinyattn", I.KIND_ATTN, I.NORM_RMSNORM, h=heads * d, T=T, p=p, batch=batch, seq=seq,
                         n_heads=heads, head_dim=d)
-    dd = I.make_inputs(cfg, seed=seed, weight_std=0.3)
+    dd = make_inputs(cfg, seed=seed, weight_std=0.3)
     return cfg, {k: O.widen_bf16(v) for k, v in dd.items()}
 
 
@@ -413,7 +414,7 @@ def test_attention_block_tiny_vs_loops():
     cfg, w = _tiny_attn()
     hpr, d, hd = cfg.n_heads // cfg.T, cfg.head_dim, cfg.hd_r
     out = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], None, batch=cfg.batch, seq=cfg.seq,
-                           heads_per_rank=hpr, head_dim=d, norm=O.RMSNORM, hs=cfg.hs)
+                           heads_per_rank=hpr, head_dim=d, norm=O.RMSNORM, hs=hs_of(cfg))
     half = d // 2
     for m in range(cfg.T):
         qkv = _naive_matmul(w["X"][m], w["Wqkv"][m].T)
@@ -437,14 +438,14 @@ def test_attention_block_tiny_vs_loops():
         np.testing.assert_allclose(out["H"][m], Hm, atol=1e-12)
         np.testing.assert_allclose(out["Zt"][m], _naive_matmul(Hm, w["Wo"][m].T), atol=1e-12)
     # Eq. A5 case split on the attention output
-    np.testing.assert_allclose(out["Z"][0, :, :cfg.hs], out["Zt"][:, :, :cfg.hs].sum(0), atol=1e-13)
-    assert np.array_equal(out["Z"][:, :, cfg.hs:], out["Zt"][:, :, cfg.hs:])
+    np.testing.assert_allclose(out["Z"][0, :, :hs_of(cfg)], out["Zt"][:, :, :hs_of(cfg)].sum(0), atol=1e-13)
+    assert np.array_equal(out["Z"][:, :, hs_of(cfg):], out["Zt"][:, :, hs_of(cfg):])
 
 
 def test_attention_block_sequences_independent_and_causal():
     cfg, w = _tiny_attn(batch=2, seq=6)
     kw = dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=cfg.n_heads // cfg.T, head_dim=cfg.head_dim,
-              norm=O.RMSNORM, hs=cfg.hs)
+              norm=O.RMSNORM, hs=hs_of(cfg))
     a = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], None, **kw)
     X2 = w["X"].copy()
     X2[:, 6 + 4:] += 1.0       # perturb the tail of sequence 1 only
@@ -570,7 +571,7 @@ def test_decode_equals_last_row_of_prefill():
     h, f = heads * d, 24
     cfg = I.BlockConfig("tinydec", I.KIND_DECODE, I.NORM_RMSNORM, h=h, T=T, p=0.5, batch=b, seq=1, ffn=f,
                         n_heads=heads, head_dim=d, kv_len=L)
-    dd = I.make_inputs(cfg, seed=2, weight_std=0.3)
+    dd = make_inputs(cfg, seed=2, weight_std=0.3)
     w = {k: O.widen_bf16(v) for k, v in dd.items()}
     hpr = heads // T
     # A prefill over L+1 tokens per sequence with random normalised inputs; its K, V fill the cache.
@@ -578,20 +579,20 @@ def test_decode_equals_last_row_of_prefill():
     Rfull = r.standard_normal((T, b * (L + 1), h))
     X1full, _, _ = O.norm_fwd(Rfull, w["gamma_attn"], None, O.RMSNORM, 1e-5)
     pre = O.attn_block_fwd(X1full, Rfull, w["Wqkv"], w["Wo"], w["gamma"], None, batch=b, seq=L + 1,
-                           heads_per_rank=hpr, head_dim=d, norm=O.RMSNORM, hs=cfg.hs)
+                           heads_per_rank=hpr, head_dim=d, norm=O.RMSNORM, hs=hs_of(cfg))
     Kc = np.zeros((T, b, hpr, L + 1, d))
     Vc = np.zeros_like(Kc)
     Kc[:, :, :, :L] = pre["K"][:, :, :, :L]
     Vc[:, :, :, :L] = pre["V"][:, :, :, :L]
     last = [s * (L + 1) + L for s in range(b)]
     Rlast = Rfull[:, last]
-    dec = O.decode_layer_fwd(Rlast, w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=cfg.hs)
+    dec = O.decode_layer_fwd(Rlast, w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=hs_of(cfg))
     np.testing.assert_allclose(dec["R1"], pre["Rp"][:, last], atol=1e-12)
     np.testing.assert_allclose(dec["X2"], pre["Xp"][:, last], atol=1e-12)
     np.testing.assert_allclose(dec["k_new"], pre["K"][:, :, :, L], atol=1e-13)
     np.testing.assert_allclose(dec["v_new"], pre["V"][:, :, :, L], atol=1e-13)
     # the MLP half equals the MLP block applied to (X2, R1)
-    mlp = O.mlp_block_fwd(dec["X2"], dec["R1"], w, w["gamma"], None, swiglu=True, norm=O.RMSNORM, hs=cfg.hs)
+    mlp = O.mlp_block_fwd(dec["X2"], dec["R1"], w, w["gamma"], None, swiglu=True, norm=O.RMSNORM, hs=hs_of(cfg))
     np.testing.assert_allclose(dec["R2"], mlp["Rp"], atol=1e-13)
 
 
@@ -599,7 +600,7 @@ def test_decode_equals_last_row_of_prefill():
 def _tiny_gqa(T=2, batch=2, seq=5, heads=8, kv_heads=4, d=4, p=0.5, seed=9, kind=I.KIND_ATTN, ffn=0, kv_len=0):
     cfg = I.BlockConfig("tinygqa", kind, I.NORM_RMSNORM, h=heads * d, T=T, p=p, batch=batch, seq=seq, ffn=ffn,
                         n_heads=heads, head_dim=d, n_kv_heads=kv_heads, kv_len=kv_len)
-    dd = I.make_inputs(cfg, seed=seed, weight_std=0.3)
+    dd = make_inputs(cfg, seed=seed, weight_std=0.3)
     return cfg, {k: O.widen_bf16(v) for k, v in dd.items()}
 
 
@@ -620,7 +621,7 @@ def test_gqa_equals_mha_with_repeated_kv_heads_forward_and_backward():
     cfg, w = _tiny_gqa()
     hpr, kvpr, d = cfg.n_heads // cfg.T, cfg.kv_heads // cfg.T, cfg.head_dim
     grp, hd, kvd = hpr // kvpr, hpr * d, kvpr * d
-    kw = dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, norm=O.RMSNORM, hs=cfg.hs)
+    kw = dict(batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, norm=O.RMSNORM, hs=hs_of(cfg))
     r = _rng(31)
     dXo, dRo = r.standard_normal(w["X"].shape), r.standard_normal(w["X"].shape)
     fg = O.attn_block_fwd(w["X"], w["R"], w["Wqkv"], w["Wo"], w["gamma"], None, kv_heads_per_rank=kvpr, **kw)
@@ -644,7 +645,7 @@ def test_gqa_decode_equals_last_row_of_prefill():
     L = 4
     cfg, w = _tiny_gqa(T=2, batch=2, seq=L + 1, heads=8, kv_heads=4, d=4, kind=I.KIND_PREFILL, ffn=24)
     hpr, kvpr, d = cfg.n_heads // cfg.T, cfg.kv_heads // cfg.T, cfg.head_dim
-    pre = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, hs=cfg.hs,
+    pre = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, hs=hs_of(cfg),
                               kv_heads_per_rank=kvpr)
     assert pre["K"].shape == (cfg.T, cfg.batch, kvpr, L + 1, d)
     Kc = np.zeros((cfg.T, cfg.batch, kvpr, L + 1, d))
@@ -652,7 +653,7 @@ def test_gqa_decode_equals_last_row_of_prefill():
     Kc[:, :, :, :L] = pre["K"][:, :, :, :L]
     Vc[:, :, :, :L] = pre["V"][:, :, :, :L]
     last = [s * (L + 1) + L for s in range(cfg.batch)]
-    dec = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=cfg.hs,
+    dec = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=hs_of(cfg),
                              kv_heads_per_rank=kvpr)
     np.testing.assert_allclose(dec["R2"], pre["R2"][:, last], atol=1e-12)
     np.testing.assert_allclose(dec["k_new"], pre["K"][:, :, :, L], atol=1e-13)
@@ -662,7 +663,7 @@ def test_gqa_decode_equals_last_row_of_prefill():
 def _tiny_prefill(T=2, b=2, heads=4, d=4, seq=6, f=24, p=0.5, seed=3, mode="divergent"):
     cfg = I.BlockConfig("tinypre", I.KIND_PREFILL, I.NORM_RMSNORM, h=heads * d, T=T, p=p, batch=b, seq=seq, ffn=f,
                         n_heads=heads, head_dim=d)
-    dd = I.make_inputs(cfg, seed=seed, weight_std=0.3, mode=mode)
+    dd = make_inputs(cfg, seed=seed, weight_std=0.3, mode=mode)
     return cfg, {k: O.widen_bf16(v) for k, v in dd.items()}
 
 
@@ -672,17 +673,64 @@ def test_prefill_layer_last_row_equals_decode_step():
     L = 5
     cfg, w = _tiny_prefill(seq=L + 1)
     hpr, d = cfg.n_heads // cfg.T, cfg.head_dim
-    pre = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, hs=cfg.hs)
+    pre = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, heads_per_rank=hpr, head_dim=d, hs=hs_of(cfg))
     Kc = np.zeros((cfg.T, cfg.batch, hpr, L + 1, d))
     Vc = np.zeros_like(Kc)
     Kc[:, :, :, :L] = pre["K"][:, :, :, :L]
     Vc[:, :, :, :L] = pre["V"][:, :, :, :L]
     last = [s * (L + 1) + L for s in range(cfg.batch)]
-    dec = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=cfg.hs)
+    dec = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, heads_per_rank=hpr, head_dim=d, hs=hs_of(cfg))
     np.testing.assert_allclose(dec["R1"], pre["R1"][:, last], atol=1e-12)
     np.testing.assert_allclose(dec["R2"], pre["R2"][:, last], atol=1e-12)
     np.testing.assert_allclose(dec["k_new"], pre["K"][:, :, :, L], atol=1e-13)
     np.testing.assert_allclose(dec["v_new"], pre["V"][:, :, :, L], atol=1e-13)
+
+
+@pytest.mark.parametrize("p", [0.0, 0.5, 0.3])
+def test_layer_private_scale_equals_prescaled_private_weight_rows(p):
+    """Private channel scaling (Sec. 4) multiplies a row-parallel output's private channels by a constant before the
+    residual add, so a layer with scale c must equal the SAME layer at scale 1 whose row-parallel weights Wo and B have
+    their private OUTPUT rows (l >= hs) multiplied by c beforehand -- in both halves of the layer, for the prefill and
+    for the decode function -- and must differ from the unscaled layer.  At p = 0 every row is private: the whole of
+    Wo and B is pre-multiplied.  Decode must still equal the last prefill row with the scale on."""
+    L = 5
+    cfg, w = _tiny_prefill(seq=L + 1, p=p, seed=13)
+    T, hpr, d = cfg.T, cfg.n_heads // cfg.T, cfg.head_dim
+    hs = hs_of(cfg)
+    c = math.sqrt(T)
+    kw = dict(heads_per_rank=hpr, head_dim=d, hs=hs)
+    pre_c = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, private_scale=c, **kw)
+    w2 = dict(w)
+    w2["Wo"], w2["B"] = w["Wo"].copy(), w["B"].copy()
+    w2["Wo"][:, hs:, :] *= c            # [T][h out][hd_r in]: output rows hs.. are the private channels
+    w2["B"][:, hs:, :] *= c
+    pre_w = O.prefill_layer_fwd(w["R"], w2, batch=cfg.batch, seq=cfg.seq, private_scale=1.0, **kw)
+    pre_1 = O.prefill_layer_fwd(w["R"], w, batch=cfg.batch, seq=cfg.seq, private_scale=1.0, **kw)
+    for name in ("R1", "X2", "R2"):
+        np.testing.assert_allclose(pre_c[name], pre_w[name], atol=1e-12)
+        assert np.abs(pre_c[name] - pre_1[name]).max() > 1e-3, name
+    # the two halves separately: R1 - R is the scaled attention output, R2 - R1 the scaled MLP output
+    for a, b in (("R1", None), ("R2", "R1")):
+        zc = pre_c[a] - (w["R"] if b is None else pre_c[b])
+        z1_in = pre_c["Zt"] if b is None else pre_c["Zt2"]
+        np.testing.assert_allclose(zc[:, :, hs:], c * z1_in[:, :, hs:], atol=1e-12)
+        np.testing.assert_allclose(zc[:, :, :hs], np.broadcast_to(z1_in[:, :, :hs].sum(0), zc[:, :, :hs].shape), atol=1e-12)
+    # decode over the cache of the first L tokens, scale on: last prefill row; and the pre-scaled-weights identity
+    Kc = np.zeros((T, cfg.batch, hpr, L + 1, d))
+    Vc = np.zeros_like(Kc)
+    Kc[:, :, :, :L] = pre_c["K"][:, :, :, :L]
+    Vc[:, :, :, :L] = pre_c["V"][:, :, :, :L]
+    last = [s * (L + 1) + L for s in range(cfg.batch)]
+    dec_c = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, private_scale=c, **kw)
+    dec_w = O.decode_layer_fwd(w["R"][:, last], w2, Kc, Vc, kv_len=L, private_scale=1.0, **kw)
+    dec_1 = O.decode_layer_fwd(w["R"][:, last], w, Kc, Vc, kv_len=L, private_scale=1.0, **kw)
+    for name in ("R1", "X2", "R2"):
+        np.testing.assert_allclose(dec_c[name], dec_w[name], atol=1e-12)
+        np.testing.assert_allclose(dec_c[name], pre_c[name][:, last], atol=1e-12)
+        assert np.abs(dec_c[name] - dec_1[name]).max() > 1e-3, name
+    # each half on its own: a mutation that drops the scale in only ONE half must not hide behind the other
+    np.testing.assert_allclose((dec_c["R2"] - dec_c["R1"])[:, :, hs:], c * dec_c["Zt2"][:, :, hs:], atol=1e-12)
+    np.testing.assert_allclose((dec_c["R1"] - w["R"][:, last])[:, :, hs:], c * dec_c["Zt"][:, :, hs:], atol=1e-12)
 
 
 def test_prefill_layer_p1_replicated_equals_dense_llama_layer():
@@ -691,7 +739,7 @@ def test_prefill_layer_p1_replicated_equals_dense_llama_layer():
     cfg, w = _tiny_prefill(T=2, b=1, heads=4, d=4, seq=5, f=24, p=1.0, seed=8, mode="replicated")
     T, h, d, s = cfg.T, cfg.h, cfg.head_dim, cfg.seq
     hpr, hd = cfg.n_heads // T, cfg.hd_r
-    out = O.prefill_layer_fwd(w["R"], w, batch=1, seq=s, heads_per_rank=hpr, head_dim=d, hs=cfg.hs)
+    out = O.prefill_layer_fwd(w["R"], w, batch=1, seq=s, heads_per_rank=hpr, head_dim=d, hs=hs_of(cfg))
     x = w["R"][0]
 
     def rms(v, g):
@@ -738,7 +786,17 @@ def test_comm_model_closed_forms():
     assert O.comm_payload_elements(s, h, 1.0) == 2 * s * h
     for p in (0.75, 0.5, 0.25, 0.0):
         assert O.comm_payload_elements(s, h, p) / O.comm_payload_elements(s, h, 1.0) == p   # (1-p)*100% reduction
-    assert O.layer_flops_per_device(s, h, 8) == (24 * s * h * h + 4 * s * s * h) / 8
+    # G counted from the layer's contractions (App. C: a 4h MLP, four h x h projections, QK^T and PV over s keys),
+    # 2 FLOPs per multiply-add, divided over r devices -- not the closed form retyped
+    gemms = [(s, h, h)] * 4 + [(s, 4 * h, h), (s, h, 4 * h), (s, s, h), (s, h, s)]        # (M, N, K)
+    assert O.layer_flops_per_device(s, h, 8) == sum(2 * m * n * k for m, n, k in gemms) / 8
+    # P(p) counted on the operator itself: the elements of one device's tensor that the partial channel-reduce sums
+    # across ranks (those that differ from the rank's own input), two reduces per layer (attention and MLP outputs)
+    for hh, p in ((16, 0.5), (16, 0.25), (24, 1.0), (8, 0.0)):
+        ss, T = 6, 3
+        Zt = _rng(77).standard_normal((T, ss, hh))
+        Z = O.partial_channel_reduce(Zt, O.shared_channels(hh, p))
+        assert 2 * int((Z[0] != Zt[0]).sum()) == O.comm_payload_elements(ss, hh, p)
     C, r = 3000.0, 8
     G = O.layer_flops_per_device(s, h, r)
     for p in (0.75, 0.5, 0.25, 0.0):
@@ -756,10 +814,10 @@ def test_inputs_bf16_roundtrip_and_structure():
     # ties round to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
     assert I.f32_to_bf16_bits(np.array([1.0 + 2.0 ** -8], dtype=np.float32))[0] == 0x3F80
     assert I.f32_to_bf16_bits(np.array([1.0 + 3 * 2.0 ** -8], dtype=np.float32))[0] == 0x3F82
-    d = I.make_inputs(I.C1, seed=0)
+    d = make_inputs(I.C1, seed=0)
     assert d["X"].shape == (2, 256, 768) and d["A"].shape == (2, 1536, 768) and d["B"].shape == (2, 768, 1536)
     assert np.array_equal(d["R"][0, :, :384], d["R"][1, :, :384])
     assert not np.array_equal(d["R"][0, :, 384:], d["R"][1, :, 384:])
-    d2 = I.make_inputs(I.C1, seed=0)
+    d2 = make_inputs(I.C1, seed=0)
     assert all(np.array_equal(d[k], d2[k]) for k in d)
     assert abs(float(O.widen_bf16(d["A"]).std()) - 0.02) < 1e-3

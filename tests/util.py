@@ -1,9 +1,23 @@
 """Helpers shared by the tests: error metrics and host<->device marshalling (no method arithmetic)."""
 import numpy as np
 
+from oracle import caat_oracle as O
 from paper_2506_19645_amd import inputs as I
 
 TOL = 2e-2   # relative error bound of the benchmark definition (bf16 storage, fp32 accumulation)
+
+
+def hs_of(cfg) -> int:
+    """Number of shared channels the ORACLE derives from (h, p) (Sec. 3, Eq. A3).  The GPU descriptor gets its own
+    count from the library's caat_shared_channels (binding.make_desc); the two are cross-checked in test_abi."""
+    return O.shared_channels(cfg.h, float(cfg.p))
+
+
+def make_inputs(cfg, **kw):
+    """inputs.make_inputs with the residual stream's rank-equal leading columns set to the oracle's shared-channel
+    count unless the test says otherwise (the generator itself knows nothing about the method)."""
+    kw.setdefault("hs_struct", hs_of(cfg))
+    return I.make_inputs(cfg, **kw)
 
 
 def rel_errs(got: np.ndarray, want: np.ndarray):
