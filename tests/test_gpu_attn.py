@@ -136,7 +136,9 @@ def test_attn_causal_on_gpu():
 ])
 def test_attn_block_bwd(T, batch, seq, heads, p, norm, scale):
     cfg = _cfg(T, batch, seq, heads, p, norm, scale)
-    d = make_inputs(cfg, seed=23, with_grads=True, weight_std=0.05)
+    # h = 4096 with 0.05-std weights gives scores with a spread of ~10 (nearly one-hot softmax rows, see the peaked-
+    # softmax test below): the benchmark's own 0.02 keeps the comparison well conditioned there
+    d = make_inputs(cfg, seed=23, with_grads=True, weight_std=0.05 if cfg.h < 4096 else 0.02)
     got = run_attn_block(cfg, d, backward=True)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)

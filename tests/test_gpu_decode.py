@@ -62,7 +62,7 @@ def oracle_decode(cfg, d):
 ])
 def test_decode_layer(T, b, heads, ffn, L, p, kv_heads, scale):
     cfg = _cfg(T, b, heads, ffn, L, p, kv_heads, scale)
-    d = make_inputs(cfg, seed=31, weight_std=0.05)
+    d = make_inputs(cfg, seed=31, weight_std=0.05 if cfg.h < 4096 else 0.02)   # h = 4096: scores stay O(1), as in the benchmark
     got = run_decode(cfg, d)
     ref = oracle_decode(cfg, d)
     assert_close(got["X1"], ref["X1"], "X1")

@@ -118,19 +118,22 @@ def test_attention_one_past_a_block_boundary():
     check_attn_bwd(got, oracle_attn_bwd(cfg, w, fwd))
 
 
-def test_profile_records_every_launch():
+@pytest.mark.parametrize("separate", [False, True])
+def test_profile_records_every_launch(separate):
     cfg = mlp_cfg(False, 2, 40, 64, 256, 0.5)
     d = make_inputs(cfg, seed=67)
     B.profile_reset()
     B.profile_enable(True)
     try:
-        run_mlp_block(cfg, d)
+        run_mlp_block(cfg, d, separate_reduce=separate)
     finally:
         B.profile_enable(False)
     rec = B.profile_records()
     names = [n for n, _ in rec]
-    assert names == ["gemm_nt_gelu_fwd", "gemm_nt_rowpar", "partial_sync_fwd", "norm_fwd", "norm_bwd", "partial_sync_bwd",
-                     "gemm_nn_gelu_bwd", "gemm_tn_wgrad", "gemm_nn_dgrad", "gemm_tn_wgrad"]
+    # the reduce + residual + norm is one launch unless the caller asks for the reduce as a kernel of its own
+    mid = ["partial_sync_fwd", "norm_fwd"] if separate else ["partial_sync_norm_fwd"]
+    assert names == ["gemm_nt_gelu_fwd", "gemm_nt_rowpar"] + mid + ["norm_bwd", "partial_sync_bwd", "gemm_nn_gelu_bwd",
+                                                                   "gemm_tn_wgrad", "gemm_nn_dgrad", "gemm_tn_wgrad"]
     assert all(ms > 0.0 for _, ms in rec)
     B.profile_reset()
     assert B.profile_records() == []

@@ -76,7 +76,7 @@ def _cfg(T, batch, seq, heads, ffn, p, scale=1.0, kv_heads=0):
 ])
 def test_prefill_layer(T, batch, seq, heads, ffn, p, scale, kv_heads):
     cfg = _cfg(T, batch, seq, heads, ffn, p, scale, kv_heads)
-    d = make_inputs(cfg, seed=41, weight_std=0.05)
+    d = make_inputs(cfg, seed=41, weight_std=0.05 if cfg.h < 4096 else 0.02)   # h = 4096: scores stay O(1), as in the benchmark
     got = run_prefill(cfg, d, kv_cap=seq + 3)
     w, ref = oracle_prefill(cfg, d)
     check_prefill(cfg, d, got, ref)
