@@ -40,7 +40,8 @@ typedef enum caat_status {
   CAAT_EALIGN = 3,      /* a device pointer is not 16-byte aligned */
   CAAT_EWORKSPACE = 4,  /* workspace smaller than caat_workspace_bytes() */
   CAAT_EHIP = 5,        /* a HIP runtime call (kernel launch) reported an error */
-  CAAT_EUNSUPPORTED = 6 /* valid request that this build does not implement */
+  CAAT_EUNSUPPORTED = 6,/* valid request that this build does not implement */
+  CAAT_ESCRATCH = 7     /* caat_norm_bwd_static only: the problem needs more than the library's fixed device scratch */
 } caat_status;
 
 typedef enum caat_kind {
@@ -192,6 +193,23 @@ int caat_norm_bwd(const void* dy, const void* dres, const void* x, const void* g
                   const float* rstd, void* g_out, void* g_scaled, float* dgamma, float* dbeta, int norm, int T,
                   long long tokens, int h, int hs, float private_scale, void* workspace, size_t ws_bytes,
                   void* hip_stream);
+
+/*
+ * caat_norm_bwd for callers that cannot allocate device memory or size a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * caat_norm_bwd, minus `workspace` / `ws_bytes`: the per-workgroup partial sums of dgamma / dbeta go to a fixed
+ * 16 MiB device array inside the library (one copy per GPU, held until the process ends).  The call allocates and
+ * frees nothing.  Limit: caat_norm_bwd_workspace_bytes(T, tokens, h) <= 16 MiB, i.e. every shape with h <= 4096 and,
+ * for 4096 < h <= 8192, at most 16 MiB / (8 h) partial rows of 8 token rows each (T*tokens <= 2048 at h = 8192);
+ * beyond that the call returns CAAT_ESCRATCH before anything is launched and leaves every output untouched.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams, or
+ * different host threads) race on it -- serialise them, or use caat_norm_bwd with separate workspaces.  The array
+ * keeps the last call's contents; nothing in it needs clearing between calls (the kernels write every partial row
+ * that the final sum reads).
+ */
+int caat_norm_bwd_static(const void* dy, const void* dres, const void* x, const void* gamma, const float* mean,
+                         const float* rstd, void* g_out, void* g_scaled, float* dgamma, float* dbeta, int norm, int T,
+                         long long tokens, int h, int hs, float private_scale, void* hip_stream);
 
 /*
  * Grouped bf16 shard GEMM with fp32 accumulation, the building block of Eq. A3's two contractions and of

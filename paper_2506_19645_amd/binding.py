@@ -15,7 +15,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcaat.so")
 
-OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EHIP, EUNSUPPORTED = range(7)
+OK, EINVAL, ESHAPE, EALIGN, EWORKSPACE, EHIP, EUNSUPPORTED, ESCRATCH = range(8)
 MLP_GELU, MLP_SWIGLU, ATTN, ATTN_DECODE, LAYER_PREFILL = range(5)
 LAYERNORM, RMSNORM = 0, 1
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
@@ -45,7 +45,7 @@ class caat_ws_layout(C.Structure):
 # the method's C ABI (include/caat.h) and the measuring tools the library exports beside it (csrc/caat_tools.h)
 EXPORTS = ["caat_shared_channels", "caat_status_string", "caat_workspace_bytes", "caat_workspace_layout",
            "caat_partial_sync", "caat_norm_fwd", "caat_partial_sync_norm_fwd", "caat_norm_bwd_workspace_bytes",
-           "caat_norm_bwd", "caat_gemm_bf16", "caat_block_fwd", "caat_block_bwd"]
+           "caat_norm_bwd", "caat_norm_bwd_static", "caat_gemm_bf16", "caat_block_fwd", "caat_block_bwd"]
 TOOL_EXPORTS = ["caat_profile_enable", "caat_profile_reset", "caat_profile_count", "caat_profile_get", "caat_hbm_probe"]
 
 _lib = None
@@ -77,6 +77,8 @@ def lib() -> C.CDLL:
         L.caat_norm_bwd_workspace_bytes.restype = sz
         L.caat_norm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, ll, i, i, f, vp, sz, vp]
         L.caat_norm_bwd.restype = i
+        L.caat_norm_bwd_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, ll, i, i, f, vp]
+        L.caat_norm_bwd_static.restype = i
         L.caat_gemm_bf16.argtypes = [vp, vp, vp, i, i, ll, ll, ll, ll, ll, ll, ll, ll, ll, vp]
         L.caat_gemm_bf16.restype = i
         L.caat_block_fwd.argtypes = [C.POINTER(caat_desc), C.POINTER(vp), vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -210,6 +212,16 @@ def norm_bwd(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, dgamma, dbeta, nor
                              _ptr(workspace), ws_bytes, _stream(stream))
     if check:
         _check(st, "caat_norm_bwd")
+    return st
+
+
+def norm_bwd_static(dy, dres, x, gamma, mean, rstd, g_out, g_scaled, dgamma, dbeta, norm: int, T: int, tokens: int,
+                    h: int, hs: int, private_scale: float, stream=None, check: bool = True) -> int:
+    st = lib().caat_norm_bwd_static(_ptr(dy), _ptr(dres), _ptr(x), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(g_out),
+                                    _ptr(g_scaled), _ptr(dgamma), _ptr(dbeta), norm, T, tokens, h, hs, private_scale,
+                                    _stream(stream))
+    if check:
+        _check(st, "caat_norm_bwd_static")
     return st
 
 

@@ -10,7 +10,17 @@
 
 using namespace caat;
 
+static __device__ __align__(256) unsigned char caat_static_scratch[(size_t)16 << 20];
+
 namespace {
+
+// ---- the one entry point that allocates nothing (caat_norm_bwd_static) keeps its partial sums here instead of in a
+// caller-supplied workspace.  Every GPU the library runs on holds its own copy of the array until the process ends.
+// In host code the array's name is only a stand-in for the symbol: the device address comes from
+// hipGetSymbolAddress, once per device with that device current, and only that pointer is ever passed to a kernel.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+void* g_static_scratch[STATIC_SCRATCH_MAX_DEVICES] = {};   // device address of caat_static_scratch, per device id
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -451,6 +461,7 @@ const char* caat_status_string(int status) {
     case CAAT_EWORKSPACE: return "workspace too small";
     case CAAT_EHIP: return "HIP runtime error at kernel launch";
     case CAAT_EUNSUPPORTED: return "valid request not implemented in this build";
+    case CAAT_ESCRATCH: return "problem needs more scratch than the library's fixed 16 MiB device array (use the entry point that takes a workspace)";
     default: return "unknown status";
   }
 }
@@ -549,6 +560,30 @@ int caat_norm_bwd(const void* dy, const void* dres, const void* x, const void* g
   return hip_status(launch_norm_bwd((const bf16_t*)dy, (const bf16_t*)dres, (const bf16_t*)x, (const bf16_t*)gamma, mean,
                                     rstd, (bf16_t*)g_out, (bf16_t*)g_scaled, dgamma, dbeta, norm, T, tokens, h, hs,
                                     private_scale, workspace, (hipStream_t)hip_stream));
+}
+
+int caat_norm_bwd_static(const void* dy, const void* dres, const void* x, const void* gamma, const float* mean,
+                         const float* rstd, void* g_out, void* g_scaled, float* dgamma, float* dbeta, int norm, int T,
+                         long long tokens, int h, int hs, float private_scale, void* hip_stream) {
+  if (!dy || !x || !gamma || !rstd || !g_out || !dgamma || T < 1 || tokens < 0 || h < 1) return CAAT_EINVAL;
+  if (norm != CAAT_LAYERNORM && norm != CAAT_RMSNORM) return CAAT_EINVAL;
+  if (norm == CAAT_LAYERNORM && (!mean || !dbeta)) return CAAT_EINVAL;
+  if (h % 8 != 0 || h > 8192 || hs < 0 || hs > h) return CAAT_ESHAPE;
+  if (misaligned(dy) || misaligned(x) || misaligned(gamma) || misaligned(g_out) || (dres && misaligned(dres)) ||
+      (g_scaled && misaligned(g_scaled)))
+    return CAAT_EALIGN;
+  if (norm_bwd_workspace_bytes(T, tokens, h) > STATIC_SCRATCH_BYTES) return CAAT_ESCRATCH;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return CAAT_EHIP;
+  void* scratch = g_static_scratch[dev];
+  if (!scratch) {   // first call on this device (it is the current one): look the array's device address up, once
+    if (hipGetSymbolAddress(&scratch, HIP_SYMBOL(caat_static_scratch)) != hipSuccess || !scratch) return CAAT_EHIP;
+    g_static_scratch[dev] = scratch;
+  }
+  // nothing in the array has to start at zero: the backward kernels write every partial row that the final sum reads
+  return hip_status(launch_norm_bwd((const bf16_t*)dy, (const bf16_t*)dres, (const bf16_t*)x, (const bf16_t*)gamma, mean,
+                                    rstd, (bf16_t*)g_out, (bf16_t*)g_scaled, dgamma, dbeta, norm, T, tokens, h, hs,
+                                    private_scale, scratch, (hipStream_t)hip_stream));
 }
 
 int caat_gemm_bf16(const void* a, const void* b, void* c, int layout, int G, long long M, long long N, long long K,

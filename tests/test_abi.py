@@ -45,8 +45,8 @@ def test_shared_channels_matches_floor():
 
 
 def test_status_strings():
-    seen = {B.status_string(s) for s in range(7)}
-    assert len(seen) == 7 and B.status_string(0) == "ok"
+    seen = {B.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and B.status_string(0) == "ok"
 
 
 def test_validation_errors_before_launch():
@@ -60,6 +60,13 @@ def test_validation_errors_before_launch():
     assert B.partial_sync(fake, None, fake, 2, 4, 16, 8, private_scale=float("nan"), stream=0, check=False) == B.EINVAL
     assert B.norm_fwd(fake, fake, None, fake, fake, fake, B.LAYERNORM, 2, 4, 16, 1e-5, stream=0, check=False) == B.EINVAL
     assert B.norm_fwd(fake, fake, None, fake, None, fake, 7, 2, 4, 16, 1e-5, stream=0, check=False) == B.EINVAL
+    # the entry point that allocates nothing refuses what its fixed 16 MiB scratch cannot hold, before any launch:
+    # h = 8192 needs 8 h bytes per partial row of 8 token rows, so more than 2048 rows do not fit
+    st = lambda T, n, h: B.norm_bwd_static(fake, None, fake, fake, None, fake, fake, None, fake, None, B.RMSNORM, T, n, h, 0,
+                                           1.0, stream=0, check=False)
+    assert st(1, 2056, 8192) == B.ESCRATCH and st(8, 4096, 8192) == B.ESCRATCH
+    assert B.norm_bwd_workspace_bytes(1, 2048, 8192) == 16 << 20 and B.norm_bwd_workspace_bytes(16, 1 << 20, 4096) == 16 << 20
+    assert st(1, 8, 8200) == B.ESHAPE and st(0, 8, 64) == B.EINVAL
     assert B.gemm_bf16(fake, fake, fake, B.GEMM_NT, 1, 8, 12, 8, 8, 8, 16, 0, 0, 0, stream=0, check=False) == B.ESHAPE
     assert B.gemm_bf16(fake, fake, fake, 5, 1, 8, 8, 8, 8, 8, 8, 0, 0, 0, stream=0, check=False) == B.EINVAL
     assert B.gemm_bf16(fake, fake, fake + 4, B.GEMM_NT, 1, 8, 8, 8, 8, 8, 8, 0, 0, 0, stream=0, check=False) == B.EALIGN
