@@ -21,20 +21,28 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
-# HBM bytes per launch read off the rocprofv3 --pmc runs of these same commands (FETCH_SIZE x 2.00 calibration factor
-# + WRITE_SIZE x 1.00), summarised in the profiles/ file of each configuration; valid for the default p only.  A kernel
-# family with several launches or kernels per step (the two weight-gradient GEMMs, the three kernels of the attention
-# backward) carries the mean per launch, respectively the sum over its kernels, like its time.
-PMC_TRAFFIC_BYTES = {("C2", 0.5): {"gemm_tn_wgrad": 403e6 + 34e6, "gemm_nt_gelu_fwd": 408e6 + 268e6,
-                                   "gemm_nt_rowpar": 471e6 + 134e6, "gemm_nn_gelu_bwd": 537e6 + 134e6,
-                                   "gemm_nn_dgrad": 403e6 + 134e6},
-                     ("C3", 0.5): {"gemm_tn_wgrad": 1010e6 + 140e6, "gemm_nt_swiglu_fwd": 1370e6 + 304e6,
-                                   "gemm_nt_rowpar": 691e6 + 268e6, "gemm_nn_swiglu_bwd": 1048e6 + 182e6,
-                                   "gemm_nn_dgrad": 1084e6 + 269e6},
-                     ("C4", 0.5): {"flash_attn_bwd": (136e6 + 67e6) + (182e6 + 34e6) + (67e6 + 1e6),
-                                   "flash_attn_fwd": 116e6 + 34e6},
-                     ("C5", 0.5): {"decode_attn": 2149e6 + 1e6},
-                     ("C6", 0.5): {"gemm_nt_swiglu_fwd": 12660e6 + 2465e6}}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.md")
+
+
+def pmc_traffic_bytes(config: str, p: float, kernel: str):
+    """HBM bytes per launch of a kernel family as the rocprofv3 --pmc runs of this same command measured them
+    (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size): read from the
+    tracked table profiles/hbm_traffic_per_launch.md (rows `| config | p | kernel family | read MB | write MB |`).
+    None if the table has no row for this configuration, p and kernel."""
+    try:
+        rows = open(TRAFFIC_TABLE).read().splitlines()
+    except OSError:
+        return None
+    for line in rows:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 5 or cells[0] != config or cells[2].strip("`") != kernel:
+            continue
+        try:
+            if abs(float(cells[1]) - p) < 1e-9:
+                return (float(cells[3]) + float(cells[4])) * 1e6
+        except ValueError:
+            continue
+    return None
 
 
 def hs_of(cfg) -> int:
@@ -64,6 +72,8 @@ def sync_bytes(name: str, cfg, hs: int) -> float:
         return 3.0 * T * n * hs * 2
     if name == "partial_sync_bwd":       # in place: read T, write T, shared channels only
         return 2.0 * T * n * hs * 2
+    if name == "partial_sync_norm_fwd":  # one launch: T partials + T residual slices + the private channels read, R' shared
+        return (3.0 * T * n * hs + T * n * (h - hs) + T * n * h) * 2 + T * n * 8   # channels and the normalised copy written
     if name == "norm_fwd":
         return 2.0 * T * n * h * 2 + T * n * 8
     if name == "norm_bwd":               # read dy, dres, x; write g and scaled g (whose shared channels the reduce writes)
@@ -176,13 +186,22 @@ class MlpBench:
         return {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / steps} for k, v in acc.items()}
 
 
+_SYNC_HOST = {}
+
+
 def standalone_sync(torch, B, cfg, hs, iters=20, nsets=8):
     """caat_partial_sync in place on the shared channels, rotating over buffer sets (> 1 GB) so that the
-    last-level cache cannot hold the working set: the HBM-bound figure."""
+    last-level cache cannot hold the working set: the HBM-bound figure.  Seeded N(0,1) partial sums from the input
+    module (one host draw, copied into every set: the rotation is about addresses, not values)."""
     if hs == 0:
         return 0.0, 0.0
+    from paper_2506_19645_amd import inputs as I
     T, n, h = cfg.T, cfg.tokens, cfg.h
-    bufs = [torch.randn(T, n, h, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(nsets)]
+    key = (T, n, h)
+    if key not in _SYNC_HOST:
+        _SYNC_HOST.clear()
+        _SYNC_HOST[key] = B.to_device(I.make_sync_inputs(T, n, h, seed=0)["Zt"])
+    bufs = [_SYNC_HOST[key].clone() for _ in range(nsets)]
     for b in bufs:
         B.partial_sync(b, None, b, T, n, h, hs, 1.0)
     torch.cuda.synchronize()
@@ -197,24 +216,52 @@ def standalone_sync(torch, B, cfg, hs, iters=20, nsets=8):
     return ms, 4.0 * T * n * hs / ms / 1e6     # GB/s, algorithmic 4*T*hs bytes per token
 
 
+def copy_ceiling(torch, B, nbytes=1 << 30, iters=10):
+    """What a plain device copy (equal read and write volumes, like the reduce and norm kernels) reaches on this machine:
+    the library's streaming probe, contiguous piece per workgroup, with and without the non-temporal hint."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    out = {}
+    for mode, name in ((3, "copy_GB/s"), (4, "copy_nontemporal_GB/s"), (1, "read_nontemporal_GB/s")):
+        for _ in range(3):
+            B.hbm_probe(src, dst, nbytes, mode)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            B.hbm_probe(src, dst, nbytes, mode)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(nbytes * (2 if mode >= 3 else 1) / (e0.elapsed_time(e1) / iters) / 1e6, 1)
+    out["note"] = "1 GiB buffers, 16-byte accesses; bytes moved = read + written"
+    return out
+
+
 def cpu_baseline(cfg, host, sample_tokens):
-    """The numpy fp64 oracle (as it stands) on the first `sample_tokens` tokens of every rank, fwd + bwd."""
+    """The numpy oracle (as it stands: float64) on the first `sample_tokens` tokens of every rank, fwd + bwd; the same
+    run in the oracle's float32 variant beside it (the precision the benchmark definition names for the CPU reference)."""
     import numpy as np
     from oracle import caat_oracle as O
     n = min(sample_tokens, cfg.tokens)
     sub = {k: (v[:, :n] if k in ("X", "R", "dXo", "dRo") else v) for k, v in host.items()}
-    w = {k: O.widen_bf16(v) for k, v in sub.items()}
     swi = cfg.kind == 1
     norm = O.LAYERNORM if cfg.norm == 0 else O.RMSNORM
     kw = dict(swiglu=swi, norm=norm, hs=O.shared_channels(cfg.h, cfg.p), eps=cfg.eps, private_scale=cfg.private_scale)
-    t0 = time.perf_counter()
-    fwd = O.mlp_block_fwd(w["X"], w["R"], w, w["gamma"], w.get("beta"), **kw)
-    O.mlp_block_bwd(w["X"], fwd, w, w["gamma"], w["dXo"], w["dRo"], **kw)
-    sec = time.perf_counter() - t0
     flops = 6.0 * n * cfg.h * cfg.ffn * (3 if swi else 2)
+    res = {}
+    for name, dt in (("fp64", np.float64), ("fp32", np.float32)):
+        w = {k: O.widen_bf16(v, dt) for k, v in sub.items()}
+        t0 = time.perf_counter()
+        fwd = O.mlp_block_fwd(w["X"], w["R"], w, w["gamma"], w.get("beta"), **kw)
+        O.mlp_block_bwd(w["X"], fwd, w, w["gamma"], w["dXo"], w["dRo"], **kw)
+        res[name] = time.perf_counter() - t0
+        del w, fwd
+    sec = res["fp64"]
     return {"value": flops / sec / 1e12, "unit": "TFLOP/s", "cores": _blas_threads(), "kind": "oracle",
             "sample": "numpy fp64 oracle, fwd+bwd, first %d of %d tokens of each of the %d ranks (%.1f s)"
-                      % (n, cfg.tokens, cfg.T, sec), "seconds": sec}
+                      % (n, cfg.tokens, cfg.T, sec), "seconds": sec,
+            "fp32_variant": {"value": flops / res["fp32"] / 1e12, "unit": "TFLOP/s", "seconds": res["fp32"],
+                             "sample": "the same oracle and sample in float32"}}
 
 
 def _blas_threads():
@@ -425,13 +472,13 @@ def bench_attention_kinds(args, cfg, base):
         value = work / ms / 1e9
         ach = fl.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e9
         roof = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-                "traffic": PMC_TRAFFIC_BYTES.get((args.config, args.p), {}).get(dom),
+                "traffic": pmc_traffic_bytes(args.config, args.p, dom),
                 "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": fl.get(dom, 0.0)}
     else:
         value = work / ms / 1e6
         ach = by.get(dom, 0.0) / prof[dom]["avg_ms"] / 1e6
         roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-                "traffic": PMC_TRAFFIC_BYTES.get((args.config, args.p), {}).get(dom),
+                "traffic": pmc_traffic_bytes(args.config, args.p, dom),
                 "avg_launch_ms": prof[dom]["avg_ms"], "bytes_per_launch": by.get(dom, 0.0)}
     out = {"metric": "partial-sync TP block TFLOP/s (% MFMA peak) + sync GB/s (% HBM) vs p, 1 GPU",
            "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
@@ -483,6 +530,40 @@ def bench_attention_kinds(args, cfg, base):
     return out
 
 
+def other_configs(args):
+    """Condensed records of the other benchmark configurations measured in the same run as the C2 headline: the 7B
+    SwiGLU MLP block (C3, forward + backward) and the decode layer (C5) at p = 0.5, and C5's p sweep."""
+    import copy
+    import gc
+    import torch
+    from paper_2506_19645_amd import inputs as I
+    out = {}
+    for name in ("C3", "C5"):
+        a = copy.copy(args)
+        a.config, a.p, a.no_cpu = name, 0.5, True
+        a.no_sweep = name != "C5"
+        a.steps, a.warmup = (20, 8) if name == "C3" else (50, 10)
+        base = I.CONFIGS[name]
+        r = bench_mlp(a, base.with_(p=0.5), base) if name == "C3" else bench_attention_kinds(a, base.with_(p=0.5), base)
+        rf = r["roofline"]
+        e = {"workload": r["config"]["workload"], "value": round(r["value"], 1), "unit": r["unit"],
+             "ms_per_step": round(r["ms_per_step"], 5), "steps": a.steps, "warmup": a.warmup,
+             "frac_of_peak": round(r["value"] / (MFMA_BF16_PEAK_TFLOPS if r["unit"] == "TFLOP/s" else HBM_PEAK_GBS), 4),
+             "dominant_kernel": {"kernel": rf["kernel"], "bound": rf["bound"], "achieved": round(rf["achieved"], 1),
+                                 "unit": rf["unit"], "frac": round(rf["frac"], 4),
+                                 "avg_launch_ms": round(rf["avg_launch_ms"], 5), "traffic": rf["traffic"]},
+             "kernels": {k: {kk: vv for kk, vv in v.items() if kk in ("avg_ms", "launches_per_step", "frac_mfma_peak", "frac_hbm_peak")}
+                         for k, v in r["kernels"].items()}}
+        if name == "C5":
+            e["latency_us_per_token_step"] = round(r["config"]["latency_us_per_token_step"], 2)
+            e["p_sweep"] = r.get("p_sweep")
+        out[name] = e
+        del r
+        gc.collect()
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -506,6 +587,8 @@ def main():
     ap.add_argument("--probe-hbm", action="store_true",
                     help="no workload: time the library's HBM streaming probe (read / copy, access pattern, "
                          "non-temporal hint) on a 2 GiB buffer and print one JSON line")
+    ap.add_argument("--no-others", action="store_true",
+                    help="default C2 run: leave out the condensed C3 / C5 records (other_configs)")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph and time its replays (launch-bound small configs)")
     args = ap.parse_args()
@@ -553,6 +636,17 @@ def main():
     if args.config in ("C4", "C5", "C6", "C7"):
         print(json.dumps(bench_attention_kinds(args, cfg, base)))
         return
+    out = bench_mlp(args, cfg, base)
+    if args.config == "C2" and not args.no_others:
+        out["other_configs"] = other_configs(args)
+    print(json.dumps(out))
+
+
+def bench_mlp(args, cfg, base):
+    """JSON for the MLP block configurations (C1-C3): forward + backward per step, TFLOP/s."""
+    import torch
+    from paper_2506_19645_amd import binding as B
+    from paper_2506_19645_amd import inputs as I
     bench = MlpBench(cfg, seed=0)
     desc = B.make_desc(cfg, reduce_in_gemm=args.reduce_in_gemm, dedup_shared=args.dedup_shared)
     k = 3 if cfg.kind == I.KIND_MLP_SWIGLU else 2
@@ -576,7 +670,7 @@ def main():
     achieved = dom_flops / prof[dom]["avg_ms"] / 1e9
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": PMC_TRAFFIC_BYTES.get((args.config, args.p), {}).get(dom),
+                "traffic": pmc_traffic_bytes(args.config, args.p, dom),
                 "avg_launch_ms": prof[dom]["avg_ms"], "flops_per_launch": dom_flops}
     if not args.no_sweep:
         roofline["power_check"] = gemm_power_check(torch, B, bench, cfg)
@@ -598,9 +692,13 @@ def main():
             c = base.with_(p=p)
             dsc = B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm)
             ms_p, _ = bench.time_steps(dsc, args.steps, args.warmup)   # same warm-up as the headline: the clocks ramp
-            pr = bench.profile_steps(dsc, 5)
+            # the reduce as a kernel of its own (the in-HBM stand-in for the collective): its time in the step against p
+            dsep = B.make_desc(c, reduce_in_gemm=args.reduce_in_gemm, separate_reduce=True)
+            ms_sep, _ = bench.time_steps(dsep, max(5, args.steps // 2), max(3, args.warmup // 2))
+            pr = bench.profile_steps(dsep, 5)
             sa_ms, sa_gbs = standalone_sync(torch, B, c, hs_of(c))
             e = {"p": p, "hs": hs_of(c), "ms_per_step": round(ms_p, 4), "TFLOP/s": round(step_flops / ms_p / 1e9, 1),
+                 "ms_per_step_reduce_as_own_kernel": round(ms_sep, 4),
                  "synced_payload_bytes_per_token_per_reduce": 2 * hs_of(c),
                  "in_hbm_sync_bytes_per_token_fwd": 6 * c.T * hs_of(c), "in_hbm_sync_bytes_per_token_bwd": 4 * c.T * hs_of(c),
                  "standalone_sync_ms": round(sa_ms, 5), "standalone_sync_GB/s": round(sa_gbs, 1),
@@ -644,9 +742,11 @@ def main():
                    "wall_ms_per_step": wall_ms},
         "roofline": roofline, "kernels": kernels, "p_sweep": sweep, "sync_time_vs_p_fit": sync_fit,
     }
+    if not args.no_sweep:
+        out["hbm_copy_ceiling"] = copy_ceiling(torch, B)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, bench.host, args.cpu_sample_tokens)
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":
