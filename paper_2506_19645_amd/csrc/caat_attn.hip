@@ -4,11 +4,14 @@
 //
 // Work split: a workgroup of 4 waves owns 128 consecutive queries of one (rank, sequence, head); each wave owns
 // 32 of them.  Keys / values are walked in blocks of 64: the K and V blocks go global -> LDS directly (double
-// buffered), chunk-swizzled on the global side.  Scores are computed transposed (S^T = K q^T) so that a lane owns
+// buffered), chunk-swizzled on the global side.  The forward kernel is software-pipelined inside a wave: the K ring
+// runs one block ahead of the V ring, and the score MFMAs of block b+1 are issued interleaved, one per step, with the
+// softmax arithmetic of block b (a wave issues in order, so what should run under an MFMA stands right behind it).  Scores are computed transposed (S^T = K q^T) so that a lane owns
 // one query row: lane l holds, for query l%32, the keys 8*(r/4) + 4*(l/32) + r%4 of each 32-key tile in register r.
 // Those registers, exponentiated and rounded to bf16, ARE the k-slices the second MFMA needs for P (the order
 // of the contraction index inside an MFMA is free as long as both operands agree), and the matching V operand
 // (4 consecutive keys of one head-dim column per read) comes from the LDS transpose read ds_read_b64_tr_b16.
+#include <type_traits>
 #include "caat_internal.h"
 
 namespace caat {
@@ -166,6 +169,14 @@ static constexpr int KCH = HD / 8;  // 16-byte chunks per K/V row
 long long attn_seq_pad(int seq) { return ((long long)seq + 63) / 64 * 64; }
 size_t attn_stats_bytes(long long n_seq, int heads, int seq) { return (size_t)(n_seq * heads * 2 * attn_seq_pad(seq)) * 4; }
 
+// maximum of three finite-or-infinite values in one instruction (the scores are MFMA results or -inf, never NaN: no
+// quieting of the inputs needed, which the generic fmaxf costs one extra instruction per operand)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 // LDS chunk swizzles (chunk = 16 bytes of a 256-byte row): K is read as MFMA fragments (32 consecutive rows, one
 // chunk) -> spread by row & 15; V is read by the transpose read (4 consecutive rows x 64 bytes) -> spread by row & 3.
 __device__ __forceinline__ int kswz(int row, int c) { return c ^ (row & 15); }
@@ -201,7 +212,7 @@ static int attn_chunk_heads(int seq) {
 __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                         float* __restrict__ stats, int seq, int seq_pad, int hd, int heads,
                                                         int kv_heads, int n_qblk, float scale_log2, int chunk) {
-  __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
+  __shared__ uint4 smem[4 * BKV * KCH];  // K slot 0, K slot 1, V slot 0, V slot 1: 64 rows x 16 chunks each = 64 KB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, hf = lane >> 5;
@@ -241,84 +252,149 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16_t* __restr
   const int kv_end = min(seq, q0 + BQ);                 // causal: keys 0 .. last query of the block
   const int nblk = (kv_end + BKV - 1) / BKV;
 
-  // global -> LDS: a wave instruction fills 4 rows (64 lanes x 16 B); 64 rows = 16 instructions per tile, 4 per wave
-  auto issue_tile = [&](int blk, int stage) {
+  // global -> LDS: a wave instruction fills 4 rows (64 lanes x 16 B); 64 rows = 16 instructions per tile, 4 per wave.
+  // LDS: two K slots, then two V slots (one 64-row tile each).  The K ring runs one block ahead of the V ring: the
+  // scores of block b+1 are computed while block b goes through the softmax (see the loop below).
+  constexpr int TILE_BYTES = BKV * KCH * 16;
+  unsigned dko[4], dvo[4];   // per-lane memory-side offsets of this wave's 4 copies of a tile (row, swizzled chunk)
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int rg = it * 4 + wave;                      // group of 4 rows
+    const int row = rg * 4 + (lane >> 4), phys = lane & 15;
+    dko[it] = (unsigned)((long long)row * ld * 2 + kswz(row, phys) * 16);
+    dvo[it] = (unsigned)((long long)row * ld * 2 + vswz(row, phys) * 16);
+  }
+  auto issue_rows = [&](const bf16_t* base, const unsigned* off, int blk, int slot_tile) {
     const int kv0 = blk * BKV;
-    const i32x4_t rk = make_rsrc(kbase + (long long)kv0 * ld);
-    const i32x4_t rv = make_rsrc(vbase + (long long)kv0 * ld);
-    uint4* kt = smem + stage * (2 * BKV * KCH);
-    uint4* vt = kt + BKV * KCH;
+    const i32x4_t rs = make_rsrc(base + (long long)kv0 * ld);
+    uint4* t = smem + slot_tile * (BKV * KCH);
+    const bool whole = kv0 + BKV <= seq;               // all 64 rows exist (every block but the last of a ragged sequence)
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int rg = it * 4 + wave;                    // group of 4 rows
-      const int row = rg * 4 + (lane >> 4), phys = lane & 15;
-      const bool in = (kv0 + row) < seq;
-      const unsigned ko = in ? (unsigned)((long long)row * ld * 2 + kswz(row, phys) * 16) : OOB_OFF;
-      const unsigned vo = in ? (unsigned)((long long)row * ld * 2 + vswz(row, phys) * 16) : OOB_OFF;
-      dma16(rk, ko, kt + rg * 64);
-      dma16(rv, vo, vt + rg * 64);
+      const int rg = it * 4 + wave;
+      const unsigned o = (whole || kv0 + rg * 4 + (lane >> 4) < seq) ? off[it] : OOB_OFF;
+      dma16(rs, o, t + rg * 64);
     }
   };
+  auto issue_k = [&](int blk) { issue_rows(kbase, dko, blk, blk & 1); };
+  auto issue_v = [&](int blk) { issue_rows(vbase, dvo, blk, 2 + (blk & 1)); };
 
-  issue_tile(0, 0);
-  for (int blk = 0; blk < nblk; ++blk) {
-    const int stage = blk & 1;
-    wait_vmcnt<0>();
-    __syncthreads();                                   // tile blk landed; everyone is done with the other stage
-    if (blk + 1 < nblk) issue_tile(blk + 1, stage ^ 1);
-    const uint4* kt = smem + stage * (2 * BKV * KCH);
-    const char* vt = reinterpret_cast<const char*>(kt + BKV * KCH);
-    const int kv0 = blk * BKV;
+  // Per-lane LDS addresses of the fragment reads, fixed for the whole kernel: what changes from read to read (slot,
+  // key tile, 16-key slice) is a compile-time constant that goes into the instruction's immediate offset, so the key loop
+  // spends no vector ALU work on addresses (they were about a third of its vector instructions).
+  //   K fragment (32 rows x one 16-byte chunk): row = 32 j + frow, logical chunk 2 ks + hf  -> koff[ks] + (slot, j) constant
+  //   V transpose read: row = 16 u + 4 hf + (i16 >> 2) (+ 8), head-dim column 32 dt + 16 grp + 4 (i16 & 3) -> voff[dt] + constant
+  typedef __attribute__((address_space(3))) const u32x4_t* lds_u4_t;
+  typedef __attribute__((address_space(3))) const char* lds_c_t;
+  typedef __attribute__((address_space(3))) short4_t* lds_s4_t;
+  lds_u4_t koff[HD / 16];
+  lds_c_t voff[HD / 32];
+  {
+    const lds_c_t lds0 = (lds_c_t)smem;
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ++ks) koff[ks] = (lds_u4_t)(lds0 + (frow * KCH + kswz(frow, ks * 2 + hf)) * 16);
+    const int i16 = lane & 15, grp = (lane >> 4) & 1;
+    const int vrow = 4 * hf + (i16 >> 2);
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt) {
+      const int col = dt * 32 + grp * 16 + (i16 & 3) * 4;
+      voff[dt] = lds0 + ((vrow * KCH + vswz(vrow, col >> 3)) * 16 + (col & 7) * 2);
+    }
+  }
+  const f32x16_t zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const bf16x2_t ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
-    // ---- S^T tiles: 2 key tiles of 32; contraction over head dim in 8 steps of 16
-    f32x16_t sacc[BKV / 32];
+  // S^T = K q^T for the 64 keys in K slot SLOT: 2 key tiles of 32, contraction over the head dim in 8 steps of 16 (the
+  // first step starts from zero instead of clearing the accumulator first)
+  auto scores = [&](f32x16_t* sacc, auto slot_c) {
+    constexpr int SLOT = decltype(slot_c)::value;
 #pragma unroll
-    for (int j = 0; j < BKV / 32; ++j) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[j][r] = 0.0f;
+    for (int j = 0; j < BKV / 32; ++j)
 #pragma unroll
       for (int ks = 0; ks < HD / 16; ++ks) {
-        const int row = j * 32 + frow;
-        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, kt[row * KCH + kswz(row, ks * 2 + hf)]);
-        sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[j], 0, 0, 0);
+        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, koff[ks][(SLOT * TILE_BYTES + j * 32 * KCH * 16) / 16]);
+        sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? zero16 : sacc[j], 0, 0, 0);
       }
-    }
-    // ---- causal mask + online softmax for query qrow (keys of register r: kv0 + 32j + 8(r/4) + 4hf + r%4)
-    float mx = -INFINITY;
-    // wave-uniform: does some key of this block exceed some query of this wave?  (only the last blocks of a tile)
+  };
+
+  // One key block, software-pipelined inside the wave: the scores of block blk are already in `scur`; the matrix unit
+  // works on the scores of block blk+1 (`snext`, from the other K slot) while the vector ALU takes block blk through the
+  // online softmax; then the second product of block blk.  SLOT = blk & 1 (compile-time: the loop alternates two
+  // instantiations, which also swaps the roles of the two score register sets without a copy).
+  auto key_block = [&](int blk, f32x16_t* scur, f32x16_t* snext, auto slot_c, auto last_c) {
+    constexpr int SLOT = decltype(slot_c)::value;
+    constexpr bool LAST = decltype(last_c)::value;
+    wait_vmcnt<0>();
+    __syncthreads();                 // K(blk+1) and V(blk) have landed; everyone is done with K(blk) and V(blk-1)
+    if (blk + 2 < nblk) issue_k(blk + 2);
+    if (blk + 1 < nblk) issue_v(blk + 1);
+    const int kv0 = blk * BKV;
+    // ---- causal mask for query qrow (keys of register r: kv0 + 32j + 8(r/4) + 4hf + r%4); wave-uniform test: does
+    // some key of this block exceed some query of this wave?  (only the last blocks of a tile)
     if ((kv0 + BKV - 1) > (q0 + wave * 32)) {
 #pragma unroll
       for (int j = 0; j < BKV / 32; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = kv0 + j * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          if (key > qrow) sacc[j][r] = -INFINITY;
+          if (key > qrow) scur[j][r] = -INFINITY;
         }
     }
+    // ---- The instruction stream of the block is laid out by hand, one MFMA per step, with a scheduling fence after
+    // every step (the compiler keeps the order of the steps and only arranges the few instructions inside one):
+    // a wave issues in order, so whatever should run under an MFMA has to stand right behind it in the stream.
+    //   steps 0-15 : score MFMAs of block blk+1 (fragments read three steps ahead); underneath: the row maximum of
+    //                block blk (steps 0-3), its exchange with the other half-row (4-5), the exponentials of keys 0-31 (6-13)
+    //   (rescale of the output accumulators, only if some row's maximum moved)
+    //   steps 16-31: second-product MFMAs, 16-key slice by slice (V fragments read three steps ahead); underneath: the
+    //                exponentials of keys 32-63 (steps 16-23), which only slices 2 and 3 need
+    auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+    auto kread = [&](int idx) -> u32x4_t {
+      return koff[idx & 7][((SLOT ^ 1) * TILE_BYTES + (idx >> 3) * 32 * KCH * 16) / 16];
+    };
+    float mx = -INFINITY, mxo = 0.0f, m_new = 0.0f, alpha = 1.0f, mb = 0.0f, psum = 0.0f;
+    unsigned pw[BKV / 2];               // the block's probabilities, bf16 pairs: pw[4 i .. 4 i + 3] = slice i's B operand
+    auto prob_pair = [&](int i) {       // pair i: registers 2 i, 2 i + 1 of the 32 scores of this lane
+      const int j = i >> 3, r = (i & 7) * 2;
+      // arguments <= 0; tiny results flush to 0
+      const float p0 = __builtin_amdgcn_exp2f(scur[j][r] * scale_log2 - mb);
+      const float p1 = __builtin_amdgcn_exp2f(scur[j][r + 1] * scale_log2 - mb);
+      pw[i] = pack2bf(p0, p1);
+      // the row sum takes the probabilities as the second product sees them (rounded to bf16), two per instruction
+      psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pw[i]), ones2, psum, false);
+      // pins the pair to this place in the stream (the optimiser would otherwise sink it to its first use)
+      asm volatile("" : "+v"(pw[i]), "+v"(psum));
+    };
+    u32x4_t kr[3];
+    if constexpr (!LAST) {
+      kr[0] = kread(0);
+      kr[1] = kread(1);
+      kr[2] = kread(2);
+    }
+    fence();
 #pragma unroll
-    for (int j = 0; j < BKV / 32; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[j][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));            // the other half of the row lives in lane ^ 32
-    const float m_new = fmaxf(m_run, mx);               // finite: key 0 is visible to every query
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
-    const float mb = m_new * scale_log2;
-    float psum = 0.0f;
-    bf16x8_t pf[BKV / 16];
-#pragma unroll
-    for (int j = 0; j < BKV / 32; ++j)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        float pv[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          pv[e] = __builtin_amdgcn_exp2f(sacc[j][t * 8 + e] * scale_log2 - mb);   // arguments <= 0; tiny results flush to 0
-          psum += pv[e];
-        }
-        const uint4 w = make_uint4(pack2bf(pv[0], pv[1]), pack2bf(pv[2], pv[3]), pack2bf(pv[4], pv[5]), pack2bf(pv[6], pv[7]));
-        pf[j * 2 + t] = __builtin_bit_cast(bf16x8_t, w);
+    for (int idx = 0; idx < 16; ++idx) {
+      if constexpr (!LAST) {
+        const int j = idx >> 3, ks = idx & 7;
+        const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, kr[idx % 3]);
+        snext[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? zero16 : snext[j], 0, 0, 0);
+        if (idx + 3 < 16) kr[idx % 3] = kread(idx + 3);
       }
-    l_run = l_run * alpha + psum;
+      if (idx < 4) {                                    // row maximum: 8 of the lane's 32 scores per step
+        const int j = idx >> 1, r0 = (idx & 1) * 8;
+#pragma unroll
+        for (int r = 0; r < 8; r += 2) mx = max3(mx, scur[j][r0 + r], scur[j][r0 + r + 1]);
+        if (idx == 3) mxo = __shfl_xor(mx, 32, 64);    // the other half of the row lives in lane ^ 32
+      } else if (idx == 5) {
+        m_new = fmaxf(m_run, fmaxf(mx, mxo));           // finite: key 0 is visible to every query
+        alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
+        mb = m_new * scale_log2;
+      } else if (idx >= 6 && idx < 14) {
+        prob_pair(idx - 6);                             // keys 0-31 of the block: pairs 0-7; pairs 8-15 under the second product
+      }
+      fence();
+    }
     // the running maximum settles after the first blocks: rescale the accumulators only if some row's maximum moved
     if (__any(m_new != m_run)) {
 #pragma unroll
@@ -329,29 +405,53 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16_t* __restr
     m_run = m_new;
 
     // ---- O^T += V^T P^T : A operand = V columns (head-dim index frow of tile dt), B operand = P (query frow).
-    // k-slice u (16 keys) of the block: lane half hf contributes keys 16u + 4hf + {0..3} and 16u + 8 + 4hf + {0..3}
+    // k-slice u (16 keys) of the block: lane half hf contributes keys 16u + 4hf + {0..3} and 16u + 8 + 4hf + {0..3};
+    // transpose read: input lane i of a 16-lane group supplies row (i/4), 8-byte column group (i%4); output lane j
+    // receives column j of those 4 rows.  Step st: slice u = st / 4, head-dim tile dt = st % 4.
+    typedef short short8_t __attribute__((ext_vector_type(8)));
+    auto vread = [&](int st, short4_t& v0, short4_t& v1) {
+      const lds_c_t a0 = voff[st & 3] + ((2 + SLOT) * TILE_BYTES + (st >> 2) * 16 * KCH * 16);
+      v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_t)a0);
+      v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_t)(a0 + 8 * KCH * 16));
+    };
+    short4_t va[3], vb[3];
+    vread(0, va[0], vb[0]);
+    vread(1, va[1], vb[1]);
+    vread(2, va[2], vb[2]);
+    fence();
 #pragma unroll
-    for (int dt = 0; dt < HD / 32; ++dt) {
-#pragma unroll
-      for (int u = 0; u < BKV / 16; ++u) {
-        // transpose read: input lane i of a 16-lane group supplies row (i/4), 8-byte column group (i%4);
-        // output lane j receives column j of those 4 rows
-        const int i16 = lane & 15, grp = (lane >> 4) & 1;
-        const int col = dt * 32 + grp * 16 + (i16 & 3) * 4;      // head-dim column of the 8-byte piece
-        short4_t v0, v1;
-        {
-          const int row = u * 16 + 4 * hf + (i16 >> 2);
-          const char* a0 = vt + (row * KCH + vswz(row, col >> 3)) * 16 + (col & 7) * 2;
-          v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)a0);
-          const int row1 = row + 8;
-          const char* a1 = vt + (row1 * KCH + vswz(row1, col >> 3)) * 16 + (col & 7) * 2;
-          v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)a1);
-        }
-        typedef short short8_t __attribute__((ext_vector_type(8)));
-        const short8_t vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv), pf[u], oacc[dt], 0, 0, 0);
-      }
+    for (int st = 0; st < 16; ++st) {
+      const int u = st >> 2, dt = st & 3;
+      const short8_t vv = {va[st % 3][0], va[st % 3][1], va[st % 3][2], va[st % 3][3],
+                           vb[st % 3][0], vb[st % 3][1], vb[st % 3][2], vb[st % 3][3]};
+      const bf16x8_t pfu = __builtin_bit_cast(bf16x8_t, make_uint4(pw[4 * u], pw[4 * u + 1], pw[4 * u + 2], pw[4 * u + 3]));
+      oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv), pfu, oacc[dt], 0, 0, 0);
+      if (st + 3 < 16) vread(st + 3, va[st % 3], vb[st % 3]);
+      if (st < 8) prob_pair(8 + st);                    // keys 32-63: needed from step 8 (slice 2) on
+      fence();
     }
+    l_run = l_run * alpha + psum;
+  };
+
+  // prologue: K(0) alone first (its scores open the pipeline), then K(1) and V(0) for the first loop iteration
+  // prologue: K(0) alone first (its scores open the pipeline), then K(1) and V(0) for the first loop iteration
+  f32x16_t sa[BKV / 32], sb[BKV / 32];
+  issue_k(0);
+  wait_vmcnt<0>();
+  __syncthreads();
+  if (1 < nblk) issue_k(1);
+  issue_v(0);
+  scores(sa, std::integral_constant<int, 0>{});
+  int blk = 0;
+  for (; blk + 2 < nblk; blk += 2) {
+    key_block(blk, sa, sb, std::integral_constant<int, 0>{}, std::false_type{});
+    key_block(blk + 1, sb, sa, std::integral_constant<int, 1>{}, std::false_type{});
+  }
+  if (blk + 1 < nblk) {       // two blocks left
+    key_block(blk, sa, sb, std::integral_constant<int, 0>{}, std::false_type{});
+    key_block(blk + 1, sb, sa, std::integral_constant<int, 1>{}, std::true_type{});
+  } else {                    // one block left
+    key_block(blk, sa, sb, std::integral_constant<int, 0>{}, std::true_type{});
   }
 
   // ---- normalise and store: lane holds out[qrow][32dt + 8(r/4) + 4hf + r%4]
@@ -484,7 +584,7 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16_t* __re
                                                            const float* __restrict__ stats, bf16_t* __restrict__ dqkv, int seq,
                                                            int seq_pad, int hd, int heads, int kv_heads, int n_qblk,
                                                            float scale_log2, float scale, int chunk) {
-  __shared__ uint4 smem[2 * 2 * BKV * KCH];  // [stage][K|V][64 rows][16 chunks] = 64 KB
+  __shared__ uint4 smem[4 * BKV * KCH];  // K slot 0, K slot 1, V slot 0, V slot 1: 64 rows x 16 chunks each = 64 KB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int frow = lane & 31, hf = lane >> 5;
