@@ -76,6 +76,8 @@ def sync_bytes(name: str, cfg, hs: int) -> float:
         return (3.0 * T * n * hs + T * n * (h - hs) + T * n * h) * 2 + T * n * 8   # channels and the normalised copy written
     if name == "norm_fwd":
         return 2.0 * T * n * h * 2 + T * n * 8
+    if name == "norm_bwd_sync":          # one launch: read dy, dres, x; write g and the reduced / scaled copy
+        return 5.0 * T * n * h * 2 + T * n * 8
     if name == "norm_bwd":               # read dy, dres, x; write g and scaled g (whose shared channels the reduce writes)
         return 5.0 * T * n * h * 2 - (T * n * hs * 2 if hs % 8 == 0 else 0) + T * n * 8
     return 0.0
@@ -416,6 +418,7 @@ def bench_attention_kinds(args, cfg, base):
             fl.update({"flash_attn_bwd": 5.0 * cfg.batch * s * s * h, "gemm_nn_dgrad": 4.0 * n * h * h,
                        "gemm_tn_wgrad": 4.0 * n * h * h})
             by.update({"rope_bwd": 2.0 * T * n * 2 * hd * 2, "partial_sync_bwd": 2.0 * T * n * hs_of(cfg) * 2,
+                       "norm_bwd_sync": 5.0 * T * n * h * 2,
                        "norm_bwd": 5.0 * T * n * h * 2 - (T * n * hs_of(cfg) * 2 if hs_of(cfg) % 8 == 0 else 0)})
             work += 5.0 * cfg.batch * s * s * h + 16.0 * n * h * h
         unit, peak = "TFLOP/s", MFMA_BF16_PEAK_TFLOPS

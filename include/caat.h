@@ -101,7 +101,10 @@ typedef struct caat_desc {
                            add and the norm that follows run as ONE kernel, which does not read the reduced channels
                            back from memory.  1: the reduce stays a kernel of its own (caat_partial_sync's kernel, the
                            in-HBM stand-in for the tensor-parallel collective, whose time against p is what the
-                           benchmark's sweep reports) followed by the norm kernel.  Same values either way. */
+                           benchmark's sweep reports) followed by the norm kernel.  Same values either way.  The
+                           backward pass does likewise: norm backward and the reduce on its result are one kernel
+                           (0, for T = 4 up to h = 2048 and T = 2 up to h = 4096 with hs % 8 == 0) or two (1, and
+                           every other shape). */
 } caat_desc;
 
 /* Byte offsets of the tensors caat_block_fwd leaves in the workspace (0 size = not present).  For tests

@@ -150,6 +150,11 @@ bool fuse_reduce_norm(const caat_desc* d) {
   return !d->separate_reduce && !d->reduce_in_gemm && !d->dedup_shared && sync_norm_takes(d->T, d->tokens, d->h, d->hs);
 }
 
+// the same for the backward pass: norm backward + the reduce on its result
+bool fuse_norm_bwd_reduce(const caat_desc* d) {
+  return !d->separate_reduce && norm_bwd_sync_takes(d->T, d->tokens, d->h, d->hs);
+}
+
 // Row-parallel projection closed by the partial channel-reduce and the residual add (Eq. A3 / A5, second line + Sec. 4):
 //   out_m = PCR_p(a_m W_m^T)_m + resid_m,   a [T,n,kdim], W [T][h][kdim], resid / out [T,n,h].
 // Default: one grouped GEMM whose epilogue finishes the private channels and leaves each rank's partial sum on the
@@ -313,14 +318,21 @@ int attn_block_bwd(const caat_desc* d, const caat_ws_layout& L, const void* cons
   hipError_t e;
   GemmParams q;
 #define CAAT_STEP(name, call) { ProfScope ps(s, name); e = (call); } if (e != hipSuccess) return CAAT_EHIP;
-  CAAT_STEP("norm_bwd", launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
-                                        mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
-                                        d->private_scale, ws + L.off_scratch, s, true))
-  // when no 8-channel vector straddles hs, the norm backward leaves the shared channels of dZt to the reduce, which
-  // reads them from dr (the same values) instead of reading them back from dZt: one write of T*n*hs values less
-  CAAT_STEP("partial_sync_bwd", d->hs % 8 == 0
-                                    ? launch_partial_sync_shared_from((const bf16_t*)dr, dZt, (int)T, n, (int)h, d->hs, s)
-                                    : launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s))
+  if (fuse_norm_bwd_reduce(d)) {
+    // norm backward and the reduce on its result in one launch (the shared channels are not read back from memory)
+    CAAT_STEP("norm_bwd_sync", launch_norm_bwd_sync((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out,
+                                                    (const bf16_t*)gamma, mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm,
+                                                    (int)T, n, (int)h, d->hs, d->private_scale, ws + L.off_scratch, s))
+  } else {
+    CAAT_STEP("norm_bwd", launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
+                                          mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
+                                          d->private_scale, ws + L.off_scratch, s, true))
+    // when no 8-channel vector straddles hs, the norm backward leaves the shared channels of dZt to the reduce, which
+    // reads them from dr (the same values) instead of reading them back from dZt: one write of T*n*hs values less
+    CAAT_STEP("partial_sync_bwd", d->hs % 8 == 0
+                                      ? launch_partial_sync_shared_from((const bf16_t*)dr, dZt, (int)T, n, (int)h, d->hs, s)
+                                      : launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s))
+  }
   // dH_m = dZt_m Wo_m (NN): [n,h] x [h,hd]
   std::memset(&q, 0, sizeof(q));
   q.a = dZt; q.lda = h; q.stride_a = n * h;
@@ -710,22 +722,32 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
   // a6/a7: norm backward per rank FIRST (Fig. 2b): g_m = dr_out_m + NormBwd(dx_out_m); dr_m = g_m un-reduced;
   // a copy with scaled private channels goes to dZt; dgamma/dbeta summed over tokens and ranks
   hipError_t e;
-  {
-    ProfScope ps(s, "norm_bwd");
-    e = launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
-                                 mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
-                                 d->private_scale, ws + L.off_scratch, s, true);
+  if (fuse_norm_bwd_reduce(d)) {
+    // ... as one launch where the shape allows: the reduce sums the rounded residual gradients straight from the
+    // registers of the norm backward instead of reading them back
+    ProfScope ps(s, "norm_bwd_sync");
+    e = launch_norm_bwd_sync((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma, mean,
+                             rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs, d->private_scale,
+                             ws + L.off_scratch, s);
+    if (e != hipSuccess) return CAAT_EHIP;
+  } else {
+    {
+      ProfScope ps(s, "norm_bwd");
+      e = launch_norm_bwd((const bf16_t*)dx_out, (const bf16_t*)dr_out, (const bf16_t*)r_out, (const bf16_t*)gamma,
+                          mean, rstd, (bf16_t*)dr, dZt, dgamma, dbeta, d->norm, (int)T, n, (int)h, d->hs,
+                          d->private_scale, ws + L.off_scratch, s, true);
+    }
+    if (e != hipSuccess) return CAAT_EHIP;
+    // a8: the same partial channel-reduce on the gradients, shared channels only, fp32 accumulation.  When no 8-channel
+    // vector straddles hs, the norm backward has left dZt's shared channels unwritten and the reduce reads them from dr
+    // (the same values) and writes the sums into dZt; otherwise it runs in place on dZt.
+    {
+      ProfScope ps(s, "partial_sync_bwd");
+      e = d->hs % 8 == 0 ? launch_partial_sync_shared_from((const bf16_t*)dr, dZt, (int)T, n, (int)h, d->hs, s)
+                         : launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s);
+    }
+    if (e != hipSuccess) return CAAT_EHIP;
   }
-  if (e != hipSuccess) return CAAT_EHIP;
-  // a8: the same partial channel-reduce on the gradients, shared channels only, fp32 accumulation.  When no 8-channel
-  // vector straddles hs, the norm backward has left dZt's shared channels unwritten and the reduce reads them from dr
-  // (the same values) and writes the sums into dZt; otherwise it runs in place on dZt.
-  {
-    ProfScope ps(s, "partial_sync_bwd");
-    e = d->hs % 8 == 0 ? launch_partial_sync_shared_from((const bf16_t*)dr, dZt, (int)T, n, (int)h, d->hs, s)
-                       : launch_partial_sync(dZt, nullptr, dZt, (int)T, n, (int)h, d->hs, 1.0f, s);
-  }
-  if (e != hipSuccess) return CAAT_EHIP;
 
   // a9 + a10: dY_m = dZt_m B_m (NN), fused with the activation derivative -> dP_m
   GemmParams q;

@@ -220,6 +220,13 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
                            const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_scaled, float* dgamma,
                            float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
                            void* workspace, hipStream_t s, bool skip_shared_scaled = false);
+// norm backward + the backward partial channel-reduce in one launch (hs % 8 == 0; T = 4 up to h = 2048, T = 2 up to
+// h = 4096: norm_bwd_sync_takes); hipErrorInvalidValue if the shape is not taken.  Same workspace as launch_norm_bwd.
+bool norm_bwd_sync_takes(int T, long long tokens, int h, int hs);
+hipError_t launch_norm_bwd_sync(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
+                                const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_red, float* dgamma,
+                                float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
+                                void* workspace, hipStream_t s);
 // shared channels of dst = sum over ranks of src's; dst's other channels are not touched (hs % 8 == 0)
 hipError_t launch_partial_sync_shared_from(const bf16_t* src, bf16_t* dst, int T, long long tokens, int h, int hs,
                                            hipStream_t s);

@@ -724,6 +724,172 @@ __global__ __launch_bounds__(256) void norm_bwd_wide_kernel(const bf16_t* __rest
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Norm backward and the backward partial channel-reduce in one launch (Fig. 2b: norm backward per rank first, the same
+// reduce `h` on the result; Sec. 4: fp32 accumulation of values that travel as bf16).  One workgroup owns one token of
+// ALL ranks at a time (thread t of NT holds the 16-byte column groups t, t+NT, ... of every rank's row, as in the
+// forward sync_norm_kernel): it computes g_m = dres_m + NormBwd(dy_m) for the T rows, stores them rounded to bf16 as the
+// un-reduced residual gradient (App. B), keeps those rounded values in registers, sums the shared channels over the
+// ranks in ascending order in fp32 -- exactly the values and the order the stand-alone reduce would read back from
+// g_out -- rounds once and stores the result to every rank's row of g_red; private channels of g_red get scale * g_m.
+// A workgroup walks a contiguous range of tokens and keeps its threads' columns of dgamma / dbeta in registers over
+// all of them (summed over tokens AND ranks), one partial row per workgroup; norm_bwd_finalize_kernel adds them up.
+// hs % 8 == 0.  Saves, against the two kernels, the read-back of the shared channels and one launch.
+template <int TT, int NG, bool LN, int NT>
+__global__ __launch_bounds__(NT) void norm_bwd_sync_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ dres,
+                                                            const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+                                                            const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                            bf16_t* __restrict__ g_out, bf16_t* __restrict__ g_red,
+                                                            float* __restrict__ partial, long long n, int h, int hs,
+                                                            float scale, long long tokens_per_block) {
+  constexpr int NW = NT / 64;
+  __shared__ float red[2][2][NW][TT];   // [token parity][c1 | c2][wave][rank]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nvec = h >> 3;
+  const float inv_h = 1.0f / (float)h;
+  const long long plane = n * (long long)h;
+  float dgam[NG][8], dbet[LN ? NG : 1][8];
+  uint4 gam[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int vi = g * NT + tid;
+    gam[g] = make_uint4(0u, 0u, 0u, 0u);
+    if (vi < nvec) gam[g] = *reinterpret_cast<const uint4*>(gamma + vi * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dgam[g][e] = 0.0f;
+      if constexpr (LN) dbet[g][e] = 0.0f;
+    }
+  }
+  const long long t0 = (long long)blockIdx.x * tokens_per_block;
+  long long t1 = t0 + tokens_per_block;
+  if (t1 > n) t1 = n;
+  for (long long i = t0; i < t1; ++i) {
+    const int par = (int)((i - t0) & 1);
+    // the three inputs of all T rows of the token are requested together (read once: non-temporal)
+    uint4 wx[NG][TT], wd[NG][TT], wr[NG][TT];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const int vi = g * NT + tid;
+#pragma unroll
+      for (int m = 0; m < TT; ++m) {
+        wx[g][m] = make_uint4(0u, 0u, 0u, 0u);
+        wd[g][m] = wx[g][m];
+        wr[g][m] = wx[g][m];
+        if (vi < nvec) {
+          const long long off = m * plane + i * h + vi * 8;
+          wx[g][m] = ld_stream(x + off);
+          wd[g][m] = ld_stream(dy + off);
+          if (dres) wr[g][m] = ld_stream(dres + off);
+        }
+      }
+    }
+    float mu[TT], rs[TT], c1[TT], c2[TT];
+#pragma unroll
+    for (int m = 0; m < TT; ++m) {
+      mu[m] = LN ? mean[m * n + i] : 0.0f;
+      rs[m] = rstd[m * n + i];
+      c1[m] = 0.0f;
+      c2[m] = 0.0f;
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      float gm[8];
+      unpack8(gam[g], gm);
+#pragma unroll
+      for (int m = 0; m < TT; ++m) {
+        float fx[8], fd[8];
+        unpack8(wx[g][m], fx);
+        unpack8(wd[g][m], fd);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (fx[e] - mu[m]) * rs[m];   // idle threads: fd = 0 and gamma = 0, so they add nothing
+          const float dxh = fd[e] * gm[e];
+          c1[m] += dxh;
+          c2[m] += dxh * xh;
+          dgam[g][e] += fd[e] * xh;
+          if constexpr (LN) dbet[g][e] += fd[e];
+        }
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < TT; ++m) {
+      if constexpr (LN) c1[m] = wave_sum(c1[m]);
+      c2[m] = wave_sum(c2[m]);
+      if (lane == 0) {
+        if constexpr (LN) red[par][0][wave][m] = c1[m];
+        red[par][1][wave][m] = c2[m];
+      }
+    }
+    __syncthreads();   // one barrier per token: the slot of the token before last is free again by then
+#pragma unroll
+    for (int m = 0; m < TT; ++m) {
+      float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {     // the waves' sums in ascending order
+        if constexpr (LN) s1 += red[par][0][w][m];
+        s2 += red[par][1][w][m];
+      }
+      if constexpr (LN) c1[m] = s1 * inv_h;
+      c2[m] = s2 * inv_h;
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const int vi = g * NT + tid;
+      if (vi < nvec) {
+        const int col = vi * 8;
+        float gm[8];
+        unpack8(gam[g], gm);
+        float sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int m = 0; m < TT; ++m) {
+          float fx[8], fd[8], r[8], o[8];
+          unpack8(wx[g][m], fx);
+          unpack8(wd[g][m], fd);
+          unpack8(wr[g][m], r);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float xh = (fx[e] - mu[m]) * rs[m];
+            const float dxh = fd[e] * gm[e];
+            o[e] = r[e] + rs[m] * (LN ? (dxh - c1[m] - xh * c2[m]) : (dxh - xh * c2[m]));
+          }
+          const long long off = m * plane + i * h + col;
+          const uint4 gb = pack8(o);
+          if (col < hs) {                 // shared channels: the reduce runs on the ROUNDED residual gradient
+            *reinterpret_cast<uint4*>(g_out + off) = gb;
+            float f[8];
+            unpack8(gb, f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[e] += f[e];
+          } else {                        // private channels: nothing reads g_out again in the backward pass
+            st_stream(g_out + off, gb);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] *= scale;
+            *reinterpret_cast<uint4*>(g_red + off) = pack8(o);
+          }
+        }
+        if (col < hs) {
+          const uint4 sb = pack8(sum);    // one rounding, the same bits on every rank
+#pragma unroll
+          for (int m = 0; m < TT; ++m) *reinterpret_cast<uint4*>(g_red + m * plane + i * h + col) = sb;
+        }
+      }
+    }
+  }
+  float* prow = partial + (long long)blockIdx.x * 2 * h;
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int vi = g * NT + tid;
+    if (vi < nvec) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        prow[vi * 8 + e] = dgam[g][e];
+        if constexpr (LN) prow[h + vi * 8 + e] = dbet[g][e];
+      }
+    }
+  }
+}
+
 // sums partial[nb][2][h] over nb in a fixed order: a workgroup owns 64 columns (a thread 4 of them, one 16-byte
 // load per partial row), its 16 row groups each add every 16th partial row (4 independent chains), and the 16 group
 // sums are combined in ascending order through LDS.  h % 8 == 0, so 2h is a multiple of 4.  Only the first `ncols`
@@ -841,6 +1007,63 @@ hipError_t launch_norm_bwd(const bf16_t* dy, const bf16_t* dres, const bf16_t* x
   else return hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   const int ncols = norm == 0 ? 2 * h : h;           // RMSNorm has no dbeta: that half of a partial row is never written
+  hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((ncols + 63) / 64)), dim3(256), 0, s, partial, (int)nb,
+                     h, ncols, dgamma, norm == 0 ? dbeta : nullptr);
+  return hipGetLastError();
+}
+
+// Shapes the fused norm backward + reduce takes: a thread (of 256) holds x, dy and dres of its column groups for all T
+// rows of a token, and the kernel only beats the two separate kernels while that is at most 4 (rank, column group)
+// pairs per input (T = 4 up to h = 2048, T = 2 up to h = 4096).  Measured beyond that budget, T = 8 and h = 4096 with
+// 256, 512 or 1024 threads: 327 - 354 us against 279 us for the two kernels (every register of a one-wave-per-SIMD
+// budget, or spills), so those shapes keep the two kernels.
+static int norm_bwd_sync_groups(int T, int h) {
+  const int ng = (h / 8 + 255) / 256;
+  return ((T == 2 || T == 4) && T * ng <= 4) ? ng : 0;
+}
+bool norm_bwd_sync_takes(int T, long long tokens, int h, int hs) {
+  if (hs <= 0 || hs % 8 != 0 || hs > h || h % 8 != 0 || h > 8192 || tokens <= 0) return false;
+  return norm_bwd_sync_groups(T, h) != 0;
+}
+
+template <int TT, int NG, int NT>
+static hipError_t norm_bwd_sync_dispatch(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
+                                         const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_red, float* partial,
+                                         int norm, long long tokens, int h, int hs, float scale, long long nb, long long tpb,
+                                         hipStream_t s) {
+  if (norm == 0)
+    hipLaunchKernelGGL((norm_bwd_sync_kernel<TT, NG, true, NT>), dim3((unsigned)nb), dim3(NT), 0, s, dy, dres, x, gamma, mean,
+                       rstd, g_out, g_red, partial, tokens, h, hs, scale, tpb);
+  else
+    hipLaunchKernelGGL((norm_bwd_sync_kernel<TT, NG, false, NT>), dim3((unsigned)nb), dim3(NT), 0, s, dy, dres, x, gamma, mean,
+                       rstd, g_out, g_red, partial, tokens, h, hs, scale, tpb);
+  return hipGetLastError();
+}
+
+// g_out = dres + NormBwd(dy) per rank (un-reduced); g_red = the partial channel-reduce of g_out (shared channels summed
+// over ranks, private channels scaled); dgamma / dbeta summed over tokens and ranks.  The workspace is the one
+// launch_norm_bwd takes (at most 512 partial rows are used).  hipErrorInvalidValue for shapes not taken.
+hipError_t launch_norm_bwd_sync(const bf16_t* dy, const bf16_t* dres, const bf16_t* x, const bf16_t* gamma,
+                                const float* mean, const float* rstd, bf16_t* g_out, bf16_t* g_red, float* dgamma,
+                                float* dbeta, int norm, int T, long long tokens, int h, int hs, float private_scale,
+                                void* workspace, hipStream_t s) {
+  if (!norm_bwd_sync_takes(T, tokens, h, hs)) return hipErrorInvalidValue;
+  // as many partial rows as the row-wise kernels would use for this shape at most, so that the same workspace serves
+  long long nb = norm_bwd_blocks((long long)T * tokens, h);
+  if (nb > NORM_BWD_MAX_BLOCKS) nb = NORM_BWD_MAX_BLOCKS;
+  if (nb > tokens) nb = tokens;
+  const long long tpb = (tokens + nb - 1) / nb;
+  nb = (tokens + tpb - 1) / tpb;                     // no empty workgroups: every partial row is written
+  float* partial = reinterpret_cast<float*>(workspace);
+  const int ng = norm_bwd_sync_groups(T, h);
+  hipError_t e = hipErrorInvalidValue;
+#define CAAT_NBS(TT_, NG_) e = norm_bwd_sync_dispatch<TT_, NG_, 256>(dy, dres, x, gamma, mean, rstd, g_out, g_red, partial, norm, tokens, h, hs, private_scale, nb, tpb, s)
+  if (T == 2 && ng == 1) CAAT_NBS(2, 1);
+  else if (T == 2 && ng == 2) CAAT_NBS(2, 2);
+  else if (T == 4 && ng == 1) CAAT_NBS(4, 1);
+#undef CAAT_NBS
+  if (e != hipSuccess) return e;
+  const int ncols = norm == 0 ? 2 * h : h;
   hipLaunchKernelGGL(norm_bwd_finalize_kernel, dim3((unsigned)((ncols + 63) / 64)), dim3(256), 0, s, partial, (int)nb,
                      h, ncols, dgamma, norm == 0 ? dbeta : nullptr);
   return hipGetLastError();

@@ -135,11 +135,23 @@ def test_attn_causal_on_gpu():
     (16, 2, 70, 32, 0.25, I.NORM_LAYERNORM, 4.0),    # T = 16, LayerNorm, private channel scaling sqrt(T)
 ])
 def test_attn_block_bwd(T, batch, seq, heads, p, norm, scale):
+    _attn_block_bwd(T, batch, seq, heads, p, norm, scale, False)
+
+
+@pytest.mark.parametrize("T,batch,seq,heads,p,norm,scale", [
+    (2, 2, 200, 4, 0.5, I.NORM_RMSNORM, 1.0),
+    (4, 1, 130, 4, 0.25, I.NORM_LAYERNORM, 2.0),
+])
+def test_attn_block_bwd_reduce_as_its_own_kernel(T, batch, seq, heads, p, norm, scale):
+    _attn_block_bwd(T, batch, seq, heads, p, norm, scale, True)
+
+
+def _attn_block_bwd(T, batch, seq, heads, p, norm, scale, separate):
     cfg = _cfg(T, batch, seq, heads, p, norm, scale)
     # h = 4096 with 0.05-std weights gives scores with a spread of ~10 (nearly one-hot softmax rows, see the peaked-
     # softmax test below): the benchmark's own 0.02 keeps the comparison well conditioned there
     d = make_inputs(cfg, seed=23, with_grads=True, weight_std=0.05 if cfg.h < 4096 else 0.02)
-    got = run_attn_block(cfg, d, backward=True)
+    got = run_attn_block(cfg, d, backward=True, separate_reduce=separate)
     w, fwd = oracle_attn_block(cfg, d)
     check_attn(cfg, d, got, fwd)
     g = oracle_attn_bwd(cfg, w, fwd)

@@ -165,18 +165,27 @@ def test_mlp_block_p0_is_local():
 
 
 @pytest.mark.parametrize("swi", [False, True])
-@pytest.mark.parametrize("T,n,h,ffn,p", [(4, 300, 512, 4 * 256, 0.5), (8, 130, 1024, 8 * 128, 0.25), (16, 70, 512, 16 * 136, 0.5)])
-def test_mlp_block_reduce_as_its_own_kernel_gives_the_same_bits(swi, T, n, h, ffn, p):
-    """separate_reduce = 1 keeps the reduce a kernel of its own (the stand-in for the collective) followed by the norm;
-    the default runs them as one launch.  Both sum the same rounded partials in the same order and round once, so
-    R' must agree bit for bit (X' to one bf16 step), and both match the oracle."""
-    cfg = _cfg(swi, T, n, h, ffn, p)
-    d = make_inputs(cfg, seed=14, weight_std=0.05)
-    a = run_mlp_block(cfg, d, backward=False)
-    b = run_mlp_block(cfg, d, backward=False, separate_reduce=True)
+@pytest.mark.parametrize("T,n,h,ffn,p,scale", [(4, 300, 512, 4 * 256, 0.5, 1.0), (8, 130, 1024, 8 * 128, 0.25, 8.0 ** 0.5),
+                                               (16, 70, 512, 16 * 136, 0.5, 1.0), (2, 90, 8192, 2 * 128, 0.5, 1.0),
+                                               (8, 33, 4096, 8 * 128, 0.75, 1.0)])
+def test_mlp_block_reduce_as_its_own_kernel_gives_the_same_bits(swi, T, n, h, ffn, p, scale):
+    """separate_reduce = 1 keeps the reduce a kernel of its own (the stand-in for the collective), after the row-parallel
+    GEMM and after the norm backward; the default runs reduce + norm (forward) and norm backward + reduce (backward) as
+    one launch each.  The forward routes sum the same rounded partials in the same order and round once: R' must
+    agree bit for bit (X' to one bf16 step: the row statistics are added up in different orders); the backward routes
+    differ in the order of the norm backward's row sums, so they are compared through the oracle; on each route the
+    reduced gradient carries the same bits on every rank's shared channels."""
+    cfg = _cfg(swi, T, n, h, ffn, p, scale)
+    d = make_inputs(cfg, seed=14, weight_std=0.05 if h < 4096 else 0.02)
+    a = run_mlp_block(cfg, d)
+    b = run_mlp_block(cfg, d, separate_reduce=True)
     assert np.array_equal(a["Rp_bits"], b["Rp_bits"])
     # the two norm kernels add a row's squares in different orders: the statistics agree to fp32 rounding, the
     # normalised values to one bf16 step
     assert ulp_distance_bf16(a["Xp_bits"], b["Xp_bits"]).max() <= 1
-    w, fwd, _ = oracle_mlp_block(cfg, d, backward=False)
-    check_mlp_block(cfg, d, a, w, fwd, {}, backward=False)
+    hs = hs_of(cfg)
+    for m in range(1, T):     # reduced gradient: the same bits on every rank's shared channels, on both routes
+        assert np.array_equal(a["dZt"][m, :, :hs], a["dZt"][0, :, :hs]) and np.array_equal(b["dZt"][m, :, :hs], b["dZt"][0, :, :hs])
+    w, fwd, g = oracle_mlp_block(cfg, d)
+    check_mlp_block(cfg, d, a, w, fwd, g)
+    check_mlp_block(cfg, d, b, w, fwd, g)
