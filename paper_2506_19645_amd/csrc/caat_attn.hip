@@ -20,6 +20,10 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// LDS pointers with a type (address space 3): reads through them are single ds_read instructions with immediate offsets
+typedef __attribute__((address_space(3))) const u32x4_t* lds_u4_t;
+typedef __attribute__((address_space(3))) const char* lds_c_t;
+typedef __attribute__((address_space(3))) short4_t* lds_s4_t;
 
 static constexpr unsigned OOB_OFF = 0x80000000u;
 
@@ -284,9 +288,6 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16_t* __restr
   // spends no vector ALU work on addresses (they were about a third of its vector instructions).
   //   K fragment (32 rows x one 16-byte chunk): row = 32 j + frow, logical chunk 2 ks + hf  -> koff[ks] + (slot, j) constant
   //   V transpose read: row = 16 u + 4 hf + (i16 >> 2) (+ 8), head-dim column 32 dt + 16 grp + 4 (i16 & 3) -> voff[dt] + constant
-  typedef __attribute__((address_space(3))) const u32x4_t* lds_u4_t;
-  typedef __attribute__((address_space(3))) const char* lds_c_t;
-  typedef __attribute__((address_space(3))) short4_t* lds_s4_t;
   lds_u4_t koff[HD / 16];
   lds_c_t voff[HD / 32];
   {
@@ -434,7 +435,6 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16_t* __restr
   };
 
   // prologue: K(0) alone first (its scores open the pipeline), then K(1) and V(0) for the first loop iteration
-  // prologue: K(0) alone first (its scores open the pipeline), then K(1) and V(0) for the first loop iteration
   f32x16_t sa[BKV / 32], sb[BKV / 32];
   issue_k(0);
   wait_vmcnt<0>();
@@ -545,10 +545,62 @@ __device__ __forceinline__ void load_row_frags(const bf16_t* base, long long ld,
     f[ks] = __builtin_bit_cast(bf16x8_t, v);
   }
 }
+// Makes the compiler wait for these register loads HERE.  It counts the loads it knows of, not the global -> LDS copies
+// issued from inline assembly: left alone it puts its waits (down to vmcnt(0)) in front of the first use of each
+// fragment inside the key / query loop, where they wait in every iteration for the copies just issued for the next
+// block -- the prefetch then covers nothing.
+__device__ __forceinline__ void settle_row_frags(bf16x8_t* f) {
+#pragma unroll
+  for (int ks = 0; ks < HD / 16; ++ks) asm volatile("" : "+v"(f[ks]));
+}
 __device__ __forceinline__ bf16x8_t pack8(const float* v) {
   const uint4 w = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
   return __builtin_bit_cast(bf16x8_t, w);
 }
+
+// Per-lane LDS addresses of the fragment reads of a [64 rows][16 chunks] tile at LDS offset 0, fixed for a whole
+// kernel: which tile, which 32-row group or 16-row slice and which stage a read means is a constant added in the
+// read's immediate offset (or, for the stage, one add per address register and block), so the loops over key / query
+// blocks spend no vector ALU work on swizzled addresses.
+//   row fragment (frag_rows): row 32 j + frow, logical chunk 2 ks + hf             -> rows[ks] + constant
+//   transpose read (frag_cols): rows 16 u + 4 hf + (i16 >> 2) and + 8, column 32 dt + 16 grp + 4 (i16 & 3) -> cols0/1[dt] + constant
+struct FragAddr {
+  lds_u4_t rows[HD / 16];
+  lds_c_t cols0[HD / 32], cols1[HD / 32];
+  __device__ __forceinline__ void init(const uint4* smem, int lane) {
+    const lds_c_t lds0 = (lds_c_t)smem;
+    const int frow = lane & 31, hf = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ++ks) rows[ks] = (lds_u4_t)(lds0 + (frow * KCH + ((ks * 2 + hf) ^ fswz(frow))) * 16);
+    const int i16 = lane & 15, grp = (lane >> 4) & 1;
+    const int row0 = 4 * hf + (i16 >> 2), row1 = row0 + 8;
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt) {
+      const int col = dt * 32 + grp * 16 + (i16 & 3) * 4;
+      cols0[dt] = lds0 + ((row0 * KCH + ((col >> 3) ^ fswz(row0))) * 16 + (col & 7) * 2);
+      cols1[dt] = lds0 + ((row1 * KCH + ((col >> 3) ^ fswz(row1))) * 16 + (col & 7) * 2);
+    }
+  }
+  // the same addresses moved by `bytes` (a stage's offset)
+  __device__ __forceinline__ FragAddr at(int bytes) const {
+    FragAddr f;
+#pragma unroll
+    for (int ks = 0; ks < HD / 16; ++ks) f.rows[ks] = (lds_u4_t)((lds_c_t)rows[ks] + bytes);
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt) f.cols0[dt] = cols0[dt] + bytes, f.cols1[dt] = cols1[dt] + bytes;
+    return f;
+  }
+  // row fragment ks of the 32-row group whose first row lies `c` bytes into the addressed stage (c: compile-time)
+  __device__ __forceinline__ bf16x8_t row_frag(int ks, int c) const { return __builtin_bit_cast(bf16x8_t, rows[ks][c / 16]); }
+  // transposed fragment of head-dim tile dt of the 16-row slice whose first row lies `c` bytes into the stage
+  __device__ __forceinline__ bf16x8_t col_frag(int dt, int c) const {
+    typedef short short8_t __attribute__((ext_vector_type(8)));
+    const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_t)(cols0[dt] + c));
+    const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_t)(cols1[dt] + c));
+    const short8_t vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+    return __builtin_bit_cast(bf16x8_t, vv);
+  }
+};
 
 // D rows of the statistics: D[query] = sum_d dO * O, fp32; 16 lanes per (row, head).
 __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __restrict__ dout, const bf16_t* __restrict__ out,
@@ -606,8 +658,11 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16_t* __re
   bf16x8_t qf[HD / 16], dof[HD / 16];
   load_row_frags(qbase, ld, qrow, qvalid, hf, qf);
   load_row_frags(dobase, hd, qrow, qvalid, hf, dof);
-  const float my_lse = qvalid ? stats[(long long)bh * 2 * seq_pad + qrow] : 0.0f;
-  const float my_d = qvalid ? stats[((long long)bh * 2 + 1) * seq_pad + qrow] : 0.0f;
+  float my_lse = qvalid ? stats[(long long)bh * 2 * seq_pad + qrow] : 0.0f;
+  float my_d = qvalid ? stats[((long long)bh * 2 + 1) * seq_pad + qrow] : 0.0f;
+  settle_row_frags(qf);
+  settle_row_frags(dof);
+  asm volatile("" : "+v"(my_lse), "+v"(my_d));
 
   f32x16_t acc[HD / 32];
 #pragma unroll
@@ -623,47 +678,53 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16_t* __re
     issue_tile64(kbase + (long long)kv0 * ld, ld, seq - kv0, kt, wave, lane);
     issue_tile64(vbase + (long long)kv0 * ld, ld, seq - kv0, kt + BKV * KCH, wave, lane);
   };
+  FragAddr fa0;
+  fa0.init(smem, lane);
+  constexpr int TILE_BYTES = BKV * KCH * 16;               // stage = K tile, V tile
+  const f32x16_t zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   issue(0, 0);
   for (int blk = 0; blk < nblk; ++blk) {
     const int stage = blk & 1;
     wait_vmcnt<0>();
     __syncthreads();
     if (blk + 1 < nblk) issue(blk + 1, stage ^ 1);
-    const uint4* kt = smem + stage * (2 * BKV * KCH);
-    const uint4* vt = kt + BKV * KCH;
     const int kv0 = blk * BKV;
     if (kv0 > q0 + wave * 32 + 31) continue;               // wave-uniform: every key of the block is masked for this wave
     const bool diag = (kv0 + BKV - 1) > (q0 + wave * 32);  // wave-uniform: some key exceeds some query
-    bf16x8_t dsf[BKV / 16];
+    const FragAddr fa = fa0.at(stage * 2 * TILE_BYTES);
+    // two instantiations: the compare-and-select per score exists only in the blocks at the diagonal
+    auto key_block = [&](auto diag_c) {
+      constexpr bool DIAG = decltype(diag_c)::value;
+      bf16x8_t dsf[BKV / 16];
 #pragma unroll
-    for (int j = 0; j < BKV / 32; ++j) {
-      f32x16_t sacc, pacc;
+      for (int j = 0; j < BKV / 32; ++j) {
+        f32x16_t sacc = zero16, pacc = zero16;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[r] = 0.0f, pacc[r] = 0.0f;
-      const int row = j * 32 + frow;
-#pragma unroll
-      for (int ks = 0; ks < HD / 16; ++ks) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt, row, ks * 2 + hf), qf[ks], sacc, 0, 0, 0);
-        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt, row, ks * 2 + hf), dof[ks], pacc, 0, 0, 0);
-      }
-      float ds[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - my_lse);
-        if (diag) {
-          const int key = kv0 + j * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          p = key > qrow ? 0.0f : p;
+        for (int ks = 0; ks < HD / 16; ++ks) {
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.row_frag(ks, j * 32 * KCH * 16), qf[ks], sacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.row_frag(ks, TILE_BYTES + j * 32 * KCH * 16), dof[ks], pacc, 0, 0, 0);
         }
-        ds[r] = p * (pacc[r] - my_d);
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(sacc[r] * scale_log2 - my_lse);
+          if constexpr (DIAG) {
+            const int key = kv0 + j * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+            p = key > qrow ? 0.0f : p;
+          }
+          ds[r] = p * (pacc[r] - my_d);
+        }
+        dsf[j * 2 + 0] = pack8(ds);
+        dsf[j * 2 + 1] = pack8(ds + 8);
       }
-      dsf[j * 2 + 0] = pack8(ds);
-      dsf[j * 2 + 1] = pack8(ds + 8);
-    }
 #pragma unroll
-    for (int dt = 0; dt < HD / 32; ++dt)
+      for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
-      for (int u = 0; u < BKV / 16; ++u)
-        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt, dt, u * 16, lane), dsf[u], acc[dt], 0, 0, 0);
+        for (int u = 0; u < BKV / 16; ++u)
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.col_frag(dt, u * 16 * KCH * 16), dsf[u], acc[dt], 0, 0, 0);
+    };
+    if (diag) key_block(std::true_type{});
+    else key_block(std::false_type{});
   }
   // lane holds dQ[qrow][32dt + 8(r/4) + 4hf + r%4]
   if (qvalid) {
@@ -717,6 +778,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
   bf16x8_t kf[HD / 16], vf[HD / 16];
   load_row_frags(kbase, ld, krow, kvalid, hf, kf);
   load_row_frags(vbase, ld, krow, kvalid, hf, vf);
+  settle_row_frags(kf);
+  settle_row_frags(vf);
 
   f32x16_t dk[HD / 32], dv[HD / 32];
 #pragma unroll
@@ -727,31 +790,136 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
   const int nqb = (seq + BQB - 1) / BQB;
   const int qb0 = k0 / BQB;
   const int nq = nqb - qb0;                                  // query blocks per query head (>= 1: k0 < seq)
-  const int n_it = nq * grp;                                 // walk: query head of the group (outer), query block (inner)
-  auto issue = [&](int it, int stage) {
-    const int g = it / nq;
-    const int q0 = (qb0 + it - g * nq) * BQB;
+  // walk: query head of the group (outer), query block (inner)
+  // global -> LDS copies of a block (query head g of the group, query block qblk): per-lane memory-side offsets are
+  // fixed for the kernel, a block only moves the two base addresses
+  unsigned qo[4], doo[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int row = (c * 4 + wave) * 4 + (lane >> 4), phys = lane & 15;
+    qo[c] = (unsigned)((long long)row * ld * 2 + ((phys ^ fswz(row)) * 16));
+    doo[c] = (unsigned)((long long)row * hd * 2 + ((phys ^ fswz(row)) * 16));
+  }
+  const unsigned so = lane < 32 ? (unsigned)(((lane >> 4) * seq_pad + 4 * (lane & 15)) * 4) : OOB_OFF;
+  auto issue = [&](int g, int qblk, int stage) {
+    const int q0 = qblk * BQB;
+    const bool whole = q0 + BQB <= seq;                      // all 64 query rows exist (every block but a ragged last one)
+    const i32x4_t rq = make_rsrc(qbase + (long long)g * HD + (long long)q0 * ld);
+    const i32x4_t rd = make_rsrc(dobase + (long long)g * HD + (long long)q0 * hd);
     uint4* qt = smem + stage * DKV_STAGE;
-    issue_tile64(qbase + (long long)g * HD + (long long)q0 * ld, ld, seq - q0, qt, wave, lane);
-    issue_tile64(dobase + (long long)g * HD + (long long)q0 * hd, hd, seq - q0, qt + BQB * KCH, wave, lane);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int rg = c * 4 + wave;
+      const bool ok = whole || q0 + rg * 4 + (lane >> 4) < seq;   // rows past the sequence read as zero
+      dma16(rq, ok ? qo[c] : OOB_OFF, qt + rg * 64);
+      dma16(rd, ok ? doo[c] : OOB_OFF, qt + BQB * KCH + rg * 64);
+    }
     if (wave == 0) {
       // lanes 0..15: lse of queries q0 + 4*lane .. +3; lanes 16..31: D likewise; the rest reads zeros.
       // q0 + 63 < seq_pad always, so the 16-byte pieces stay inside this (sequence, head)'s rows of statistics.
-      const i32x4_t rs = make_rsrc(stats_bh + (long long)g * 2 * seq_pad);
-      const unsigned off = lane < 32 ? (unsigned)(((lane >> 4) * seq_pad + q0 + 4 * (lane & 15)) * 4) : OOB_OFF;
-      dma16(rs, off, qt + 2 * BQB * KCH);
+      const i32x4_t rs = make_rsrc(stats_bh + (long long)g * 2 * seq_pad + q0);
+      dma16(rs, so, qt + 2 * BQB * KCH);
     }
   };
-  issue(0, 0);
-  for (int it = 0; it < n_it; ++it) {
-    const int stage = it & 1;
-    wait_vmcnt<0>();
-    __syncthreads();
-    if (it + 1 < n_it) issue(it + 1, stage ^ 1);
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) const f32x4_t* lds_f4_t;
+  constexpr int TILE_BYTES = BQB * KCH * 16, STAGE_BYTES = DKV_STAGE * 16;   // stage = Q tile, dO tile, statistics
+  FragAddr fa0;
+  fa0.init(smem, lane);
+  const lds_f4_t soff = (lds_f4_t)((lds_c_t)smem + 2 * TILE_BYTES + hf * 16);
+  const f32x16_t zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+  // A block of 64 queries none of which is masked for this wave (every block of the walk but the one or two at the
+  // diagonal), both 32-query tiles in one hand-laid instruction stream: a wave issues in order and is alone on its
+  // SIMD here, so the vector work of one tile has to stand right behind the MFMAs of the other to run under them.
+  //   steps  0-15: S and dP of tile 0 (row fragments read three steps ahead)
+  //   steps 16-31: S and dP of tile 1; underneath: P and dS of tile 0, one query per step
+  //   steps 32-47: dV += dO^T P, dK += Q^T dS of tile 0 (transpose reads three steps ahead); underneath: P, dS of tile 1
+  //   steps 48-63: the same products of tile 1
+  // Every accumulator sees its MFMAs in the order of the tile-by-tile code below, so the two give the same bits.
+  auto full_block = [&](int stage) {
+    const FragAddr fa = fa0.at(stage * STAGE_BYTES);       // one add per address register and block
+    const lds_f4_t scur = (lds_f4_t)((lds_c_t)soff + stage * STAGE_BYTES);
+    auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+    auto rread = [&](int idx) -> u32x4_t {   // idx 0..31: tile idx / 16, head-dim slice (idx % 16) / 2, Q (even) or dO (odd)
+      return fa.rows[(idx & 15) >> 1][((idx & 1) * TILE_BYTES + (idx >> 4) * 32 * KCH * 16) / 16];
+    };
+    // idx 0..31: tile idx / 16, 16-query slice (idx % 16) / 8, head-dim tile (idx % 8) / 2, dO (even) or Q (odd)
+    auto cread = [&](int idx, short4_t& v0, short4_t& v1) {
+      const int dt = (idx & 7) >> 1;
+      const int c = ((idx & 1) ? 0 : TILE_BYTES) + ((idx >> 4) * 32 + ((idx & 15) >> 3) * 16) * KCH * 16;
+      v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_t)(fa.cols0[dt] + c));
+      v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_t)(fa.cols1[dt] + c));
+    };
+    f32x16_t sc[2], dp[2];
+    unsigned pw[2][8], dw[2][8];      // P and dS of the two tiles as bf16 pairs: words 4 t .. 4 t + 3 = slice t's B operand
+    f32x4_t l4[4], d4[4];             // lse and D of the 16 queries of this lane's registers
+    float pprev = 0.0f, dprev = 0.0f;
+    auto stats = [&](int j, int i) {  // query group i of tile j
+      l4[i] = scur[8 * j + 2 * i];
+      d4[i] = scur[16 + 8 * j + 2 * i];
+    };
+    auto prob = [&](int j, int r) {   // register r of tile j
+      const float pr = __builtin_amdgcn_exp2f(sc[j][r] * scale_log2 - l4[r >> 2][r & 3]);
+      const float dr = pr * (dp[j][r] - d4[r >> 2][r & 3]);
+      if (r & 1) {
+        pw[j][r >> 1] = pack2bf(pprev, pr);
+        dw[j][r >> 1] = pack2bf(dprev, dr);
+        asm volatile("" : "+v"(pw[j][r >> 1]), "+v"(dw[j][r >> 1]));   // pins the pair to this step
+      } else {
+        pprev = pr;
+        dprev = dr;
+        asm volatile("" : "+v"(pprev), "+v"(dprev));
+      }
+    };
+    u32x4_t fr[3];
+    fr[0] = rread(0);
+    fr[1] = rread(1);
+    fr[2] = rread(2);
+    fence();
+    short4_t va[3], vb[3];
+#pragma unroll
+    for (int idx = 0; idx < 32; ++idx) {
+      const int j = idx >> 4, ks = (idx & 15) >> 1;
+      const bf16x8_t f = __builtin_bit_cast(bf16x8_t, fr[idx % 3]);
+      if (idx & 1)
+        dp[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, vf[ks], ks == 0 ? zero16 : dp[j], 0, 0, 0);
+      else
+        sc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, kf[ks], ks == 0 ? zero16 : sc[j], 0, 0, 0);
+      if (idx + 3 < 32) fr[idx % 3] = rread(idx + 3);
+      else cread(idx + 3 - 32, va[(idx + 3) % 3], vb[(idx + 3) % 3]);   // the ring goes on into the transpose reads
+      if (idx >= 12 && idx < 16) stats(0, idx - 12);
+      if (idx >= 16) prob(0, idx - 16);
+      fence();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) stats(1, i);
+    fence();
+    typedef short short8_t __attribute__((ext_vector_type(8)));
+#pragma unroll
+    for (int idx = 0; idx < 32; ++idx) {
+      const int j = idx >> 4, t = (idx & 15) >> 3, dt = (idx & 7) >> 1;
+      const int sl = (idx + 32) % 3;
+      const short8_t vv = {va[sl][0], va[sl][1], va[sl][2], va[sl][3], vb[sl][0], vb[sl][1], vb[sl][2], vb[sl][3]};
+      const bf16x8_t a = __builtin_bit_cast(bf16x8_t, vv);
+      if (idx & 1) {
+        const bf16x8_t b = __builtin_bit_cast(bf16x8_t, make_uint4(dw[j][4 * t], dw[j][4 * t + 1], dw[j][4 * t + 2], dw[j][4 * t + 3]));
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, dk[dt], 0, 0, 0);
+      } else {
+        const bf16x8_t b = __builtin_bit_cast(bf16x8_t, make_uint4(pw[j][4 * t], pw[j][4 * t + 1], pw[j][4 * t + 2], pw[j][4 * t + 3]));
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, dv[dt], 0, 0, 0);
+      }
+      if (idx + 3 < 32) cread(idx + 3, va[sl], vb[sl]);
+      if (idx < 16) prob(1, idx);
+      fence();
+    }
+  };
+
+  // a block at the diagonal, tile by tile: a tile may be skipped (all its queries precede this wave's keys) or masked
+  auto diag_block = [&](int q0, int stage) {
     const uint4* qt = smem + stage * DKV_STAGE;
     const uint4* dot = qt + BQB * KCH;
     const float4* st = reinterpret_cast<const float4*>(qt + 2 * BQB * KCH);
-    const int q0 = (qb0 + it % nq) * BQB;
     // scores and dP of one 32-query tile: 16 MFMAs over the head dim
     auto scores = [&](int j, f32x16_t& sacc, f32x16_t& pacc) {
 #pragma unroll
@@ -809,6 +977,29 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
       scores(j, sacc, pacc);
       probs(j, qs < kw0 + 31, sacc, pacc, pf, df);           // wave-uniform: some key exceeds some query
       accumulate(j, pf, df);
+    }
+  };
+  // block it has landed and everyone is done with block it - 1: fetch block it + 1 = (query head ng, query block nb)
+  auto next_stage = [&](int it, int ng, int nb) {
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (ng < grp) issue(ng, nb, (it + 1) & 1);
+  };
+  issue(0, qb0, 0);
+  int it = 0;
+  for (int g = 0; g < grp; ++g) {
+    // the first two blocks of a query head's walk (128 queries = the workgroup's keys) touch the diagonal for some wave;
+    // from the third on no wave has a masked or skipped query, and every wave takes the fused two-tile stream
+    int b = 0;
+    for (; b < 2 && b < nq; ++b, ++it) {
+      const bool last = b + 1 == nq;
+      next_stage(it, last ? g + 1 : g, last ? qb0 : qb0 + b + 1);
+      diag_block((qb0 + b) * BQB, it & 1);
+    }
+    for (; b < nq; ++b, ++it) {
+      const bool last = b + 1 == nq;
+      next_stage(it, last ? g + 1 : g, last ? qb0 : qb0 + b + 1);
+      full_block(it & 1);
     }
   }
   // lane holds dK[krow][32dt + 8(r/4) + 4hf + r%4] and dV likewise
