@@ -410,7 +410,8 @@ def bench_attention_kinds(args, cfg, base):
         fl = {"gemm_nt_qkv": 2.0 * n * h * 3 * h, "flash_attn_fwd": 2.0 * cfg.batch * s * s * h,   # causal half of 4 s^2 h
               "gemm_nt_rowpar": 2.0 * n * h * h}
         by = {"rope": 2.0 * T * n * 2 * hd * 2, "partial_sync_fwd": 3.0 * T * n * hs_of(cfg) * 2,
-              "norm_fwd": 2.0 * T * n * h * 2}
+              "norm_fwd": 2.0 * T * n * h * 2,
+              "partial_sync_norm_fwd": (3.0 * T * n * hs_of(cfg) + T * n * (h - hs_of(cfg)) + T * n * h) * 2}
         work = sum(fl.values())
         if bwd:
             # five contractions instead of two in the attention core; the two NN and the two TN launches of a step
