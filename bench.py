@@ -191,14 +191,19 @@ class MlpBench:
 _SYNC_HOST = {}
 
 
-def standalone_sync(torch, B, cfg, hs, iters=20, nsets=8):
+def standalone_sync(torch, B, cfg, hs, iters=20, nsets=8, compact=False):
     """caat_partial_sync in place on the shared channels, rotating over buffer sets (> 1 GB) so that the
     last-level cache cannot hold the working set: the HBM-bound figure.  Seeded N(0,1) partial sums from the input
-    module (one host draw, copied into every set: the rotation is about addresses, not values)."""
+    module (one host draw, copied into every set: the rotation is about addresses, not values).
+    compact: the shared channels alone as [T, n, hs] buffers (rows of hs channels, all of them shared) -- the layout
+    of a communication buffer, where the synced bytes lie contiguously instead of as the first hs channels of rows of h."""
     if hs == 0:
         return 0.0, 0.0
     from paper_2506_19645_amd import inputs as I
-    T, n, h = cfg.T, cfg.tokens, cfg.h
+    T, n, h = cfg.T, cfg.tokens, (hs if compact else cfg.h)
+    # enough sets that the bytes the launches TOUCH (2 T n hs per set) exceed the 256 MB memory-side cache several times
+    nsets = max(nsets, int(1.2e9 / (2.0 * T * n * hs)) + 1)
+    iters = max(iters, nsets)
     key = (T, n, h)
     if key not in _SYNC_HOST:
         _SYNC_HOST.clear()
@@ -701,12 +706,15 @@ def bench_mlp(args, cfg, base):
             ms_sep, _ = bench.time_steps(dsep, max(5, args.steps // 2), max(3, args.warmup // 2))
             pr = bench.profile_steps(dsep, 5)
             sa_ms, sa_gbs = standalone_sync(torch, B, c, hs_of(c))
+            sc_ms, sc_gbs = standalone_sync(torch, B, c, hs_of(c), compact=True)
             e = {"p": p, "hs": hs_of(c), "ms_per_step": round(ms_p, 4), "TFLOP/s": round(step_flops / ms_p / 1e9, 1),
                  "ms_per_step_reduce_as_own_kernel": round(ms_sep, 4),
                  "synced_payload_bytes_per_token_per_reduce": 2 * hs_of(c),
                  "in_hbm_sync_bytes_per_token_fwd": 6 * c.T * hs_of(c), "in_hbm_sync_bytes_per_token_bwd": 4 * c.T * hs_of(c),
                  "standalone_sync_ms": round(sa_ms, 5), "standalone_sync_GB/s": round(sa_gbs, 1),
-                 "standalone_sync_frac_hbm": round(sa_gbs / HBM_PEAK_GBS, 4)}
+                 "standalone_sync_frac_hbm": round(sa_gbs / HBM_PEAK_GBS, 4),
+                 "standalone_sync_compact_ms": round(sc_ms, 5), "standalone_sync_compact_GB/s": round(sc_gbs, 1),
+                 "standalone_sync_compact_frac_hbm": round(sc_gbs / HBM_PEAK_GBS, 4)}
             for nm in ("partial_sync_fwd", "partial_sync_bwd"):
                 if nm in pr:
                     e[nm + "_ms"] = round(pr[nm]["avg_ms"], 5)
@@ -721,7 +729,7 @@ def bench_mlp(args, cfg, base):
     if len(sweep) >= 3:
         ps = [e["p"] for e in sweep]
         fit = {}
-        for key in ("partial_sync_fwd_ms", "partial_sync_bwd_ms", "standalone_sync_ms"):
+        for key in ("partial_sync_fwd_ms", "partial_sync_bwd_ms", "standalone_sync_ms", "standalone_sync_compact_ms"):
             ts = [e[key] for e in sweep]
             pm, tm = sum(ps) / len(ps), sum(ts) / len(ts)
             sxx = sum((a - pm) ** 2 for a in ps)
