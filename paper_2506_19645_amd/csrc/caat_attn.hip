@@ -854,22 +854,25 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const bf16_t* __rest
     f32x16_t sc[2], dp[2];
     unsigned pw[2][8], dw[2][8];      // P and dS of the two tiles as bf16 pairs: words 4 t .. 4 t + 3 = slice t's B operand
     f32x4_t l4[4], d4[4];             // lse and D of the 16 queries of this lane's registers
-    float pprev = 0.0f, dprev = 0.0f;
     auto stats = [&](int j, int i) {  // query group i of tile j
       l4[i] = scur[8 * j + 2 * i];
       d4[i] = scur[16 + 8 * j + 2 * i];
     };
-    auto prob = [&](int j, int r) {   // register r of tile j
-      const float pr = __builtin_amdgcn_exp2f(sc[j][r] * scale_log2 - l4[r >> 2][r & 3]);
-      const float dr = pr * (dp[j][r] - d4[r >> 2][r & 3]);
-      if (r & 1) {
-        pw[j][r >> 1] = pack2bf(pprev, pr);
-        dw[j][r >> 1] = pack2bf(dprev, dr);
-        asm volatile("" : "+v"(pw[j][r >> 1]), "+v"(dw[j][r >> 1]));   // pins the pair to this step
+    // P and dS of registers 2k, 2k+1 of tile j over two steps, so that the two chains of a step are independent of each
+    // other and a step's results are first used a step later (nothing waits on the exponential it has just issued)
+    float e0 = 0.0f, e1 = 0.0f, t0 = 0.0f, t1 = 0.0f;
+    auto prob = [&](int j, int step) {
+      const int k = step >> 1, r = 2 * k;
+      if ((step & 1) == 0) {
+        e0 = __builtin_amdgcn_exp2f(sc[j][r] * scale_log2 - l4[r >> 2][r & 3]);
+        e1 = __builtin_amdgcn_exp2f(sc[j][r + 1] * scale_log2 - l4[r >> 2][(r & 3) + 1]);
+        t0 = dp[j][r] - d4[r >> 2][r & 3];
+        t1 = dp[j][r + 1] - d4[r >> 2][(r & 3) + 1];
+        asm volatile("" : "+v"(e0), "+v"(e1), "+v"(t0), "+v"(t1));      // pins the work to this step
       } else {
-        pprev = pr;
-        dprev = dr;
-        asm volatile("" : "+v"(pprev), "+v"(dprev));
+        pw[j][k] = pack2bf(e0, e1);
+        dw[j][k] = pack2bf(e0 * t0, e1 * t1);
+        asm volatile("" : "+v"(pw[j][k]), "+v"(dw[j][k]));
       }
     };
     u32x4_t fr[3];
