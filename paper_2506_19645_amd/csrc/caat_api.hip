@@ -414,13 +414,15 @@ int layer_fwd(const caat_desc* d, const caat_ws_layout& L, const void* const* we
   q.c = QKV; q.ldc = qw; q.stride_c = n * qw;
   q.G = (int)T; q.M = (int)n; q.N = (int)qw; q.K = (int)h;
   CAAT_STEP("gemm_nt_qkv", launch_gemm(q, 0, EPI_PLAIN, s))
-  CAAT_STEP("rope_kv_append", launch_rope_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * d->batch, d->seq, (int)hpr, (int)kvpr,
-                                                 d->head_dim, d->rope_base, d->kv_cap, d->kv_len, s))
   if (prefill) {
+    CAAT_STEP("rope_kv_append", launch_rope_append(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, T * d->batch, d->seq, (int)hpr, (int)kvpr,
+                                                   d->head_dim, d->rope_base, d->kv_cap, d->kv_len, s))
     CAAT_STEP("flash_attn_fwd", launch_flash_fwd(QKV, H, nullptr, T * d->batch, d->seq, (int)hpr, (int)kvpr, d->head_dim, s))
   } else {
-    CAAT_STEP("decode_attn", launch_decode_attn(QKV, (const bf16_t*)kv_k, (const bf16_t*)kv_v, H, T * n, (int)hpr, (int)kvpr,
-                                                d->head_dim, d->kv_cap, d->kv_len + 1, s))
+    // decode: the attention kernel rotates q and the new k itself, appends k, v to the caches and attends to
+    // kv_len cached keys plus the new one
+    CAAT_STEP("decode_attn", launch_decode_attn(QKV, (bf16_t*)kv_k, (bf16_t*)kv_v, H, T * n, (int)hpr, (int)kvpr,
+                                                d->head_dim, d->kv_cap, d->kv_len + 1, d->rope_base, s))
   }
   // the reduce after o_proj and the RMSNorm in front of the MLP run as one launch where the fused kernel takes the
   // shape: for decode-sized batches both are start-up latency, for prompts the fused kernel does not read the

@@ -1056,66 +1056,133 @@ hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* 
 
 
 // ---------------------------------------------------------------------------------------------------------
-// Decode: one new token per sequence, whose rotated k and v the RoPE kernel above has appended to the caches at
-// position kv_len: attention of the single query over kv_len + 1 cached keys.  Pure streaming (the KV read is
-// the layer's dominant HBM traffic), so there is no MFMA here: a workgroup owns one (rank, sequence, head);
-// 16 lanes own one key row (256 B), a wave takes 4 consecutive keys per step, the 4 waves 16; every 16-lane group
-// runs its own online softmax and the 16 partial results are merged through LDS in a fixed order.
-__global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ kc,
-                                                          const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, int hpr,
-                                                          int kvpr, long long cap, int nkeys, float scale_log2) {
+// Decode: one new token per sequence at position kv_len: attention of its single query over the kv_len cached keys
+// and its own.  Pure streaming (the KV read is the layer's dominant HBM traffic), so there is no MFMA here: a workgroup
+// owns one (rank, sequence, head); 16 lanes own one key row (256 B), a wave takes 4 consecutive keys per step, the 4
+// waves 16; every 16-lane group runs its own online softmax and the 16 partial results are merged through LDS in a
+// fixed order.
+// ROPE: the kernel also does what the RoPE + append kernel would have done for this token (one launch less per decode
+// step): qkv holds the UN-rotated projections; q and the new k are rotated here for position nkeys - 1 (rounded to
+// bf16 exactly as that kernel stores them), the new k and v take part in the attention from registers, keys
+// 0 .. nkeys-2 are streamed from the caches, and the first query head of every key / value group writes the new rows
+// into the caches for later steps.  Nobody reads cache row nkeys - 1 in this launch.
+template <bool ROPE>
+__global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ kc,
+                                                          bf16_t* __restrict__ vc, bf16_t* __restrict__ out, int hpr,
+                                                          int kvpr, long long cap, int nkeys, float scale_log2,
+                                                          float log2_base) {
   __shared__ float s_acc[16][128];
   __shared__ float s_m[16], s_l[16];
+  __shared__ float s_cs[64], s_sn[64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;
   const long long sh = blockIdx.x;                 // seq * hpr + head
   const long long sq = sh / hpr;
   const int head = (int)(sh - sq * hpr);
-  float q[8];
-  {
-    const uint4 w = *reinterpret_cast<const uint4*>(qkv + sq * (long long)(hpr + 2 * kvpr) * 128 + (long long)head * 128 + c * 8);
-    q[0] = lo_bf(w.x); q[1] = hi_bf(w.x); q[2] = lo_bf(w.y); q[3] = hi_bf(w.y);
-    q[4] = lo_bf(w.z); q[5] = hi_bf(w.z); q[6] = lo_bf(w.w); q[7] = hi_bf(w.w);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) q[e] *= scale_log2;
-  }
-  const long long kvh = sq * kvpr + head / (hpr / kvpr);               // grouped-query attention: the group's cache rows
+  const int grp = hpr / kvpr;
+  const long long kvh = sq * kvpr + head / grp;    // grouped-query attention: the group's cache rows
   const __amdgpu_buffer_rsrc_t rk = attn_rsrc(kc + kvh * cap * 128);
   const __amdgpu_buffer_rsrc_t rv = attn_rsrc(vc + kvh * cap * 128);
-  float m = -INFINITY, l = 0.0f, acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int ncache = ROPE ? nkeys - 1 : nkeys;     // keys that come from the caches
   constexpr int UN = 4;   // loads per lane and stream in flight; 2 and 8 measured the same (319 - 321 us at batch 64, 2048 keys)
-  for (int key0 = wave * 4 + g; key0 < nkeys; key0 += 16 * UN) {
-    u32x4_t kv[UN], vv[UN];
+  u32x4_t kv[UN], vv[UN];
+  auto fetch = [&](int key0) {
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       const int key = key0 + 16 * u;
-      const unsigned off = key < nkeys ? (unsigned)key * 256u + c * 16 : OOB_OFF;
+      const unsigned off = key < ncache ? (unsigned)key * 256u + c * 16 : OOB_OFF;
       // read-once stream: the non-temporal hint (cache policy bit 1) measured 7.1 TB/s against 6.2 TB/s for plain
       // loads on a 2 GiB read with this access pattern
       kv[u] = __builtin_amdgcn_raw_buffer_load_b128(rk, (int)off, 0, 2);
       vv[u] = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)off, 0, 2);
     }
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const bool valid = (key0 + 16 * u) < nkeys;
-      float s = q[0] * lo_bf(kv[u].x) + q[1] * hi_bf(kv[u].x) + q[2] * lo_bf(kv[u].y) + q[3] * hi_bf(kv[u].y) +
-                q[4] * lo_bf(kv[u].z) + q[5] * hi_bf(kv[u].z) + q[6] * lo_bf(kv[u].w) + q[7] * hi_bf(kv[u].w);
-      s += __shfl_xor(s, 1, 64);
-      s += __shfl_xor(s, 2, 64);
-      s += __shfl_xor(s, 4, 64);
-      s += __shfl_xor(s, 8, 64);
-      const float m_new = valid ? fmaxf(m, s) : m;
-      const float alpha = valid ? exp2f(m - m_new) : 1.0f;     // m = -inf on the first key: exp2(-inf) = 0
-      const float p = valid ? exp2f(s - m_new) : 0.0f;
-      l = l * alpha + p;
-      const unsigned w[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc[2 * e] = acc[2 * e] * alpha + p * lo_bf(w[e]);
-        acc[2 * e + 1] = acc[2 * e + 1] * alpha + p * hi_bf(w[e]);
+  };
+  int key0 = wave * 4 + g;
+  fetch(key0);                                     // the first keys are on their way while q is prepared
+  const bf16_t* row = qkv + sq * (long long)(hpr + 2 * kvpr) * 128;
+  float q[8];
+  uint4 knew = make_uint4(0u, 0u, 0u, 0u), vnew = knew;   // the token's own key (rotated) and value, 8 dims per lane
+  {
+    uint4 w = *reinterpret_cast<const uint4*>(row + (long long)head * 128 + c * 8);
+    if constexpr (ROPE) {
+      const uint4 kw = *reinterpret_cast<const uint4*>(row + (long long)(hpr + head / grp) * 128 + c * 8);
+      vnew = *reinterpret_cast<const uint4*>(row + (long long)(hpr + kvpr + head / grp) * 128 + c * 8);
+      // angle j of the position, j = 0 .. 63, once per workgroup (the same expressions as the RoPE + append kernel)
+      if (tid < 64) {
+        const float inv = exp2f(-2.0f * (float)tid / 128.0f * log2_base);
+        float sn, cs;
+        sincosf((float)(nkeys - 1) * inv, &sn, &cs);
+        s_cs[tid] = cs;
+        s_sn[tid] = sn;
       }
-      m = m_new;
+      __syncthreads();
+      // lanes c < 8 hold dims 8c .. 8c+7 (x1 of the pairs), lanes c >= 8 the dims 64 further on (x2): partner = lane ^ 8
+      auto rotate = [&](const uint4& v) -> uint4 {
+        const unsigned own[4] = {v.x, v.y, v.z, v.w};
+        unsigned res[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned oth = (unsigned)__shfl_xor((int)own[i], 8, 64);
+          float y[2];
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int j = (c & 7) * 8 + i * 2 + e;
+            const float mine = e ? hi_bf(own[i]) : lo_bf(own[i]), theirs = e ? hi_bf(oth) : lo_bf(oth);
+            const float cs = s_cs[j], sn = s_sn[j];
+            y[e] = c < 8 ? mine * cs - theirs * sn : mine * cs + theirs * sn;
+          }
+          res[i] = pack2bf(y[0], y[1]);
+        }
+        return make_uint4(res[0], res[1], res[2], res[3]);
+      };
+      w = rotate(w);
+      knew = rotate(kw);
+      if (head % grp == 0 && wave == 0 && g == 0) {          // one 16-lane group writes the 256-byte rows
+        const long long dst = (kvh * cap + (nkeys - 1)) * 128 + c * 8;
+        st_stream(kc + dst, knew);
+        st_stream(vc + dst, vnew);
+      }
     }
+    q[0] = lo_bf(w.x); q[1] = hi_bf(w.x); q[2] = lo_bf(w.y); q[3] = hi_bf(w.y);
+    q[4] = lo_bf(w.z); q[5] = hi_bf(w.z); q[6] = lo_bf(w.w); q[7] = hi_bf(w.w);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[e] *= scale_log2;
+  }
+  float m = -INFINITY, l = 0.0f, acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  // one key: score of the 16-lane group, online-softmax update with its value row
+  auto take = [&](const u32x4_t& kx, const u32x4_t& vx, bool valid) {
+    float s = q[0] * lo_bf(kx.x) + q[1] * hi_bf(kx.x) + q[2] * lo_bf(kx.y) + q[3] * hi_bf(kx.y) +
+              q[4] * lo_bf(kx.z) + q[5] * hi_bf(kx.z) + q[6] * lo_bf(kx.w) + q[7] * hi_bf(kx.w);
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    s += __shfl_xor(s, 4, 64);
+    s += __shfl_xor(s, 8, 64);
+    const float m_new = valid ? fmaxf(m, s) : m;
+    const float alpha = valid ? exp2f(m - m_new) : 1.0f;     // m = -inf on the first key: exp2(-inf) = 0
+    const float p = valid ? exp2f(s - m_new) : 0.0f;
+    l = l * alpha + p;
+    const unsigned w[4] = {vx.x, vx.y, vx.z, vx.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc[2 * e] = acc[2 * e] * alpha + p * lo_bf(w[e]);
+      acc[2 * e + 1] = acc[2 * e + 1] * alpha + p * hi_bf(w[e]);
+    }
+    m = m_new;
+  };
+  while (key0 < ncache) {
+    u32x4_t kcur[UN], vcur[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) kcur[u] = kv[u], vcur[u] = vv[u];
+    const int k0 = key0;
+    key0 += 16 * UN;
+    if (key0 < ncache) fetch(key0);
+#pragma unroll
+    for (int u = 0; u < UN; ++u) take(kcur[u], vcur[u], (k0 + 16 * u) < ncache);
+  }
+  if constexpr (ROPE) {
+    // the token's own key and value: one stream takes them (the same for every workgroup: a fixed order of summation)
+    const u32x4_t kx = {knew.x, knew.y, knew.z, knew.w}, vx = {vnew.x, vnew.y, vnew.z, vnew.w};
+    take(kx, vx, wave == 0 && g == 0);
   }
   const int stream = wave * 4 + g;
 #pragma unroll
@@ -1140,17 +1207,24 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restri
   }
 }
 
-// out [n_seq, hpr*128] = softmax(q K^T / sqrt(d)) V over keys 0 .. nkeys-1 of caches [n_seq][kvpr][cap][128]
-hipError_t launch_decode_attn(const bf16_t* qkv, const bf16_t* kc, const bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
-                              int kvpr, int d, long long cap, long long nkeys, hipStream_t s) {
+// out [n_seq, hpr*128] = softmax(q K^T / sqrt(d)) V over keys 0 .. nkeys-1 of caches [n_seq][kvpr][cap][128].
+// rope_base > 0: qkv holds the un-rotated projections of the token at position nkeys - 1; the kernel rotates q and k,
+// uses the new key / value from registers and stores them at cache row nkeys - 1 (no RoPE + append launch needed).
+// rope_base = 0: q is rotated already and all nkeys keys are in the caches.
+hipError_t launch_decode_attn(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
+                              int kvpr, int d, long long cap, long long nkeys, float rope_base, hipStream_t s) {
   if (d != HD || kvpr < 1 || hpr % kvpr != 0 || nkeys < 1 || nkeys > cap || cap * 256 >= 0x7FFFFFFFLL)
     return hipErrorInvalidValue;
   const long long blocks = n_seq * hpr;
   if (blocks == 0) return hipSuccess;
   if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)d);
-  hipLaunchKernelGGL(decode_attn_kernel, dim3((unsigned)blocks), dim3(256), 0, s, qkv, kc, vc, out, hpr, kvpr, cap, (int)nkeys,
-                     scale_log2);
+  if (rope_base > 0.0f)
+    hipLaunchKernelGGL(decode_attn_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, qkv, kc, vc, out, hpr, kvpr, cap,
+                       (int)nkeys, scale_log2, log2f(rope_base));
+  else
+    hipLaunchKernelGGL(decode_attn_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, qkv, kc, vc, out, hpr, kvpr, cap,
+                       (int)nkeys, scale_log2, 0.0f);
   return hipGetLastError();
 }
 

@@ -245,7 +245,7 @@ hipError_t launch_flash_fwd(const bf16_t* qkv, bf16_t* out, float* stats, long l
                             int d, hipStream_t s);
 hipError_t launch_flash_bwd(const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, float* stats, bf16_t* dqkv,
                             long long n_seq, int seq, int heads, int kv_heads, int d, hipStream_t s);
-hipError_t launch_decode_attn(const bf16_t* qkv, const bf16_t* kc, const bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
-                              int kvpr, int d, long long cap, long long nkeys, hipStream_t s);
+hipError_t launch_decode_attn(const bf16_t* qkv, bf16_t* kc, bf16_t* vc, bf16_t* out, long long n_seq, int hpr,
+                              int kvpr, int d, long long cap, long long nkeys, float rope_base, hipStream_t s);
 
 }  // namespace caat
