@@ -751,11 +751,11 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
     if (e != hipSuccess) return CAAT_EHIP;
   }
 
-  // The four GEMMs of the backward pass.  Order: the weight gradient dB first, then the activation-derivative GEMM and
-  // its two consumers.  Whichever GEMM runs right behind the streaming norm-backward kernel measured about 20 us slower
-  // than elsewhere in the sequence (that kernel's 268 MB of fresh writes are still draining), and the weight-gradient
-  // GEMM, which writes least, loses least there: h = 2048, T = 4, 8192 tokens: step 1.645 -> 1.637 ms against the
-  // order G, B, X, A; the other four admissible orders measured 1.645 - 1.679 ms.
+  // The four GEMMs of the backward pass, in the order G (activation-derivative GEMM), B (dB), X (dX), A (dA).
+  // Whichever GEMM runs right behind the streaming norm-backward kernel measured about 20 us slower than elsewhere in
+  // the sequence (that kernel's fresh writes are still draining).  The six admissible orders (h = 2048, T = 4, 8192
+  // tokens): B G X A 1.637 ms per step, G B X A 1.645, the rest 1.645 - 1.679; B first only moves the slow slot from G
+  // to the weight-gradient GEMM (213 -> 221 us averaged over its two launches), so the plain order stays.
   GemmParams q;
   auto run_B = [&]() {
     std::memset(&q, 0, sizeof(q));
@@ -794,9 +794,9 @@ int caat_block_bwd(const caat_desc* d, const void* const* weights, const void* x
     ProfScope ps(s, "gemm_tn_wgrad");
     return launch_gemm(q, 2, EPI_PLAIN, s);
   };
-  e = run_B();   // a9: dB_m [h, f/T] = dZt_m^T Y_m (TN, reduction over tokens)
-  if (e != hipSuccess) return CAAT_EHIP;
   e = run_G();   // a9 + a10: dY_m = dZt_m B_m (NN), fused with the activation derivative -> dP_m
+  if (e != hipSuccess) return CAAT_EHIP;
+  e = run_B();   // a9: dB_m [h, f/T] = dZt_m^T Y_m (TN, reduction over tokens)
   if (e != hipSuccess) return CAAT_EHIP;
   e = run_X();   // a11: dX_m = dP_m A_m (NN); NOT reduced over ranks (Sec. 4: the only reduce sits at the row-parallel output)
   if (e != hipSuccess) return CAAT_EHIP;

@@ -133,7 +133,7 @@ def test_profile_records_every_launch(separate):
     # forward: reduce + residual + norm in one launch, backward: norm backward + reduce in one launch, unless the
     # caller asks for the reduce as a kernel of its own
     mid = ["partial_sync_fwd", "norm_fwd", "norm_bwd", "partial_sync_bwd"] if separate else ["partial_sync_norm_fwd", "norm_bwd_sync"]
-    assert names == ["gemm_nt_gelu_fwd", "gemm_nt_rowpar"] + mid + ["gemm_tn_wgrad", "gemm_nn_gelu_bwd", "gemm_nn_dgrad",
+    assert names == ["gemm_nt_gelu_fwd", "gemm_nt_rowpar"] + mid + ["gemm_nn_gelu_bwd", "gemm_tn_wgrad", "gemm_nn_dgrad",
                                                                    "gemm_tn_wgrad"]
     assert all(ms > 0.0 for _, ms in rec)
     B.profile_reset()
