@@ -92,7 +92,8 @@ hipError_t launch_rope(bf16_t* qkv, long long rows, int seq, int ld, int n_rot, 
 }
 
 // RoPE on q and k in place and, in the same pass, the store of the rotated k and of v into the KV caches
-// [n_seq][kvpr][cap][128] at positions pos0 .. pos0+seq-1 (decode: seq = 1; prefill: the whole prompt).  One thread
+// [n_seq][kvpr][cap][128] at positions pos0 .. pos0+seq-1 (the prompts of a prefill; a decode step does the same for
+// its one token inside the attention kernel).  One thread
 // rotates 8 pairs (j, j + d/2) of one q or k head of one token; the threads of a k head also write their two rotated
 // chunks to the key cache and copy the matching two chunks of v to the value cache, so a k / v head is covered by
 // its 8 threads.  d = 128 only (the cache rows are 128 wide).
